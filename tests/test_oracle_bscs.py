@@ -1,0 +1,255 @@
+"""Pins of the oracle's Bounded Speculation with Cached States (Sec. 3.3,
+Appendix A): exactness against brute-force greedy decoding, the paper's two
+worked examples, the layer-count model of Eq. 3, and the accept rule.  CPU only."""
+import itertools
+
+import numpy as np
+import pytest
+
+import sb_inputs as si
+import oracle as orc
+from helpers import tiny_model, params, all_accept_weights
+from oracle import Oracle
+
+
+@pytest.fixture(scope="module")
+def model6():
+    # 6 layers, exit heads after layers 1..3
+    return tiny_model(n_layers=6, n_exit_heads=3, seed=21)
+
+
+def test_speculative_output_equals_bruteforce_greedy(model6):
+    shape, w, m = model6
+    n_new = 20
+    for pseed in (1, 2, 3):
+        prompt = si.make_prompt(shape.vocab, 8, 100 + pseed)
+        bf = m.greedy_nocache(prompt, n_new).tolist()
+        for d_max, w_max, thr in itertools.product((1, 2, 3), (1, 2, 4, 6), (0.0, 2.0 / shape.vocab, 0.5, 1.1)):
+            s = m.session()
+            out = s.generate(prompt, n_new, params(d_max, w_max, thr)).tolist()
+            assert out == bf, (pseed, d_max, w_max, thr)
+            st = s.stats()
+            if thr == 0.0:      # every token exits at layer 1: rounds are width-bound
+                assert st["exit_hist"][1] == st["draft_steps"]
+            if thr > 1.0:       # never exits: every round is depth-bound with one row
+                assert st["drafts"] == 0 and st["exit_hist"][0] == st["draft_steps"]
+
+
+def test_forced_exit_schedules_keep_greedy_output(model6):
+    shape, w, m = model6
+    prompt = si.make_prompt(shape.vocab, 8, 200)
+    n_new = 24
+    bf = m.greedy_nocache(prompt, n_new).tolist()
+    for seed in range(4):
+        fe = si.forced_exit_schedule(seed, 200, 0, 3)       # 0 = forced no-exit
+        for w_max in (2, 4, 5):
+            s = m.session()
+            assert s.generate(prompt, n_new, params(3, w_max, 0.5, forced_exit=fe)).tolist() == bf
+
+
+def test_reductions_to_autoregressive_decoding(model6):
+    shape, w, m = model6
+    L = shape.n_layers
+    prompt = si.make_prompt(shape.vocab, 8, 300)
+    n_new = 12
+    bf = m.greedy_nocache(prompt, n_new).tolist()
+    prefill_sweeps = len(prompt) * L
+    # w_max = 1: one row, one emitted token per round
+    s = m.session(); assert s.generate(prompt, n_new, params(2, 1, 0.0)).tolist() == bf
+    st = s.stats()
+    assert st["accept_hist"][1] == st["rounds"] == n_new - 1
+    assert st["layer_sweeps"] - prefill_sweeps == L * (n_new - 1)
+    # threshold above 1: never exits, every round depth-bound with one row, L sweeps per token
+    s = m.session(); assert s.generate(prompt, n_new, params(3, 4, 1.5)).tolist() == bf
+    st = s.stats()
+    assert st["rounds"] == n_new - 1 and st["row_layers"] - prefill_sweeps == L * (n_new - 1)
+    assert st["head_evals"] == 3 * (n_new - 1)
+    # d_max = 0: plain greedy decoding, no exit head is ever evaluated
+    s = m.session(); assert s.generate(prompt, n_new, params(0, 1)).tolist() == bf
+    assert s.stats()["head_evals"] == 0
+
+
+def _run_forced_round(m, shape, gd, prompt):
+    s = m.session()
+    s.trace_enable()
+    s.prefill(prompt)
+    p = params(gd["d_max"][0], gd["w_max"][0], 0.5, forced_exit=gd["forced_exit"])
+    results = []
+    while True:
+        r = s.draft_step(p)
+        results.append(r)
+        if r["status"] != orc.EXITED:
+            break
+    return s, p, results
+
+
+def test_worked_example_depth_bound(golden):
+    gd = golden("worked_example_depth_bound.txt")
+    shape, w, m = tiny_model(n_layers=9, n_exit_heads=6, seed=22)
+    s, p, res = _run_forced_round(m, shape, gd, si.make_prompt(shape.vocab, 5, 400))
+    assert len(res) == gd["n_draft_steps"][0]
+    assert [r["exit_layer"] for r in res] == gd["forced_exit"]
+    assert res[-1]["status"] == orc.DEPTH_BOUND
+    assert s.open_slots() == gd["verify_rows"][0]
+    assert [s.slot_reached(i) for i in range(s.open_slots())] == gd["reached_before_verify"]
+    # layer passes while drafting: (layer, rows) per step, under lazy Reuse
+    tr = [t for t in s.trace() if t[0] == orc.PH_DRAFT]
+    assert [(t[1], t[3]) for t in tr] == [(1, 1), (2, 1),                       # step 1 exits at 2
+                                          (1, 1), (2, 1), (3, 2), (4, 2),       # step 2 pulls row 1 along
+                                          (1, 1), (2, 1), (3, 1), (4, 1), (5, 3), (6, 3)]
+    v = s.verify(p)
+    assert v["n_rows"] == gd["verify_rows"][0] and v["n_drafts"] == gd["n_drafts"][0]
+    assert v["align_layer"] == gd["align_layer"][0]
+    tr = s.trace()
+    assert sum(1 for t in tr if t[0] == orc.PH_ALIGN) == gd["n_align_passes"][0]
+    ver = [t for t in tr if t[0] == orc.PH_VERIFY]
+    assert ver[0][1] == gd["verify_first_layer"][0] and ver[-1][1] == shape.n_layers
+    assert all(t[3] == gd["verify_rows"][0] and t[2] == 0 for t in ver)
+    assert [t[1] for t in ver] == list(range(7, shape.n_layers + 1))
+
+
+def test_worked_example_width_bound(golden):
+    gd = golden("worked_example_width_bound.txt")
+    shape, w, m = tiny_model(n_layers=9, n_exit_heads=6, seed=23)
+    s, p, res = _run_forced_round(m, shape, gd, si.make_prompt(shape.vocab, 5, 401))
+    assert len(res) == gd["n_draft_steps"][0]
+    assert [r["status"] for r in res] == [orc.EXITED] * 3 + [orc.WIDTH_BOUND]
+    assert [s.slot_reached(i) for i in range(4)] == gd["reached_after_drafting"]
+    v = s.verify(p)
+    assert v["n_rows"] == gd["verify_rows"][0] and v["n_drafts"] == gd["n_drafts"][0]
+    assert v["align_layer"] == gd["align_layer"][0]
+    tr = s.trace()
+    al = [t for t in tr if t[0] == orc.PH_ALIGN]
+    assert [t[1] for t in al] == gd["align_layers"]
+    assert all(t[3] == gd["align_rows"][0] and t[2] == 3 for t in al)      # only the fourth row
+    ver = [t for t in tr if t[0] == orc.PH_VERIFY]
+    assert [t[1] for t in ver] == list(range(gd["verify_first_layer"][0], shape.n_layers + 1))
+    assert all(t[3] == 4 for t in ver)
+    # a further draft step is refused once a bound was hit; verify with no rows too
+    assert s.verify(p, check=False) == -4
+
+
+def test_layer_sweeps_match_eq3_when_all_exits_at_dmax():
+    shape, w, m = tiny_model(n_layers=8, n_exit_heads=3, seed=24)
+    L, d_max = shape.n_layers, 3
+    prompt = si.make_prompt(shape.vocab, 6, 500)
+    for w_max in (1, 2, 4):
+        s = m.session()
+        s.prefill(prompt)
+        base = s.stats()["layer_sweeps"]
+        p = params(d_max, w_max, 0.5, forced_exit=[d_max] * 64)
+        for rounds in range(1, 4):
+            while s.draft_step(p)["status"] == orc.EXITED:
+                pass
+            s.verify(p)
+            sweeps = s.stats()["layer_sweeps"] - base
+            assert sweeps == rounds * (w_max * d_max + L - d_max)
+            assert abs(sweeps / rounds / L - orc.round_time(L, d_max, w_max)) < 1e-12
+
+
+def test_all_accept_fixture_emits_w_max_per_round():
+    shape = si.tiny_shape(n_layers=6, n_exit_heads=3)
+    w = all_accept_weights(shape, si.make_weights(shape, 25, gain_jitter=0.1), k=2)
+    m = Oracle(shape, w, 160)
+    prompt = si.make_prompt(shape.vocab, 7, 600)
+    n_new = 25
+    bf = m.greedy_nocache(prompt, n_new).tolist()
+    for w_max in (2, 3, 5):
+        s = m.session()
+        out = s.generate(prompt, n_new, params(3, w_max, 0.5, forced_exit=[2, 3] * 100)).tolist()
+        assert out == bf
+        st = s.stats()
+        full = st["accept_hist"][w_max]
+        assert full >= st["rounds"] - 1 and st["rounds"] == -(-(n_new - 1) // w_max)
+    # an exit at layer 1 (< k) is not the final hidden state: drafts can be rejected, output still exact
+    s = m.session()
+    assert s.generate(prompt, n_new, params(3, 4, 0.5, forced_exit=[1] * 100)).tolist() == bf
+
+
+def test_all_reject_emits_exactly_one_token_per_round(model6):
+    # App. D worst case: maximum width, every draft rejected -> one token decoded per cycle
+    shape, w, m = model6
+    prompt = si.make_prompt(shape.vocab, 8, 700)
+    n_new = 10
+    bf = m.greedy_nocache(prompt, n_new).tolist()
+    w_max = 4
+    rounds = n_new - 1
+    fd = []
+    for r in range(rounds):
+        fd += [(bf[r + 1] + 1) % shape.vocab] + [-1] * (w_max - 1)   # first draft wrong
+    s = m.session()
+    out = s.generate(prompt, n_new, params(3, w_max, 0.5, forced_exit=[1] * len(fd), forced_draft=fd))
+    assert out.tolist() == bf
+    st = s.stats()
+    assert st["rounds"] == rounds and st["accept_hist"][1] == rounds
+
+
+def test_draft_injection_realises_accept_schedule(model6):
+    shape, w, m = model6
+    prompt = si.make_prompt(shape.vocab, 8, 800)
+    n_new = 40
+    bf = m.greedy_nocache(prompt, n_new + 8).tolist()
+    w_max = 4
+    acc = si.accept_schedule(9, 64, w_max)
+    fd, rounds = si.injection_schedule(bf, acc, w_max, shape.vocab)
+    fe = si.forced_exit_schedule(10, len(fd), 1, 3)
+    s = m.session()
+    s.prefill(prompt)
+    p = params(3, w_max, 0.5, forced_exit=fe, forced_draft=fd)
+    emitted = [bf[0]]
+    for r in range(rounds):
+        while s.draft_step(p)["status"] == orc.EXITED:
+            pass
+        v = s.verify(p)
+        assert v["n_emit"] == acc[r], (r, v, acc[r])
+        emitted += v["tokens"][: v["n_emit"]]
+    assert emitted == bf[: len(emitted)]
+    assert s.committed_len() == len(prompt) + len(emitted) - 1
+
+
+def test_lazy_and_eager_reuse_agree_bit_for_bit(model6):
+    shape, w, m = model6
+    prompt = si.make_prompt(shape.vocab, 8, 900)
+    fe = [1, 3, 2, 0, 3, 1, 2, 2, 0, 1, 1, 3] * 4
+    outs, hs = [], []
+    for eager in (False, True):
+        s = m.session(); s.set_eager_align(eager); s.prefill(prompt)
+        p = params(3, 4, 0.5, forced_exit=fe)
+        toks, hid = [], []
+        for _ in range(6):
+            while s.draft_step(p)["status"] == orc.EXITED:
+                pass
+            hid.append([s.slot_hidden(i) for i in range(s.open_slots())])
+            v = s.verify(p)
+            toks += v["tokens"][: v["n_emit"]]
+            hid.append(s.verify_logits(0))
+        outs.append(toks); hs.append(hid)
+    assert outs[0] == outs[1]
+    for a, b in zip(hs[0], hs[1]):
+        if isinstance(a, list):
+            # eager rows stand at the deepest layer already; compare after verification instead
+            continue
+        assert np.array_equal(a, b)
+
+
+def test_max_new_truncation_eos_and_errors(model6):
+    shape, w, m = model6
+    prompt = si.make_prompt(shape.vocab, 8, 1000)
+    bf = m.greedy_nocache(prompt, 12).tolist()
+    # truncated emission leaves a session that continues correctly
+    s = m.session()
+    out = s.generate(prompt, 5, params(3, 4, 0.0)).tolist()
+    assert out == bf[:5] and s.committed_len() == len(prompt) + 4
+    # eos stops generation right after the eos token
+    s = m.session()
+    out = s.generate(prompt, 12, params(3, 4, 0.0, eos_id=bf[3])).tolist()
+    assert out == bf[: bf.index(bf[3]) + 1]
+    # parameter errors
+    s = m.session()
+    s.prefill(prompt)
+    assert s.draft_step(params(4, 2), check=False) == -1          # d_max beyond the exit heads
+    assert s.draft_step(params(2, 0), check=False) == -1          # w_max < 1
+    assert s.draft_step(params(2, 2, T=[1.0, 0.0]), check=False) == -1   # non-positive temperature
+    assert s.verify(params(2, 2), check=False) == -4              # nothing to verify
+    s2 = m.session()
+    assert s2.draft_step(params(2, 2), check=False) == -4         # no prefill yet
