@@ -1,0 +1,255 @@
+/*
+ * specbound.h -- C ABI of libspecbound: the batch-1 bounded self-speculative
+ * decode step (SpecBound) as hand-written gfx950 kernels.
+ *
+ * The calls follow the paper's statement of the method: a draft phase that runs
+ * each new token through the shallow layers and tests an early-exit head after
+ * every layer (Annealed Confidence Threshold, Sec. 3.2, Eq. 1-2), bounded by a
+ * depth bound d_max and a width bound w_max (Bounded Speculation with Cached
+ * States, Sec. 3.3, Appendix A), and a verify phase that sends the cached hidden
+ * states of at most w_max rows through the remaining layers in one causal pass
+ * and keeps the longest prefix that matches greedy decoding, so that the output
+ * is exactly that of greedy autoregressive decoding.
+ *
+ * Conventions
+ *  - Every call returns SB_OK (0) or a negative error; sb_last_error() gives the
+ *    message of the calling thread's last failure.  A failing call leaves the
+ *    session as it was.
+ *  - "device" pointers are HIP device memory on the model's GPU; "host" pointers
+ *    are ordinary memory.  Nothing the caller passes is freed by the library.
+ *  - Weights are BORROWED: the device buffers named in sb_weights must outlive
+ *    the model.  The host arrays of pointers are copied at load time.
+ *  - The KV pool and the workspace are caller-owned device memory, borrowed for
+ *    the session's lifetime.  sb_query_sizes() says how large they must be.
+ *  - All kernels are enqueued on the stream given to sb_load_model (a
+ *    hipStream_t cast to void*; NULL = the default stream).  Calls that return
+ *    results to the host synchronise that stream before returning.
+ *  - One session = one sequence (batch 1).  Calls on one session must not
+ *    overlap; sessions of one model share its stream.
+ */
+#ifndef SPECBOUND_H
+#define SPECBOUND_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SB_MAX_W 8      /* largest width bound / rows per pass */
+#define SB_KV_BLOCK 16  /* tokens per KV page */
+#define SB_MAX_EXIT_LAYERS 64
+
+enum { SB_OK = 0, SB_EINVAL = -1, SB_ENOMEM = -2, SB_ECAPACITY = -3, SB_ESTATE = -4, SB_EDEVICE = -5 };
+enum { SB_FP32 = 0, SB_BF16 = 1 };
+/* status of a draft step */
+enum { SB_EXITED = 1, SB_WIDTH_BOUND = 2, SB_DEPTH_BOUND = 3 };
+/* projection kernels: plain vector-ALU dot products, or MFMA tiles (bf16 weights only) */
+enum { SB_PROJ_AUTO = 0, SB_PROJ_VALU = 1, SB_PROJ_MFMA = 2 };
+
+/* LLaMA-style pre-norm decoder: RMSNorm, rotary embedding (half-split pairing,
+ * theta_i = rope_base^(-2i/head_dim)), multi-head or grouped-query causal
+ * attention with scale 1/sqrt(head_dim), SwiGLU feed-forward, untied LM head;
+ * one exit head (own RMSNorm gain + own [vocab x d_model] matrix) after each of
+ * layers 1..n_exit_heads (the per-layer early-exit heads of Sec. 3.1 / 4.1). */
+typedef struct sb_config {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float rms_eps, rope_base;
+    int32_t weight_dtype;  /* SB_FP32 or SB_BF16: element type of every matrix */
+    int32_t kv_dtype;      /* SB_FP32 or SB_BF16: K and V are rounded to this on cache store */
+    int32_t n_exit_heads;
+    int32_t max_seq;       /* capacity in tokens, a multiple of SB_KV_BLOCK */
+    int32_t proj_kernel;   /* SB_PROJ_*; AUTO = MFMA for bf16 weights, VALU for fp32 */
+} sb_config;
+
+/* Device pointers.  Matrices are row-major [out][in] in weight_dtype; norm gains
+ * are float32 vectors of d_model.  w_qkv stacks the q heads, then the k heads,
+ * then the v heads: [(n_heads + 2 n_kv_heads) head_dim][d_model].  w_gate_up
+ * stacks the gate rows above the up rows: [2 d_ffn][d_model].  The arrays of
+ * pointers are host arrays with n_layers (resp. n_exit_heads) entries. */
+typedef struct sb_weights {
+    const void *embed;        /* [vocab][d_model] */
+    const float *final_norm;
+    const void *lm_head;      /* [vocab][d_model] */
+    const float *const *attn_norm;
+    const void *const *w_qkv;
+    const void *const *w_o;   /* [d_model][n_heads head_dim] */
+    const float *const *ffn_norm;
+    const void *const *w_gate_up;
+    const void *const *w_down; /* [d_model][d_ffn] */
+    const float *const *exit_norm;
+    const void *const *exit_head; /* [vocab][d_model] each */
+} sb_weights;
+
+/* Speculation parameters (Sec. 3.2-3.3; evaluation values in Sec. 4.1).  All
+ * pointers are host memory, read during the call only.
+ *  d_max      depth bound, 0..min(n_exit_heads, n_layers-1).  0 disables
+ *             drafting: every round is one row through all layers, i.e. plain
+ *             greedy decoding (the library's own baseline).
+ *  w_max      width bound, 1..SB_MAX_W: number of exited drafts that ends a round.
+ *  T          T[l-1] > 0 is the temperature of layer l = 1..d_max (Eq. 1 gives
+ *             one such schedule; any array is accepted).
+ *  threshold  exit when max softmax(z/T_l) >= threshold (Eq. 2); > 1 never exits.
+ *  forced_exit / forced_draft  optional per-draft-step overrides, indexed by the
+ *             session's draft-step counter, n_forced entries each: forced_exit[k]
+ *             in 1..d_max makes step k exit exactly there, 0 makes it never exit;
+ *             forced_draft[k] >= 0 replaces the drafted token id, -1 keeps the
+ *             head's arg max.  Exit heads of all layers up to the exit layer are
+ *             still evaluated.  Steps past n_forced use the computed test. */
+typedef struct sb_params {
+    int32_t d_max, w_max;
+    const float *T;
+    float threshold;
+    int32_t eos_id; /* -1: none */
+    const int32_t *forced_exit;
+    const int32_t *forced_draft;
+    int64_t n_forced;
+} sb_params;
+
+typedef struct sb_draft_result {
+    int32_t token;      /* drafted token id, -1 if the step hit the depth bound */
+    int32_t exit_layer; /* 1..d_max, 0 if none */
+    int32_t status;     /* SB_EXITED, SB_WIDTH_BOUND or SB_DEPTH_BOUND */
+    float confidence;   /* Eq. 2 at the last evaluated layer */
+} sb_draft_result;
+
+typedef struct sb_verify_result {
+    int32_t n_rows;      /* M: rows verified */
+    int32_t n_drafts;    /* drafts checked */
+    int32_t n_matched;   /* m: leading drafts equal to the greedy tokens */
+    int32_t n_emit;      /* min(m + 1, M) tokens emitted, >= 1 */
+    int32_t align_layer; /* D: deepest layer reached while drafting */
+    int32_t tokens[SB_MAX_W]; /* greedy token after each row; the first n_emit are emitted */
+} sb_verify_result;
+
+typedef struct sb_stats {
+    int64_t rounds, draft_steps, drafts, emitted;
+    int64_t layer_sweeps; /* layer passes: one sweep over a layer's weights each */
+    int64_t row_layers;   /* sum of rows over layer passes */
+    int64_t head_evals;   /* exit-head evaluations */
+    int64_t final_head_sweeps;
+    int64_t accept_hist[SB_MAX_W + 1];
+    int64_t exit_hist[SB_MAX_EXIT_LAYERS + 1]; /* [0] = depth bound */
+    int64_t weight_bytes; /* algorithmic bytes of weights swept (layers + heads) */
+    int64_t kv_bytes;     /* algorithmic bytes of K/V read by attention */
+    double prefill_ms, decode_ms; /* wall time of the last sb_generate */
+} sb_stats;
+
+typedef struct sb_sizes { size_t kv_pool_bytes, workspace_bytes; } sb_sizes;
+
+typedef struct sb_model sb_model;
+typedef struct sb_session sb_session;
+
+const char *sb_last_error(void);
+
+/* Eq. 1: T[l-1] = 1 + alpha (1 - l / L) for l = 1..n.  Host arithmetic. */
+int32_t sb_temperature_schedule(double alpha, int32_t L, int32_t n, float *T /*host, n floats*/);
+
+/* Bytes of device memory a session of this configuration needs. */
+int32_t sb_query_sizes(const sb_config *cfg, sb_sizes *out);
+
+/* Validates cfg and weights (SB_EINVAL), builds the rotary table on the device
+ * (SB_EDEVICE / SB_ENOMEM on failure).  stream: hipStream_t or NULL. */
+int32_t sb_load_model(const sb_config *cfg, const sb_weights *w, void *stream, sb_model **out);
+void sb_free_model(sb_model *m);
+
+/* kv_pool, workspace: device memory of at least sb_query_sizes() bytes, 256-byte
+ * aligned (SB_ENOMEM if too small, SB_EINVAL if NULL / misaligned).  page_order:
+ * optional host array with a permutation of 0..max_seq/SB_KV_BLOCK-1, the
+ * physical page used for each logical KV page (NULL = identity). */
+int32_t sb_new_session(sb_model *m, void *kv_pool, size_t kv_pool_bytes, void *workspace,
+                       size_t workspace_bytes, const int32_t *page_order, sb_session **out);
+void sb_free_session(sb_session *s);
+
+/* Prefill (identical to the base model, Sec. 4.3): all n prompt tokens (host
+ * ids in [0, vocab)) through all layers; *first_token is the greedy token after
+ * the prompt.  Resets the session.  SB_ECAPACITY if n > max_seq. */
+int32_t sb_prefill(sb_session *s, const int32_t *prompt, int32_t n, int32_t *first_token);
+
+/* One draft step (Sec. 3.3): the next token (the last emitted token, or the
+ * previous draft) goes through layers 1..d_max; after each layer its exit head is
+ * evaluated (RMSNorm, full-vocabulary projection, softmax at temperature T_l, Eq. 2)
+ * and the token exits at the first layer whose confidence reaches the threshold.
+ * Earlier rows of the round whose hidden state stands one layer below are taken
+ * through the same layer in the same weight sweep (cache "Reuse").  SB_ESTATE if
+ * there is no pending token or a bound was already hit this round; SB_ECAPACITY
+ * if the KV capacity would be exceeded. */
+int32_t sb_draft_step(sb_session *s, const sb_params *p, sb_draft_result *out);
+
+/* Verification: align every cached row to the deepest layer reached, run all
+ * rows through the remaining layers in one causal pass over the paged KV cache,
+ * compare the drafts with the full model's greedy tokens, emit min(m+1, M)
+ * tokens, commit their KV entries and drop the rest.  SB_ESTATE with no open row. */
+int32_t sb_verify(sb_session *s, const sb_params *p, sb_verify_result *out);
+
+/* Prefill + rounds of draft steps and verification until max_new tokens are out
+ * (or eos_id was emitted).  out_tokens: host, out_cap >= max_new.  The first
+ * output token is the one the prefill yields.  SB_ECAPACITY if
+ * n + max_new + w_max > max_seq.  stats may be NULL. */
+int32_t sb_generate(sb_session *s, const int32_t *prompt, int32_t n, int32_t max_new,
+                    const sb_params *p, int32_t *out_tokens, int32_t out_cap, int32_t *n_out,
+                    sb_stats *stats);
+
+int32_t sb_get_stats(const sb_session *s, sb_stats *out);
+int32_t sb_committed_len(const sb_session *s);
+
+/* ---- parity taps (not for timed runs) ---------------------------------- */
+/* With debug on, head kernels also store their logits. */
+int32_t sb_debug_enable(sb_session *s, int32_t on);
+/* layer >= 1: logits of the last evaluation of that layer's exit head (row is
+ * ignored); layer == 0: final-head logits of verified row `row` (or of the
+ * prefill's last position, row 0).  out: host, cap >= vocab floats. */
+int32_t sb_debug_logits(sb_session *s, int32_t layer, int32_t row, float *out, int32_t cap);
+/* Hidden state (d_model floats, host) of open row `slot`. */
+int32_t sb_debug_hidden(sb_session *s, int32_t slot, float *out, int32_t cap);
+/* K and V (as floats, n_kv_heads*head_dim each, host) cached for (layer, pos). */
+int32_t sb_debug_kv(sb_session *s, int32_t layer, int32_t pos, float *k_out, float *v_out, int32_t cap);
+
+/* ---- single kernels, for parity tests and roofline measurement ---------- */
+/* All pointers are device memory; stream as above; calls do not synchronise.
+ * M rows, 1 <= M <= SB_MAX_W. */
+
+/* out[m][i] = x[m][i] / sqrt(mean_i x[m][i]^2 + eps) * gain[i]; x, out: [M][d] float. */
+int32_t sb_op_rmsnorm(const float *x, const float *gain, float *out, int32_t M, int32_t d, float eps,
+                      void *stream);
+/* y[m][n] = sum_k W[n][k] x[m][k]; W [N][K] in w_dtype, x [M][K], y [M][N] float.
+ * kernel: SB_PROJ_VALU or SB_PROJ_MFMA (bf16 only; K % 128 == 0, N % 16 == 0).
+ * scratch: device, sb_op_gemv_scratch_bytes(M, K) bytes (MFMA operand staging). */
+int32_t sb_op_gemv(const void *W, int32_t w_dtype, int32_t N, int32_t K, const float *x, float *y,
+                   int32_t M, int32_t kernel, void *scratch, void *stream);
+size_t sb_op_gemv_scratch_bytes(int32_t M, int32_t K);
+/* Exit-head evaluation on already normalised rows x [M][K]: z = W x (never
+ * written unless logits != NULL, [M][N] float), arg max (lowest index on ties) and
+ * confidence p = 1 / sum_j exp((z_j - z_max)/T) (Eq. 2).  argmax_out [M] int32,
+ * conf_out [M] float.  scratch: sb_op_head_scratch_bytes(M, N, K) bytes, zeroed
+ * once by the caller before first use. */
+int32_t sb_op_head(const void *W, int32_t w_dtype, int32_t N, int32_t K, const float *x, int32_t M,
+                   float T, int32_t kernel, int32_t *argmax_out, float *conf_out, float *logits,
+                   void *scratch, void *stream);
+size_t sb_op_head_scratch_bytes(int32_t M, int32_t N, int32_t K);
+
+/* Rotary table as the library builds it: cos/sin of pos * base^(-2i/head_dim),
+ * evaluated in double and rounded to float; [n_pos][head_dim/2] each, host. */
+int32_t sb_rope_table_host(int32_t head_dim, float base, int32_t n_pos, float *cos_out, float *sin_out);
+/* Rotary embedding + KV append for M new rows at positions pos0..pos0+M-1.
+ * qkv [M][(n_heads + 2 n_kv_heads) head_dim] float: q heads are rotated in place,
+ * rotated k and v are written (rounded to kv_dtype) to the paged pool
+ * [layer][2][n_pages][n_kv_heads][SB_KV_BLOCK][head_dim]; table [n_pages] maps
+ * logical to physical pages; rope_cos/sin: device tables covering pos0+M rows. */
+int32_t sb_op_rope_append(float *qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,
+                          void *pool, const int32_t *table, int32_t n_pages, int32_t layer,
+                          const float *rope_cos, const float *rope_sin, int32_t pos0, int32_t M, void *stream);
+/* Causal attention of the M rotated query rows in qkv against keys 0..pos of the
+ * paged pool (scale 1/sqrt(head_dim)); out [M][n_heads head_dim] float.  scratch:
+ * sb_op_attention_scratch_bytes() bytes, its first 4096 bytes zeroed once by the
+ * caller before first use. */
+int32_t sb_op_attention(const float *qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,
+                        const void *pool, const int32_t *table, int32_t n_pages, int32_t layer, int32_t pos0,
+                        int32_t M, float *out, void *scratch, void *stream);
+size_t sb_op_attention_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t kv_dtype, int32_t n_pages);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECBOUND_H */

@@ -1,0 +1,8 @@
+"""MI355X-native bounded self-speculative decoding (SpecBound): Python binding of
+libspecbound.so.  The HIP library is the product; this package only marshals
+arguments.  Importing it never falls back to a CPU path."""
+from .binding import (Model, Session, Params, SbError, lib, query_sizes, make_config,
+                      temperature_schedule, op_rmsnorm, op_gemv, op_head, op_rope_append,
+                      op_attention, rope_table, SYMBOLS, SB_MAX_W, SB_KV_BLOCK, FP32, BF16, EXITED,
+                      WIDTH_BOUND, DEPTH_BOUND, PROJ_AUTO, PROJ_VALU, PROJ_MFMA, OK, EINVAL, ENOMEM,
+                      ECAPACITY, ESTATE, EDEVICE)

@@ -1,0 +1,101 @@
+// Internal launch interface between the host state machine and the HIP kernels.
+// Plain pointers and sizes; every function enqueues on `stream` and returns the
+// launch status.  Operand shapes are validated by the callers (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/specbound.h"
+
+namespace sb {
+
+// ---- device-resident record of the current round (read back once per sync) ----
+struct DevRound {
+    int32_t slot_tok[SB_MAX_W + 1];  // input token of each row (row 0: pending token)
+    int32_t drafts[SB_MAX_W];        // drafted token of each row
+    int32_t exit_layer[SB_MAX_W];    // exit layer of each row, 0 = none
+    float conf[SB_MAX_W];            // confidence at the row's last evaluated head
+    int32_t head_argmax[SB_MAX_W];   // arg max at the row's last evaluated head
+    int32_t exit_flag;               // set by the head kernel when the current row exits
+    int32_t g[SB_MAX_W];             // verification: greedy token after each row
+    float gconf[SB_MAX_W];           // verification: max softmax probability (T = 1)
+    int32_t n_matched, n_emit;
+};
+
+struct RowToks { int32_t tok[SB_MAX_W]; };  // >= 0: host-known id; -1: read slot_tok on the device
+
+enum Epilogue { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
+enum HeadPost { POST_NONE = 0, POST_EXIT = 1, POST_ACCEPT = 2 };
+
+// What the last block of a head kernel does once the arg max / confidence of all
+// rows are known.
+struct HeadArgs {
+    float T;               // temperature of Eq. 2
+    float* partials;       // [M][n_blocks][4] (max, index, sum, -)
+    uint32_t* counter;     // zero before the launch; the kernel leaves it zero
+    float* logits;         // optional [M][N] store of z (parity tap), else nullptr
+    int32_t* argmax_out;   // optional [M]
+    float* conf_out;       // optional [M]
+    int32_t post;          // HeadPost
+    DevRound* round;       // for POST_EXIT / POST_ACCEPT
+    int32_t slot;          // POST_EXIT: row being drafted
+    int32_t layer;         // POST_EXIT: 1-based layer of this head
+    int32_t forced_exit;   // POST_EXIT: -1 computed, 0 never, else exit iff == layer
+    int32_t forced_draft;  // POST_EXIT: >= 0 overrides the drafted id
+    float threshold;       // POST_EXIT
+    int32_t n_drafts;      // POST_ACCEPT
+};
+
+struct GemvArgs {
+    const void* W;     // [rows][K] row-major, bf16 bits or float
+    int32_t w_dtype;   // SB_FP32 / SB_BF16
+    int32_t N;         // outputs per row of x (EPI_SWIGLU: d_ffn, W has 2N rows)
+    int32_t K;
+    const float* x;    // [M][K] float (VALU path)
+    const uint16_t* xs;  // MFMA path: split bf16 operand, [16][K]: rows 0-7 high parts, 8-15 low parts
+    float* y;          // [M][ldy]: STORE writes, RESID adds, SWIGLU writes silu(g)*u (float)
+    uint16_t* ys;      // MFMA pipeline: optional split-bf16 copy of the output [16][ldy]
+    int32_t ldy;
+    int32_t M;
+    int32_t epi;       // Epilogue
+    HeadArgs head;     // EPI_HEAD
+};
+
+int head_blocks_valu(int32_t N);
+int head_blocks_mfma(int32_t N);
+
+hipError_t launch_embed(const void* E, int32_t w_dtype, int32_t vocab, int32_t d, float* H, int32_t M,
+                        RowToks toks, const int32_t* slot_tok, int32_t* exit_flag_to_clear, hipStream_t st);
+hipError_t launch_rmsnorm(const float* x, const float* gain, float* out, uint16_t* out_split, int32_t ld_split,
+                          int32_t M, int32_t d, float eps, hipStream_t st);
+hipError_t launch_gemv_valu(const GemvArgs& a, hipStream_t st);
+hipError_t launch_gemv_mfma(const GemvArgs& a, hipStream_t st);
+hipError_t launch_split(const float* x, uint16_t* xs, int32_t M, int32_t K, hipStream_t st);
+
+struct KvLayout {
+    void* pool;            // [layer][2][n_pages][n_kv_heads][SB_KV_BLOCK][head_dim]
+    const int32_t* table;  // logical page -> physical page (device)
+    int32_t n_pages, n_kv_heads, head_dim, kv_dtype;
+};
+
+hipError_t launch_rope_append(float* qkv, int32_t qkv_rows, int32_t n_heads, const KvLayout& kv, int32_t layer,
+                              const float* rope_cos, const float* rope_sin, int32_t pos0, int32_t M,
+                              hipStream_t st);
+
+struct AttnArgs {
+    const float* q;      // [M][qkv_rows], q heads first, already rotated
+    int32_t qkv_rows, n_heads;
+    KvLayout kv;
+    int32_t layer, pos0, M;
+    float* partials;     // [M*n_heads][max_chunks][head_dim + 2]
+    int32_t max_chunks;
+    uint32_t* counters;  // [n_kv_heads * q_groups], zero before and after
+    float* out;          // [M][n_heads*head_dim]
+    uint16_t* out_split; // optional split-bf16 copy [16][n_heads*head_dim]
+};
+int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype);
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
+
+hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t st);
+
+}  // namespace sb

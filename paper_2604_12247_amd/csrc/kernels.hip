@@ -1,0 +1,813 @@
+// gfx950 kernels of the bounded self-speculative decode step.
+//
+// Every kernel here is written so that the value computed for one token row
+// depends only on that row's inputs, its absolute position and the operand
+// shapes -- never on how many other rows share the launch.  That is what makes a
+// row verified in a pass of M rows bit-identical to the same row decoded alone,
+// and hence speculative output identical to greedy decoding by the same library
+// (the exactness property of Sec. 3.3).
+#include "kernels.h"
+
+#include <math.h>
+
+namespace sb {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+#define SB_INF __builtin_inff()
+
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+// float -> bf16, round to nearest even (finite inputs)
+__device__ __forceinline__ uint16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float ldf(const float* p) { return *p; }
+__device__ __forceinline__ float ldf(const uint16_t* p) { return bf2f(*p); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// value v of row m, column i -> the two bf16 parts used by the MFMA path:
+// rows 0..7 hold the high parts, rows 8..15 the low parts (v ~= hi + lo).
+__device__ __forceinline__ void split_store(uint16_t* xs, int ld, int m, int i, float v) {
+    uint16_t hi = f2bf(v);
+    uint16_t lo = f2bf(v - bf2f(hi));
+    xs[(size_t)m * ld + i] = hi;
+    xs[(size_t)(8 + m) * ld + i] = lo;
+}
+
+// ---------------------------------------------------------------- embedding
+template <typename WT>
+__global__ void embed_kernel(const WT* __restrict__ E, int vocab, int d, float* __restrict__ H, RowToks toks,
+                             const int32_t* __restrict__ slot_tok, int32_t* clear_flag) {
+    int r = blockIdx.x;
+    int tok = toks.tok[r];
+    if (tok < 0) tok = slot_tok[r];
+    if (tok < 0 || tok >= vocab) tok = 0;  // never index outside the table
+    if (clear_flag && r == 0 && threadIdx.x == 0) *clear_flag = 0;
+    const WT* e = E + (size_t)tok * d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) H[(size_t)r * d + i] = ldf(e + i);
+}
+
+hipError_t launch_embed(const void* E, int32_t w_dtype, int32_t vocab, int32_t d, float* H, int32_t M,
+                        RowToks toks, const int32_t* slot_tok, int32_t* clear_flag, hipStream_t st) {
+    if (w_dtype == SB_BF16)
+        embed_kernel<uint16_t><<<M, 256, 0, st>>>((const uint16_t*)E, vocab, d, H, toks, slot_tok, clear_flag);
+    else
+        embed_kernel<float><<<M, 256, 0, st>>>((const float*)E, vocab, d, H, toks, slot_tok, clear_flag);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- RMSNorm
+// out = x / sqrt(mean(x^2) + eps) * gain, one block per row.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                      float* __restrict__ out, uint16_t* __restrict__ outs, int lds,
+                                                      int d, float eps) {
+    __shared__ float red[4];
+    int r = blockIdx.x, tid = threadIdx.x;
+    const float* xr = x + (size_t)r * d;
+    float ss = 0.f;
+    for (int i = tid; i < d; i += 256) {
+        float v = xr[i];
+        ss += v * v;
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    float tot = ((red[0] + red[1]) + red[2]) + red[3];
+    float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int i = tid; i < d; i += 256) {
+        float v = xr[i] * inv * gain[i];
+        if (out) out[(size_t)r * d + i] = v;
+        if (outs) split_store(outs, lds, r, i, v);
+    }
+}
+
+hipError_t launch_rmsnorm(const float* x, const float* gain, float* out, uint16_t* out_split, int32_t ld_split,
+                          int32_t M, int32_t d, float eps, hipStream_t st) {
+    rmsnorm_kernel<<<M, 256, 0, st>>>(x, gain, out, out_split, ld_split, d, eps);
+    return hipGetLastError();
+}
+
+__global__ void split_kernel(const float* __restrict__ x, uint16_t* __restrict__ xs, int K) {
+    int m = blockIdx.y;
+    int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < K) split_store(xs, K, m, i, x[(size_t)m * K + i]);
+}
+hipError_t launch_split(const float* x, uint16_t* xs, int32_t M, int32_t K, hipStream_t st) {
+    split_kernel<<<dim3((K + 255) / 256, M), 256, 0, st>>>(x, xs, K);
+    return hipGetLastError();
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    fill_u32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(p, n, v);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- head reduction
+// Called by every block of a head kernel after it has written its partial
+// (max, arg max, sum of exp((z - max)/T)) per row.  The block that arrives last
+// merges all partials in a fixed order -- so the result does not depend on block
+// scheduling -- and carries out the exit test (Eq. 2) or the acceptance rule.
+__device__ void head_finish(const HeadArgs& h, int M, int nb) {
+    __shared__ int s_last;
+    __shared__ float r_max[4], r_sum[4];
+    __shared__ int r_idx[4];
+    __shared__ float s_gmax;
+    __shared__ int s_gidx;
+    __shared__ int s_am[SB_MAX_W];
+    __shared__ float s_cf[SB_MAX_W];
+    int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        unsigned prev = atomicAdd(h.counter, 1u);
+        s_last = (prev == (unsigned)(nb - 1));
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    for (int m = 0; m < M; ++m) {
+        const volatile float* p = h.partials + (size_t)m * nb * 4;
+        float mx = -SB_INF;
+        int idx = 0x7fffffff;
+        for (int b = tid; b < nb; b += 256) {
+            float v = p[b * 4];
+            int i = __float_as_int(p[b * 4 + 1]);
+            if (v > mx || (v == mx && i < idx)) { mx = v; idx = i; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            float ov = __shfl_xor(mx, o, 64);
+            int oi = __shfl_xor(idx, o, 64);
+            if (ov > mx || (ov == mx && oi < idx)) { mx = ov; idx = oi; }
+        }
+        if (lane == 0) { r_max[wave] = mx; r_idx[wave] = idx; }
+        __syncthreads();
+        if (tid == 0) {
+            float gm = r_max[0];
+            int gi = r_idx[0];
+            for (int w = 1; w < 4; ++w)
+                if (r_max[w] > gm || (r_max[w] == gm && r_idx[w] < gi)) { gm = r_max[w]; gi = r_idx[w]; }
+            s_gmax = gm;
+            s_gidx = gi == 0x7fffffff ? 0 : gi;
+        }
+        __syncthreads();
+        float gmax = s_gmax;
+        float s = 0.f;
+        for (int b = tid; b < nb; b += 256) s += p[b * 4 + 2] * expf((p[b * 4] - gmax) / h.T);
+        s = wave_sum(s);
+        if (lane == 0) r_sum[wave] = s;
+        __syncthreads();
+        if (tid == 0) {
+            float S = ((r_sum[0] + r_sum[1]) + r_sum[2]) + r_sum[3];
+            s_am[m] = s_gidx;
+            s_cf[m] = 1.0f / S;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        for (int m = 0; m < M; ++m) {
+            if (h.argmax_out) h.argmax_out[m] = s_am[m];
+            if (h.conf_out) h.conf_out[m] = s_cf[m];
+        }
+        if (h.post == POST_EXIT) {
+            // Early exit at the first layer whose confidence reaches the threshold
+            // (Sec. 3.2), or exactly at the forced layer.
+            DevRound* R = h.round;
+            int s = h.slot;
+            float cf = s_cf[0];
+            int am = s_am[0];
+            R->conf[s] = cf;
+            R->head_argmax[s] = am;
+            bool ex = h.forced_exit >= 0 ? (h.layer == h.forced_exit) : (cf >= h.threshold);
+            if (ex) {
+                int tok = h.forced_draft >= 0 ? h.forced_draft : am;
+                R->drafts[s] = tok;
+                R->slot_tok[s + 1] = tok;
+                R->exit_layer[s] = h.layer;
+                R->exit_flag = 1;
+            }
+        } else if (h.post == POST_ACCEPT) {
+            // Keep the longest prefix of drafts equal to the greedy tokens; the row
+            // after it yields one more token: min(m + 1, M) >= 1 are emitted.
+            DevRound* R = h.round;
+            int mt = 0;
+            for (int m = 0; m < M; ++m) { R->g[m] = s_am[m]; R->gconf[m] = s_cf[m]; }
+            while (mt < h.n_drafts && mt < M && R->drafts[mt] == s_am[mt]) ++mt;
+            R->n_matched = mt;
+            R->n_emit = mt + 1 < M ? mt + 1 : M;
+        }
+        *h.counter = 0;
+        __threadfence();
+    }
+}
+
+// Partial (max, arg max, sum exp) of the block's logits zs[i][m], i < rows.
+template <int ROWS>
+__device__ __forceinline__ void head_partial(const HeadArgs& h, float (*zs)[SB_MAX_W], int M, int n0, int N, int nb) {
+    int tid = threadIdx.x;
+    if (tid < M) {
+        int m = tid;
+        float mx = -SB_INF;
+        int idx = 0x7fffffff;
+        for (int i = 0; i < ROWS; ++i) {
+            int n = n0 + i;
+            if (n < N) {
+                float z = zs[i][m];
+                if (z > mx) { mx = z; idx = n; }
+                if (h.logits) h.logits[(size_t)m * N + n] = z;
+            }
+        }
+        float s = 0.f;
+        for (int i = 0; i < ROWS; ++i)
+            if (n0 + i < N) s += expf((zs[i][m] - mx) / h.T);
+        float* p = h.partials + ((size_t)m * nb + blockIdx.x) * 4;
+        p[0] = mx;
+        p[1] = __int_as_float(idx);
+        p[2] = s;
+    }
+}
+
+// ---------------------------------------------------------------- GEMV, vector ALU
+// y[m][n] = sum_k W[n][k] x[m][k] for M rows sharing one sweep over W.  One wave
+// owns 4 weight rows; lanes stride the K dimension in 16-byte pieces (128-bit
+// loads), partial sums are combined with a fixed shuffle tree.  x is staged in
+// LDS in chunks.  The order in which a row's products are added is a function of
+// K alone.
+__device__ __forceinline__ void load8(const uint16_t* p, float (&w)[8]) {
+    uint4 v = *reinterpret_cast<const uint4*>(p);
+    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
+    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
+    w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
+    w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+__device__ __forceinline__ void load8(const float* p, float (&w)[8]) {
+    float4 a = *reinterpret_cast<const float4*>(p);
+    float4 b = *reinterpret_cast<const float4*>(p + 4);
+    w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+    w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + expf(-g)) * u; }
+
+template <typename WT, int M, int EPI>
+__global__ __launch_bounds__(256) void gemv_valu_kernel(GemvArgs a) {
+    constexpr int R = 4;
+    constexpr int KC = (M <= 4) ? 2048 : 1024;
+    constexpr int OUT_PER_BLOCK = (EPI == EPI_SWIGLU) ? 8 : 16;
+    __shared__ __attribute__((aligned(16))) float xs[M][KC];
+    __shared__ float zs[16][SB_MAX_W];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const WT* __restrict__ W = reinterpret_cast<const WT*>(a.W);
+    const int N = a.N, K = a.K;
+    const int n0 = blockIdx.x * OUT_PER_BLOCK;
+    const int total_rows = (EPI == EPI_SWIGLU) ? 2 * N : N;
+
+    int outn[R];
+    const WT* wrow[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int n, row;
+        if (EPI == EPI_SWIGLU) {
+            n = n0 + wave * 2 + (r & 1);
+            row = (r < 2) ? n : N + n;
+        } else {
+            n = n0 + wave * 4 + r;
+            row = n;
+        }
+        outn[r] = n;
+        if (row > total_rows - 1) row = total_rows - 1;  // loads stay inside W; the result is dropped
+        wrow[r] = W + (size_t)row * K;
+    }
+
+    float acc[R][M];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int m = 0; m < M; ++m) acc[r][m] = 0.f;
+
+    for (int k0 = 0; k0 < K; k0 += KC) {
+        const int kc = (K - k0 < KC) ? (K - k0) : KC;
+        __syncthreads();
+        for (int i = tid * 4; i < M * KC; i += 1024) {
+            int m = i / KC, kk = i - m * KC;
+            if (kk < kc)
+                *reinterpret_cast<float4*>(&xs[m][kk]) =
+                    *reinterpret_cast<const float4*>(a.x + (size_t)m * K + k0 + kk);
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int kk = lane * 8; kk < kc; kk += 512) {
+            float w[R][8];
+#pragma unroll
+            for (int r = 0; r < R; ++r) load8(wrow[r] + k0 + kk, w[r]);
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                float4 xa = *reinterpret_cast<const float4*>(&xs[m][kk]);
+                float4 xb = *reinterpret_cast<const float4*>(&xs[m][kk + 4]);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float s = acc[r][m];
+                    s = fmaf(w[r][0], xa.x, s); s = fmaf(w[r][1], xa.y, s);
+                    s = fmaf(w[r][2], xa.z, s); s = fmaf(w[r][3], xa.w, s);
+                    s = fmaf(w[r][4], xb.x, s); s = fmaf(w[r][5], xb.y, s);
+                    s = fmaf(w[r][6], xb.z, s); s = fmaf(w[r][7], xb.w, s);
+                    acc[r][m] = s;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int m = 0; m < M; ++m) acc[r][m] = wave_sum(acc[r][m]);
+
+    if (EPI == EPI_STORE || EPI == EPI_RESID) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+                if (lane == r * M + m && outn[r] < N) {
+                    float* yp = a.y + (size_t)m * a.ldy + outn[r];
+                    *yp = (EPI == EPI_RESID) ? (*yp + acc[r][m]) : acc[r][m];
+                }
+    } else if (EPI == EPI_SWIGLU) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+                if (lane == j * M + m && outn[j] < N)
+                    a.y[(size_t)m * a.ldy + outn[j]] = silu_mul(acc[j][m], acc[2 + j][m]);
+    } else {  // EPI_HEAD
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+                if (lane == r * M + m) zs[wave * 4 + r][m] = acc[r][m];
+        __syncthreads();
+        head_partial<16>(a.head, zs, M, n0, N, gridDim.x);
+        head_finish(a.head, M, gridDim.x);
+    }
+}
+
+int head_blocks_valu(int32_t N) { return (N + 15) / 16; }
+
+template <typename WT, int M>
+static hipError_t launch_gemv_valu_m(const GemvArgs& a, hipStream_t st) {
+    switch (a.epi) {
+        case EPI_STORE: gemv_valu_kernel<WT, M, EPI_STORE><<<(a.N + 15) / 16, 256, 0, st>>>(a); break;
+        case EPI_RESID: gemv_valu_kernel<WT, M, EPI_RESID><<<(a.N + 15) / 16, 256, 0, st>>>(a); break;
+        case EPI_SWIGLU: gemv_valu_kernel<WT, M, EPI_SWIGLU><<<(a.N + 7) / 8, 256, 0, st>>>(a); break;
+        case EPI_HEAD: gemv_valu_kernel<WT, M, EPI_HEAD><<<(a.N + 15) / 16, 256, 0, st>>>(a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+template <typename WT>
+static hipError_t launch_gemv_valu_t(const GemvArgs& a, hipStream_t st) {
+    switch (a.M) {
+        case 1: return launch_gemv_valu_m<WT, 1>(a, st);
+        case 2: return launch_gemv_valu_m<WT, 2>(a, st);
+        case 3: return launch_gemv_valu_m<WT, 3>(a, st);
+        case 4: return launch_gemv_valu_m<WT, 4>(a, st);
+        case 5: return launch_gemv_valu_m<WT, 5>(a, st);
+        case 6: return launch_gemv_valu_m<WT, 6>(a, st);
+        case 7: return launch_gemv_valu_m<WT, 7>(a, st);
+        case 8: return launch_gemv_valu_m<WT, 8>(a, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+hipError_t launch_gemv_valu(const GemvArgs& a, hipStream_t st) {
+    if (a.K % 8 != 0 || a.N < 1) return hipErrorInvalidValue;
+    return a.w_dtype == SB_BF16 ? launch_gemv_valu_t<uint16_t>(a, st) : launch_gemv_valu_t<float>(a, st);
+}
+
+// ---------------------------------------------------------------- GEMV, MFMA tiles
+// bf16 weights only.  The M <= 8 activation rows are given as two bf16 parts each
+// (x ~= hi + lo, 16 bits of mantissa), laid out as the 16 columns of one
+// 16x16x32 MFMA B operand: columns 0-7 high parts, 8-15 low parts.  A 16-row
+// tile of W is the A operand, read straight from HBM with 128-bit loads: lane
+// (i = l%16, q = l/16) reads 64 contiguous bytes of row i per 128-wide k block.
+// The four waves of a block take k blocks round-robin and are summed through LDS
+// in wave order.  Products of bf16 values are exact in fp32, so the only rounding
+// is fp32 accumulation.  Columns never mix, hence row results do not depend on M.
+template <int RT, int EPI>
+__global__ __launch_bounds__(256) void gemv_mfma_kernel(GemvArgs a) {
+    __shared__ __attribute__((aligned(16))) float red[4][RT][64][4];
+    __shared__ float cs[RT][16][17];
+    __shared__ float zs[16 * RT][SB_MAX_W];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15, lq = lane >> 4;
+    const uint16_t* __restrict__ W = reinterpret_cast<const uint16_t*>(a.W);
+    const int N = a.N, K = a.K, M = a.M;
+    const int KB = K >> 7;  // k blocks of 128
+    const int n0 = blockIdx.x * ((EPI == EPI_SWIGLU) ? 16 : 16 * RT);
+
+    const uint16_t* wp[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        int row = (EPI == EPI_SWIGLU) ? (t == 0 ? n0 + li : N + n0 + li) : (n0 + t * 16 + li);
+        int total = (EPI == EPI_SWIGLU) ? 2 * N : N;
+        if (row > total - 1) row = total - 1;
+        wp[t] = W + (size_t)row * K + lq * 32;
+    }
+    const bool bact = (li & 7) < M;
+    const uint16_t* bp = a.xs + (size_t)li * K + lq * 32;
+
+    f32x4 acc[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // two register buffers, named apart so that neither is indexed dynamically
+    uint4 wA[RT][4], bA[4], wB[RT][4], bB[4];
+    auto load_block = [&](uint4 (&wr)[RT][4], uint4 (&br)[4], int kb) {
+        const size_t off = (size_t)kb * 128;
+#pragma unroll
+        for (int t = 0; t < RT; ++t)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) wr[t][u] = *reinterpret_cast<const uint4*>(wp[t] + off + u * 8);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            br[u] = bact ? *reinterpret_cast<const uint4*>(bp + off + u * 8) : make_uint4(0, 0, 0, 0);
+    };
+    auto mma_block = [&](const uint4 (&wr)[RT][4], const uint4 (&br)[4]) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            bf16x8 bv = __builtin_bit_cast(bf16x8, br[u]);
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wr[t][u]), bv, acc[t],
+                                                                 0, 0, 0);
+        }
+    };
+    int kb = wave;
+    if (kb < KB) {
+        load_block(wA, bA, kb);
+        while (true) {
+            if (kb + 4 < KB) load_block(wB, bB, kb + 4);
+            mma_block(wA, bA);
+            kb += 4;
+            if (kb >= KB) break;
+            if (kb + 4 < KB) load_block(wA, bA, kb + 4);
+            mma_block(wB, bB);
+            kb += 4;
+            if (kb >= KB) break;
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < RT; ++t) *reinterpret_cast<f32x4*>(&red[wave][t][lane][0]) = acc[t];
+    __syncthreads();
+    // C layout of the 16x16 tile: lane (j = l%16, g = l/16), register r -> row 4g + r, column j.
+    for (int e = tid; e < RT * 256; e += 256) {
+        int t = e >> 8, l = (e >> 2) & 63, r = e & 3;
+        float v = ((red[0][t][l][r] + red[1][t][l][r]) + red[2][t][l][r]) + red[3][t][l][r];
+        cs[t][4 * (l >> 4) + r][l & 15] = v;
+    }
+    __syncthreads();
+
+    if (EPI == EPI_STORE || EPI == EPI_RESID) {
+        for (int e = tid; e < RT * 16 * 8; e += 256) {
+            int t = e >> 7, m = (e >> 4) & 7, i = e & 15;
+            int n = n0 + t * 16 + i;
+            if (m < M && n < N) {
+                float v = cs[t][i][m] + cs[t][i][m + 8];
+                float* yp = a.y + (size_t)m * a.ldy + n;
+                if (EPI == EPI_RESID) v += *yp;
+                *yp = v;
+            }
+        }
+    } else if (EPI == EPI_SWIGLU) {
+        if (tid < 128) {
+            int m = tid >> 4, i = tid & 15;
+            int n = n0 + i;
+            if (m < M && n < N) {
+                float g = cs[0][i][m] + cs[0][i][m + 8];
+                float u = cs[1][i][m] + cs[1][i][m + 8];
+                float v = silu_mul(g, u);
+                if (a.y) a.y[(size_t)m * a.ldy + n] = v;
+                if (a.ys) split_store(a.ys, a.ldy, m, n, v);
+            }
+        }
+    } else {  // EPI_HEAD
+        for (int e = tid; e < RT * 16 * 8; e += 256) {
+            int t = e >> 7, m = (e >> 4) & 7, i = e & 15;
+            zs[t * 16 + i][m] = cs[t][i][m] + cs[t][i][m + 8];
+        }
+        __syncthreads();
+        head_partial<16 * RT>(a.head, zs, M, n0, N, gridDim.x);
+        head_finish(a.head, M, gridDim.x);
+    }
+}
+
+// Row tiles per block: fixed by the operand shape alone (never by M).
+static int mfma_row_tiles(int32_t N) { return N >= 16384 ? 2 : 1; }
+int head_blocks_mfma(int32_t N) { return (N + 16 * mfma_row_tiles(N) - 1) / (16 * mfma_row_tiles(N)); }
+
+hipError_t launch_gemv_mfma(const GemvArgs& a, hipStream_t st) {
+    if (a.w_dtype != SB_BF16 || a.K % 128 != 0 || a.N % 16 != 0 || a.M < 1 || a.M > 8 || !a.xs)
+        return hipErrorInvalidValue;
+    const int rt = mfma_row_tiles(a.N);
+    switch (a.epi) {
+        case EPI_STORE:
+            if (rt == 2) gemv_mfma_kernel<2, EPI_STORE><<<(a.N + 31) / 32, 256, 0, st>>>(a);
+            else gemv_mfma_kernel<1, EPI_STORE><<<a.N / 16, 256, 0, st>>>(a);
+            break;
+        case EPI_RESID:
+            if (rt == 2) gemv_mfma_kernel<2, EPI_RESID><<<(a.N + 31) / 32, 256, 0, st>>>(a);
+            else gemv_mfma_kernel<1, EPI_RESID><<<a.N / 16, 256, 0, st>>>(a);
+            break;
+        case EPI_SWIGLU: gemv_mfma_kernel<2, EPI_SWIGLU><<<a.N / 16, 256, 0, st>>>(a); break;
+        case EPI_HEAD:
+            if (rt == 2) gemv_mfma_kernel<2, EPI_HEAD><<<(a.N + 31) / 32, 256, 0, st>>>(a);
+            else gemv_mfma_kernel<1, EPI_HEAD><<<a.N / 16, 256, 0, st>>>(a);
+            break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- RoPE + KV append
+// Rotates q in place and writes rotated k and v of M new rows into the paged
+// cache (rounded to the cache type).  Half-split pairing (i, i + hd/2); the
+// cos/sin table is built on the host in double and held in float.
+template <typename KVT>
+__device__ __forceinline__ void kv_store(KVT* p, float v);
+template <> __device__ __forceinline__ void kv_store<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void kv_store<uint16_t>(uint16_t* p, float v) { *p = f2bf(v); }
+
+template <typename KVT>
+__global__ void rope_append_kernel(float* __restrict__ qkv, int qkv_rows, int Hq, KvLayout kv, int layer,
+                                   const float* __restrict__ rc, const float* __restrict__ rs, int pos0) {
+    const int head = blockIdx.x, r = blockIdx.y;
+    const int hd = kv.head_dim, half = hd >> 1, Hkv = kv.n_kv_heads;
+    const int pos = pos0 + r;
+    float* src = qkv + (size_t)r * qkv_rows + (size_t)head * hd;
+    const float* c = rc + (size_t)pos * half;
+    const float* s = rs + (size_t)pos * half;
+    if (head < Hq) {
+        for (int i = threadIdx.x; i < half; i += blockDim.x) {
+            float x = src[i], y = src[i + half];
+            src[i] = x * c[i] - y * s[i];
+            src[i + half] = y * c[i] + x * s[i];
+        }
+        return;
+    }
+    const bool is_k = head < Hq + Hkv;
+    const int kh = is_k ? head - Hq : head - Hq - Hkv;
+    const int page = kv.table[pos / SB_KV_BLOCK], t = pos % SB_KV_BLOCK;
+    KVT* dst = reinterpret_cast<KVT*>(kv.pool) +
+               ((((size_t)(layer * 2 + (is_k ? 0 : 1)) * kv.n_pages + page) * Hkv + kh) * SB_KV_BLOCK + t) * hd;
+    if (is_k) {
+        for (int i = threadIdx.x; i < half; i += blockDim.x) {
+            float x = src[i], y = src[i + half];
+            kv_store<KVT>(dst + i, x * c[i] - y * s[i]);
+            kv_store<KVT>(dst + i + half, y * c[i] + x * s[i]);
+        }
+    } else {
+        for (int i = threadIdx.x; i < hd; i += blockDim.x) kv_store<KVT>(dst + i, src[i]);
+    }
+}
+
+hipError_t launch_rope_append(float* qkv, int32_t qkv_rows, int32_t n_heads, const KvLayout& kv, int32_t layer,
+                              const float* rope_cos, const float* rope_sin, int32_t pos0, int32_t M,
+                              hipStream_t st) {
+    dim3 grid(n_heads + 2 * kv.n_kv_heads, M);
+    if (kv.kv_dtype == SB_BF16)
+        rope_append_kernel<uint16_t><<<grid, 64, 0, st>>>(qkv, qkv_rows, n_heads, kv, layer, rope_cos, rope_sin, pos0);
+    else
+        rope_append_kernel<float><<<grid, 64, 0, st>>>(qkv, qkv_rows, n_heads, kv, layer, rope_cos, rope_sin, pos0);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- attention over the paged KV cache
+// M causal query rows at positions pos0..pos0+M-1 against keys 0..pos.  The key
+// range is cut into fixed chunks of absolute positions; one block handles one
+// (kv head, chunk, group of <= 16 queries), stages the chunk's K then V pages in
+// LDS (each page read once for all rows and all query heads of the group) and
+// writes a partial (max, sum, weighted V) per query.  The block that finishes
+// last for a kv head merges the chunks in ascending order.  A row's result
+// depends on its own position and keys only.
+template <typename KVT> struct KvVec;
+template <> struct KvVec<uint16_t> {
+    static constexpr int EPV = 8;
+    static __device__ __forceinline__ void load8(const uint16_t* p, float (&f)[8]) { sb::load8(p, f); }
+};
+template <> struct KvVec<float> {
+    static constexpr int EPV = 4;
+    static __device__ __forceinline__ void load8(const float* p, float (&f)[8]) { sb::load8(p, f); }
+};
+
+template <typename KVT, int HD>
+__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
+    constexpr int CH = (HD * sizeof(KVT) <= 256) ? 128 : 64;  // keys per chunk
+    constexpr int EPV = KvVec<KVT>::EPV;                      // elements per 16 bytes
+    constexpr int LDT = HD + EPV;                             // padded tile row
+    constexpr int QG = 16;                                    // queries per block
+    constexpr int QSPLIT = 256 / CH, QPT = QG / QSPLIT;
+    constexpr int NS = 256 / HD, KPS = CH / NS;
+    static_assert(CH * LDT * sizeof(KVT) >= NS * QG * HD * sizeof(float), "tile reused for the split combine");
+    __shared__ __attribute__((aligned(16))) KVT tile[CH * LDT];
+    __shared__ __attribute__((aligned(16))) float qs[QG * HD];
+    __shared__ __attribute__((aligned(16))) float sp[QG * CH];
+    __shared__ float s_m[QG], s_l[QG];
+    __shared__ int s_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x, chunk = blockIdx.y, qg = blockIdx.z;
+    const int Hq = a.n_heads, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
+    const int nq_total = a.M * G, q0 = qg * QG;
+    const int nq = (nq_total - q0 < QG) ? (nq_total - q0) : QG;
+    const int key0 = chunk * CH, n_total = a.pos0 + a.M;
+    const float scale = 1.0f / sqrtf((float)HD);
+
+    for (int i = tid; i < QG * HD; i += 256) {
+        int qi = i / HD, d = i - qi * HD;
+        float v = 0.f;
+        if (qi < nq) {
+            int qq = q0 + qi, r = qq / G, gi = qq - r * G;
+            v = a.q[(size_t)r * a.qkv_rows + (size_t)(g * G + gi) * HD + d];
+        }
+        qs[i] = v;
+    }
+
+    const size_t page_elems = (size_t)Hkv * SB_KV_BLOCK * HD;
+    auto load_tile = [&](int which) {
+        const KVT* base = reinterpret_cast<const KVT*>(a.kv.pool) +
+                          (size_t)(a.layer * 2 + which) * a.kv.n_pages * page_elems;
+        constexpr int UNITS = SB_KV_BLOCK * HD / EPV;
+        for (int pg = 0; pg < CH / SB_KV_BLOCK; ++pg) {
+            const int kbase = key0 + pg * SB_KV_BLOCK;
+            const bool page_ok = kbase < n_total;
+            const KVT* src = base;
+            if (page_ok) src = base + (size_t)a.kv.table[kbase / SB_KV_BLOCK] * page_elems + (size_t)g * SB_KV_BLOCK * HD;
+            for (int u = tid; u < UNITS; u += 256) {
+                int e = u * EPV, t = e / HD, d = e - t * HD;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (page_ok && kbase + t < n_total) v = *reinterpret_cast<const uint4*>(src + e);
+                *reinterpret_cast<uint4*>(&tile[(pg * SB_KV_BLOCK + t) * LDT + d]) = v;
+            }
+        }
+    };
+    load_tile(0);
+    __syncthreads();
+
+    {   // scores: thread = (key t, query subset qh)
+        const int t = tid % CH, qh = tid / CH;
+        float acc[QPT];
+#pragma unroll
+        for (int j = 0; j < QPT; ++j) acc[j] = 0.f;
+#pragma unroll 2
+        for (int d = 0; d < HD; d += 8) {
+            float kf[8];
+            KvVec<KVT>::load8(&tile[t * LDT + d], kf);
+#pragma unroll
+            for (int j = 0; j < QPT; ++j) {
+                const float* qp = &qs[(qh + j * QSPLIT) * HD + d];
+                float4 qa = *reinterpret_cast<const float4*>(qp);
+                float4 qb = *reinterpret_cast<const float4*>(qp + 4);
+                float s = acc[j];
+                s = fmaf(qa.x, kf[0], s); s = fmaf(qa.y, kf[1], s); s = fmaf(qa.z, kf[2], s); s = fmaf(qa.w, kf[3], s);
+                s = fmaf(qb.x, kf[4], s); s = fmaf(qb.y, kf[5], s); s = fmaf(qb.z, kf[6], s); s = fmaf(qb.w, kf[7], s);
+                acc[j] = s;
+            }
+        }
+        const int key = key0 + t;
+#pragma unroll
+        for (int j = 0; j < QPT; ++j) {
+            int qi = qh + j * QSPLIT;
+            int r = (q0 + qi) / G;
+            bool valid = qi < nq && key <= a.pos0 + r;
+            sp[qi * CH + t] = valid ? acc[j] * scale : -SB_INF;
+        }
+    }
+    __syncthreads();
+    for (int qi = wave; qi < QG; qi += 4) {
+        float s0 = sp[qi * CH + lane];
+        float s1 = (CH == 128) ? sp[qi * CH + 64 + lane] : -SB_INF;
+        float mx = wave_max(fmaxf(s0, s1));
+        float p0 = (mx == -SB_INF) ? 0.f : expf(s0 - mx);
+        float p1 = (mx == -SB_INF) ? 0.f : expf(s1 - mx);
+        float l = wave_sum(p0 + p1);
+        sp[qi * CH + lane] = p0;
+        if (CH == 128) sp[qi * CH + 64 + lane] = p1;
+        if (lane == 0) { s_m[qi] = mx; s_l[qi] = l; }
+    }
+    __syncthreads();
+    load_tile(1);
+    __syncthreads();
+
+    float o[QG];
+    {   // weighted values: thread = (dim d, key split ks)
+        const int d = tid % HD, ks = tid / HD;
+#pragma unroll
+        for (int qi = 0; qi < QG; ++qi) o[qi] = 0.f;
+#pragma unroll 2
+        for (int tt = 0; tt < KPS; tt += 4) {
+            const int t = ks * KPS + tt;
+            float v0 = ldf(&tile[(t + 0) * LDT + d]), v1 = ldf(&tile[(t + 1) * LDT + d]);
+            float v2 = ldf(&tile[(t + 2) * LDT + d]), v3 = ldf(&tile[(t + 3) * LDT + d]);
+#pragma unroll
+            for (int qi = 0; qi < QG; ++qi) {
+                float4 p = *reinterpret_cast<const float4*>(&sp[qi * CH + t]);
+                float s = o[qi];
+                s = fmaf(p.x, v0, s); s = fmaf(p.y, v1, s); s = fmaf(p.z, v2, s); s = fmaf(p.w, v3, s);
+                o[qi] = s;
+            }
+        }
+        __syncthreads();
+        float* comb = reinterpret_cast<float*>(tile);
+#pragma unroll
+        for (int qi = 0; qi < QG; ++qi) comb[(ks * QG + qi) * HD + d] = o[qi];
+    }
+    __syncthreads();
+    {
+        const float* comb = reinterpret_cast<const float*>(tile);
+        const int stride = HD + 2;
+        for (int i = tid; i < QG * HD; i += 256) {
+            int qi = i / HD, d = i - qi * HD;
+            if (qi >= nq) continue;
+            int qq = q0 + qi, r = qq / G, gi = qq - r * G;
+            if (key0 > a.pos0 + r) continue;  // no key of this chunk is visible to the row
+            float v = comb[qi * HD + d];
+#pragma unroll
+            for (int s = 1; s < NS; ++s) v += comb[(s * QG + qi) * HD + d];
+            float* p = a.partials + ((size_t)(r * Hq + g * G + gi) * a.max_chunks + chunk) * stride;
+            p[2 + d] = v;
+            if (d == 0) { p[0] = s_m[qi]; p[1] = s_l[qi]; }
+        }
+    }
+    // last block of this (kv head, query group) merges the chunks
+    __threadfence();
+    __syncthreads();
+    uint32_t* ctr = a.counters + g * gridDim.z + qg;
+    if (tid == 0) {
+        unsigned prev = atomicAdd(ctr, 1u);
+        s_last = (prev == gridDim.y - 1);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    {
+        const int stride = HD + 2;
+        for (int i = tid; i < nq * HD; i += 256) {
+            int qi = i / HD, d = i - qi * HD;
+            int qq = q0 + qi, r = qq / G, gi = qq - r * G, hq = g * G + gi;
+            int nc = (a.pos0 + r) / CH + 1;
+            const volatile float* p = a.partials + (size_t)(r * Hq + hq) * a.max_chunks * stride;
+            float mx = -SB_INF;
+            for (int c = 0; c < nc; ++c) mx = fmaxf(mx, p[c * stride]);
+            float L = 0.f, O = 0.f;
+            for (int c = 0; c < nc; ++c) {
+                float w = expf(p[c * stride] - mx);
+                L += p[c * stride + 1] * w;
+                O += p[c * stride + 2 + d] * w;
+            }
+            float v = O / L;
+            size_t col = (size_t)hq * HD + d;
+            if (a.out) a.out[(size_t)r * Hq * HD + col] = v;
+            if (a.out_split) split_store(a.out_split, Hq * HD, r, (int)col, v);
+        }
+        if (tid == 0) { *ctr = 0; __threadfence(); }
+    }
+}
+
+int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype) {
+    return (head_dim * (kv_dtype == SB_BF16 ? 2 : 4) <= 256) ? 128 : 64;
+}
+
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
+    const int hd = a.kv.head_dim;
+    if ((hd != 64 && hd != 128) || a.M < 1 || a.M > SB_MAX_W || a.n_heads % a.kv.n_kv_heads) return hipErrorInvalidValue;
+    const int ch = attn_chunk_keys(hd, a.kv.kv_dtype);
+    const int n_chunks = (a.pos0 + a.M + ch - 1) / ch;
+    if (n_chunks > a.max_chunks) return hipErrorInvalidValue;
+    const int G = a.n_heads / a.kv.n_kv_heads;
+    dim3 grid(a.kv.n_kv_heads, n_chunks, (a.M * G + 15) / 16);
+    if (a.kv.kv_dtype == SB_BF16) {
+        if (hd == 128) attn_kernel<uint16_t, 128><<<grid, 256, 0, st>>>(a);
+        else attn_kernel<uint16_t, 64><<<grid, 256, 0, st>>>(a);
+    } else {
+        if (hd == 128) attn_kernel<float, 128><<<grid, 256, 0, st>>>(a);
+        else attn_kernel<float, 64><<<grid, 256, 0, st>>>(a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace sb

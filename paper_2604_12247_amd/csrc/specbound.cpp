@@ -1,0 +1,812 @@
+// Host side of libspecbound: the C ABI, argument validation, and the state
+// machine of Bounded Speculation with Cached States (Sec. 3.3, Appendix A) that
+// decides which rows go through which layer and enqueues the kernels.  All
+// arithmetic of the method runs in the kernels; the host only keeps integers
+// (positions, reached layers, counters).
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace sb;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) return fail(SB_EDEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+size_t esize(int dtype) { return dtype == SB_BF16 ? 2 : 4; }
+
+int check_config(const sb_config* c) {
+    if (!c) return fail(SB_EINVAL, "config is NULL");
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 1 || c->vocab < 1)
+        return fail(SB_EINVAL, "config: non-positive dimension");
+    if (c->n_heads % c->n_kv_heads) return fail(SB_EINVAL, "config: n_heads must be a multiple of n_kv_heads");
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(SB_EINVAL, "config: head_dim must be 64 or 128");
+    if (c->weight_dtype != SB_FP32 && c->weight_dtype != SB_BF16) return fail(SB_EINVAL, "config: weight_dtype");
+    if (c->kv_dtype != SB_FP32 && c->kv_dtype != SB_BF16) return fail(SB_EINVAL, "config: kv_dtype");
+    if (c->n_exit_heads < 0 || c->n_exit_heads > c->n_layers || c->n_exit_heads > SB_MAX_EXIT_LAYERS)
+        return fail(SB_EINVAL, "config: n_exit_heads out of range");
+    if (c->max_seq < SB_KV_BLOCK || c->max_seq % SB_KV_BLOCK)
+        return fail(SB_EINVAL, "config: max_seq must be a positive multiple of %d", SB_KV_BLOCK);
+    if (c->d_model % 8 || c->d_ffn % 8 || (c->n_heads * c->head_dim) % 8)
+        return fail(SB_EINVAL, "config: d_model, d_ffn and n_heads*head_dim must be multiples of 8");
+    if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return fail(SB_EINVAL, "config: rms_eps / rope_base");
+    if (c->proj_kernel < SB_PROJ_AUTO || c->proj_kernel > SB_PROJ_MFMA) return fail(SB_EINVAL, "config: proj_kernel");
+    if (c->proj_kernel == SB_PROJ_MFMA) {
+        if (c->weight_dtype != SB_BF16) return fail(SB_EINVAL, "config: the MFMA projection path needs bf16 weights");
+        if (c->d_model % 128 || c->d_ffn % 128 || (c->n_heads * c->head_dim) % 128 || c->vocab % 16)
+            return fail(SB_EINVAL, "config: the MFMA path needs K %% 128 == 0 and N %% 16 == 0");
+    }
+    return SB_OK;
+}
+
+int resolve_proj(const sb_config* c) {
+    if (c->proj_kernel != SB_PROJ_AUTO) return c->proj_kernel;
+    bool ok = c->weight_dtype == SB_BF16 && c->d_model % 128 == 0 && c->d_ffn % 128 == 0 &&
+              (c->n_heads * c->head_dim) % 128 == 0 && c->vocab % 16 == 0;
+    return ok ? SB_PROJ_MFMA : SB_PROJ_VALU;
+}
+
+struct WsLayout {
+    size_t H, xn, xs, qkv, att, atts, u, us, attn_part, head_part, logits_exit, logits_final, counters, round,
+        table, total;
+    int max_chunks, head_blocks, n_pages;
+};
+
+WsLayout ws_layout(const sb_config* c) {
+    WsLayout L{};
+    const size_t d = c->d_model, f = c->d_ffn, V = c->vocab, hq = (size_t)c->n_heads * c->head_dim;
+    const size_t qkv_rows = (size_t)(c->n_heads + 2 * c->n_kv_heads) * c->head_dim;
+    L.n_pages = c->max_seq / SB_KV_BLOCK;
+    const int ch = attn_chunk_keys(c->head_dim, c->kv_dtype);
+    L.max_chunks = (c->max_seq + ch - 1) / ch;
+    const int hb_v = head_blocks_valu(c->vocab), hb_m = head_blocks_mfma(c->vocab);
+    L.head_blocks = hb_v > hb_m ? hb_v : hb_m;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    L.H = take(SB_MAX_W * d * 4);
+    L.xn = take(SB_MAX_W * d * 4);
+    L.xs = take(16 * d * 2);
+    L.qkv = take(SB_MAX_W * qkv_rows * 4);
+    L.att = take(SB_MAX_W * hq * 4);
+    L.atts = take(16 * hq * 2);
+    L.u = take(SB_MAX_W * f * 4);
+    L.us = take(16 * f * 2);
+    L.attn_part = take((size_t)SB_MAX_W * c->n_heads * L.max_chunks * (c->head_dim + 2) * 4);
+    L.head_part = take((size_t)SB_MAX_W * L.head_blocks * 16);
+    L.logits_exit = take((size_t)(c->n_exit_heads > 0 ? c->n_exit_heads : 1) * V * 4);
+    L.logits_final = take((size_t)SB_MAX_W * V * 4);
+    L.counters = take(1024 * 4);
+    L.round = take(sizeof(DevRound));
+    L.table = take((size_t)L.n_pages * 4);
+    L.total = off;
+    return L;
+}
+
+size_t kv_pool_bytes(const sb_config* c) {
+    return (size_t)c->n_layers * 2 * (c->max_seq / SB_KV_BLOCK) * c->n_kv_heads * SB_KV_BLOCK * c->head_dim *
+           esize(c->kv_dtype);
+}
+
+}  // namespace
+
+struct sb_model {
+    sb_config cfg;
+    const void *embed, *lm_head;
+    const float* final_norm;
+    std::vector<const float*> attn_norm, ffn_norm, exit_norm;
+    std::vector<const void*> w_qkv, w_o, w_gate_up, w_down, exit_head;
+    hipStream_t stream;
+    float *rope_cos, *rope_sin;
+    int proj;
+    int64_t layer_bytes, head_bytes;
+};
+
+struct sb_session {
+    sb_model* m;
+    char* ws;
+    WsLayout L;
+    KvLayout kv;
+    DevRound* d_round;
+    DevRound* h_round;  // pinned host copy
+    int32_t c, pending;
+    bool has_pending;
+    int n_slots, n_drafts;
+    int reached[SB_MAX_W], exit_layer[SB_MAX_W];
+    int32_t draft_host[SB_MAX_W];  // drafted id if the host knows it, else -1
+    bool round_closed;
+    int64_t draft_counter;
+    bool debug;
+    bool final_logits_valid;
+    sb_stats st;
+};
+
+namespace {
+
+template <typename T>
+T* wsp(sb_session* s, size_t off) { return reinterpret_cast<T*>(s->ws + off); }
+
+int check_params(const sb_session* s, const sb_params* p) {
+    const sb_config& c = s->m->cfg;
+    if (!p) return fail(SB_EINVAL, "params is NULL");
+    if (p->w_max < 1 || p->w_max > SB_MAX_W) return fail(SB_EINVAL, "w_max must be in 1..%d", SB_MAX_W);
+    int dlim = c.n_exit_heads < c.n_layers - 1 ? c.n_exit_heads : c.n_layers - 1;
+    if (p->d_max < 0 || p->d_max > dlim) return fail(SB_EINVAL, "d_max must be in 0..%d", dlim);
+    if (p->d_max > 0 && !p->T) return fail(SB_EINVAL, "T is NULL");
+    for (int l = 0; l < p->d_max; ++l)
+        if (!(p->T[l] > 0.f)) return fail(SB_EINVAL, "T[%d] must be positive", l);
+    if (p->n_forced < 0) return fail(SB_EINVAL, "n_forced < 0");
+    return SB_OK;
+}
+
+int readback(sb_session* s) {
+    HIP_TRY(hipMemcpyAsync(s->h_round, s->d_round, sizeof(DevRound), hipMemcpyDeviceToHost, s->m->stream));
+    HIP_TRY(hipStreamSynchronize(s->m->stream));
+    return SB_OK;
+}
+
+int gemv(sb_session* s, GemvArgs& a) {
+    hipError_t e = s->m->proj == SB_PROJ_MFMA ? launch_gemv_mfma(a, s->m->stream) : launch_gemv_valu(a, s->m->stream);
+    if (e != hipSuccess) return fail(SB_EDEVICE, "projection launch (N=%d K=%d M=%d epi=%d): %s", a.N, a.K, a.M, a.epi,
+                                     hipGetErrorString(e));
+    return SB_OK;
+}
+
+// One decoder layer (0-based l) on rows slot0..slot0+M-1, whose positions are
+// c+slot0.. : RMSNorm -> QKV -> RoPE + KV append -> attention -> W_o (+residual)
+// -> RMSNorm -> gate/up + SwiGLU -> W_down (+residual).
+int run_layer(sb_session* s, int l, int slot0, int M) {
+    sb_model* m = s->m;
+    const sb_config& c = m->cfg;
+    const bool mf = m->proj == SB_PROJ_MFMA;
+    hipStream_t st = m->stream;
+    const int d = c.d_model, f = c.d_ffn, hq = c.n_heads * c.head_dim;
+    const int qkv_rows = (c.n_heads + 2 * c.n_kv_heads) * c.head_dim;
+    const int pos0 = s->c + slot0;
+    if (pos0 + M > c.max_seq) return fail(SB_ECAPACITY, "KV capacity exceeded");
+    float* H = wsp<float>(s, s->L.H) + (size_t)slot0 * d;
+    float* xn = wsp<float>(s, s->L.xn);
+    uint16_t* xs = wsp<uint16_t>(s, s->L.xs);
+    float* qkv = wsp<float>(s, s->L.qkv);
+    float* att = wsp<float>(s, s->L.att);
+    uint16_t* atts = wsp<uint16_t>(s, s->L.atts);
+    float* u = wsp<float>(s, s->L.u);
+    uint16_t* us = wsp<uint16_t>(s, s->L.us);
+
+    HIP_TRY(launch_rmsnorm(H, m->attn_norm[l], mf ? nullptr : xn, mf ? xs : nullptr, d, M, d, c.rms_eps, st));
+    GemvArgs g{};
+    g.w_dtype = c.weight_dtype; g.M = M;
+    g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = d; g.x = xn; g.xs = xs; g.y = qkv; g.ldy = qkv_rows; g.epi = EPI_STORE;
+    int rc = gemv(s, g);
+    if (rc) return rc;
+    HIP_TRY(launch_rope_append(qkv, qkv_rows, c.n_heads, s->kv, l, m->rope_cos, m->rope_sin, pos0, M, st));
+    AttnArgs a{};
+    a.q = qkv; a.qkv_rows = qkv_rows; a.n_heads = c.n_heads; a.kv = s->kv; a.layer = l; a.pos0 = pos0; a.M = M;
+    a.partials = wsp<float>(s, s->L.attn_part); a.max_chunks = s->L.max_chunks;
+    a.counters = wsp<uint32_t>(s, s->L.counters) + 16;
+    a.out = mf ? nullptr : att; a.out_split = mf ? atts : nullptr;
+    HIP_TRY(launch_attention(a, st));
+    g.W = m->w_o[l]; g.N = d; g.K = hq; g.x = att; g.xs = atts; g.y = H; g.ldy = d; g.epi = EPI_RESID;
+    if ((rc = gemv(s, g))) return rc;
+    HIP_TRY(launch_rmsnorm(H, m->ffn_norm[l], mf ? nullptr : xn, mf ? xs : nullptr, d, M, d, c.rms_eps, st));
+    g.W = m->w_gate_up[l]; g.N = f; g.K = d; g.x = xn; g.xs = xs; g.y = mf ? nullptr : u; g.ys = mf ? us : nullptr;
+    g.ldy = f; g.epi = EPI_SWIGLU;
+    if ((rc = gemv(s, g))) return rc;
+    g.W = m->w_down[l]; g.N = d; g.K = f; g.x = u; g.xs = us; g.y = H; g.ys = nullptr; g.ldy = d; g.epi = EPI_RESID;
+    if ((rc = gemv(s, g))) return rc;
+
+    s->st.layer_sweeps += 1;
+    s->st.row_layers += M;
+    s->st.weight_bytes += m->layer_bytes;
+    s->st.kv_bytes += (int64_t)(pos0 + M) * 2 * c.n_kv_heads * c.head_dim * (int64_t)esize(c.kv_dtype);
+    return SB_OK;
+}
+
+// RMSNorm + head projection + arg max / confidence for M rows starting at `rows`.
+int run_head(sb_session* s, const void* W, const float* gain, const float* rows, int M, HeadArgs h) {
+    sb_model* m = s->m;
+    const sb_config& c = m->cfg;
+    const bool mf = m->proj == SB_PROJ_MFMA;
+    float* xn = wsp<float>(s, s->L.xn);
+    uint16_t* xs = wsp<uint16_t>(s, s->L.xs);
+    HIP_TRY(launch_rmsnorm(rows, gain, mf ? nullptr : xn, mf ? xs : nullptr, c.d_model, M, c.d_model, c.rms_eps,
+                           m->stream));
+    h.partials = wsp<float>(s, s->L.head_part);
+    h.counter = wsp<uint32_t>(s, s->L.counters);
+    h.round = s->d_round;
+    GemvArgs g{};
+    g.W = W; g.w_dtype = c.weight_dtype; g.N = c.vocab; g.K = c.d_model; g.x = xn; g.xs = xs; g.M = M;
+    g.epi = EPI_HEAD; g.head = h;
+    int rc = gemv(s, g);
+    if (rc) return rc;
+    s->st.weight_bytes += m->head_bytes;
+    return SB_OK;
+}
+
+void reset_session(sb_session* s) {
+    s->c = 0; s->has_pending = false; s->n_slots = 0; s->n_drafts = 0; s->round_closed = false;
+    s->draft_counter = 0; s->final_logits_valid = false;
+    memset(&s->st, 0, sizeof s->st);
+}
+
+int prefill_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first_token) {
+    sb_model* m = s->m;
+    const sb_config& c = m->cfg;
+    if (!prompt || !first_token) return fail(SB_EINVAL, "prefill: NULL argument");
+    if (n < 1) return fail(SB_EINVAL, "prefill: empty prompt");
+    if (n > c.max_seq) return fail(SB_ECAPACITY, "prefill: prompt of %d tokens exceeds max_seq %d", n, c.max_seq);
+    for (int i = 0; i < n; ++i)
+        if (prompt[i] < 0 || prompt[i] >= c.vocab) return fail(SB_EINVAL, "prefill: token id %d out of range", prompt[i]);
+    reset_session(s);
+    float* H = wsp<float>(s, s->L.H);
+    int last_rows = 0;
+    for (int i0 = 0; i0 < n; i0 += SB_MAX_W) {
+        int M = n - i0 < SB_MAX_W ? n - i0 : SB_MAX_W;
+        RowToks t;
+        for (int r = 0; r < SB_MAX_W; ++r) t.tok[r] = r < M ? prompt[i0 + r] : 0;
+        HIP_TRY(launch_embed(m->embed, c.weight_dtype, c.vocab, c.d_model, H, M, t, s->d_round->slot_tok, nullptr,
+                             m->stream));
+        for (int l = 0; l < c.n_layers; ++l) {
+            int rc = run_layer(s, l, 0, M);
+            if (rc) return rc;
+        }
+        s->c += M;
+        last_rows = M;
+    }
+    HeadArgs h{};
+    h.T = 1.0f; h.post = POST_NONE;
+    h.argmax_out = s->d_round->g; h.conf_out = s->d_round->gconf;
+    h.logits = s->debug ? wsp<float>(s, s->L.logits_final) : nullptr;
+    int rc = run_head(s, m->lm_head, m->final_norm, H + (size_t)(last_rows - 1) * c.d_model, 1, h);
+    if (rc) return rc;
+    s->st.final_head_sweeps++;
+    if ((rc = readback(s))) return rc;
+    s->final_logits_valid = s->debug;
+    s->pending = s->h_round->g[0];
+    s->has_pending = true;
+    *first_token = s->pending;
+    return SB_OK;
+}
+
+// sync: read the step's result back before returning (always done when the exit
+// decision is computed on the device, since it gates the next layer's launch).
+int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, bool sync) {
+    int rc = check_params(s, p);
+    if (rc) return rc;
+    sb_model* m = s->m;
+    const sb_config& c = m->cfg;
+    if (!s->has_pending) return fail(SB_ESTATE, "draft_step: no pending token (prefill first)");
+    if (s->round_closed) return fail(SB_ESTATE, "draft_step: a bound was hit, call sb_verify");
+    if (s->n_slots >= p->w_max) return fail(SB_ESTATE, "draft_step: w_max rows are open");
+    if (s->c + s->n_slots >= c.max_seq) return fail(SB_ECAPACITY, "draft_step: KV capacity exceeded");
+    const int64_t k = s->draft_counter;
+    int forced = (p->forced_exit && k < p->n_forced) ? p->forced_exit[k] : -1;
+    int over = (p->forced_draft && k < p->n_forced) ? p->forced_draft[k] : -1;
+    if (forced > p->d_max) return fail(SB_EINVAL, "forced_exit[%lld] = %d exceeds d_max", (long long)k, forced);
+    if (over >= c.vocab) return fail(SB_EINVAL, "forced_draft[%lld] = %d out of range", (long long)k, over);
+    if (forced < -1) forced = -1;
+    if (over < -1) over = -1;
+    const bool computed = forced < 0;
+
+    const int idx = s->n_slots;
+    RowToks t;
+    for (int r = 0; r < SB_MAX_W; ++r) t.tok[r] = 0;
+    t.tok[0] = idx == 0 ? s->pending : s->draft_host[idx - 1];  // -1: the id is on the device only
+    float* Hrow = wsp<float>(s, s->L.H) + (size_t)idx * c.d_model;
+    HIP_TRY(launch_embed(m->embed, c.weight_dtype, c.vocab, c.d_model, Hrow, 1, t, s->d_round->slot_tok + idx,
+                         &s->d_round->exit_flag, m->stream));
+    s->draft_counter++;
+    s->st.draft_steps++;
+    s->n_slots++;
+    s->reached[idx] = 0;
+    s->exit_layer[idx] = 0;
+    s->draft_host[idx] = -1;
+
+    int exit_at = 0;
+    for (int l = 1; l <= p->d_max; ++l) {
+        int j0 = idx;
+        while (j0 > 0 && s->reached[j0 - 1] == l - 1) --j0;
+        if ((rc = run_layer(s, l - 1, j0, idx - j0 + 1))) return rc;
+        for (int j = j0; j <= idx; ++j) s->reached[j] = l;
+        HeadArgs h{};
+        h.T = p->T[l - 1]; h.post = POST_EXIT; h.slot = idx; h.layer = l; h.forced_exit = forced; h.forced_draft = over;
+        h.threshold = p->threshold;
+        h.logits = s->debug ? wsp<float>(s, s->L.logits_exit) + (size_t)(l - 1) * c.vocab : nullptr;
+        if ((rc = run_head(s, m->exit_head[l - 1], m->exit_norm[l - 1], Hrow, 1, h))) return rc;
+        s->st.head_evals++;
+        if (computed) {
+            if ((rc = readback(s))) return rc;
+            if (s->h_round->exit_flag) { exit_at = l; break; }
+        } else if (l == forced) {
+            exit_at = l;
+            break;
+        }
+    }
+    if (!computed && sync && p->d_max > 0)
+        if ((rc = readback(s))) return rc;
+    const bool have = (computed || sync) && p->d_max > 0;
+
+    sb_draft_result res{-1, 0, SB_DEPTH_BOUND, 0.f};
+    if (have) res.confidence = s->h_round->conf[idx];
+    if (exit_at) {
+        s->exit_layer[idx] = exit_at;
+        s->draft_host[idx] = over >= 0 ? over : (have ? s->h_round->drafts[idx] : -1);
+        s->n_drafts++;
+        s->st.drafts++;
+        s->st.exit_hist[exit_at]++;
+        res.token = s->draft_host[idx];
+        res.exit_layer = exit_at;
+        res.status = s->n_drafts == p->w_max ? SB_WIDTH_BOUND : SB_EXITED;
+    } else {
+        s->st.exit_hist[0]++;
+    }
+    if (res.status != SB_EXITED) s->round_closed = true;
+    if (out) *out = res;
+    return SB_OK;
+}
+
+int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
+    int rc = check_params(s, p);
+    if (rc) return rc;
+    if (s->n_slots == 0) return fail(SB_ESTATE, "verify: no open row");
+    sb_model* m = s->m;
+    const sb_config& c = m->cfg;
+    const int M = s->n_slots, D = s->reached[0];
+    for (int j = 1; j < M; ++j)
+        if (s->reached[j] > s->reached[j - 1]) return fail(SB_ESTATE, "verify: reached layers not monotone");
+    // align: rows standing below the deepest layer reached catch up (Appendix A)
+    for (int l = 2; l <= D; ++l) {
+        int j0 = M;
+        while (j0 > 0 && s->reached[j0 - 1] == l - 1) --j0;
+        if (j0 == M) continue;
+        if ((rc = run_layer(s, l - 1, j0, M - j0))) return rc;
+        for (int j = j0; j < M; ++j) s->reached[j] = l;
+    }
+    // one parallel pass of all rows through the remaining layers
+    for (int l = D + 1; l <= c.n_layers; ++l) {
+        if ((rc = run_layer(s, l - 1, 0, M))) return rc;
+        for (int j = 0; j < M; ++j) s->reached[j] = l;
+    }
+    HeadArgs h{};
+    h.T = 1.0f; h.post = POST_ACCEPT; h.n_drafts = s->n_drafts;
+    h.logits = s->debug ? wsp<float>(s, s->L.logits_final) : nullptr;
+    if ((rc = run_head(s, m->lm_head, m->final_norm, wsp<float>(s, s->L.H), M, h))) return rc;
+    s->st.final_head_sweeps++;
+    if ((rc = readback(s))) return rc;
+    s->final_logits_valid = s->debug;
+    const DevRound& R = *s->h_round;
+    if (R.n_emit < 1 || R.n_emit > M) return fail(SB_EDEVICE, "verify: device returned n_emit = %d", R.n_emit);
+    sb_verify_result res{};
+    res.n_rows = M; res.n_drafts = s->n_drafts; res.n_matched = R.n_matched; res.n_emit = R.n_emit; res.align_layer = D;
+    for (int i = 0; i < SB_MAX_W; ++i) res.tokens[i] = i < M ? R.g[i] : -1;
+    // commit the emitted rows; KV entries of the other rows are simply left
+    // beyond the committed length and overwritten by the next round
+    s->c += R.n_emit;
+    s->pending = R.g[R.n_emit - 1];
+    s->n_slots = 0; s->n_drafts = 0; s->round_closed = false;
+    s->st.rounds++; s->st.emitted += R.n_emit; s->st.accept_hist[R.n_emit]++;
+    if (out) *out = res;
+    return SB_OK;
+}
+
+double now_ms() {
+    return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+}  // namespace
+
+// ============================================================================ C ABI
+extern "C" {
+
+const char* sb_last_error(void) { return g_err.c_str(); }
+
+int32_t sb_temperature_schedule(double alpha, int32_t L, int32_t n, float* T) {
+    if (!T || L < 1 || n < 0) return fail(SB_EINVAL, "temperature_schedule: bad argument");
+    for (int l = 1; l <= n; ++l) T[l - 1] = (float)(1.0 + alpha * (1.0 - (double)l / (double)L));
+    return SB_OK;
+}
+
+int32_t sb_query_sizes(const sb_config* cfg, sb_sizes* out) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!out) return fail(SB_EINVAL, "query_sizes: out is NULL");
+    out->kv_pool_bytes = kv_pool_bytes(cfg);
+    out->workspace_bytes = ws_layout(cfg).total;
+    return SB_OK;
+}
+
+int32_t sb_load_model(const sb_config* cfg, const sb_weights* w, void* stream, sb_model** out) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!w || !out) return fail(SB_EINVAL, "load_model: NULL argument");
+    if (!w->embed || !w->final_norm || !w->lm_head || !w->attn_norm || !w->w_qkv || !w->w_o || !w->ffn_norm ||
+        !w->w_gate_up || !w->w_down)
+        return fail(SB_EINVAL, "load_model: NULL weight pointer");
+    if (cfg->n_exit_heads > 0 && (!w->exit_norm || !w->exit_head)) return fail(SB_EINVAL, "load_model: NULL exit heads");
+    sb_model* m = new sb_model();
+    m->cfg = *cfg;
+    m->embed = w->embed; m->lm_head = w->lm_head; m->final_norm = w->final_norm;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        if (!w->attn_norm[l] || !w->w_qkv[l] || !w->w_o[l] || !w->ffn_norm[l] || !w->w_gate_up[l] || !w->w_down[l]) {
+            delete m;
+            return fail(SB_EINVAL, "load_model: NULL weight pointer in layer %d", l);
+        }
+        m->attn_norm.push_back(w->attn_norm[l]); m->w_qkv.push_back(w->w_qkv[l]); m->w_o.push_back(w->w_o[l]);
+        m->ffn_norm.push_back(w->ffn_norm[l]); m->w_gate_up.push_back(w->w_gate_up[l]);
+        m->w_down.push_back(w->w_down[l]);
+    }
+    for (int l = 0; l < cfg->n_exit_heads; ++l) {
+        if (!w->exit_norm[l] || !w->exit_head[l]) {
+            delete m;
+            return fail(SB_EINVAL, "load_model: NULL exit head %d", l);
+        }
+        m->exit_norm.push_back(w->exit_norm[l]); m->exit_head.push_back(w->exit_head[l]);
+    }
+    m->stream = (hipStream_t)stream;
+    m->proj = resolve_proj(cfg);
+    const int64_t es = (int64_t)esize(cfg->weight_dtype), d = cfg->d_model, f = cfg->d_ffn;
+    const int64_t qkv_rows = (int64_t)(cfg->n_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
+    m->layer_bytes = es * (qkv_rows * d + d * (int64_t)cfg->n_heads * cfg->head_dim + 3 * f * d);
+    m->head_bytes = es * (int64_t)cfg->vocab * d;
+    // rotary table: angle = pos * base^(-2i/hd) in double, cos/sin rounded to float
+    const int half = cfg->head_dim / 2;
+    std::vector<float> hc((size_t)cfg->max_seq * half), hs((size_t)cfg->max_seq * half);
+    for (int p = 0; p < cfg->max_seq; ++p)
+        for (int i = 0; i < half; ++i) {
+            double theta = std::pow((double)cfg->rope_base, -2.0 * (double)i / (double)cfg->head_dim);
+            double a = (double)p * theta;
+            hc[(size_t)p * half + i] = (float)std::cos(a);
+            hs[(size_t)p * half + i] = (float)std::sin(a);
+        }
+    m->rope_cos = m->rope_sin = nullptr;
+    hipError_t e = hipMalloc((void**)&m->rope_cos, hc.size() * 4);
+    if (e == hipSuccess) e = hipMalloc((void**)&m->rope_sin, hs.size() * 4);
+    if (e == hipSuccess) e = hipMemcpy(m->rope_cos, hc.data(), hc.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(m->rope_sin, hs.data(), hs.size() * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (m->rope_cos) (void)hipFree(m->rope_cos);
+        if (m->rope_sin) (void)hipFree(m->rope_sin);
+        delete m;
+        return fail(e == hipErrorOutOfMemory ? SB_ENOMEM : SB_EDEVICE, "load_model: rotary table: %s", hipGetErrorString(e));
+    }
+    *out = m;
+    return SB_OK;
+}
+
+void sb_free_model(sb_model* m) {
+    if (!m) return;
+    (void)hipFree(m->rope_cos);
+    (void)hipFree(m->rope_sin);
+    delete m;
+}
+
+int32_t sb_new_session(sb_model* m, void* kv_pool, size_t kv_bytes, void* workspace, size_t ws_bytes,
+                       const int32_t* page_order, sb_session** out) {
+    if (!m || !out) return fail(SB_EINVAL, "new_session: NULL argument");
+    if (!kv_pool || !workspace) return fail(SB_EINVAL, "new_session: NULL device buffer");
+    if (((uintptr_t)kv_pool & 255) || ((uintptr_t)workspace & 255))
+        return fail(SB_EINVAL, "new_session: buffers must be 256-byte aligned");
+    WsLayout L = ws_layout(&m->cfg);
+    if (kv_bytes < kv_pool_bytes(&m->cfg)) return fail(SB_ENOMEM, "new_session: kv_pool too small (%zu < %zu)", kv_bytes, kv_pool_bytes(&m->cfg));
+    if (ws_bytes < L.total) return fail(SB_ENOMEM, "new_session: workspace too small (%zu < %zu)", ws_bytes, L.total);
+    std::vector<int32_t> table(L.n_pages);
+    if (page_order) {
+        std::vector<char> seen(L.n_pages, 0);
+        for (int i = 0; i < L.n_pages; ++i) {
+            int32_t pg = page_order[i];
+            if (pg < 0 || pg >= L.n_pages || seen[pg]) return fail(SB_EINVAL, "new_session: page_order is not a permutation");
+            seen[pg] = 1;
+            table[i] = pg;
+        }
+    } else {
+        for (int i = 0; i < L.n_pages; ++i) table[i] = i;
+    }
+    sb_session* s = new sb_session();
+    s->m = m; s->ws = (char*)workspace; s->L = L;
+    s->d_round = wsp<DevRound>(s, L.round);
+    s->kv.pool = kv_pool; s->kv.table = wsp<int32_t>(s, L.table); s->kv.n_pages = L.n_pages;
+    s->kv.n_kv_heads = m->cfg.n_kv_heads; s->kv.head_dim = m->cfg.head_dim; s->kv.kv_dtype = m->cfg.kv_dtype;
+    s->debug = false;
+    s->h_round = nullptr;
+    reset_session(s);
+    hipError_t e = hipHostMalloc((void**)&s->h_round, sizeof(DevRound), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMemcpyAsync(wsp<int32_t>(s, L.table), table.data(), (size_t)L.n_pages * 4, hipMemcpyHostToDevice, m->stream);
+    if (e == hipSuccess) e = launch_fill_u32(wsp<uint32_t>(s, L.counters), 1024, 0u, m->stream);
+    if (e == hipSuccess) e = launch_fill_u32(reinterpret_cast<uint32_t*>(s->d_round), sizeof(DevRound) / 4, 0u, m->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+    if (e != hipSuccess) {
+        if (s->h_round) (void)hipHostFree(s->h_round);
+        delete s;
+        return fail(SB_EDEVICE, "new_session: %s", hipGetErrorString(e));
+    }
+    memset(s->h_round, 0, sizeof(DevRound));
+    *out = s;
+    return SB_OK;
+}
+
+void sb_free_session(sb_session* s) {
+    if (!s) return;
+    (void)hipStreamSynchronize(s->m->stream);
+    if (s->h_round) (void)hipHostFree(s->h_round);
+    delete s;
+}
+
+int32_t sb_prefill(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first_token) {
+    if (!s) return fail(SB_EINVAL, "prefill: session is NULL");
+    return prefill_impl(s, prompt, n, first_token);
+}
+
+int32_t sb_draft_step(sb_session* s, const sb_params* p, sb_draft_result* out) {
+    if (!s || !out) return fail(SB_EINVAL, "draft_step: NULL argument");
+    return draft_step_impl(s, p, out, true);
+}
+
+int32_t sb_verify(sb_session* s, const sb_params* p, sb_verify_result* out) {
+    if (!s || !out) return fail(SB_EINVAL, "verify: NULL argument");
+    return verify_impl(s, p, out);
+}
+
+int32_t sb_generate(sb_session* s, const int32_t* prompt, int32_t n, int32_t max_new, const sb_params* p,
+                    int32_t* out_tokens, int32_t out_cap, int32_t* n_out, sb_stats* stats) {
+    if (!s) return fail(SB_EINVAL, "generate: session is NULL");
+    int rc = check_params(s, p);
+    if (rc) return rc;
+    if (!out_tokens || !n_out || max_new < 1 || out_cap < max_new) return fail(SB_EINVAL, "generate: bad output buffer");
+    if ((int64_t)n + max_new + p->w_max > s->m->cfg.max_seq)
+        return fail(SB_ECAPACITY, "generate: n + max_new + w_max = %lld exceeds max_seq %d",
+                    (long long)n + max_new + p->w_max, s->m->cfg.max_seq);
+    double t0 = now_ms();
+    int32_t tok;
+    if ((rc = prefill_impl(s, prompt, n, &tok))) return rc;
+    double t1 = now_ms();
+    int cnt = 0;
+    out_tokens[cnt++] = tok;
+    while (cnt < max_new && !(p->eos_id >= 0 && out_tokens[cnt - 1] == p->eos_id)) {
+        sb_draft_result dr;
+        do {
+            if ((rc = draft_step_impl(s, p, &dr, false))) return rc;
+        } while (dr.status == SB_EXITED);
+        sb_verify_result vr;
+        if ((rc = verify_impl(s, p, &vr))) return rc;
+        int take = 0;
+        while (take < vr.n_emit && cnt < max_new) {
+            out_tokens[cnt++] = vr.tokens[take++];
+            if (p->eos_id >= 0 && out_tokens[cnt - 1] == p->eos_id) break;
+        }
+        if (take < vr.n_emit) {  // emission cut short: give the uncommitted positions back
+            s->c -= vr.n_emit - take;
+            s->st.emitted -= vr.n_emit - take;
+            s->pending = out_tokens[cnt - 1];
+        }
+    }
+    double t2 = now_ms();
+    s->st.prefill_ms = t1 - t0;
+    s->st.decode_ms = t2 - t1;
+    *n_out = cnt;
+    if (stats) *stats = s->st;
+    return SB_OK;
+}
+
+int32_t sb_get_stats(const sb_session* s, sb_stats* out) {
+    if (!s || !out) return fail(SB_EINVAL, "get_stats: NULL argument");
+    *out = s->st;
+    return SB_OK;
+}
+
+int32_t sb_committed_len(const sb_session* s) { return s ? s->c : SB_EINVAL; }
+
+int32_t sb_debug_enable(sb_session* s, int32_t on) {
+    if (!s) return fail(SB_EINVAL, "debug_enable: session is NULL");
+    s->debug = on != 0;
+    return SB_OK;
+}
+
+int32_t sb_debug_logits(sb_session* s, int32_t layer, int32_t row, float* out, int32_t cap) {
+    if (!s || !out) return fail(SB_EINVAL, "debug_logits: NULL argument");
+    const sb_config& c = s->m->cfg;
+    if (!s->debug) return fail(SB_ESTATE, "debug_logits: debug is off");
+    if (cap < c.vocab) return fail(SB_EINVAL, "debug_logits: cap < vocab");
+    const float* src;
+    if (layer == 0) {
+        if (row < 0 || row >= SB_MAX_W) return fail(SB_EINVAL, "debug_logits: row out of range");
+        src = wsp<float>(s, s->L.logits_final) + (size_t)row * c.vocab;
+    } else {
+        if (layer < 1 || layer > c.n_exit_heads) return fail(SB_EINVAL, "debug_logits: layer out of range");
+        src = wsp<float>(s, s->L.logits_exit) + (size_t)(layer - 1) * c.vocab;
+    }
+    HIP_TRY(hipStreamSynchronize(s->m->stream));
+    HIP_TRY(hipMemcpy(out, src, (size_t)c.vocab * 4, hipMemcpyDeviceToHost));
+    return SB_OK;
+}
+
+int32_t sb_debug_hidden(sb_session* s, int32_t slot, float* out, int32_t cap) {
+    if (!s || !out) return fail(SB_EINVAL, "debug_hidden: NULL argument");
+    const sb_config& c = s->m->cfg;
+    if (slot < 0 || slot >= SB_MAX_W || cap < c.d_model) return fail(SB_EINVAL, "debug_hidden: bad slot / cap");
+    HIP_TRY(hipStreamSynchronize(s->m->stream));
+    HIP_TRY(hipMemcpy(out, wsp<float>(s, s->L.H) + (size_t)slot * c.d_model, (size_t)c.d_model * 4, hipMemcpyDeviceToHost));
+    return SB_OK;
+}
+
+int32_t sb_debug_kv(sb_session* s, int32_t layer, int32_t pos, float* k_out, float* v_out, int32_t cap) {
+    if (!s || !k_out || !v_out) return fail(SB_EINVAL, "debug_kv: NULL argument");
+    const sb_config& c = s->m->cfg;
+    const int w = c.n_kv_heads * c.head_dim;
+    if (layer < 0 || layer >= c.n_layers || pos < 0 || pos >= c.max_seq || cap < w) return fail(SB_EINVAL, "debug_kv: out of range");
+    HIP_TRY(hipStreamSynchronize(s->m->stream));
+    std::vector<int32_t> table(s->L.n_pages);
+    HIP_TRY(hipMemcpy(table.data(), s->kv.table, table.size() * 4, hipMemcpyDeviceToHost));
+    const size_t es = esize(c.kv_dtype);
+    const int page = table[pos / SB_KV_BLOCK], t = pos % SB_KV_BLOCK;
+    std::vector<char> tmp((size_t)c.head_dim * es);
+    for (int which = 0; which < 2; ++which)
+        for (int h = 0; h < c.n_kv_heads; ++h) {
+            size_t off = ((((size_t)(layer * 2 + which) * s->L.n_pages + page) * c.n_kv_heads + h) * SB_KV_BLOCK + t) * c.head_dim;
+            HIP_TRY(hipMemcpy(tmp.data(), (const char*)s->kv.pool + off * es, tmp.size(), hipMemcpyDeviceToHost));
+            float* dst = (which == 0 ? k_out : v_out) + (size_t)h * c.head_dim;
+            for (int i = 0; i < c.head_dim; ++i) {
+                if (c.kv_dtype == SB_BF16) {
+                    uint32_t u = (uint32_t)((const uint16_t*)tmp.data())[i] << 16;
+                    memcpy(&dst[i], &u, 4);
+                } else {
+                    dst[i] = ((const float*)tmp.data())[i];
+                }
+            }
+        }
+    return SB_OK;
+}
+
+// ---- single kernels -------------------------------------------------------
+int32_t sb_op_rmsnorm(const float* x, const float* gain, float* out, int32_t M, int32_t d, float eps, void* stream) {
+    if (!x || !gain || !out || M < 1 || M > SB_MAX_W || d < 1) return fail(SB_EINVAL, "op_rmsnorm: bad argument");
+    HIP_TRY(launch_rmsnorm(x, gain, out, nullptr, 0, M, d, eps, (hipStream_t)stream));
+    return SB_OK;
+}
+
+size_t sb_op_gemv_scratch_bytes(int32_t M, int32_t K) { return K > 0 ? align_up((size_t)16 * K * 2, 256) : 0; }
+
+static int op_check(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, int32_t M, int32_t kernel) {
+    if (!W || !x) return fail(SB_EINVAL, "op: NULL operand");
+    if (w_dtype != SB_FP32 && w_dtype != SB_BF16) return fail(SB_EINVAL, "op: w_dtype");
+    if (N < 1 || K < 8 || K % 8 || M < 1 || M > SB_MAX_W) return fail(SB_EINVAL, "op: need N >= 1, K %% 8 == 0, 1 <= M <= %d", SB_MAX_W);
+    if (kernel != SB_PROJ_VALU && kernel != SB_PROJ_MFMA) return fail(SB_EINVAL, "op: kernel must be VALU or MFMA");
+    if (kernel == SB_PROJ_MFMA && (w_dtype != SB_BF16 || K % 128 || N % 16))
+        return fail(SB_EINVAL, "op: MFMA path needs bf16 weights, K %% 128 == 0, N %% 16 == 0");
+    if (((uintptr_t)W & 15) || ((uintptr_t)x & 15)) return fail(SB_EINVAL, "op: operands must be 16-byte aligned");
+    return SB_OK;
+}
+
+int32_t sb_op_gemv(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, float* y, int32_t M,
+                   int32_t kernel, void* scratch, void* stream) {
+    int rc = op_check(W, w_dtype, N, K, x, M, kernel);
+    if (rc) return rc;
+    if (!y) return fail(SB_EINVAL, "op_gemv: y is NULL");
+    GemvArgs g{};
+    g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.y = y; g.ldy = N; g.M = M; g.epi = EPI_STORE;
+    if (kernel == SB_PROJ_MFMA) {
+        if (!scratch || ((uintptr_t)scratch & 15)) return fail(SB_EINVAL, "op_gemv: MFMA path needs aligned scratch");
+        g.xs = (uint16_t*)scratch;
+        HIP_TRY(launch_split(x, (uint16_t*)scratch, M, K, (hipStream_t)stream));
+        HIP_TRY(launch_gemv_mfma(g, (hipStream_t)stream));
+    } else {
+        HIP_TRY(launch_gemv_valu(g, (hipStream_t)stream));
+    }
+    return SB_OK;
+}
+
+size_t sb_op_head_scratch_bytes(int32_t M, int32_t N, int32_t K) {
+    if (N < 1 || K < 1) return 0;
+    int nb = head_blocks_valu(N);
+    return 256 + align_up((size_t)SB_MAX_W * nb * 16, 256) + align_up((size_t)16 * K * 2, 256);
+}
+
+int32_t sb_op_head(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, int32_t M, float T,
+                   int32_t kernel, int32_t* argmax_out, float* conf_out, float* logits, void* scratch, void* stream) {
+    int rc = op_check(W, w_dtype, N, K, x, M, kernel);
+    if (rc) return rc;
+    if (!argmax_out || !conf_out || !scratch || ((uintptr_t)scratch & 255)) return fail(SB_EINVAL, "op_head: bad output / scratch");
+    if (!(T > 0.f)) return fail(SB_EINVAL, "op_head: T must be positive");
+    int nb = head_blocks_valu(N);
+    char* sc = (char*)scratch;
+    GemvArgs g{};
+    g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.M = M; g.epi = EPI_HEAD;
+    g.head.T = T; g.head.counter = (uint32_t*)sc; g.head.partials = (float*)(sc + 256);
+    g.head.logits = logits; g.head.argmax_out = argmax_out; g.head.conf_out = conf_out; g.head.post = POST_NONE;
+    if (kernel == SB_PROJ_MFMA) {
+        g.xs = (uint16_t*)(sc + 256 + align_up((size_t)SB_MAX_W * nb * 16, 256));
+        HIP_TRY(launch_split(x, const_cast<uint16_t*>(g.xs), M, K, (hipStream_t)stream));
+        HIP_TRY(launch_gemv_mfma(g, (hipStream_t)stream));
+    } else {
+        HIP_TRY(launch_gemv_valu(g, (hipStream_t)stream));
+    }
+    return SB_OK;
+}
+
+int32_t sb_rope_table_host(int32_t head_dim, float base, int32_t n_pos, float* cos_out, float* sin_out) {
+    if (head_dim < 2 || (head_dim & 1) || !(base > 0.f) || n_pos < 0 || !cos_out || !sin_out)
+        return fail(SB_EINVAL, "rope_table_host: bad argument");
+    const int half = head_dim / 2;
+    for (int p = 0; p < n_pos; ++p)
+        for (int i = 0; i < half; ++i) {
+            double theta = std::pow((double)base, -2.0 * (double)i / (double)head_dim);
+            double a = (double)p * theta;
+            cos_out[(size_t)p * half + i] = (float)std::cos(a);
+            sin_out[(size_t)p * half + i] = (float)std::sin(a);
+        }
+    return SB_OK;
+}
+
+static int attn_op_check(int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype, const void* pool,
+                         const int32_t* table, int32_t n_pages, int32_t layer, int32_t pos0, int32_t M) {
+    if (n_heads < 1 || n_kv_heads < 1 || n_heads % n_kv_heads) return fail(SB_EINVAL, "op: head counts");
+    if (head_dim != 64 && head_dim != 128) return fail(SB_EINVAL, "op: head_dim must be 64 or 128");
+    if (kv_dtype != SB_FP32 && kv_dtype != SB_BF16) return fail(SB_EINVAL, "op: kv_dtype");
+    if (!pool || !table || n_pages < 1 || layer < 0) return fail(SB_EINVAL, "op: pool / table");
+    if (M < 1 || M > SB_MAX_W || pos0 < 0 || pos0 + M > n_pages * SB_KV_BLOCK)
+        return fail(SB_ECAPACITY, "op: rows %d..%d outside the %d-page pool", pos0, pos0 + M - 1, n_pages);
+    if ((uintptr_t)pool & 15) return fail(SB_EINVAL, "op: pool must be 16-byte aligned");
+    return SB_OK;
+}
+
+int32_t sb_op_rope_append(float* qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,
+                          void* pool, const int32_t* table, int32_t n_pages, int32_t layer, const float* rope_cos,
+                          const float* rope_sin, int32_t pos0, int32_t M, void* stream) {
+    int rc = attn_op_check(n_heads, n_kv_heads, head_dim, kv_dtype, pool, table, n_pages, layer, pos0, M);
+    if (rc) return rc;
+    if (!qkv || !rope_cos || !rope_sin) return fail(SB_EINVAL, "op_rope_append: NULL operand");
+    KvLayout kv{pool, table, n_pages, n_kv_heads, head_dim, kv_dtype};
+    HIP_TRY(launch_rope_append(qkv, (n_heads + 2 * n_kv_heads) * head_dim, n_heads, kv, layer, rope_cos, rope_sin,
+                               pos0, M, (hipStream_t)stream));
+    return SB_OK;
+}
+
+size_t sb_op_attention_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t kv_dtype, int32_t n_pages) {
+    if (n_heads < 1 || n_pages < 1 || (head_dim != 64 && head_dim != 128)) return 0;
+    const int ch = attn_chunk_keys(head_dim, kv_dtype);
+    const int max_chunks = (n_pages * SB_KV_BLOCK + ch - 1) / ch;
+    return 4096 + align_up((size_t)SB_MAX_W * n_heads * max_chunks * (head_dim + 2) * 4, 256);
+}
+
+int32_t sb_op_attention(const float* qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,
+                        const void* pool, const int32_t* table, int32_t n_pages, int32_t layer, int32_t pos0,
+                        int32_t M, float* out, void* scratch, void* stream) {
+    int rc = attn_op_check(n_heads, n_kv_heads, head_dim, kv_dtype, pool, table, n_pages, layer, pos0, M);
+    if (rc) return rc;
+    if (!qkv || !out || !scratch || ((uintptr_t)scratch & 255)) return fail(SB_EINVAL, "op_attention: NULL / misaligned operand");
+    if (n_kv_heads * ((M * (n_heads / n_kv_heads) + 15) / 16) > 1024) return fail(SB_EINVAL, "op_attention: too many kv heads");
+    const int ch = attn_chunk_keys(head_dim, kv_dtype);
+    AttnArgs a{};
+    a.q = qkv; a.qkv_rows = (n_heads + 2 * n_kv_heads) * head_dim; a.n_heads = n_heads;
+    a.kv = KvLayout{const_cast<void*>(pool), table, n_pages, n_kv_heads, head_dim, kv_dtype};
+    a.layer = layer; a.pos0 = pos0; a.M = M;
+    a.counters = (uint32_t*)scratch;
+    a.partials = (float*)((char*)scratch + 4096);
+    a.max_chunks = (n_pages * SB_KV_BLOCK + ch - 1) / ch;
+    a.out = out; a.out_split = nullptr;
+    HIP_TRY(launch_attention(a, (hipStream_t)stream));
+    return SB_OK;
+}
+
+}  // extern "C"

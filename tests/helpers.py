@@ -36,3 +36,36 @@ def all_accept_weights(shape, w, k):
         w[f"exit_head.{l}"] = w["lm_head"]
         w[f"exit_norm.{l}"] = w["final_norm"]
     return w
+
+
+# ---------------------------------------------------------------- GPU side
+def gpu_model(shape, w, max_seq, proj=0):
+    import paper_2604_12247_amd as sb
+    return sb.Model(shape, w, max_seq, proj_kernel=proj)
+
+
+def gpu_params(d_max, w_max, threshold=0.5, forced_exit=None, forced_draft=None, T=None, eos_id=-1):
+    import paper_2604_12247_amd as sb
+    return sb.Params(d_max, w_max, linear_T(d_max) if T is None else T, threshold,
+                     forced_exit=forced_exit, forced_draft=forced_draft, eos_id=eos_id)
+
+
+def teacher_forced_check(oracle_model, prompt, gpu_tokens, gap_tol=1e-2):
+    """Score the GPU's output with the oracle position by position.  A position
+    passes if the GPU token is the oracle's arg max, or the oracle's logit gap
+    between its arg max and the GPU token is below gap_tol (flagged near-tie).
+    Returns (n_flagged, n_scored); raises on a real mismatch."""
+    s = oracle_model.session()
+    first = s.prefill(prompt)
+    z = s.verify_logits(0)
+    flagged = 0
+    toks = list(gpu_tokens)
+    for i, t in enumerate(toks):
+        am = int(np.argmax(z))
+        if t != am:
+            gap = z[am] - z[t]
+            assert gap < gap_tol, f"position {i}: gpu token {t}, oracle {am}, logit gap {gap}"
+            flagged += 1
+        if i + 1 < len(toks):
+            _, z = s.step(t)
+    return flagged, len(toks)

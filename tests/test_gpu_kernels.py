@@ -1,0 +1,207 @@
+"""GPU parity of the single kernels against the CPU oracle, through the C ABI.
+Sizes span several tiles and ragged tails; the oracle is double precision."""
+import numpy as np
+import pytest
+
+import oracle as orc
+import sb_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def T():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def _dev(T, a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return T.from_numpy(a).cuda()
+
+
+def _rand_w(g, N, K, bf16, std=0.02):
+    w = (g.standard_normal((N, K)) * std).astype(np.float32)
+    return si.round_to_bf16(w) if bf16 else w
+
+
+def _oracle_rows(W, x):
+    return np.stack([orc.matvec(W, x[m].astype(np.float64)) for m in range(x.shape[0])])
+
+
+@pytest.mark.parametrize("M,d", [(1, 256), (3, 4096), (8, 5120), (2, 688)])
+def test_rmsnorm(T, M, d):
+    import paper_2604_12247_amd as sb
+    g = np.random.default_rng(M * 1000 + d)
+    x = g.standard_normal((M, d)).astype(np.float32) * 0.3
+    gain = (1 + 0.1 * g.standard_normal(d)).astype(np.float32)
+    out = sb.op_rmsnorm(_dev(T, x), _dev(T, gain), 1e-6).cpu().numpy()
+    ref = np.stack([orc.rmsnorm(x[m], gain, 1e-6) for m in range(M)])
+    assert np.max(np.abs(out - ref)) <= 2e-6 * np.max(np.abs(ref))
+
+
+VALU_CASES = [  # (N, K, bf16): N ragged against the 16-row block, K ragged against the 512 stride
+    (50, 688, False), (768, 256, False), (1024, 256, True), (100, 4096, True), (4096, 11008, True),
+    (37, 2056, False),
+]
+
+
+@pytest.mark.parametrize("N,K,bf16", VALU_CASES)
+@pytest.mark.parametrize("M", [1, 3, 8])
+def test_gemv_valu(T, N, K, bf16, M):
+    import paper_2604_12247_amd as sb
+    g = np.random.default_rng(N + K + M)
+    W = _rand_w(g, N, K, bf16)
+    x = g.standard_normal((M, K)).astype(np.float32)
+    y = sb.op_gemv(_dev(T, W), _dev(T, x), sb.PROJ_VALU).cpu().numpy()
+    ref = _oracle_rows(W, x)
+    assert np.max(np.abs(y - ref)) <= 1e-5 * np.max(np.abs(ref)) + 1e-7
+
+
+MFMA_CASES = [(16, 128), (64, 256), (4096, 4096), (12288, 4096), (4096, 11008), (32000, 4096), (48, 384)]
+
+
+@pytest.mark.parametrize("N,K", MFMA_CASES)
+@pytest.mark.parametrize("M", [1, 5, 8])
+def test_gemv_mfma(T, N, K, M):
+    import paper_2604_12247_amd as sb
+    g = np.random.default_rng(N + K + M + 1)
+    W = _rand_w(g, N, K, True)
+    x = g.standard_normal((M, K)).astype(np.float32)
+    y = sb.op_gemv(_dev(T, W), _dev(T, x), sb.PROJ_MFMA).cpu().numpy()
+    ref = _oracle_rows(W, x)
+    # activations carry 16 mantissa bits (two bf16 parts): error ~ 2^-17 per term
+    assert np.max(np.abs(y - ref)) <= 3e-5 * np.max(np.abs(ref)) + 1e-7
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_gemv_row_result_does_not_depend_on_m(T, kernel):
+    """A row's output is bit-identical whether it is computed alone or with others."""
+    import paper_2604_12247_amd as sb
+    k = sb.PROJ_VALU if kernel == "valu" else sb.PROJ_MFMA
+    g = np.random.default_rng(5)
+    for N, K in ((4096, 4096), (1024, 11008), (32000, 256)):
+        W = _dev(T, _rand_w(g, N, K, True))
+        x = g.standard_normal((8, K)).astype(np.float32)
+        y8 = sb.op_gemv(W, _dev(T, x), k).cpu().numpy()
+        for M in (1, 2, 5):
+            yM = sb.op_gemv(W, _dev(T, x[:M]), k).cpu().numpy()
+            assert np.array_equal(yM, y8[:M]), (N, K, M)
+        # and a row does not care which slot it sits in
+        y1 = sb.op_gemv(W, _dev(T, x[3:4]), k).cpu().numpy()
+        assert np.array_equal(y1[0], y8[3])
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+@pytest.mark.parametrize("N,K,M", [(1024, 256, 1), (32000, 4096, 1), (32000, 4096, 6), (128256, 512, 2)])
+def test_head_argmax_and_confidence(T, kernel, N, K, M):
+    import paper_2604_12247_amd as sb
+    k = sb.PROJ_VALU if kernel == "valu" else sb.PROJ_MFMA
+    g = np.random.default_rng(N + K + M)
+    W = _rand_w(g, N, K, True, std=0.05)
+    x = g.standard_normal((M, K)).astype(np.float32)
+    for Tl in (2.0, 1.0):
+        am, cf, z = sb.op_head(_dev(T, W), _dev(T, x), Tl, k, want_logits=True)
+        am, cf, z = am.cpu().numpy(), cf.cpu().numpy(), z.cpu().numpy()
+        ref = _oracle_rows(W, x)
+        assert np.max(np.abs(z - ref)) <= 2e-2 * np.max(np.abs(ref))
+        assert np.max(np.abs(z - ref)) <= 1e-4 * np.max(np.abs(ref))      # what the kernels actually reach
+        for m in range(M):
+            o_am, o_cf = orc.act(ref[m], Tl)
+            top2 = np.sort(ref[m])[-2:]
+            if top2[1] - top2[0] >= 1e-2:
+                assert am[m] == o_am
+            assert am[m] == int(np.argmax(z[m]))      # consistent with its own logits, lowest index
+            assert abs(cf[m] - o_cf) <= 1e-3
+            assert abs(cf[m] - o_cf) <= 1e-5 + 1e-4 * o_cf
+
+
+def test_head_ties_take_lowest_index(T):
+    import paper_2604_12247_amd as sb
+    # identical weight rows give exactly equal logits in any arithmetic
+    g = np.random.default_rng(9)
+    row = si.round_to_bf16((g.standard_normal(256) * 0.05).astype(np.float32))
+    W = si.round_to_bf16((g.standard_normal((1024, 256)) * 0.001).astype(np.float32))
+    x = si.bf16_to_f32(row).astype(np.float32)[None, :] * 4
+    for rows in ((700, 33), (5, 1000), (512, 511)):
+        W2 = W.copy()
+        for r in rows:
+            W2[r] = row
+        for k in (sb.PROJ_VALU, sb.PROJ_MFMA):
+            am, cf, _ = sb.op_head(_dev(T, W2), _dev(T, x), 1.0, k)
+            assert int(am.cpu()[0]) == min(rows)
+
+
+def _attention_case(T, Hq, Hkv, hd, kv_bf16, n_ctx, M, base, shuffle, seed):
+    """Append n_ctx + M rows in passes, then compare the last pass's output rows."""
+    import paper_2604_12247_amd as sb
+    g = np.random.default_rng(seed)
+    kvd = sb.BF16 if kv_bf16 else sb.FP32
+    n_tot = n_ctx + M
+    n_pages = (n_tot + 15) // 16 + 1
+    rows = (Hq + 2 * Hkv) * hd
+    qkv = g.standard_normal((n_tot, rows)).astype(np.float32)
+    es = 2 if kv_bf16 else 4
+    pool = T.empty(3 * 2 * n_pages * Hkv * 16 * hd * es, dtype=T.uint8, device="cuda")
+    pool.fill_(0xFF)     # NaN patterns: unwritten cache must never leak into a result
+    order = g.permutation(n_pages).astype(np.int32) if shuffle else np.arange(n_pages, dtype=np.int32)
+    table = _dev(T, order)
+    c, s = sb.rope_table(hd, base, n_pages * 16)
+    cd, sd = _dev(T, c), _dev(T, s)
+    layer = 1
+    pos = 0
+    out = None
+    passes = [8] * (n_ctx // 8) + ([n_ctx % 8] if n_ctx % 8 else []) + [M]
+    scratch = T.zeros(sb.lib().sb_op_attention_scratch_bytes(Hq, hd, kvd, n_pages), dtype=T.uint8, device="cuda")
+    for m in passes:
+        q = _dev(T, qkv[pos:pos + m])
+        sb.op_rope_append(q, Hq, Hkv, hd, kvd, pool, table, layer, cd, sd, pos)
+        if pos + m == n_tot:
+            out = sb.op_attention(q, Hq, Hkv, hd, kvd, pool, table, layer, pos, scratch).cpu().numpy()
+        pos += m
+    # oracle: rotate, round K/V as the cache does, attend
+    def rnd(a):
+        return si.bf16_to_f32(si.round_to_bf16(a.astype(np.float32))) if kv_bf16 else a.astype(np.float32)
+    K = np.zeros((n_tot, Hkv, hd), np.float32); V = np.zeros_like(K)
+    for t in range(n_tot):
+        for h in range(Hkv):
+            K[t, h] = rnd(orc.rope_apply(qkv[t, (Hq + h) * hd:(Hq + h + 1) * hd], t, base))
+            V[t, h] = rnd(qkv[t, (Hq + Hkv + h) * hd:(Hq + Hkv + h + 1) * hd])
+    G = Hq // Hkv
+    worst = 0.0
+    for r in range(M):
+        p = n_ctx + r
+        for h in range(Hq):
+            q = orc.rope_apply(qkv[p, h * hd:(h + 1) * hd], p, base)
+            ref = orc.attention_head(q, K[:p + 1, h // G], V[:p + 1, h // G])
+            got = out[r, h * hd:(h + 1) * hd]
+            worst = max(worst, float(np.max(np.abs(got - ref))))
+    return worst, out
+
+
+ATT_CASES = [  # Hq, Hkv, hd, kv_bf16, n_ctx, M, rope base, shuffled pages
+    (4, 4, 64, False, 0, 1, 1e4, False),       # a single key
+    (4, 4, 64, False, 29, 4, 1e4, True),
+    (4, 2, 64, True, 130, 8, 1e4, True),       # crosses a chunk boundary inside the pass
+    (8, 8, 128, True, 300, 6, 1e4, True),
+    (8, 2, 128, True, 257, 6, 5e5, True),      # GQA, two query groups
+    (2, 2, 128, False, 70, 3, 1e4, False),     # fp32 cache with 64-key chunks
+]
+
+
+@pytest.mark.parametrize("case", ATT_CASES)
+def test_rope_append_attention(T, case):
+    worst, _ = _attention_case(T, *case, seed=sum(int(x) for x in case[:6]))
+    assert worst <= 2e-5, worst
+
+
+def test_attention_row_result_does_not_depend_on_m(T):
+    """The same position gives the same bits alone and inside a pass of 6 rows."""
+    args = (8, 8, 128, True)
+    _, out6 = _attention_case(T, *args, 250, 6, 1e4, True, seed=77)
+    for r in (0, 3, 5):
+        _, out1 = _attention_case(T, *args, 250 + r, 1, 1e4, True, seed=77)
+        assert np.array_equal(out1[0], out6[r])
