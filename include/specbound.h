@@ -222,8 +222,7 @@ size_t sb_op_gemv_scratch_bytes(int32_t M, int32_t K);
 /* Exit-head evaluation on already normalised rows x [M][K]: z = W x (never
  * written unless logits != NULL, [M][N] float), arg max (lowest index on ties) and
  * confidence p = 1 / sum_j exp((z_j - z_max)/T) (Eq. 2).  argmax_out [M] int32,
- * conf_out [M] float.  scratch: sb_op_head_scratch_bytes(M, N, K) bytes, zeroed
- * once by the caller before first use. */
+ * conf_out [M] float.  scratch: sb_op_head_scratch_bytes(M, N, K) bytes. */
 int32_t sb_op_head(const void *W, int32_t w_dtype, int32_t N, int32_t K, const float *x, int32_t M,
                    float T, int32_t kernel, int32_t *argmax_out, float *conf_out, float *logits,
                    void *scratch, void *stream);
@@ -242,8 +241,7 @@ int32_t sb_op_rope_append(float *qkv, int32_t n_heads, int32_t n_kv_heads, int32
                           const float *rope_cos, const float *rope_sin, int32_t pos0, int32_t M, void *stream);
 /* Causal attention of the M rotated query rows in qkv against keys 0..pos of the
  * paged pool (scale 1/sqrt(head_dim)); out [M][n_heads head_dim] float.  scratch:
- * sb_op_attention_scratch_bytes() bytes, its first 4096 bytes zeroed once by the
- * caller before first use. */
+ * sb_op_attention_scratch_bytes() bytes. */
 int32_t sb_op_attention(const float *qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,
                         const void *pool, const int32_t *table, int32_t n_pages, int32_t layer, int32_t pos0,
                         int32_t M, float *out, void *scratch, void *stream);

@@ -27,12 +27,11 @@ struct RowToks { int32_t tok[SB_MAX_W]; };  // >= 0: host-known id; -1: read slo
 enum Epilogue { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
 enum HeadPost { POST_NONE = 0, POST_EXIT = 1, POST_ACCEPT = 2 };
 
-// What the last block of a head kernel does once the arg max / confidence of all
-// rows are known.
+// What the merge stage of a head evaluation does once the arg max / confidence
+// of all rows are known.
 struct HeadArgs {
     float T;               // temperature of Eq. 2
     float* partials;       // [M][n_blocks][4] (max, index, sum, -)
-    uint32_t* counter;     // zero before the launch; the kernel leaves it zero
     float* logits;         // optional [M][N] store of z (parity tap), else nullptr
     int32_t* argmax_out;   // optional [M]
     float* conf_out;       // optional [M]
@@ -89,7 +88,6 @@ struct AttnArgs {
     int32_t layer, pos0, M;
     float* partials;     // [M*n_heads][max_chunks][head_dim + 2]
     int32_t max_chunks;
-    uint32_t* counters;  // [n_kv_heads * q_groups], zero before and after
     float* out;          // [M][n_heads*head_dim]
     uint16_t* out_split; // optional split-bf16 copy [16][n_heads*head_dim]
 };

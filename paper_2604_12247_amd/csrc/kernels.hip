@@ -121,12 +121,13 @@ hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------- head reduction
-// Called by every block of a head kernel after it has written its partial
-// (max, arg max, sum of exp((z - max)/T)) per row.  The block that arrives last
-// merges all partials in a fixed order -- so the result does not depend on block
-// scheduling -- and carries out the exit test (Eq. 2) or the acceptance rule.
-__device__ void head_finish(const HeadArgs& h, int M, int nb) {
-    __shared__ int s_last;
+// Second stage of a head evaluation: one block merges the per-block partials
+// (max, arg max, sum of exp((z - max)/T)) of every row in a fixed order -- so the
+// result does not depend on block scheduling -- and carries out the exit test
+// (Eq. 2) or the acceptance rule.  It is a kernel of its own: publishing the
+// partials inside the projection kernel would need a device-wide fence per
+// block, which on this chip writes back and invalidates a whole L2.
+__global__ __launch_bounds__(256) void head_merge_kernel(HeadArgs h, int M, int nb) {
     __shared__ float r_max[4], r_sum[4];
     __shared__ int r_idx[4];
     __shared__ float s_gmax;
@@ -134,17 +135,8 @@ __device__ void head_finish(const HeadArgs& h, int M, int nb) {
     __shared__ int s_am[SB_MAX_W];
     __shared__ float s_cf[SB_MAX_W];
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        unsigned prev = atomicAdd(h.counter, 1u);
-        s_last = (prev == (unsigned)(nb - 1));
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
     for (int m = 0; m < M; ++m) {
-        const volatile float* p = h.partials + (size_t)m * nb * 4;
+        const float* p = h.partials + (size_t)m * nb * 4;
         float mx = -SB_INF;
         int idx = 0x7fffffff;
         for (int b = tid; b < nb; b += 256) {
@@ -214,9 +206,12 @@ __device__ void head_finish(const HeadArgs& h, int M, int nb) {
             R->n_matched = mt;
             R->n_emit = mt + 1 < M ? mt + 1 : M;
         }
-        *h.counter = 0;
-        __threadfence();
     }
+}
+
+hipError_t launch_head_merge(const HeadArgs& h, int32_t M, int32_t nb, hipStream_t st) {
+    head_merge_kernel<<<1, 256, 0, st>>>(h, M, nb);
+    return hipGetLastError();
 }
 
 // Partial (max, arg max, sum exp) of the block's logits zs[i][m], i < rows.
@@ -363,7 +358,6 @@ __global__ __launch_bounds__(256) void gemv_valu_kernel(GemvArgs a) {
                 if (lane == r * M + m) zs[wave * 4 + r][m] = acc[r][m];
         __syncthreads();
         head_partial<16>(a.head, zs, M, n0, N, gridDim.x);
-        head_finish(a.head, M, gridDim.x);
     }
 }
 
@@ -375,7 +369,11 @@ static hipError_t launch_gemv_valu_m(const GemvArgs& a, hipStream_t st) {
         case EPI_STORE: gemv_valu_kernel<WT, M, EPI_STORE><<<(a.N + 15) / 16, 256, 0, st>>>(a); break;
         case EPI_RESID: gemv_valu_kernel<WT, M, EPI_RESID><<<(a.N + 15) / 16, 256, 0, st>>>(a); break;
         case EPI_SWIGLU: gemv_valu_kernel<WT, M, EPI_SWIGLU><<<(a.N + 7) / 8, 256, 0, st>>>(a); break;
-        case EPI_HEAD: gemv_valu_kernel<WT, M, EPI_HEAD><<<(a.N + 15) / 16, 256, 0, st>>>(a); break;
+        case EPI_HEAD: {
+            gemv_valu_kernel<WT, M, EPI_HEAD><<<(a.N + 15) / 16, 256, 0, st>>>(a);
+            hipError_t e = hipGetLastError();
+            return e != hipSuccess ? e : launch_head_merge(a.head, M, (a.N + 15) / 16, st);
+        }
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -512,7 +510,6 @@ __global__ __launch_bounds__(256) void gemv_mfma_kernel(GemvArgs a) {
         }
         __syncthreads();
         head_partial<16 * RT>(a.head, zs, M, n0, N, gridDim.x);
-        head_finish(a.head, M, gridDim.x);
     }
 }
 
@@ -534,10 +531,12 @@ hipError_t launch_gemv_mfma(const GemvArgs& a, hipStream_t st) {
             else gemv_mfma_kernel<1, EPI_RESID><<<a.N / 16, 256, 0, st>>>(a);
             break;
         case EPI_SWIGLU: gemv_mfma_kernel<2, EPI_SWIGLU><<<a.N / 16, 256, 0, st>>>(a); break;
-        case EPI_HEAD:
+        case EPI_HEAD: {
             if (rt == 2) gemv_mfma_kernel<2, EPI_HEAD><<<(a.N + 31) / 32, 256, 0, st>>>(a);
             else gemv_mfma_kernel<1, EPI_HEAD><<<a.N / 16, 256, 0, st>>>(a);
-            break;
+            hipError_t e = hipGetLastError();
+            return e != hipSuccess ? e : launch_head_merge(a.head, a.M, head_blocks_mfma(a.N), st);
+        }
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -627,7 +626,6 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     __shared__ __attribute__((aligned(16))) float qs[QG * HD];
     __shared__ __attribute__((aligned(16))) float sp[QG * CH];
     __shared__ float s_m[QG], s_l[QG];
-    __shared__ int s_last;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x, chunk = blockIdx.y, qg = blockIdx.z;
@@ -753,39 +751,28 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
             if (d == 0) { p[0] = s_m[qi]; p[1] = s_l[qi]; }
         }
     }
-    // last block of this (kv head, query group) merges the chunks
-    __threadfence();
-    __syncthreads();
-    uint32_t* ctr = a.counters + g * gridDim.z + qg;
-    if (tid == 0) {
-        unsigned prev = atomicAdd(ctr, 1u);
-        s_last = (prev == gridDim.y - 1);
+}
+
+// Second stage: one block per (row, query head) merges that row's chunk partials
+// in ascending chunk order (online-softmax rule).
+template <int HD, int CH>
+__global__ void attn_merge_kernel(AttnArgs a) {
+    const int r = blockIdx.y, hq = blockIdx.x, d = threadIdx.x;
+    const int Hq = a.n_heads, stride = HD + 2;
+    const int nc = (a.pos0 + r) / CH + 1;
+    const float* p = a.partials + (size_t)(r * Hq + hq) * a.max_chunks * stride;
+    float mx = -SB_INF;
+    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, p[c * stride]);
+    float L = 0.f, O = 0.f;
+    for (int c = 0; c < nc; ++c) {
+        float w = expf(p[c * stride] - mx);
+        L += p[c * stride + 1] * w;
+        O += p[c * stride + 2 + d] * w;
     }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    {
-        const int stride = HD + 2;
-        for (int i = tid; i < nq * HD; i += 256) {
-            int qi = i / HD, d = i - qi * HD;
-            int qq = q0 + qi, r = qq / G, gi = qq - r * G, hq = g * G + gi;
-            int nc = (a.pos0 + r) / CH + 1;
-            const volatile float* p = a.partials + (size_t)(r * Hq + hq) * a.max_chunks * stride;
-            float mx = -SB_INF;
-            for (int c = 0; c < nc; ++c) mx = fmaxf(mx, p[c * stride]);
-            float L = 0.f, O = 0.f;
-            for (int c = 0; c < nc; ++c) {
-                float w = expf(p[c * stride] - mx);
-                L += p[c * stride + 1] * w;
-                O += p[c * stride + 2 + d] * w;
-            }
-            float v = O / L;
-            size_t col = (size_t)hq * HD + d;
-            if (a.out) a.out[(size_t)r * Hq * HD + col] = v;
-            if (a.out_split) split_store(a.out_split, Hq * HD, r, (int)col, v);
-        }
-        if (tid == 0) { *ctr = 0; __threadfence(); }
-    }
+    float v = O / L;
+    size_t col = (size_t)hq * HD + d;
+    if (a.out) a.out[(size_t)r * Hq * HD + col] = v;
+    if (a.out_split) split_store(a.out_split, Hq * HD, r, (int)col, v);
 }
 
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype) {
@@ -800,12 +787,13 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     if (n_chunks > a.max_chunks) return hipErrorInvalidValue;
     const int G = a.n_heads / a.kv.n_kv_heads;
     dim3 grid(a.kv.n_kv_heads, n_chunks, (a.M * G + 15) / 16);
+    dim3 mgrid(a.n_heads, a.M);
     if (a.kv.kv_dtype == SB_BF16) {
-        if (hd == 128) attn_kernel<uint16_t, 128><<<grid, 256, 0, st>>>(a);
-        else attn_kernel<uint16_t, 64><<<grid, 256, 0, st>>>(a);
+        if (hd == 128) { attn_kernel<uint16_t, 128><<<grid, 256, 0, st>>>(a); attn_merge_kernel<128, 128><<<mgrid, 128, 0, st>>>(a); }
+        else { attn_kernel<uint16_t, 64><<<grid, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 64, 0, st>>>(a); }
     } else {
-        if (hd == 128) attn_kernel<float, 128><<<grid, 256, 0, st>>>(a);
-        else attn_kernel<float, 64><<<grid, 256, 0, st>>>(a);
+        if (hd == 128) { attn_kernel<float, 128><<<grid, 256, 0, st>>>(a); attn_merge_kernel<128, 64><<<mgrid, 128, 0, st>>>(a); }
+        else { attn_kernel<float, 64><<<grid, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 64, 0, st>>>(a); }
     }
     return hipGetLastError();
 }

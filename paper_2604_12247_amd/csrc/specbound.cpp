@@ -70,7 +70,7 @@ int resolve_proj(const sb_config* c) {
 }
 
 struct WsLayout {
-    size_t H, xn, xs, qkv, att, atts, u, us, attn_part, head_part, logits_exit, logits_final, counters, round,
+    size_t H, xn, xs, qkv, att, atts, u, us, attn_part, head_part, logits_exit, logits_final, round,
         table, total;
     int max_chunks, head_blocks, n_pages;
 };
@@ -98,7 +98,6 @@ WsLayout ws_layout(const sb_config* c) {
     L.head_part = take((size_t)SB_MAX_W * L.head_blocks * 16);
     L.logits_exit = take((size_t)(c->n_exit_heads > 0 ? c->n_exit_heads : 1) * V * 4);
     L.logits_final = take((size_t)SB_MAX_W * V * 4);
-    L.counters = take(1024 * 4);
     L.round = take(sizeof(DevRound));
     L.table = take((size_t)L.n_pages * 4);
     L.total = off;
@@ -205,7 +204,6 @@ int run_layer(sb_session* s, int l, int slot0, int M) {
     AttnArgs a{};
     a.q = qkv; a.qkv_rows = qkv_rows; a.n_heads = c.n_heads; a.kv = s->kv; a.layer = l; a.pos0 = pos0; a.M = M;
     a.partials = wsp<float>(s, s->L.attn_part); a.max_chunks = s->L.max_chunks;
-    a.counters = wsp<uint32_t>(s, s->L.counters) + 16;
     a.out = mf ? nullptr : att; a.out_split = mf ? atts : nullptr;
     HIP_TRY(launch_attention(a, st));
     g.W = m->w_o[l]; g.N = d; g.K = hq; g.x = att; g.xs = atts; g.y = H; g.ldy = d; g.epi = EPI_RESID;
@@ -234,7 +232,6 @@ int run_head(sb_session* s, const void* W, const float* gain, const float* rows,
     HIP_TRY(launch_rmsnorm(rows, gain, mf ? nullptr : xn, mf ? xs : nullptr, c.d_model, M, c.d_model, c.rms_eps,
                            m->stream));
     h.partials = wsp<float>(s, s->L.head_part);
-    h.counter = wsp<uint32_t>(s, s->L.counters);
     h.round = s->d_round;
     GemvArgs g{};
     g.W = W; g.w_dtype = c.weight_dtype; g.N = c.vocab; g.K = c.d_model; g.x = xn; g.xs = xs; g.M = M;
@@ -533,7 +530,6 @@ int32_t sb_new_session(sb_model* m, void* kv_pool, size_t kv_bytes, void* worksp
     reset_session(s);
     hipError_t e = hipHostMalloc((void**)&s->h_round, sizeof(DevRound), hipHostMallocDefault);
     if (e == hipSuccess) e = hipMemcpyAsync(wsp<int32_t>(s, L.table), table.data(), (size_t)L.n_pages * 4, hipMemcpyHostToDevice, m->stream);
-    if (e == hipSuccess) e = launch_fill_u32(wsp<uint32_t>(s, L.counters), 1024, 0u, m->stream);
     if (e == hipSuccess) e = launch_fill_u32(reinterpret_cast<uint32_t*>(s->d_round), sizeof(DevRound) / 4, 0u, m->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
     if (e != hipSuccess) {
@@ -732,7 +728,7 @@ int32_t sb_op_head(const void* W, int32_t w_dtype, int32_t N, int32_t K, const f
     char* sc = (char*)scratch;
     GemvArgs g{};
     g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.M = M; g.epi = EPI_HEAD;
-    g.head.T = T; g.head.counter = (uint32_t*)sc; g.head.partials = (float*)(sc + 256);
+    g.head.T = T; g.head.partials = (float*)(sc + 256);
     g.head.logits = logits; g.head.argmax_out = argmax_out; g.head.conf_out = conf_out; g.head.post = POST_NONE;
     if (kernel == SB_PROJ_MFMA) {
         g.xs = (uint16_t*)(sc + 256 + align_up((size_t)SB_MAX_W * nb * 16, 256));
@@ -795,13 +791,11 @@ int32_t sb_op_attention(const float* qkv, int32_t n_heads, int32_t n_kv_heads, i
     int rc = attn_op_check(n_heads, n_kv_heads, head_dim, kv_dtype, pool, table, n_pages, layer, pos0, M);
     if (rc) return rc;
     if (!qkv || !out || !scratch || ((uintptr_t)scratch & 255)) return fail(SB_EINVAL, "op_attention: NULL / misaligned operand");
-    if (n_kv_heads * ((M * (n_heads / n_kv_heads) + 15) / 16) > 1024) return fail(SB_EINVAL, "op_attention: too many kv heads");
     const int ch = attn_chunk_keys(head_dim, kv_dtype);
     AttnArgs a{};
     a.q = qkv; a.qkv_rows = (n_heads + 2 * n_kv_heads) * head_dim; a.n_heads = n_heads;
     a.kv = KvLayout{const_cast<void*>(pool), table, n_pages, n_kv_heads, head_dim, kv_dtype};
     a.layer = layer; a.pos0 = pos0; a.M = M;
-    a.counters = (uint32_t*)scratch;
     a.partials = (float*)((char*)scratch + 4096);
     a.max_chunks = (n_pages * SB_KV_BLOCK + ch - 1) / ch;
     a.out = out; a.out_split = nullptr;
