@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Throughput of the bounded self-speculative decode path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: the
+decode phase (draft steps + verification rounds) that generates the workload's
+gen_len tokens at batch 1 from a prefilled prompt, with the forced exit /
+acceptance schedule of the configuration.  Weights, prompt and KV cache are
+resident in HBM when the timed region starts.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2]
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C2", help="C1..C5 (sb_inputs.CONFIGS)")
+    ap.add_argument("--gen", type=int, default=0, help="override the number of generated tokens")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-table", action="store_true")
+    ap.add_argument("--proj", default="auto", choices=["auto", "valu", "mfma"])
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (the decode path is one sequence at batch 1); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2604_12247_amd as sb
+    import sb_inputs as si
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl = si.CONFIGS[args.config]
+    shape = wl.shape
+    gen_len = args.gen or wl.gen_len
+    P = wl.prompt_len
+    max_seq = (P + gen_len + 4 * wl.w_max + 16 + 15) // 16 * 16
+
+    t0 = time.time()
+    weights = si.make_weights(shape, wl.weight_seed)
+    log(f"[bench] {wl.name}: weights generated in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    proj = {"auto": sb.PROJ_AUTO, "valu": sb.PROJ_VALU, "mfma": sb.PROJ_MFMA}[args.proj]
+    model = sb.Model(shape, weights, max_seq, device="cuda:0", proj_kernel=proj)
+    sess = model.session()
+    torch.cuda.synchronize()
+    log(f"[bench] uploaded in {time.time() - t0:.1f}s")
+    prompt = si.make_prompt(shape.vocab, P, wl.prompt_seed)
+    T = wl.temperatures()
+
+    # ---- prefill (reported separately, not part of a step)
+    t0 = time.perf_counter()
+    first = sess.prefill(prompt)
+    prefill_ms = (time.perf_counter() - t0) * 1e3
+    log(f"[bench] prefill {P} tokens: {prefill_ms:.1f} ms")
+
+    # ---- the library's own greedy decoding: baseline and source of the continuation
+    p_ar = sb.Params(0, 1, [], wl.threshold)
+    n_ar = gen_len + 2 * wl.w_max
+    ar_ms = []
+    for i in range(2):
+        sess.rewind(P, first)
+        G, st = sess.decode(n_ar, p_ar)
+        ar_ms.append(st["decode_ms"] / n_ar)
+    ar_tok_s = 1e3 / min(ar_ms)
+    ar_bytes_per_tok = (st["weight_bytes"] + st["kv_bytes"]) / n_ar
+    log(f"[bench] greedy AR: {ar_tok_s:.1f} tok/s ({ar_bytes_per_tok / 1e9:.2f} GB/token, "
+        f"{ar_tok_s * ar_bytes_per_tok / 1e9:.0f} GB/s algorithmic)")
+    greedy = [first] + G.tolist()
+
+    # ---- forced schedule: exit layer ~ U{exit_lo..d_max}, emitted tokens per round ~ U{1..w_max},
+    # realised by draft injection so that verification is real and the output stays greedy
+    accepts = si.accept_schedule(wl.sched_seed, 2 * gen_len, wl.w_max)
+    fd, rounds = si.injection_schedule(greedy, accepts, wl.w_max, shape.vocab)
+    fe = si.forced_exit_schedule(wl.sched_seed, len(fd), wl.exit_lo, wl.d_max)
+    p_spec = sb.Params(wl.d_max, wl.w_max, T, wl.threshold, forced_exit=fe, forced_draft=fd)
+
+    def step():
+        sess.rewind(P, first)
+        out, st = sess.decode(gen_len, p_spec)
+        return out, st
+
+    for _ in range(args.warmup):
+        out, st = step()
+        assert out.tolist() == greedy[1:gen_len + 1], "speculative output differs from greedy decoding"
+    # dominant kernel (gate/up projection) timed live with HIP events on the library's stream
+    sess.profile_begin(["gate_up"], max_launches=1 << 18)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out, st = step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = sess.profile_end()
+    assert out.tolist() == greedy[1:gen_len + 1], "speculative output differs from greedy decoding"
+    ms_per_step = elapsed * 1e3 / args.steps
+    tok_s = gen_len / (ms_per_step / 1e3)
+    log(f"[bench] speculative: {tok_s:.1f} tok/s, {st['rounds']} rounds, "
+        f"{st['emitted'] / st['rounds']:.2f} tokens/round, speedup {tok_s / ar_tok_s:.3f}x")
+
+    gu = prof["gate_up"]
+    gu_us = gu["total_ms"] * 1e3 / gu["launches"]
+    gu_bytes = gu["bytes"] / gu["launches"]
+    roofline = {"bound": "hbm", "kernel": "gate_up projection + SwiGLU (gemv_mfma_kernel<2,SWIGLU>)",
+                "achieved": round(gu_bytes / gu_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gu_bytes / gu_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": int(gu_bytes), "avg_us": round(gu_us, 2), "launches": gu["launches"]}
+
+    kernels = None
+    if not args.no_kernel_table:
+        sess.profile_begin(None, max_launches=1 << 18)
+        step()
+        allp = sess.profile_end()
+        kernels = {k: {"launches": v["launches"], "avg_us": round(v["total_ms"] * 1e3 / v["launches"], 2),
+                       "GB/s": round(v["bytes"] / (v["total_ms"] * 1e6), 1),
+                       "frac_of_hbm_peak": round(v["bytes"] / (v["total_ms"] * 1e6) / HBM_PEAK_GBS, 4)}
+                   for k, v in allp.items()}
+        for k, v in kernels.items():
+            log(f"[bench]   {k:12s} {v['launches']:7d} launches  {v['avg_us']:8.2f} us  {v['GB/s']:8.1f} GB/s")
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(shape, weights, prompt, wl)
+
+    spec_bytes = st["weight_bytes"] + st["kv_bytes"]
+    line = {
+        "metric": "batch1_generated_tokens_per_s", "value": round(tok_s, 2), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights, f32 accumulate" if shape.weight_dtype == si.configs.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "prompt_len": P, "gen_len": gen_len, "d_max": wl.d_max,
+                   "w_max": wl.w_max, "threshold": wl.threshold, "T": [round(t, 4) for t in T],
+                   "schedule": f"forced exit layer U[{wl.exit_lo},{wl.d_max}], tokens per round U[1,{wl.w_max}] "
+                               "by draft injection; output checked equal to greedy decoding",
+                   "batch": 1},
+        "greedy_ar_tokens_per_s": round(ar_tok_s, 2), "speedup_vs_greedy_ar": round(tok_s / ar_tok_s, 4),
+        "tokens_per_round": round(st["emitted"] / st["rounds"], 3), "prefill_ms": round(prefill_ms, 1),
+        "algorithmic_GB_per_step": round(spec_bytes / 1e9, 2),
+        "algorithmic_GBps_whole_path": round(spec_bytes / 1e6 / ms_per_step, 1),
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+def cpu_baseline(shape, weights, prompt, wl):
+    """The oracle's greedy decoding on the host cores, on a bounded sample."""
+    from oracle import Oracle, OrcParams, num_threads
+    n_prompt = 4
+    om = Oracle(shape, weights, 64)
+    s = om.session()
+    t0 = time.perf_counter()
+    s.prefill(prompt[:n_prompt])
+    per_tok = (time.perf_counter() - t0) / n_prompt
+    n = int(max(2, min(24, 15.0 / max(per_tok, 1e-3))))
+    t0 = time.perf_counter()
+    tok = 0
+    for _ in range(n):
+        tok, _ = s.step(tok, want_logits=False)
+    dt = time.perf_counter() - t0
+    log(f"[bench] oracle: {n / dt:.2f} tok/s on {num_threads()} threads")
+    return {"value": round(n / dt, 3), "unit": "tokens/s", "cores": num_threads(), "kind": "oracle",
+            "sample": f"greedy decoding of {n} tokens after a {n_prompt}-token prompt at the {wl.name} shape "
+                      "(double-precision oracle, teacher-forced)"}
+
+
+if __name__ == "__main__":
+    main()

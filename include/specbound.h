@@ -191,6 +191,19 @@ int32_t sb_generate(sb_session *s, const int32_t *prompt, int32_t n, int32_t max
                     const sb_params *p, int32_t *out_tokens, int32_t out_cap, int32_t *n_out,
                     sb_stats *stats);
 
+/* Continue from the current state (after sb_prefill, sb_verify or sb_rewind):
+ * rounds of draft steps and verification until max_new further tokens are out or
+ * eos_id was emitted.  SB_ESTATE without a pending token or with open rows;
+ * SB_ECAPACITY if committed + max_new + w_max > max_seq.  Fills decode_ms. */
+int32_t sb_decode(sb_session *s, int32_t max_new, const sb_params *p, int32_t *out_tokens, int32_t out_cap,
+                  int32_t *n_out, sb_stats *stats);
+
+/* Drop every cached position >= n_keep (0 < n_keep <= committed length) and any
+ * open rows, make `pending_token` the next token to feed, set the draft-step
+ * counter (index into forced_exit / forced_draft) and clear the statistics.
+ * Lets a caller decode again from the end of a prefill. */
+int32_t sb_rewind(sb_session *s, int32_t n_keep, int32_t pending_token, int64_t draft_counter);
+
 int32_t sb_get_stats(const sb_session *s, sb_stats *out);
 int32_t sb_committed_len(const sb_session *s);
 
@@ -205,6 +218,18 @@ int32_t sb_debug_logits(sb_session *s, int32_t layer, int32_t row, float *out, i
 int32_t sb_debug_hidden(sb_session *s, int32_t slot, float *out, int32_t cap);
 /* K and V (as floats, n_kv_heads*head_dim each, host) cached for (layer, pos). */
 int32_t sb_debug_kv(sb_session *s, int32_t layer, int32_t pos, float *k_out, float *v_out, int32_t cap);
+
+/* ---- per-kernel timing with HIP events on the model's stream -------------- */
+enum { SB_K_RMSNORM = 0, SB_K_QKV, SB_K_ATTN, SB_K_WO, SB_K_GATEUP, SB_K_DOWN, SB_K_EXIT_HEAD,
+       SB_K_FINAL_HEAD, SB_K_COUNT };
+/* From now on every launch of a kernel class whose bit (1 << SB_K_*) is set in
+ * class_mask is bracketed by a pair of events, up to max_launches pairs in all
+ * (further launches run untimed).  SB_ENOMEM if the events cannot be created. */
+int32_t sb_profile_begin(sb_session *s, uint32_t class_mask, int32_t max_launches);
+/* Synchronises, then per class: timed launches, their summed duration in ms and
+ * their summed algorithmic bytes (weights + activations in/out for projections,
+ * K/V read for attention).  Arrays of SB_K_COUNT, host.  Ends the timing. */
+int32_t sb_profile_end(sb_session *s, int64_t *launches, double *total_ms, int64_t *bytes);
 
 /* ---- single kernels, for parity tests and roofline measurement ---------- */
 /* All pointers are device memory; stream as above; calls do not synchronise.
@@ -228,23 +253,27 @@ int32_t sb_op_head(const void *W, int32_t w_dtype, int32_t N, int32_t K, const f
                    void *scratch, void *stream);
 size_t sb_op_head_scratch_bytes(int32_t M, int32_t N, int32_t K);
 
+/* Plain device-to-device copy kernel (128-bit loads and stores), nbytes % 16 == 0,
+ * both pointers 16-byte aligned.  A bandwidth yardstick of known traffic
+ * (nbytes read + nbytes written) for calibrating profiler counters. */
+int32_t sb_op_copy(void *dst, const void *src, size_t nbytes, void *stream);
+/* Plain streaming read of nbytes (sum-reduced into *sink, 4 bytes, device). */
+int32_t sb_op_read(const void *src, size_t nbytes, float *sink, void *stream);
+
 /* Rotary table as the library builds it: cos/sin of pos * base^(-2i/head_dim),
  * evaluated in double and rounded to float; [n_pos][head_dim/2] each, host. */
 int32_t sb_rope_table_host(int32_t head_dim, float base, int32_t n_pos, float *cos_out, float *sin_out);
-/* Rotary embedding + KV append for M new rows at positions pos0..pos0+M-1.
- * qkv [M][(n_heads + 2 n_kv_heads) head_dim] float: q heads are rotated in place,
- * rotated k and v are written (rounded to kv_dtype) to the paged pool
+/* Rotary embedding, KV append and causal attention for M new rows at positions
+ * pos0..pos0+M-1.  qkv [M][(n_heads + 2 n_kv_heads) head_dim] float holds the
+ * rows' raw projections (q heads, k heads, v heads).  Rotated k and v of the new
+ * rows are written (rounded to kv_dtype) into the paged pool
  * [layer][2][n_pages][n_kv_heads][SB_KV_BLOCK][head_dim]; table [n_pages] maps
- * logical to physical pages; rope_cos/sin: device tables covering pos0+M rows. */
-int32_t sb_op_rope_append(float *qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,
-                          void *pool, const int32_t *table, int32_t n_pages, int32_t layer,
-                          const float *rope_cos, const float *rope_sin, int32_t pos0, int32_t M, void *stream);
-/* Causal attention of the M rotated query rows in qkv against keys 0..pos of the
- * paged pool (scale 1/sqrt(head_dim)); out [M][n_heads head_dim] float.  scratch:
- * sb_op_attention_scratch_bytes() bytes. */
+ * logical to physical pages; rope_cos/sin: device tables with at least pos0+M
+ * rows.  Each row attends to keys 0..its own position (scale 1/sqrt(head_dim));
+ * out [M][n_heads head_dim] float.  scratch: sb_op_attention_scratch_bytes(). */
 int32_t sb_op_attention(const float *qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,
-                        const void *pool, const int32_t *table, int32_t n_pages, int32_t layer, int32_t pos0,
-                        int32_t M, float *out, void *scratch, void *stream);
+                        void *pool, const int32_t *table, int32_t n_pages, int32_t layer, const float *rope_cos,
+                        const float *rope_sin, int32_t pos0, int32_t M, float *out, void *scratch, void *stream);
 size_t sb_op_attention_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t kv_dtype, int32_t n_pages);
 
 #ifdef __cplusplus

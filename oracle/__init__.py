@@ -7,9 +7,9 @@ never imports the HIP library.
 from .oracle import (Oracle, OracleSession, OrcParams, load_lib, matvec, rmsnorm, act,
                      rope_angles, rope_apply, attention_head, temperature_schedule,
                      expected_accept, round_time, speedup, EXITED, WIDTH_BOUND, DEPTH_BOUND,
-                     PH_DRAFT, PH_ALIGN, PH_VERIFY)
+                     PH_DRAFT, PH_ALIGN, PH_VERIFY, num_threads)
 
 __all__ = ["Oracle", "OracleSession", "OrcParams", "load_lib", "matvec", "rmsnorm", "act",
            "rope_angles", "rope_apply", "attention_head", "temperature_schedule",
            "expected_accept", "round_time", "speedup", "EXITED", "WIDTH_BOUND",
-           "DEPTH_BOUND", "PH_DRAFT", "PH_ALIGN", "PH_VERIFY"]
+           "DEPTH_BOUND", "PH_DRAFT", "PH_ALIGN", "PH_VERIFY", "num_threads"]

@@ -84,6 +84,10 @@ def load_lib(bits: int = 64) -> C.CDLL:
     return _libs[bits]
 
 
+def num_threads() -> int:
+    return load_lib(64).orc_num_threads()
+
+
 def _real(bits: int):
     return np.float64 if bits == 64 else np.float32
 

@@ -20,6 +20,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #ifdef ORC_F32
 typedef float real;
@@ -713,3 +716,12 @@ int32_t orc_greedy_nocache(orc_model *m, const int32_t *prompt, int32_t n, int32
 }
 
 int32_t orc_real_bytes(void) { return (int32_t)sizeof(real); }
+
+/* threads the matrix-vector loops run on */
+int32_t orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

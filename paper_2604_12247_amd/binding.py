@@ -78,8 +78,12 @@ SYMBOLS = ["sb_last_error", "sb_temperature_schedule", "sb_query_sizes", "sb_loa
            "sb_new_session", "sb_free_session", "sb_prefill", "sb_draft_step", "sb_verify", "sb_generate",
            "sb_get_stats", "sb_committed_len", "sb_debug_enable", "sb_debug_logits", "sb_debug_hidden",
            "sb_debug_kv", "sb_op_rmsnorm", "sb_op_gemv", "sb_op_gemv_scratch_bytes", "sb_op_head",
-           "sb_op_head_scratch_bytes", "sb_rope_table_host", "sb_op_rope_append", "sb_op_attention",
-           "sb_op_attention_scratch_bytes"]
+           "sb_op_head_scratch_bytes", "sb_rope_table_host", "sb_op_attention",
+           "sb_op_attention_scratch_bytes", "sb_decode", "sb_rewind", "sb_profile_begin", "sb_profile_end", "sb_op_copy",
+           "sb_op_read"]
+
+KERNEL_CLASSES = ["rmsnorm", "qkv", "attention", "wo", "gate_up", "down", "exit_head",
+                  "final_head"]
 
 _lib: Optional[C.CDLL] = None
 
@@ -108,6 +112,10 @@ def lib() -> C.CDLL:
         L.sb_verify.argtypes = [vp, C.POINTER(sb_params), C.POINTER(sb_verify_result)]
         L.sb_generate.argtypes = [vp, vp, i32, i32, C.POINTER(sb_params), vp, i32, C.POINTER(i32),
                                   C.POINTER(sb_stats)]
+        L.sb_decode.argtypes = [vp, i32, C.POINTER(sb_params), vp, i32, C.POINTER(i32), C.POINTER(sb_stats)]
+        L.sb_rewind.argtypes = [vp, i32, i32, C.c_int64]
+        L.sb_profile_begin.argtypes = [vp, C.c_uint32, i32]
+        L.sb_profile_end.argtypes = [vp, vp, vp, vp]
         L.sb_get_stats.argtypes = [vp, C.POINTER(sb_stats)]
         L.sb_committed_len.argtypes = [vp]
         L.sb_debug_enable.argtypes = [vp, i32]
@@ -121,9 +129,10 @@ def lib() -> C.CDLL:
         L.sb_op_head.argtypes = [vp, i32, i32, i32, vp, i32, f32, i32, vp, vp, vp, vp, vp]
         L.sb_op_head_scratch_bytes.argtypes = [i32, i32, i32]
         L.sb_op_head_scratch_bytes.restype = sz
+        L.sb_op_copy.argtypes = [vp, vp, sz, vp]
+        L.sb_op_read.argtypes = [vp, sz, vp, vp]
         L.sb_rope_table_host.argtypes = [i32, f32, i32, vp, vp]
-        L.sb_op_rope_append.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, i32, vp, vp, i32, i32, vp]
-        L.sb_op_attention.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, i32, i32, i32, vp, vp, vp]
+        L.sb_op_attention.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp]
         L.sb_op_attention_scratch_bytes.argtypes = [i32, i32, i32, i32]
         L.sb_op_attention_scratch_bytes.restype = sz
         _lib = L
@@ -299,6 +308,32 @@ class Session:
                                 out.ctypes.data, max_new, C.byref(n), C.byref(st)))
         return out[:n.value].copy(), _stats_dict(st)
 
+    def decode(self, max_new: int, p: Params):
+        """Continue from the current state; returns (tokens, stats dict)."""
+        out = np.empty(max_new, dtype=np.int32)
+        n = C.c_int32()
+        st = sb_stats()
+        check(lib().sb_decode(self.h, max_new, C.byref(p.c), out.ctypes.data, max_new, C.byref(n), C.byref(st)))
+        return out[:n.value].copy(), _stats_dict(st)
+
+    def rewind(self, n_keep: int, pending_token: int, draft_counter: int = 0):
+        check(lib().sb_rewind(self.h, n_keep, int(pending_token), draft_counter))
+
+    def profile_begin(self, classes=None, max_launches: int = 1 << 16):
+        mask = 0
+        for name in (classes or KERNEL_CLASSES):
+            mask |= 1 << KERNEL_CLASSES.index(name)
+        check(lib().sb_profile_begin(self.h, mask, max_launches))
+
+    def profile_end(self) -> dict:
+        n = len(KERNEL_CLASSES)
+        launches = np.zeros(n, dtype=np.int64)
+        ms = np.zeros(n, dtype=np.float64)
+        nbytes = np.zeros(n, dtype=np.int64)
+        check(lib().sb_profile_end(self.h, launches.ctypes.data, ms.ctypes.data, nbytes.ctypes.data))
+        return {k: dict(launches=int(launches[i]), total_ms=float(ms[i]), bytes=int(nbytes[i]))
+                for i, k in enumerate(KERNEL_CLASSES) if launches[i]}
+
     def stats(self) -> dict:
         st = sb_stats()
         check(lib().sb_get_stats(self.h, C.byref(st)))
@@ -386,21 +421,30 @@ def rope_table(head_dim: int, base: float, n_pos: int):
     return c, s
 
 
-def op_rope_append(qkv, n_heads, n_kv_heads, head_dim, kv_dtype, pool, table, layer, rope_cos, rope_sin, pos0):
-    import torch
-    check(lib().sb_op_rope_append(qkv.data_ptr(), n_heads, n_kv_heads, head_dim, kv_dtype, pool.data_ptr(),
-                                  table.data_ptr(), table.numel(), layer, rope_cos.data_ptr(),
-                                  rope_sin.data_ptr(), pos0, qkv.shape[0], _stream_ptr(torch, qkv.device)))
-
-
-def op_attention(qkv, n_heads, n_kv_heads, head_dim, kv_dtype, pool, table, layer, pos0, scratch=None):
+def op_attention(qkv, n_heads, n_kv_heads, head_dim, kv_dtype, pool, table, layer, rope_cos, rope_sin, pos0,
+                 scratch=None):
+    """RoPE + KV append + causal attention of the rows in qkv [M, (Hq+2Hkv)*hd] (raw projections)."""
     import torch
     M = qkv.shape[0]
     out = torch.empty((M, n_heads * head_dim), dtype=torch.float32, device=qkv.device)
     if scratch is None:
-        scratch = torch.zeros(lib().sb_op_attention_scratch_bytes(n_heads, head_dim, kv_dtype, table.numel()),
+        scratch = torch.empty(lib().sb_op_attention_scratch_bytes(n_heads, head_dim, kv_dtype, table.numel()),
                               dtype=torch.uint8, device=qkv.device)
     check(lib().sb_op_attention(qkv.data_ptr(), n_heads, n_kv_heads, head_dim, kv_dtype, pool.data_ptr(),
-                                table.data_ptr(), table.numel(), layer, pos0, M, out.data_ptr(),
-                                scratch.data_ptr(), _stream_ptr(torch, qkv.device)))
+                                table.data_ptr(), table.numel(), layer, rope_cos.data_ptr(), rope_sin.data_ptr(),
+                                pos0, M, out.data_ptr(), scratch.data_ptr(), _stream_ptr(torch, qkv.device)))
     return out
+
+
+def op_copy(dst, src):
+    """Plain copy kernel between two equally sized cuda tensors (bandwidth yardstick)."""
+    import torch
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    check(lib().sb_op_copy(dst.data_ptr(), src.data_ptr(), n, _stream_ptr(torch, src.device)))
+
+
+def op_read(src, sink):
+    import torch
+    check(lib().sb_op_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                           _stream_ptr(torch, src.device)))

@@ -77,12 +77,10 @@ struct KvLayout {
     int32_t n_pages, n_kv_heads, head_dim, kv_dtype;
 };
 
-hipError_t launch_rope_append(float* qkv, int32_t qkv_rows, int32_t n_heads, const KvLayout& kv, int32_t layer,
-                              const float* rope_cos, const float* rope_sin, int32_t pos0, int32_t M,
-                              hipStream_t st);
-
 struct AttnArgs {
-    const float* q;      // [M][qkv_rows], q heads first, already rotated
+    const float* q;      // [M][qkv_rows]: raw projections, q heads, then k heads, then v heads
+    const float* rope_cos;  // [pos][head_dim/2]
+    const float* rope_sin;
     int32_t qkv_rows, n_heads;
     KvLayout kv;
     int32_t layer, pos0, M;
@@ -94,6 +92,8 @@ struct AttnArgs {
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
 
+hipError_t launch_copy(void* dst, const void* src, size_t nbytes, hipStream_t st);
+hipError_t launch_read(const void* src, size_t nbytes, float* sink, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t st);
 
 }  // namespace sb

@@ -140,6 +140,12 @@ struct sb_session {
     bool debug;
     bool final_logits_valid;
     sb_stats st;
+    // per-kernel event timing
+    uint32_t prof_mask;
+    std::vector<hipEvent_t> prof_ev;   // pairs
+    std::vector<int> prof_cls;
+    std::vector<int64_t> prof_bytes;
+    size_t prof_used;                  // pairs used
 };
 
 namespace {
@@ -166,7 +172,30 @@ int readback(sb_session* s) {
     return SB_OK;
 }
 
-int gemv(sb_session* s, GemvArgs& a) {
+// Event pair around the launches of one kernel class, when that class is timed.
+struct ProfScope {
+    sb_session* s;
+    long idx;
+    ProfScope(sb_session* s_, int cls, int64_t bytes) : s(s_), idx(-1) {
+        if (!(s->prof_mask & (1u << cls)) || s->prof_used * 2 + 2 > s->prof_ev.size()) return;
+        idx = (long)s->prof_used++;
+        s->prof_cls[idx] = cls;
+        s->prof_bytes[idx] = bytes;
+        (void)hipEventRecord(s->prof_ev[2 * idx], s->m->stream);
+    }
+    ~ProfScope() {
+        if (idx >= 0) (void)hipEventRecord(s->prof_ev[2 * idx + 1], s->m->stream);
+    }
+};
+
+int64_t gemv_bytes(const GemvArgs& a) {
+    const int64_t rows = a.epi == EPI_SWIGLU ? 2 * (int64_t)a.N : a.N;
+    const int64_t out = a.epi == EPI_HEAD ? 0 : (int64_t)a.M * a.N * 4;
+    return rows * a.K * (int64_t)esize(a.w_dtype) + (int64_t)a.M * a.K * 4 + out;
+}
+
+int gemv(sb_session* s, GemvArgs& a, int cls) {
+    ProfScope ps(s, cls, gemv_bytes(a));
     hipError_t e = s->m->proj == SB_PROJ_MFMA ? launch_gemv_mfma(a, s->m->stream) : launch_gemv_valu(a, s->m->stream);
     if (e != hipSuccess) return fail(SB_EDEVICE, "projection launch (N=%d K=%d M=%d epi=%d): %s", a.N, a.K, a.M, a.epi,
                                      hipGetErrorString(e));
@@ -174,7 +203,7 @@ int gemv(sb_session* s, GemvArgs& a) {
 }
 
 // One decoder layer (0-based l) on rows slot0..slot0+M-1, whose positions are
-// c+slot0.. : RMSNorm -> QKV -> RoPE + KV append -> attention -> W_o (+residual)
+// c+slot0.. : RMSNorm -> QKV -> attention (with RoPE + KV append) -> W_o (+residual)
 // -> RMSNorm -> gate/up + SwiGLU -> W_down (+residual).
 int run_layer(sb_session* s, int l, int slot0, int M) {
     sb_model* m = s->m;
@@ -194,31 +223,41 @@ int run_layer(sb_session* s, int l, int slot0, int M) {
     float* u = wsp<float>(s, s->L.u);
     uint16_t* us = wsp<uint16_t>(s, s->L.us);
 
-    HIP_TRY(launch_rmsnorm(H, m->attn_norm[l], mf ? nullptr : xn, mf ? xs : nullptr, d, M, d, c.rms_eps, st));
+    {
+        ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * d * 8);
+        HIP_TRY(launch_rmsnorm(H, m->attn_norm[l], mf ? nullptr : xn, mf ? xs : nullptr, d, M, d, c.rms_eps, st));
+    }
     GemvArgs g{};
     g.w_dtype = c.weight_dtype; g.M = M;
     g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = d; g.x = xn; g.xs = xs; g.y = qkv; g.ldy = qkv_rows; g.epi = EPI_STORE;
-    int rc = gemv(s, g);
+    int rc = gemv(s, g, SB_K_QKV);
     if (rc) return rc;
-    HIP_TRY(launch_rope_append(qkv, qkv_rows, c.n_heads, s->kv, l, m->rope_cos, m->rope_sin, pos0, M, st));
     AttnArgs a{};
-    a.q = qkv; a.qkv_rows = qkv_rows; a.n_heads = c.n_heads; a.kv = s->kv; a.layer = l; a.pos0 = pos0; a.M = M;
+    a.q = qkv; a.rope_cos = m->rope_cos; a.rope_sin = m->rope_sin; a.qkv_rows = qkv_rows; a.n_heads = c.n_heads;
+    a.kv = s->kv; a.layer = l; a.pos0 = pos0; a.M = M;
     a.partials = wsp<float>(s, s->L.attn_part); a.max_chunks = s->L.max_chunks;
     a.out = mf ? nullptr : att; a.out_split = mf ? atts : nullptr;
-    HIP_TRY(launch_attention(a, st));
+    const int64_t kv_read = (int64_t)(pos0 + M) * 2 * c.n_kv_heads * c.head_dim * (int64_t)esize(c.kv_dtype);
+    {
+        ProfScope ps(s, SB_K_ATTN, kv_read);
+        HIP_TRY(launch_attention(a, st));
+    }
     g.W = m->w_o[l]; g.N = d; g.K = hq; g.x = att; g.xs = atts; g.y = H; g.ldy = d; g.epi = EPI_RESID;
-    if ((rc = gemv(s, g))) return rc;
-    HIP_TRY(launch_rmsnorm(H, m->ffn_norm[l], mf ? nullptr : xn, mf ? xs : nullptr, d, M, d, c.rms_eps, st));
+    if ((rc = gemv(s, g, SB_K_WO))) return rc;
+    {
+        ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * d * 8);
+        HIP_TRY(launch_rmsnorm(H, m->ffn_norm[l], mf ? nullptr : xn, mf ? xs : nullptr, d, M, d, c.rms_eps, st));
+    }
     g.W = m->w_gate_up[l]; g.N = f; g.K = d; g.x = xn; g.xs = xs; g.y = mf ? nullptr : u; g.ys = mf ? us : nullptr;
     g.ldy = f; g.epi = EPI_SWIGLU;
-    if ((rc = gemv(s, g))) return rc;
+    if ((rc = gemv(s, g, SB_K_GATEUP))) return rc;
     g.W = m->w_down[l]; g.N = d; g.K = f; g.x = u; g.xs = us; g.y = H; g.ys = nullptr; g.ldy = d; g.epi = EPI_RESID;
-    if ((rc = gemv(s, g))) return rc;
+    if ((rc = gemv(s, g, SB_K_DOWN))) return rc;
 
     s->st.layer_sweeps += 1;
     s->st.row_layers += M;
     s->st.weight_bytes += m->layer_bytes;
-    s->st.kv_bytes += (int64_t)(pos0 + M) * 2 * c.n_kv_heads * c.head_dim * (int64_t)esize(c.kv_dtype);
+    s->st.kv_bytes += kv_read;
     return SB_OK;
 }
 
@@ -229,14 +268,17 @@ int run_head(sb_session* s, const void* W, const float* gain, const float* rows,
     const bool mf = m->proj == SB_PROJ_MFMA;
     float* xn = wsp<float>(s, s->L.xn);
     uint16_t* xs = wsp<uint16_t>(s, s->L.xs);
-    HIP_TRY(launch_rmsnorm(rows, gain, mf ? nullptr : xn, mf ? xs : nullptr, c.d_model, M, c.d_model, c.rms_eps,
-                           m->stream));
+    {
+        ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * c.d_model * 8);
+        HIP_TRY(launch_rmsnorm(rows, gain, mf ? nullptr : xn, mf ? xs : nullptr, c.d_model, M, c.d_model, c.rms_eps,
+                               m->stream));
+    }
     h.partials = wsp<float>(s, s->L.head_part);
     h.round = s->d_round;
     GemvArgs g{};
     g.W = W; g.w_dtype = c.weight_dtype; g.N = c.vocab; g.K = c.d_model; g.x = xn; g.xs = xs; g.M = M;
     g.epi = EPI_HEAD; g.head = h;
-    int rc = gemv(s, g);
+    int rc = gemv(s, g, h.post == POST_EXIT ? SB_K_EXIT_HEAD : SB_K_FINAL_HEAD);
     if (rc) return rc;
     s->st.weight_bytes += m->head_bytes;
     return SB_OK;
@@ -412,6 +454,35 @@ double now_ms() {
     return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
 
+// Rounds of draft steps + verification until *cnt == max_new or eos.  While the
+// exit decisions are forced the host knows the round's shape in advance, so a
+// whole round is enqueued without waiting and read back once, after verification.
+int decode_impl(sb_session* s, const sb_params* p, int32_t* out_tokens, int* cnt_io, int max_new) {
+    int cnt = *cnt_io, rc;
+    double t1 = now_ms();
+    while (cnt < max_new && !(p->eos_id >= 0 && cnt > 0 && out_tokens[cnt - 1] == p->eos_id)) {
+        sb_draft_result dr;
+        do {
+            if ((rc = draft_step_impl(s, p, &dr, false))) return rc;
+        } while (dr.status == SB_EXITED);
+        sb_verify_result vr;
+        if ((rc = verify_impl(s, p, &vr))) return rc;
+        int take = 0;
+        while (take < vr.n_emit && cnt < max_new) {
+            out_tokens[cnt++] = vr.tokens[take++];
+            if (p->eos_id >= 0 && out_tokens[cnt - 1] == p->eos_id) break;
+        }
+        if (take < vr.n_emit) {  // emission cut short: give the uncommitted positions back
+            s->c -= vr.n_emit - take;
+            s->st.emitted -= vr.n_emit - take;
+            s->pending = out_tokens[cnt - 1];
+        }
+    }
+    s->st.decode_ms = now_ms() - t1;
+    *cnt_io = cnt;
+    return SB_OK;
+}
+
 }  // namespace
 
 // ============================================================================ C ABI
@@ -526,6 +597,8 @@ int32_t sb_new_session(sb_model* m, void* kv_pool, size_t kv_bytes, void* worksp
     s->kv.pool = kv_pool; s->kv.table = wsp<int32_t>(s, L.table); s->kv.n_pages = L.n_pages;
     s->kv.n_kv_heads = m->cfg.n_kv_heads; s->kv.head_dim = m->cfg.head_dim; s->kv.kv_dtype = m->cfg.kv_dtype;
     s->debug = false;
+    s->prof_mask = 0;
+    s->prof_used = 0;
     s->h_round = nullptr;
     reset_session(s);
     hipError_t e = hipHostMalloc((void**)&s->h_round, sizeof(DevRound), hipHostMallocDefault);
@@ -546,6 +619,7 @@ void sb_free_session(sb_session* s) {
     if (!s) return;
     (void)hipStreamSynchronize(s->m->stream);
     if (s->h_round) (void)hipHostFree(s->h_round);
+    for (hipEvent_t x : s->prof_ev) (void)hipEventDestroy(x);
     delete s;
 }
 
@@ -577,31 +651,85 @@ int32_t sb_generate(sb_session* s, const int32_t* prompt, int32_t n, int32_t max
     int32_t tok;
     if ((rc = prefill_impl(s, prompt, n, &tok))) return rc;
     double t1 = now_ms();
-    int cnt = 0;
-    out_tokens[cnt++] = tok;
-    while (cnt < max_new && !(p->eos_id >= 0 && out_tokens[cnt - 1] == p->eos_id)) {
-        sb_draft_result dr;
-        do {
-            if ((rc = draft_step_impl(s, p, &dr, false))) return rc;
-        } while (dr.status == SB_EXITED);
-        sb_verify_result vr;
-        if ((rc = verify_impl(s, p, &vr))) return rc;
-        int take = 0;
-        while (take < vr.n_emit && cnt < max_new) {
-            out_tokens[cnt++] = vr.tokens[take++];
-            if (p->eos_id >= 0 && out_tokens[cnt - 1] == p->eos_id) break;
-        }
-        if (take < vr.n_emit) {  // emission cut short: give the uncommitted positions back
-            s->c -= vr.n_emit - take;
-            s->st.emitted -= vr.n_emit - take;
-            s->pending = out_tokens[cnt - 1];
-        }
-    }
-    double t2 = now_ms();
+    out_tokens[0] = tok;
+    int cnt = 1;
+    if ((rc = decode_impl(s, p, out_tokens, &cnt, max_new))) return rc;
     s->st.prefill_ms = t1 - t0;
-    s->st.decode_ms = t2 - t1;
     *n_out = cnt;
     if (stats) *stats = s->st;
+    return SB_OK;
+}
+
+int32_t sb_decode(sb_session* s, int32_t max_new, const sb_params* p, int32_t* out_tokens, int32_t out_cap,
+                  int32_t* n_out, sb_stats* stats) {
+    if (!s) return fail(SB_EINVAL, "decode: session is NULL");
+    int rc = check_params(s, p);
+    if (rc) return rc;
+    if (!out_tokens || !n_out || max_new < 1 || out_cap < max_new) return fail(SB_EINVAL, "decode: bad output buffer");
+    if (!s->has_pending) return fail(SB_ESTATE, "decode: no pending token (prefill first)");
+    if (s->n_slots) return fail(SB_ESTATE, "decode: a round is open, call sb_verify first");
+    if ((int64_t)s->c + max_new + p->w_max > s->m->cfg.max_seq)
+        return fail(SB_ECAPACITY, "decode: committed + max_new + w_max = %lld exceeds max_seq %d",
+                    (long long)s->c + max_new + p->w_max, s->m->cfg.max_seq);
+    int cnt = 0;
+    if ((rc = decode_impl(s, p, out_tokens, &cnt, max_new))) return rc;
+    *n_out = cnt;
+    if (stats) *stats = s->st;
+    return SB_OK;
+}
+
+int32_t sb_rewind(sb_session* s, int32_t n_keep, int32_t pending_token, int64_t draft_counter) {
+    if (!s) return fail(SB_EINVAL, "rewind: session is NULL");
+    if (n_keep < 1 || n_keep > s->c) return fail(SB_EINVAL, "rewind: n_keep must be in 1..%d", s->c);
+    if (pending_token < 0 || pending_token >= s->m->cfg.vocab) return fail(SB_EINVAL, "rewind: token id out of range");
+    if (draft_counter < 0) return fail(SB_EINVAL, "rewind: draft_counter < 0");
+    HIP_TRY(hipStreamSynchronize(s->m->stream));
+    reset_session(s);
+    s->c = n_keep;
+    s->pending = pending_token;
+    s->has_pending = true;
+    s->draft_counter = draft_counter;
+    return SB_OK;
+}
+
+int32_t sb_profile_begin(sb_session* s, uint32_t class_mask, int32_t max_launches) {
+    if (!s) return fail(SB_EINVAL, "profile_begin: session is NULL");
+    if (max_launches < 1 || max_launches > (1 << 22)) return fail(SB_EINVAL, "profile_begin: max_launches out of range");
+    if (!s->prof_ev.empty()) return fail(SB_ESTATE, "profile_begin: timing already running");
+    s->prof_ev.reserve((size_t)max_launches * 2);
+    for (int i = 0; i < max_launches * 2; ++i) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) {
+            for (hipEvent_t x : s->prof_ev) (void)hipEventDestroy(x);
+            s->prof_ev.clear();
+            return fail(SB_ENOMEM, "profile_begin: cannot create %d events", max_launches * 2);
+        }
+        s->prof_ev.push_back(e);
+    }
+    s->prof_cls.assign(max_launches, 0);
+    s->prof_bytes.assign(max_launches, 0);
+    s->prof_used = 0;
+    s->prof_mask = class_mask;
+    return SB_OK;
+}
+
+int32_t sb_profile_end(sb_session* s, int64_t* launches, double* total_ms, int64_t* bytes) {
+    if (!s || !launches || !total_ms || !bytes) return fail(SB_EINVAL, "profile_end: NULL argument");
+    if (s->prof_ev.empty()) return fail(SB_ESTATE, "profile_end: timing is not running");
+    s->prof_mask = 0;
+    hipError_t e = hipStreamSynchronize(s->m->stream);
+    for (int k = 0; k < SB_K_COUNT; ++k) { launches[k] = 0; total_ms[k] = 0.0; bytes[k] = 0; }
+    for (size_t i = 0; i < s->prof_used && e == hipSuccess; ++i) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, s->prof_ev[2 * i], s->prof_ev[2 * i + 1]);
+        launches[s->prof_cls[i]]++;
+        total_ms[s->prof_cls[i]] += ms;
+        bytes[s->prof_cls[i]] += s->prof_bytes[i];
+    }
+    for (hipEvent_t x : s->prof_ev) (void)hipEventDestroy(x);
+    s->prof_ev.clear();
+    s->prof_used = 0;
+    if (e != hipSuccess) return fail(SB_EDEVICE, "profile_end: %s", hipGetErrorString(e));
     return SB_OK;
 }
 
@@ -740,6 +868,19 @@ int32_t sb_op_head(const void* W, int32_t w_dtype, int32_t N, int32_t K, const f
     return SB_OK;
 }
 
+int32_t sb_op_copy(void* dst, const void* src, size_t nbytes, void* stream) {
+    if (!dst || !src || (nbytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
+        return fail(SB_EINVAL, "op_copy: NULL / misaligned operand");
+    HIP_TRY(launch_copy(dst, src, nbytes, (hipStream_t)stream));
+    return SB_OK;
+}
+
+int32_t sb_op_read(const void* src, size_t nbytes, float* sink, void* stream) {
+    if (!src || !sink || (nbytes & 15) || ((uintptr_t)src & 15)) return fail(SB_EINVAL, "op_read: NULL / misaligned operand");
+    HIP_TRY(launch_read(src, nbytes, sink, (hipStream_t)stream));
+    return SB_OK;
+}
+
 int32_t sb_rope_table_host(int32_t head_dim, float base, int32_t n_pos, float* cos_out, float* sin_out) {
     if (head_dim < 2 || (head_dim & 1) || !(base > 0.f) || n_pos < 0 || !cos_out || !sin_out)
         return fail(SB_EINVAL, "rope_table_host: bad argument");
@@ -766,37 +907,27 @@ static int attn_op_check(int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, 
     return SB_OK;
 }
 
-int32_t sb_op_rope_append(float* qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,
-                          void* pool, const int32_t* table, int32_t n_pages, int32_t layer, const float* rope_cos,
-                          const float* rope_sin, int32_t pos0, int32_t M, void* stream) {
-    int rc = attn_op_check(n_heads, n_kv_heads, head_dim, kv_dtype, pool, table, n_pages, layer, pos0, M);
-    if (rc) return rc;
-    if (!qkv || !rope_cos || !rope_sin) return fail(SB_EINVAL, "op_rope_append: NULL operand");
-    KvLayout kv{pool, table, n_pages, n_kv_heads, head_dim, kv_dtype};
-    HIP_TRY(launch_rope_append(qkv, (n_heads + 2 * n_kv_heads) * head_dim, n_heads, kv, layer, rope_cos, rope_sin,
-                               pos0, M, (hipStream_t)stream));
-    return SB_OK;
-}
-
 size_t sb_op_attention_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t kv_dtype, int32_t n_pages) {
     if (n_heads < 1 || n_pages < 1 || (head_dim != 64 && head_dim != 128)) return 0;
     const int ch = attn_chunk_keys(head_dim, kv_dtype);
     const int max_chunks = (n_pages * SB_KV_BLOCK + ch - 1) / ch;
-    return 4096 + align_up((size_t)SB_MAX_W * n_heads * max_chunks * (head_dim + 2) * 4, 256);
+    return align_up((size_t)SB_MAX_W * n_heads * max_chunks * (head_dim + 2) * 4, 256);
 }
 
 int32_t sb_op_attention(const float* qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,
-                        const void* pool, const int32_t* table, int32_t n_pages, int32_t layer, int32_t pos0,
-                        int32_t M, float* out, void* scratch, void* stream) {
+                        void* pool, const int32_t* table, int32_t n_pages, int32_t layer, const float* rope_cos,
+                        const float* rope_sin, int32_t pos0, int32_t M, float* out, void* scratch, void* stream) {
     int rc = attn_op_check(n_heads, n_kv_heads, head_dim, kv_dtype, pool, table, n_pages, layer, pos0, M);
     if (rc) return rc;
-    if (!qkv || !out || !scratch || ((uintptr_t)scratch & 255)) return fail(SB_EINVAL, "op_attention: NULL / misaligned operand");
+    if (!qkv || !out || !rope_cos || !rope_sin || !scratch || ((uintptr_t)scratch & 255))
+        return fail(SB_EINVAL, "op_attention: NULL / misaligned operand");
     const int ch = attn_chunk_keys(head_dim, kv_dtype);
     AttnArgs a{};
-    a.q = qkv; a.qkv_rows = (n_heads + 2 * n_kv_heads) * head_dim; a.n_heads = n_heads;
-    a.kv = KvLayout{const_cast<void*>(pool), table, n_pages, n_kv_heads, head_dim, kv_dtype};
+    a.q = qkv; a.rope_cos = rope_cos; a.rope_sin = rope_sin;
+    a.qkv_rows = (n_heads + 2 * n_kv_heads) * head_dim; a.n_heads = n_heads;
+    a.kv = KvLayout{pool, table, n_pages, n_kv_heads, head_dim, kv_dtype};
     a.layer = layer; a.pos0 = pos0; a.M = M;
-    a.partials = (float*)((char*)scratch + 4096);
+    a.partials = (float*)scratch;
     a.max_chunks = (n_pages * SB_KV_BLOCK + ch - 1) / ch;
     a.out = out; a.out_split = nullptr;
     HIP_TRY(launch_attention(a, (hipStream_t)stream));

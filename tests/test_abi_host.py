@@ -87,5 +87,5 @@ def test_null_and_invalid_arguments_are_rejected_on_the_host():
     assert L.sb_op_gemv(x.ctypes.data, 0, 16, 60, x.ctypes.data, x.ctypes.data, 1, sb.PROJ_VALU, None, None) == sb.EINVAL
     assert L.sb_op_gemv(x.ctypes.data, 0, 16, 64, x.ctypes.data, x.ctypes.data, 9, sb.PROJ_VALU, None, None) == sb.EINVAL
     assert L.sb_op_gemv(x.ctypes.data, 0, 16, 128, x.ctypes.data, x.ctypes.data, 1, sb.PROJ_MFMA, None, None) == sb.EINVAL
-    assert L.sb_op_attention(x.ctypes.data, 4, 4, 64, 0, x.ctypes.data, x.ctypes.data, 2, 0, 30, 4,
-                             x.ctypes.data, x.ctypes.data, None) == sb.ECAPACITY
+    assert L.sb_op_attention(x.ctypes.data, 4, 4, 64, 0, x.ctypes.data, x.ctypes.data, 2, 0, x.ctypes.data,
+                             x.ctypes.data, 30, 4, x.ctypes.data, x.ctypes.data, None) == sb.ECAPACITY

@@ -256,3 +256,36 @@ def test_state_and_capacity_errors(sb):
     assert out.tolist() == ar[:5].tolist()
     out, _ = gm.session().generate(prompt, 12, gpu_params(2, 4, 0.0, eos_id=int(ar[3])))
     assert out.tolist() == ar[: ar.tolist().index(ar[3]) + 1].tolist()
+
+
+def test_rewind_decode_and_kernel_timing(sb):
+    shape, w, om, gm = _build(sb, "bf16-mfma", n_layers=4, n_exit=2, seed=39)
+    prompt = si.make_prompt(shape.vocab, 20, 49)
+    p = gpu_params(2, 4, 0.5, forced_exit=si.forced_exit_schedule(4, 300, 1, 2))
+    ref, _ = gm.session().generate(prompt, 30, p)
+    s = gm.session()
+    first = s.prefill(prompt)
+    assert first == ref[0]
+    for _ in range(2):
+        s.rewind(len(prompt), first)
+        out, st = s.decode(29, p)
+        assert out.tolist() == ref[1:].tolist()
+        assert st["emitted"] >= 29 - 0 and st["decode_ms"] > 0
+    # decode in two pieces continues where the first stopped (the forced arrays keep their index)
+    s.rewind(len(prompt), first)
+    a, _ = s.decode(10, gpu_params(0, 1))
+    b, _ = s.decode(19, gpu_params(0, 1))
+    assert a.tolist() + b.tolist() == ref[1:].tolist()
+    with pytest.raises(sb.SbError):
+        s.rewind(10 ** 6, 0)
+    # per-kernel event timing: every class of the layer shows up with plausible byte counts
+    s.rewind(len(prompt), first)
+    s.profile_begin(None, max_launches=4096)
+    s.decode(8, p)
+    prof = s.profile_end()
+    for k in ("rmsnorm", "qkv", "attention", "wo", "gate_up", "down", "exit_head", "final_head"):
+        assert prof[k]["launches"] > 0 and prof[k]["total_ms"] > 0, k
+    es = 2
+    assert prof["gate_up"]["bytes"] // prof["gate_up"]["launches"] >= 2 * shape.d_ffn * shape.d_model * es
+    with pytest.raises(sb.SbError):
+        s.profile_end()

@@ -155,12 +155,12 @@ def _attention_case(T, Hq, Hkv, hd, kv_bf16, n_ctx, M, base, shuffle, seed):
     pos = 0
     out = None
     passes = [8] * (n_ctx // 8) + ([n_ctx % 8] if n_ctx % 8 else []) + [M]
-    scratch = T.zeros(sb.lib().sb_op_attention_scratch_bytes(Hq, hd, kvd, n_pages), dtype=T.uint8, device="cuda")
+    scratch = T.empty(sb.lib().sb_op_attention_scratch_bytes(Hq, hd, kvd, n_pages), dtype=T.uint8, device="cuda")
     for m in passes:
         q = _dev(T, qkv[pos:pos + m])
-        sb.op_rope_append(q, Hq, Hkv, hd, kvd, pool, table, layer, cd, sd, pos)
+        o = sb.op_attention(q, Hq, Hkv, hd, kvd, pool, table, layer, cd, sd, pos, scratch)
         if pos + m == n_tot:
-            out = sb.op_attention(q, Hq, Hkv, hd, kvd, pool, table, layer, pos, scratch).cpu().numpy()
+            out = o.cpu().numpy()
         pos += m
     # oracle: rotate, round K/V as the cache does, attend
     def rnd(a):
@@ -194,6 +194,7 @@ ATT_CASES = [  # Hq, Hkv, hd, kv_bf16, n_ctx, M, rope base, shuffled pages
 
 @pytest.mark.parametrize("case", ATT_CASES)
 def test_rope_append_attention(T, case):
+    """One call per pass: rotary embedding, KV append and attention over the paged cache."""
     worst, _ = _attention_case(T, *case, seed=sum(int(x) for x in case[:6]))
     assert worst <= 2e-5, worst
 
