@@ -222,10 +222,12 @@ int32_t sb_debug_kv(sb_session *s, int32_t layer, int32_t pos, float *k_out, flo
 /* ---- per-kernel timing with HIP events on the model's stream -------------- */
 enum { SB_K_RMSNORM = 0, SB_K_QKV, SB_K_ATTN, SB_K_WO, SB_K_GATEUP, SB_K_DOWN, SB_K_EXIT_HEAD,
        SB_K_FINAL_HEAD, SB_K_COUNT };
-/* From now on every launch of a kernel class whose bit (1 << SB_K_*) is set in
- * class_mask is bracketed by a pair of events, up to max_launches pairs in all
- * (further launches run untimed).  SB_ENOMEM if the events cannot be created. */
-int32_t sb_profile_begin(sb_session *s, uint32_t class_mask, int32_t max_launches);
+/* From now on every sample_every-th launch of a kernel class whose bit
+ * (1 << SB_K_*) is set in class_mask is bracketed by a pair of events, up to
+ * max_launches pairs in all (further launches run untimed).  An event pair costs
+ * several microseconds of idle GPU time, so sample sparsely inside timed runs.
+ * SB_ENOMEM if the events cannot be created. */
+int32_t sb_profile_begin(sb_session *s, uint32_t class_mask, int32_t max_launches, int32_t sample_every);
 /* Synchronises, then per class: timed launches, their summed duration in ms and
  * their summed algorithmic bytes (weights + activations in/out for projections,
  * K/V read for attention).  Arrays of SB_K_COUNT, host.  Ends the timing. */

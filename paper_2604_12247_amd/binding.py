@@ -114,7 +114,7 @@ def lib() -> C.CDLL:
                                   C.POINTER(sb_stats)]
         L.sb_decode.argtypes = [vp, i32, C.POINTER(sb_params), vp, i32, C.POINTER(i32), C.POINTER(sb_stats)]
         L.sb_rewind.argtypes = [vp, i32, i32, C.c_int64]
-        L.sb_profile_begin.argtypes = [vp, C.c_uint32, i32]
+        L.sb_profile_begin.argtypes = [vp, C.c_uint32, i32, i32]
         L.sb_profile_end.argtypes = [vp, vp, vp, vp]
         L.sb_get_stats.argtypes = [vp, C.POINTER(sb_stats)]
         L.sb_committed_len.argtypes = [vp]
@@ -319,11 +319,11 @@ class Session:
     def rewind(self, n_keep: int, pending_token: int, draft_counter: int = 0):
         check(lib().sb_rewind(self.h, n_keep, int(pending_token), draft_counter))
 
-    def profile_begin(self, classes=None, max_launches: int = 1 << 16):
+    def profile_begin(self, classes=None, max_launches: int = 1 << 16, sample_every: int = 1):
         mask = 0
         for name in (classes or KERNEL_CLASSES):
             mask |= 1 << KERNEL_CLASSES.index(name)
-        check(lib().sb_profile_begin(self.h, mask, max_launches))
+        check(lib().sb_profile_begin(self.h, mask, max_launches, sample_every))
 
     def profile_end(self) -> dict:
         n = len(KERNEL_CLASSES)

@@ -307,6 +307,12 @@ __device__ __forceinline__ void head_partial(const HeadArgs& h, float (*zs)[SB_M
 // loads), partial sums are combined with a fixed shuffle tree.  x is staged in
 // LDS in chunks.  The order in which a row's products are added is a function of
 // K alone.
+__device__ __forceinline__ void unpack8(uint4 v, float (&w)[8]) {
+    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
+    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
+    w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
+    w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
+}
 __device__ __forceinline__ void load8(const uint16_t* p, float (&w)[8]) {
     uint4 v = *reinterpret_cast<const uint4*>(p);
     w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
@@ -691,26 +697,24 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     }
 
     // One tile = CH keys x HD values of K (which = 0) or V (which = 1).  Old keys
-    // come from the cache; keys of the new rows are built from qkv.
-    auto load_tile = [&](int which) {
-        KVT* base = reinterpret_cast<KVT*>(a.kv.pool) + (size_t)(a.layer * 2 + which) * a.kv.n_pages * page_elems;
-        uint4 v[NIT];
+    // come from the cache; keys of the new rows are built from qkv.  fetch() only
+    // issues loads into registers, so both tiles' memory round trips overlap with
+    // each other and with the score computation; commit() puts a tile into LDS.
+    auto tile_base = [&](int which) {
+        return reinterpret_cast<KVT*>(a.kv.pool) + (size_t)(a.layer * 2 + which) * a.kv.n_pages * page_elems;
+    };
+    auto fetch = [&](int which, uint4 (&v)[NIT]) {
+        const KVT* base = tile_base(which);
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int u = tid + it * 256;
             const int t = u / UPK, d = (u - t * UPK) * EPV;
             const int key = key0 + t;
             v[it] = make_uint4(0, 0, 0, 0);
-            if (key < a.pos0)
+            if (key < a.pos0) {
                 v[it] = *reinterpret_cast<const uint4*>(base + (size_t)pages[t / SB_KV_BLOCK] * page_elems +
                                                         ((size_t)g * SB_KV_BLOCK + (t % SB_KV_BLOCK)) * HD + d);
-        }
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int u = tid + it * 256;
-            const int t = u / UPK, d = (u - t * UPK) * EPV;
-            const int key = key0 + t;
-            if (key >= a.pos0 && key < n_total) {
+            } else if (key < n_total) {
                 const int r = key - a.pos0;
                 float f[EPV];
                 if (which == 0) {
@@ -728,14 +732,26 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
                     for (int e = 0; e < EPV; ++e) f[e] = vp[d + e];
                 }
                 v[it] = KvVec<KVT>::pack(f);
-                if (qg == 0)  // KV append: exactly one block per (kv head, key)
-                    *reinterpret_cast<uint4*>(base + (size_t)pages[t / SB_KV_BLOCK] * page_elems +
-                                              ((size_t)g * SB_KV_BLOCK + (t % SB_KV_BLOCK)) * HD + d) = v[it];
             }
+        }
+    };
+    auto commit = [&](int which, const uint4 (&v)[NIT]) {
+        KVT* base = tile_base(which);
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int u = tid + it * 256;
+            const int t = u / UPK, d = (u - t * UPK) * EPV;
+            const int key = key0 + t;
+            if (qg == 0 && key >= a.pos0 && key < n_total)  // KV append: exactly one block per (kv head, key)
+                *reinterpret_cast<uint4*>(base + (size_t)pages[t / SB_KV_BLOCK] * page_elems +
+                                          ((size_t)g * SB_KV_BLOCK + (t % SB_KV_BLOCK)) * HD + d) = v[it];
             *reinterpret_cast<uint4*>(&tile[t * LDT + d]) = v[it];
         }
     };
-    load_tile(0);
+    uint4 kreg[NIT], vreg[NIT];
+    fetch(0, kreg);
+    fetch(1, vreg);
+    commit(0, kreg);
     __syncthreads();
 
     {   // scores: thread = (key t, query subset qh)
@@ -749,6 +765,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
             KvVec<KVT>::load8(&tile[t * LDT + d], kf);
 #pragma unroll
             for (int j = 0; j < QPT; ++j) {
+                if (qh + j * QSPLIT >= nq) continue;  // uniform per wave
                 const float* qp = &qs[(qh + j * QSPLIT) * HD + d];
                 float4 qa = *reinterpret_cast<const float4*>(qp);
                 float4 qb = *reinterpret_cast<const float4*>(qp + 4);
@@ -768,7 +785,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         }
     }
     __syncthreads();
-    for (int qi = wave; qi < QG; qi += 4) {
+    for (int qi = wave; qi < nq; qi += 4) {
         float s0 = sp[qi * CH + lane];
         float s1 = (CH == 128) ? sp[qi * CH + 64 + lane] : -SB_INF;
         float mx = wave_max(fmaxf(s0, s1));
@@ -780,7 +797,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         if (lane == 0) { s_m[qi] = mx; s_l[qi] = l; }
     }
     __syncthreads();
-    load_tile(1);
+    commit(1, vreg);
     __syncthreads();
 
     float o[QG];
@@ -795,6 +812,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
             float v2 = ldf(&tile[(t + 2) * LDT + d]), v3 = ldf(&tile[(t + 3) * LDT + d]);
 #pragma unroll
             for (int qi = 0; qi < QG; ++qi) {
+                if (qi >= nq) continue;
                 float4 p = *reinterpret_cast<const float4*>(&sp[qi * CH + t]);
                 float s = o[qi];
                 s = fmaf(p.x, v0, s); s = fmaf(p.y, v1, s); s = fmaf(p.z, v2, s); s = fmaf(p.w, v3, s);
@@ -829,16 +847,33 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
 // in ascending chunk order (online-softmax rule).
 template <int HD, int CH>
 __global__ void attn_merge_kernel(AttnArgs a) {
+    constexpr int MAXC = 512;
+    __shared__ float sm[MAXC], sl[MAXC];
     const int r = blockIdx.y, hq = blockIdx.x, d = threadIdx.x;
     const int Hq = a.n_heads, stride = HD + 2;
     const int nc = (a.pos0 + r) / CH + 1;
     const float* p = a.partials + (size_t)(r * Hq + hq) * a.max_chunks * stride;
+    for (int c = d; c < nc; c += HD) {
+        sm[c] = p[c * stride];
+        sl[c] = p[c * stride + 1];
+    }
+    __syncthreads();
     float mx = -SB_INF;
-    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, p[c * stride]);
+    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, sm[c]);
     float L = 0.f, O = 0.f;
-    for (int c = 0; c < nc; ++c) {
-        float w = expf(p[c * stride] - mx);
-        L += p[c * stride + 1] * w;
+    int c = 0;
+    for (; c + 4 <= nc; c += 4) {  // four independent loads in flight
+        float a0 = p[(c + 0) * stride + 2 + d], a1 = p[(c + 1) * stride + 2 + d];
+        float a2 = p[(c + 2) * stride + 2 + d], a3 = p[(c + 3) * stride + 2 + d];
+        float w0 = expf(sm[c] - mx), w1 = expf(sm[c + 1] - mx), w2 = expf(sm[c + 2] - mx), w3 = expf(sm[c + 3] - mx);
+        L += sl[c] * w0; O += a0 * w0;
+        L += sl[c + 1] * w1; O += a1 * w1;
+        L += sl[c + 2] * w2; O += a2 * w2;
+        L += sl[c + 3] * w3; O += a3 * w3;
+    }
+    for (; c < nc; ++c) {
+        float w = expf(sm[c] - mx);
+        L += sl[c] * w;
         O += p[c * stride + 2 + d] * w;
     }
     float v = O / L;
@@ -856,7 +891,7 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     if ((hd != 64 && hd != 128) || a.M < 1 || a.M > SB_MAX_W || a.n_heads % a.kv.n_kv_heads) return hipErrorInvalidValue;
     const int ch = attn_chunk_keys(hd, a.kv.kv_dtype);
     const int n_chunks = (a.pos0 + a.M + ch - 1) / ch;
-    if (n_chunks > a.max_chunks) return hipErrorInvalidValue;
+    if (n_chunks > a.max_chunks || n_chunks > 512) return hipErrorInvalidValue;
     const int G = a.n_heads / a.kv.n_kv_heads;
     dim3 grid(a.kv.n_kv_heads, n_chunks, (a.M * G + 15) / 16);
     if (!a.rope_cos || !a.rope_sin) return hipErrorInvalidValue;

@@ -142,6 +142,8 @@ struct sb_session {
     sb_stats st;
     // per-kernel event timing
     uint32_t prof_mask;
+    int prof_every;                    // time every n-th launch of a class
+    int64_t prof_seen[SB_K_COUNT];
     std::vector<hipEvent_t> prof_ev;   // pairs
     std::vector<int> prof_cls;
     std::vector<int64_t> prof_bytes;
@@ -178,6 +180,7 @@ struct ProfScope {
     long idx;
     ProfScope(sb_session* s_, int cls, int64_t bytes) : s(s_), idx(-1) {
         if (!(s->prof_mask & (1u << cls)) || s->prof_used * 2 + 2 > s->prof_ev.size()) return;
+        if (s->prof_seen[cls]++ % s->prof_every) return;
         idx = (long)s->prof_used++;
         s->prof_cls[idx] = cls;
         s->prof_bytes[idx] = bytes;
@@ -599,6 +602,7 @@ int32_t sb_new_session(sb_model* m, void* kv_pool, size_t kv_bytes, void* worksp
     s->debug = false;
     s->prof_mask = 0;
     s->prof_used = 0;
+    s->prof_every = 1;
     s->h_round = nullptr;
     reset_session(s);
     hipError_t e = hipHostMalloc((void**)&s->h_round, sizeof(DevRound), hipHostMallocDefault);
@@ -692,9 +696,10 @@ int32_t sb_rewind(sb_session* s, int32_t n_keep, int32_t pending_token, int64_t 
     return SB_OK;
 }
 
-int32_t sb_profile_begin(sb_session* s, uint32_t class_mask, int32_t max_launches) {
+int32_t sb_profile_begin(sb_session* s, uint32_t class_mask, int32_t max_launches, int32_t sample_every) {
     if (!s) return fail(SB_EINVAL, "profile_begin: session is NULL");
     if (max_launches < 1 || max_launches > (1 << 22)) return fail(SB_EINVAL, "profile_begin: max_launches out of range");
+    if (sample_every < 1) return fail(SB_EINVAL, "profile_begin: sample_every must be >= 1");
     if (!s->prof_ev.empty()) return fail(SB_ESTATE, "profile_begin: timing already running");
     s->prof_ev.reserve((size_t)max_launches * 2);
     for (int i = 0; i < max_launches * 2; ++i) {
@@ -709,6 +714,8 @@ int32_t sb_profile_begin(sb_session* s, uint32_t class_mask, int32_t max_launche
     s->prof_cls.assign(max_launches, 0);
     s->prof_bytes.assign(max_launches, 0);
     s->prof_used = 0;
+    s->prof_every = sample_every;
+    for (int k = 0; k < SB_K_COUNT; ++k) s->prof_seen[k] = 0;
     s->prof_mask = class_mask;
     return SB_OK;
 }
