@@ -58,13 +58,29 @@ struct GemvArgs {
     int32_t M;
     int32_t epi;       // Epilogue
     HeadArgs head;     // EPI_HEAD
+    // RMSNorm folded into the MFMA projections.  Input side: xs holds the two bf16
+    // parts of gain * h (not yet scaled); the kernel multiplies its outputs by
+    // 1/sqrt(sum_sq/K + eps), sum_sq = ssq_in[m][0..ssq_nb) added in index order.
+    const float* ssq_in;  // nullptr: xs is used as it is
+    int32_t ssq_nb, ssq_ld;
+    float eps;
+    // Output side (EPI_RESID): after h += y, also write the parts of gainA * h to nxA
+    // (and of gainB * h to nxB) and the sum of squares of the block's 16-row tile
+    // to ssq_out[m][tile]; all row-major with the leading dimension of y / ssq_ld.
+    const float* gainA; uint16_t* nxA;
+    const float* gainB; uint16_t* nxB;
+    float* ssq_out;
 };
+
+// RMSNorm outputs produced together with an embedding row (first layer's input).
+struct EmbedNorm { const float* gain; uint16_t* nx; float* ssq_out; int32_t ssq_ld; };
 
 int head_blocks_valu(int32_t N);
 int head_blocks_mfma(int32_t N);
 
 hipError_t launch_embed(const void* E, int32_t w_dtype, int32_t vocab, int32_t d, float* H, int32_t M,
-                        RowToks toks, const int32_t* slot_tok, int32_t* exit_flag_to_clear, hipStream_t st);
+                        RowToks toks, const int32_t* slot_tok, int32_t* exit_flag_to_clear, EmbedNorm en,
+                        hipStream_t st);
 hipError_t launch_rmsnorm(const float* x, const float* gain, float* out, uint16_t* out_split, int32_t ld_split,
                           int32_t M, int32_t d, float eps, hipStream_t st);
 hipError_t launch_gemv_valu(const GemvArgs& a, hipStream_t st);

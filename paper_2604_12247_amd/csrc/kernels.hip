@@ -49,23 +49,37 @@ __device__ __forceinline__ void split_store(uint16_t* xs, int ld, int m, int i, 
 
 // ---------------------------------------------------------------- embedding
 template <typename WT>
-__global__ void embed_kernel(const WT* __restrict__ E, int vocab, int d, float* __restrict__ H, RowToks toks,
-                             const int32_t* __restrict__ slot_tok, int32_t* clear_flag) {
-    int r = blockIdx.x;
+__global__ __launch_bounds__(256) void embed_kernel(const WT* __restrict__ E, int vocab, int d, float* __restrict__ H,
+                                                    RowToks toks, const int32_t* __restrict__ slot_tok,
+                                                    int32_t* clear_flag, EmbedNorm en) {
+    __shared__ float red[4];
+    int r = blockIdx.x, tid = threadIdx.x;
     int tok = toks.tok[r];
     if (tok < 0) tok = slot_tok[r];
     if (tok < 0 || tok >= vocab) tok = 0;  // never index outside the table
-    if (clear_flag && r == 0 && threadIdx.x == 0) *clear_flag = 0;
+    if (clear_flag && r == 0 && tid == 0) *clear_flag = 0;
     const WT* e = E + (size_t)tok * d;
-    for (int i = threadIdx.x; i < d; i += blockDim.x) H[(size_t)r * d + i] = ldf(e + i);
+    float ss = 0.f;
+    for (int i = tid; i < d; i += 256) {
+        float v = ldf(e + i);
+        H[(size_t)r * d + i] = v;
+        ss += v * v;
+        if (en.nx) split_store(en.nx, d, r, i, v * en.gain[i]);
+    }
+    if (en.ssq_out) {  // the row's sum of squares, as a single partial
+        ss = wave_sum(ss);
+        if ((tid & 63) == 0) red[tid >> 6] = ss;
+        __syncthreads();
+        if (tid == 0) en.ssq_out[(size_t)r * en.ssq_ld] = ((red[0] + red[1]) + red[2]) + red[3];
+    }
 }
 
 hipError_t launch_embed(const void* E, int32_t w_dtype, int32_t vocab, int32_t d, float* H, int32_t M,
-                        RowToks toks, const int32_t* slot_tok, int32_t* clear_flag, hipStream_t st) {
+                        RowToks toks, const int32_t* slot_tok, int32_t* clear_flag, EmbedNorm en, hipStream_t st) {
     if (w_dtype == SB_BF16)
-        embed_kernel<uint16_t><<<M, 256, 0, st>>>((const uint16_t*)E, vocab, d, H, toks, slot_tok, clear_flag);
+        embed_kernel<uint16_t><<<M, 256, 0, st>>>((const uint16_t*)E, vocab, d, H, toks, slot_tok, clear_flag, en);
     else
-        embed_kernel<float><<<M, 256, 0, st>>>((const float*)E, vocab, d, H, toks, slot_tok, clear_flag);
+        embed_kernel<float><<<M, 256, 0, st>>>((const float*)E, vocab, d, H, toks, slot_tok, clear_flag, en);
     return hipGetLastError();
 }
 
@@ -479,6 +493,7 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     __shared__ __attribute__((aligned(16))) float red[WPB][RT][64][4];
     __shared__ float cs[RT][16][17];
     __shared__ float zs[16 * RT][SB_MAX_W];
+    __shared__ float s_inv[SB_MAX_W];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lq = lane >> 4;
     const uint16_t* __restrict__ W = reinterpret_cast<const uint16_t*>(a.W);
@@ -524,8 +539,20 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
         }
     };
     int kb = wave;
+    if (kb < KB) load_block(wA, bA, kb);
+    // RMSNorm scale of each row from the partial sums of squares its producer left
+    // (added in index order; the first weight loads are already in flight)
+    if (a.ssq_in) {
+        for (int m = wave; m < M; m += WPB) {
+            float t = 0.f;
+            for (int b = lane; b < a.ssq_nb; b += 64) t += a.ssq_in[(size_t)m * a.ssq_ld + b];
+            t = wave_sum(t);
+            if (lane == 0) s_inv[m] = 1.0f / sqrtf(t / (float)K + a.eps);
+        }
+    } else if (tid < SB_MAX_W) {
+        s_inv[tid] = 1.0f;
+    }
     if (kb < KB) {
-        load_block(wA, bA, kb);
         while (true) {
             if (kb + WPB < KB) load_block(wB, bB, kb + WPB);
             mma_block(wA, bA);
@@ -554,11 +581,29 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
         for (int e = tid; e < RT * 16 * 8; e += NT) {
             int t = e >> 7, m = (e >> 4) & 7, i = e & 15;
             int n = n0 + t * 16 + i;
+            float sq = 0.f;
             if (m < M && n < N) {
-                float v = cs[t][i][m] + cs[t][i][m + 8];
+                float v = (cs[t][i][m] + cs[t][i][m + 8]) * s_inv[m];
                 float* yp = a.y + (size_t)m * a.ldy + n;
                 if (EPI == EPI_RESID) v += *yp;
                 *yp = v;
+                if (EPI == EPI_RESID) {
+                    if (a.nxA) split_store(a.nxA, a.ldy, m, n, v * a.gainA[n]);
+                    if (a.nxB) split_store(a.nxB, a.ldy, m, n, v * a.gainB[n]);
+                    sq = v * v;
+                }
+            }
+            if (EPI == EPI_RESID) zs[t * 16 + i][m] = sq;
+        }
+        if (EPI == EPI_RESID && a.ssq_out) {  // sum of squares of each 16-row tile, rows in index order
+            __syncthreads();
+            if (tid < RT * 8) {
+                int t = tid >> 3, m = tid & 7;
+                if (m < M && n0 + t * 16 < N) {
+                    float sum = 0.f;
+                    for (int i = 0; i < 16; ++i) sum += zs[t * 16 + i][m];
+                    a.ssq_out[(size_t)m * a.ssq_ld + blockIdx.x * RT + t] = sum;
+                }
             }
         }
     } else if (EPI == EPI_SWIGLU) {
@@ -566,8 +611,8 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
             int m = tid >> 4, i = tid & 15;
             int n = n0 + i;
             if (m < M && n < N) {
-                float g = cs[0][i][m] + cs[0][i][m + 8];
-                float u = cs[1][i][m] + cs[1][i][m + 8];
+                float g = (cs[0][i][m] + cs[0][i][m + 8]) * s_inv[m];
+                float u = (cs[1][i][m] + cs[1][i][m + 8]) * s_inv[m];
                 float v = silu_mul(g, u);
                 if (a.y) a.y[(size_t)m * a.ldy + n] = v;
                 if (a.ys) split_store(a.ys, a.ldy, m, n, v);
@@ -576,7 +621,7 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     } else {  // EPI_HEAD
         for (int e = tid; e < RT * 16 * 8; e += NT) {
             int t = e >> 7, m = (e >> 4) & 7, i = e & 15;
-            zs[t * 16 + i][m] = cs[t][i][m] + cs[t][i][m + 8];
+            zs[t * 16 + i][m] = (cs[t][i][m] + cs[t][i][m + 8]) * (m < M ? s_inv[m] : 0.f);
         }
         __syncthreads();
         head_partial<16 * RT>(a.head, zs, M, n0, N, gridDim.x);

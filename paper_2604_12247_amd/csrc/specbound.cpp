@@ -70,9 +70,9 @@ int resolve_proj(const sb_config* c) {
 }
 
 struct WsLayout {
-    size_t H, xn, xs, qkv, att, atts, u, us, attn_part, head_part, logits_exit, logits_final, round,
-        table, total;
-    int max_chunks, head_blocks, n_pages;
+    size_t H, xn, xs_attn, xs_ffn, xs_exit, ssq_attn, ssq_ffn, qkv, att, atts, u, us, attn_part, head_part,
+        logits_exit, logits_final, round, table, total;
+    int max_chunks, head_blocks, n_pages, ssq_ld;
 };
 
 WsLayout ws_layout(const sb_config* c) {
@@ -88,7 +88,14 @@ WsLayout ws_layout(const sb_config* c) {
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     L.H = take(SB_MAX_W * d * 4);
     L.xn = take(SB_MAX_W * d * 4);
-    L.xs = take(16 * d * 2);
+    // slot-indexed inputs of the MFMA projections: bf16 parts of gain * h, and the
+    // partial sums of squares that give the RMSNorm scale
+    L.ssq_ld = (int)((d + 15) / 16);
+    L.xs_attn = take(16 * d * 2);
+    L.xs_ffn = take(16 * d * 2);
+    L.xs_exit = take(16 * d * 2);
+    L.ssq_attn = take((size_t)SB_MAX_W * L.ssq_ld * 4);
+    L.ssq_ffn = take((size_t)SB_MAX_W * L.ssq_ld * 4);
     L.qkv = take(SB_MAX_W * qkv_rows * 4);
     L.att = take(SB_MAX_W * hq * 4);
     L.atts = take(16 * hq * 2);
@@ -208,7 +215,11 @@ int gemv(sb_session* s, GemvArgs& a, int cls) {
 // One decoder layer (0-based l) on rows slot0..slot0+M-1, whose positions are
 // c+slot0.. : RMSNorm -> QKV -> attention (with RoPE + KV append) -> W_o (+residual)
 // -> RMSNorm -> gate/up + SwiGLU -> W_down (+residual).
-int run_layer(sb_session* s, int l, int slot0, int M) {
+// On the MFMA path the two RMSNorms are folded into the projections: whoever
+// writes a hidden row (embedding, W_o, W_down) also leaves gain * h in bf16 parts
+// and the partial sums of squares, per slot, for the projection that reads it
+// next.  head_gain (nullable) asks W_down to do the same for the head that follows.
+int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
     sb_model* m = s->m;
     const sb_config& c = m->cfg;
     const bool mf = m->proj == SB_PROJ_MFMA;
@@ -219,22 +230,28 @@ int run_layer(sb_session* s, int l, int slot0, int M) {
     if (pos0 + M > c.max_seq) return fail(SB_ECAPACITY, "KV capacity exceeded");
     float* H = wsp<float>(s, s->L.H) + (size_t)slot0 * d;
     float* xn = wsp<float>(s, s->L.xn);
-    uint16_t* xs = wsp<uint16_t>(s, s->L.xs);
+    uint16_t* xs_attn = wsp<uint16_t>(s, s->L.xs_attn) + (size_t)slot0 * d;
+    uint16_t* xs_ffn = wsp<uint16_t>(s, s->L.xs_ffn) + (size_t)slot0 * d;
+    uint16_t* xs_exit = wsp<uint16_t>(s, s->L.xs_exit) + (size_t)slot0 * d;
+    float* ssq_attn = wsp<float>(s, s->L.ssq_attn) + (size_t)slot0 * s->L.ssq_ld;
+    float* ssq_ffn = wsp<float>(s, s->L.ssq_ffn) + (size_t)slot0 * s->L.ssq_ld;
     float* qkv = wsp<float>(s, s->L.qkv);
     float* att = wsp<float>(s, s->L.att);
     uint16_t* atts = wsp<uint16_t>(s, s->L.atts);
     float* u = wsp<float>(s, s->L.u);
     uint16_t* us = wsp<uint16_t>(s, s->L.us);
+    int rc;
 
-    {
+    if (!mf) {
         ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * d * 8);
-        HIP_TRY(launch_rmsnorm(H, m->attn_norm[l], mf ? nullptr : xn, mf ? xs : nullptr, d, M, d, c.rms_eps, st));
+        HIP_TRY(launch_rmsnorm(H, m->attn_norm[l], xn, nullptr, d, M, d, c.rms_eps, st));
     }
     GemvArgs g{};
-    g.w_dtype = c.weight_dtype; g.M = M;
-    g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = d; g.x = xn; g.xs = xs; g.y = qkv; g.ldy = qkv_rows; g.epi = EPI_STORE;
-    int rc = gemv(s, g, SB_K_QKV);
-    if (rc) return rc;
+    g.w_dtype = c.weight_dtype; g.M = M; g.eps = c.rms_eps; g.ssq_ld = s->L.ssq_ld;
+    g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = d; g.x = xn; g.xs = xs_attn; g.y = qkv; g.ldy = qkv_rows; g.epi = EPI_STORE;
+    if (mf) { g.ssq_in = ssq_attn; g.ssq_nb = l == 0 ? 1 : d / 16; }  // layer 0 reads what the embedding left
+    if ((rc = gemv(s, g, SB_K_QKV))) return rc;
+
     AttnArgs a{};
     a.q = qkv; a.rope_cos = m->rope_cos; a.rope_sin = m->rope_sin; a.qkv_rows = qkv_rows; a.n_heads = c.n_heads;
     a.kv = s->kv; a.layer = l; a.pos0 = pos0; a.M = M;
@@ -245,16 +262,29 @@ int run_layer(sb_session* s, int l, int slot0, int M) {
         ProfScope ps(s, SB_K_ATTN, kv_read);
         HIP_TRY(launch_attention(a, st));
     }
+
+    g.ssq_in = nullptr;
     g.W = m->w_o[l]; g.N = d; g.K = hq; g.x = att; g.xs = atts; g.y = H; g.ldy = d; g.epi = EPI_RESID;
+    if (mf) { g.gainA = m->ffn_norm[l]; g.nxA = xs_ffn; g.ssq_out = ssq_ffn; }
     if ((rc = gemv(s, g, SB_K_WO))) return rc;
-    {
+    g.gainA = nullptr; g.nxA = nullptr; g.ssq_out = nullptr;
+
+    if (!mf) {
         ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * d * 8);
-        HIP_TRY(launch_rmsnorm(H, m->ffn_norm[l], mf ? nullptr : xn, mf ? xs : nullptr, d, M, d, c.rms_eps, st));
+        HIP_TRY(launch_rmsnorm(H, m->ffn_norm[l], xn, nullptr, d, M, d, c.rms_eps, st));
     }
-    g.W = m->w_gate_up[l]; g.N = f; g.K = d; g.x = xn; g.xs = xs; g.y = mf ? nullptr : u; g.ys = mf ? us : nullptr;
+    g.W = m->w_gate_up[l]; g.N = f; g.K = d; g.x = xn; g.xs = xs_ffn; g.y = mf ? nullptr : u; g.ys = mf ? us : nullptr;
     g.ldy = f; g.epi = EPI_SWIGLU;
+    if (mf) { g.ssq_in = ssq_ffn; g.ssq_nb = d / 16; }
     if ((rc = gemv(s, g, SB_K_GATEUP))) return rc;
+    g.ssq_in = nullptr;
+
     g.W = m->w_down[l]; g.N = d; g.K = f; g.x = u; g.xs = us; g.y = H; g.ys = nullptr; g.ldy = d; g.epi = EPI_RESID;
+    if (mf) {
+        if (l + 1 < c.n_layers) { g.gainA = m->attn_norm[l + 1]; g.nxA = xs_attn; }
+        if (head_gain) { g.gainB = head_gain; g.nxB = xs_exit; }
+        g.ssq_out = ssq_attn;
+    }
     if ((rc = gemv(s, g, SB_K_DOWN))) return rc;
 
     s->st.layer_sweeps += 1;
@@ -264,27 +294,45 @@ int run_layer(sb_session* s, int l, int slot0, int M) {
     return SB_OK;
 }
 
-// RMSNorm + head projection + arg max / confidence for M rows starting at `rows`.
-int run_head(sb_session* s, const void* W, const float* gain, const float* rows, int M, HeadArgs h) {
+// Head projection + arg max / confidence for the M rows starting at slot `slot0`.
+// VALU path: RMSNorm kernel first.  MFMA path: the last W_down already left
+// gain * h and the sums of squares for these slots (run_layer's head_gain).
+int run_head(sb_session* s, const void* W, const float* gain, int slot0, int M, HeadArgs h) {
     sb_model* m = s->m;
     const sb_config& c = m->cfg;
     const bool mf = m->proj == SB_PROJ_MFMA;
     float* xn = wsp<float>(s, s->L.xn);
-    uint16_t* xs = wsp<uint16_t>(s, s->L.xs);
-    {
+    const float* rows = wsp<float>(s, s->L.H) + (size_t)slot0 * c.d_model;
+    if (!mf) {
         ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * c.d_model * 8);
-        HIP_TRY(launch_rmsnorm(rows, gain, mf ? nullptr : xn, mf ? xs : nullptr, c.d_model, M, c.d_model, c.rms_eps,
-                               m->stream));
+        HIP_TRY(launch_rmsnorm(rows, gain, xn, nullptr, c.d_model, M, c.d_model, c.rms_eps, m->stream));
     }
     h.partials = wsp<float>(s, s->L.head_part);
     h.round = s->d_round;
     GemvArgs g{};
-    g.W = W; g.w_dtype = c.weight_dtype; g.N = c.vocab; g.K = c.d_model; g.x = xn; g.xs = xs; g.M = M;
+    g.W = W; g.w_dtype = c.weight_dtype; g.N = c.vocab; g.K = c.d_model; g.x = xn; g.M = M;
+    g.xs = wsp<uint16_t>(s, s->L.xs_exit) + (size_t)slot0 * c.d_model;
+    if (mf) {
+        g.ssq_in = wsp<float>(s, s->L.ssq_attn) + (size_t)slot0 * s->L.ssq_ld;
+        g.ssq_nb = c.d_model / 16; g.ssq_ld = s->L.ssq_ld; g.eps = c.rms_eps;
+    }
     g.epi = EPI_HEAD; g.head = h;
     int rc = gemv(s, g, h.post == POST_EXIT ? SB_K_EXIT_HEAD : SB_K_FINAL_HEAD);
     if (rc) return rc;
     s->st.weight_bytes += m->head_bytes;
     return SB_OK;
+}
+
+// What the embedding kernel leaves for layer 0's QKV projection (MFMA path).
+EmbedNorm embed_norm(sb_session* s, int slot0) {
+    EmbedNorm en{nullptr, nullptr, nullptr, 0};
+    if (s->m->proj == SB_PROJ_MFMA) {
+        en.gain = s->m->attn_norm[0];
+        en.nx = wsp<uint16_t>(s, s->L.xs_attn) + (size_t)slot0 * s->m->cfg.d_model;
+        en.ssq_out = wsp<float>(s, s->L.ssq_attn) + (size_t)slot0 * s->L.ssq_ld;
+        en.ssq_ld = s->L.ssq_ld;
+    }
+    return en;
 }
 
 void reset_session(sb_session* s) {
@@ -309,9 +357,10 @@ int prefill_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first
         RowToks t;
         for (int r = 0; r < SB_MAX_W; ++r) t.tok[r] = r < M ? prompt[i0 + r] : 0;
         HIP_TRY(launch_embed(m->embed, c.weight_dtype, c.vocab, c.d_model, H, M, t, s->d_round->slot_tok, nullptr,
-                             m->stream));
+                             embed_norm(s, 0), m->stream));
+        const bool last_chunk = i0 + M >= n;
         for (int l = 0; l < c.n_layers; ++l) {
-            int rc = run_layer(s, l, 0, M);
+            int rc = run_layer(s, l, 0, M, (last_chunk && l == c.n_layers - 1) ? m->final_norm : nullptr);
             if (rc) return rc;
         }
         s->c += M;
@@ -321,7 +370,7 @@ int prefill_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first
     h.T = 1.0f; h.post = POST_NONE;
     h.argmax_out = s->d_round->g; h.conf_out = s->d_round->gconf;
     h.logits = s->debug ? wsp<float>(s, s->L.logits_final) : nullptr;
-    int rc = run_head(s, m->lm_head, m->final_norm, H + (size_t)(last_rows - 1) * c.d_model, 1, h);
+    int rc = run_head(s, m->lm_head, m->final_norm, last_rows - 1, 1, h);
     if (rc) return rc;
     s->st.final_head_sweeps++;
     if ((rc = readback(s))) return rc;
@@ -358,7 +407,7 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
     t.tok[0] = idx == 0 ? s->pending : s->draft_host[idx - 1];  // -1: the id is on the device only
     float* Hrow = wsp<float>(s, s->L.H) + (size_t)idx * c.d_model;
     HIP_TRY(launch_embed(m->embed, c.weight_dtype, c.vocab, c.d_model, Hrow, 1, t, s->d_round->slot_tok + idx,
-                         &s->d_round->exit_flag, m->stream));
+                         &s->d_round->exit_flag, embed_norm(s, idx), m->stream));
     s->draft_counter++;
     s->st.draft_steps++;
     s->n_slots++;
@@ -370,13 +419,13 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
     for (int l = 1; l <= p->d_max; ++l) {
         int j0 = idx;
         while (j0 > 0 && s->reached[j0 - 1] == l - 1) --j0;
-        if ((rc = run_layer(s, l - 1, j0, idx - j0 + 1))) return rc;
+        if ((rc = run_layer(s, l - 1, j0, idx - j0 + 1, m->exit_norm[l - 1]))) return rc;
         for (int j = j0; j <= idx; ++j) s->reached[j] = l;
         HeadArgs h{};
         h.T = p->T[l - 1]; h.post = POST_EXIT; h.slot = idx; h.layer = l; h.forced_exit = forced; h.forced_draft = over;
         h.threshold = p->threshold;
         h.logits = s->debug ? wsp<float>(s, s->L.logits_exit) + (size_t)(l - 1) * c.vocab : nullptr;
-        if ((rc = run_head(s, m->exit_head[l - 1], m->exit_norm[l - 1], Hrow, 1, h))) return rc;
+        if ((rc = run_head(s, m->exit_head[l - 1], m->exit_norm[l - 1], idx, 1, h))) return rc;
         s->st.head_evals++;
         if (computed) {
             if ((rc = readback(s))) return rc;
@@ -423,18 +472,18 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
         int j0 = M;
         while (j0 > 0 && s->reached[j0 - 1] == l - 1) --j0;
         if (j0 == M) continue;
-        if ((rc = run_layer(s, l - 1, j0, M - j0))) return rc;
+        if ((rc = run_layer(s, l - 1, j0, M - j0, nullptr))) return rc;
         for (int j = j0; j < M; ++j) s->reached[j] = l;
     }
     // one parallel pass of all rows through the remaining layers
     for (int l = D + 1; l <= c.n_layers; ++l) {
-        if ((rc = run_layer(s, l - 1, 0, M))) return rc;
+        if ((rc = run_layer(s, l - 1, 0, M, l == c.n_layers ? m->final_norm : nullptr))) return rc;
         for (int j = 0; j < M; ++j) s->reached[j] = l;
     }
     HeadArgs h{};
     h.T = 1.0f; h.post = POST_ACCEPT; h.n_drafts = s->n_drafts;
     h.logits = s->debug ? wsp<float>(s, s->L.logits_final) : nullptr;
-    if ((rc = run_head(s, m->lm_head, m->final_norm, wsp<float>(s, s->L.H), M, h))) return rc;
+    if ((rc = run_head(s, m->lm_head, m->final_norm, 0, M, h))) return rc;
     s->st.final_head_sweeps++;
     if ((rc = readback(s))) return rc;
     s->final_logits_valid = s->debug;
