@@ -147,6 +147,13 @@ struct sb_session {
     bool debug;
     bool final_logits_valid;
     sb_stats st;
+    // Exit heads run on a second stream next to the following layer when the exit
+    // layer is known in advance (forced schedules): events order the two streams.
+    hipStream_t head_stream;
+    hipEvent_t ev_main[4], ev_head[4];
+    unsigned ev_i;
+    bool head_pending;      // ev_head[(ev_i - 1) % 4] not yet waited for by the main stream
+    int head_pending_ev;
     // per-kernel event timing
     uint32_t prof_mask;
     int prof_every;                    // time every n-th launch of a class
@@ -175,7 +182,11 @@ int check_params(const sb_session* s, const sb_params* p) {
     return SB_OK;
 }
 
+int join_head(sb_session* s);
+
 int readback(sb_session* s) {
+    int jrc = join_head(s);
+    if (jrc) return jrc;
     HIP_TRY(hipMemcpyAsync(s->h_round, s->d_round, sizeof(DevRound), hipMemcpyDeviceToHost, s->m->stream));
     HIP_TRY(hipStreamSynchronize(s->m->stream));
     return SB_OK;
@@ -184,19 +195,28 @@ int readback(sb_session* s) {
 // Event pair around the launches of one kernel class, when that class is timed.
 struct ProfScope {
     sb_session* s;
+    hipStream_t st;
     long idx;
-    ProfScope(sb_session* s_, int cls, int64_t bytes) : s(s_), idx(-1) {
+    ProfScope(sb_session* s_, int cls, int64_t bytes, hipStream_t st_) : s(s_), st(st_), idx(-1) {
         if (!(s->prof_mask & (1u << cls)) || s->prof_used * 2 + 2 > s->prof_ev.size()) return;
         if (s->prof_seen[cls]++ % s->prof_every) return;
         idx = (long)s->prof_used++;
         s->prof_cls[idx] = cls;
         s->prof_bytes[idx] = bytes;
-        (void)hipEventRecord(s->prof_ev[2 * idx], s->m->stream);
+        (void)hipEventRecord(s->prof_ev[2 * idx], st);
     }
     ~ProfScope() {
-        if (idx >= 0) (void)hipEventRecord(s->prof_ev[2 * idx + 1], s->m->stream);
+        if (idx >= 0) (void)hipEventRecord(s->prof_ev[2 * idx + 1], st);
     }
 };
+
+// Main stream waits for the exit head that is still running on the head stream.
+int join_head(sb_session* s) {
+    if (!s->head_pending) return SB_OK;
+    HIP_TRY(hipStreamWaitEvent(s->m->stream, s->ev_head[s->head_pending_ev], 0));
+    s->head_pending = false;
+    return SB_OK;
+}
 
 int64_t gemv_bytes(const GemvArgs& a) {
     const int64_t rows = a.epi == EPI_SWIGLU ? 2 * (int64_t)a.N : a.N;
@@ -204,9 +224,9 @@ int64_t gemv_bytes(const GemvArgs& a) {
     return rows * a.K * (int64_t)esize(a.w_dtype) + (int64_t)a.M * a.K * 4 + out;
 }
 
-int gemv(sb_session* s, GemvArgs& a, int cls) {
-    ProfScope ps(s, cls, gemv_bytes(a));
-    hipError_t e = s->m->proj == SB_PROJ_MFMA ? launch_gemv_mfma(a, s->m->stream) : launch_gemv_valu(a, s->m->stream);
+int gemv(sb_session* s, GemvArgs& a, int cls, hipStream_t st) {
+    ProfScope ps(s, cls, gemv_bytes(a), st);
+    hipError_t e = s->m->proj == SB_PROJ_MFMA ? launch_gemv_mfma(a, st) : launch_gemv_valu(a, st);
     if (e != hipSuccess) return fail(SB_EDEVICE, "projection launch (N=%d K=%d M=%d epi=%d): %s", a.N, a.K, a.M, a.epi,
                                      hipGetErrorString(e));
     return SB_OK;
@@ -243,14 +263,14 @@ int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
     int rc;
 
     if (!mf) {
-        ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * d * 8);
+        ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * d * 8, st);
         HIP_TRY(launch_rmsnorm(H, m->attn_norm[l], xn, nullptr, d, M, d, c.rms_eps, st));
     }
     GemvArgs g{};
     g.w_dtype = c.weight_dtype; g.M = M; g.eps = c.rms_eps; g.ssq_ld = s->L.ssq_ld;
     g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = d; g.x = xn; g.xs = xs_attn; g.y = qkv; g.ldy = qkv_rows; g.epi = EPI_STORE;
     if (mf) { g.ssq_in = ssq_attn; g.ssq_nb = l == 0 ? 1 : d / 16; }  // layer 0 reads what the embedding left
-    if ((rc = gemv(s, g, SB_K_QKV))) return rc;
+    if ((rc = gemv(s, g, SB_K_QKV, st))) return rc;
 
     AttnArgs a{};
     a.q = qkv; a.rope_cos = m->rope_cos; a.rope_sin = m->rope_sin; a.qkv_rows = qkv_rows; a.n_heads = c.n_heads;
@@ -259,24 +279,24 @@ int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
     a.out = mf ? nullptr : att; a.out_split = mf ? atts : nullptr;
     const int64_t kv_read = (int64_t)(pos0 + M) * 2 * c.n_kv_heads * c.head_dim * (int64_t)esize(c.kv_dtype);
     {
-        ProfScope ps(s, SB_K_ATTN, kv_read);
+        ProfScope ps(s, SB_K_ATTN, kv_read, st);
         HIP_TRY(launch_attention(a, st));
     }
 
     g.ssq_in = nullptr;
     g.W = m->w_o[l]; g.N = d; g.K = hq; g.x = att; g.xs = atts; g.y = H; g.ldy = d; g.epi = EPI_RESID;
     if (mf) { g.gainA = m->ffn_norm[l]; g.nxA = xs_ffn; g.ssq_out = ssq_ffn; }
-    if ((rc = gemv(s, g, SB_K_WO))) return rc;
+    if ((rc = gemv(s, g, SB_K_WO, st))) return rc;
     g.gainA = nullptr; g.nxA = nullptr; g.ssq_out = nullptr;
 
     if (!mf) {
-        ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * d * 8);
+        ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * d * 8, st);
         HIP_TRY(launch_rmsnorm(H, m->ffn_norm[l], xn, nullptr, d, M, d, c.rms_eps, st));
     }
     g.W = m->w_gate_up[l]; g.N = f; g.K = d; g.x = xn; g.xs = xs_ffn; g.y = mf ? nullptr : u; g.ys = mf ? us : nullptr;
     g.ldy = f; g.epi = EPI_SWIGLU;
     if (mf) { g.ssq_in = ssq_ffn; g.ssq_nb = d / 16; }
-    if ((rc = gemv(s, g, SB_K_GATEUP))) return rc;
+    if ((rc = gemv(s, g, SB_K_GATEUP, st))) return rc;
     g.ssq_in = nullptr;
 
     g.W = m->w_down[l]; g.N = d; g.K = f; g.x = u; g.xs = us; g.y = H; g.ys = nullptr; g.ldy = d; g.epi = EPI_RESID;
@@ -285,7 +305,9 @@ int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
         if (head_gain) { g.gainB = head_gain; g.nxB = xs_exit; }
         g.ssq_out = ssq_attn;
     }
-    if ((rc = gemv(s, g, SB_K_DOWN))) return rc;
+    // W_down overwrites what a still-running exit head reads (its slot's parts and sums of squares)
+    if ((rc = join_head(s))) return rc;
+    if ((rc = gemv(s, g, SB_K_DOWN, st))) return rc;
 
     s->st.layer_sweeps += 1;
     s->st.row_layers += M;
@@ -297,15 +319,15 @@ int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
 // Head projection + arg max / confidence for the M rows starting at slot `slot0`.
 // VALU path: RMSNorm kernel first.  MFMA path: the last W_down already left
 // gain * h and the sums of squares for these slots (run_layer's head_gain).
-int run_head(sb_session* s, const void* W, const float* gain, int slot0, int M, HeadArgs h) {
+int run_head(sb_session* s, const void* W, const float* gain, int slot0, int M, HeadArgs h, hipStream_t st) {
     sb_model* m = s->m;
     const sb_config& c = m->cfg;
     const bool mf = m->proj == SB_PROJ_MFMA;
     float* xn = wsp<float>(s, s->L.xn);
     const float* rows = wsp<float>(s, s->L.H) + (size_t)slot0 * c.d_model;
     if (!mf) {
-        ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * c.d_model * 8);
-        HIP_TRY(launch_rmsnorm(rows, gain, xn, nullptr, c.d_model, M, c.d_model, c.rms_eps, m->stream));
+        ProfScope ps(s, SB_K_RMSNORM, (int64_t)M * c.d_model * 8, st);
+        HIP_TRY(launch_rmsnorm(rows, gain, xn, nullptr, c.d_model, M, c.d_model, c.rms_eps, st));
     }
     h.partials = wsp<float>(s, s->L.head_part);
     h.round = s->d_round;
@@ -317,7 +339,7 @@ int run_head(sb_session* s, const void* W, const float* gain, int slot0, int M, 
         g.ssq_nb = c.d_model / 16; g.ssq_ld = s->L.ssq_ld; g.eps = c.rms_eps;
     }
     g.epi = EPI_HEAD; g.head = h;
-    int rc = gemv(s, g, h.post == POST_EXIT ? SB_K_EXIT_HEAD : SB_K_FINAL_HEAD);
+    int rc = gemv(s, g, h.post == POST_EXIT ? SB_K_EXIT_HEAD : SB_K_FINAL_HEAD, st);
     if (rc) return rc;
     s->st.weight_bytes += m->head_bytes;
     return SB_OK;
@@ -349,6 +371,10 @@ int prefill_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first
     if (n > c.max_seq) return fail(SB_ECAPACITY, "prefill: prompt of %d tokens exceeds max_seq %d", n, c.max_seq);
     for (int i = 0; i < n; ++i)
         if (prompt[i] < 0 || prompt[i] >= c.vocab) return fail(SB_EINVAL, "prefill: token id %d out of range", prompt[i]);
+    {
+        int jrc = join_head(s);
+        if (jrc) return jrc;
+    }
     reset_session(s);
     float* H = wsp<float>(s, s->L.H);
     int last_rows = 0;
@@ -370,7 +396,7 @@ int prefill_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first
     h.T = 1.0f; h.post = POST_NONE;
     h.argmax_out = s->d_round->g; h.conf_out = s->d_round->gconf;
     h.logits = s->debug ? wsp<float>(s, s->L.logits_final) : nullptr;
-    int rc = run_head(s, m->lm_head, m->final_norm, last_rows - 1, 1, h);
+    int rc = run_head(s, m->lm_head, m->final_norm, last_rows - 1, 1, h, m->stream);
     if (rc) return rc;
     s->st.final_head_sweeps++;
     if ((rc = readback(s))) return rc;
@@ -401,6 +427,9 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
     if (over < -1) over = -1;
     const bool computed = forced < 0;
 
+    // the previous step's last exit head wrote the token this step embeds
+    if ((rc = join_head(s))) return rc;
+    const bool overlap = !computed && m->proj == SB_PROJ_MFMA && s->head_stream;
     const int idx = s->n_slots;
     RowToks t;
     for (int r = 0; r < SB_MAX_W; ++r) t.tok[r] = 0;
@@ -425,7 +454,18 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
         h.T = p->T[l - 1]; h.post = POST_EXIT; h.slot = idx; h.layer = l; h.forced_exit = forced; h.forced_draft = over;
         h.threshold = p->threshold;
         h.logits = s->debug ? wsp<float>(s, s->L.logits_exit) + (size_t)(l - 1) * c.vocab : nullptr;
-        if ((rc = run_head(s, m->exit_head[l - 1], m->exit_norm[l - 1], idx, 1, h))) return rc;
+        if (overlap) {
+            // the head only reads what W_down left for it: let it run beside the next layer
+            const unsigned e = s->ev_i++ & 3;
+            HIP_TRY(hipEventRecord(s->ev_main[e], m->stream));
+            HIP_TRY(hipStreamWaitEvent(s->head_stream, s->ev_main[e], 0));
+            if ((rc = run_head(s, m->exit_head[l - 1], m->exit_norm[l - 1], idx, 1, h, s->head_stream))) return rc;
+            HIP_TRY(hipEventRecord(s->ev_head[e], s->head_stream));
+            s->head_pending = true;
+            s->head_pending_ev = (int)e;
+        } else {
+            if ((rc = run_head(s, m->exit_head[l - 1], m->exit_norm[l - 1], idx, 1, h, m->stream))) return rc;
+        }
         s->st.head_evals++;
         if (computed) {
             if ((rc = readback(s))) return rc;
@@ -464,6 +504,7 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     if (s->n_slots == 0) return fail(SB_ESTATE, "verify: no open row");
     sb_model* m = s->m;
     const sb_config& c = m->cfg;
+    if ((rc = join_head(s))) return rc;
     const int M = s->n_slots, D = s->reached[0];
     for (int j = 1; j < M; ++j)
         if (s->reached[j] > s->reached[j - 1]) return fail(SB_ESTATE, "verify: reached layers not monotone");
@@ -483,7 +524,8 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     HeadArgs h{};
     h.T = 1.0f; h.post = POST_ACCEPT; h.n_drafts = s->n_drafts;
     h.logits = s->debug ? wsp<float>(s, s->L.logits_final) : nullptr;
-    if ((rc = run_head(s, m->lm_head, m->final_norm, 0, M, h))) return rc;
+    if ((rc = join_head(s))) return rc;
+    if ((rc = run_head(s, m->lm_head, m->final_norm, 0, M, h, m->stream))) return rc;
     s->st.final_head_sweeps++;
     if ((rc = readback(s))) return rc;
     s->final_logits_valid = s->debug;
@@ -500,6 +542,24 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     s->st.rounds++; s->st.emitted += R.n_emit; s->st.accept_hist[R.n_emit]++;
     if (out) *out = res;
     return SB_OK;
+}
+
+hipError_t sync_all(sb_session* s) {
+    hipError_t e = hipStreamSynchronize(s->m->stream);
+    if (e == hipSuccess && s->head_stream) e = hipStreamSynchronize(s->head_stream);
+    s->head_pending = false;
+    return e;
+}
+
+void free_session_resources(sb_session* s) {
+    if (s->h_round) (void)hipHostFree(s->h_round);
+    for (int i = 0; i < 4; ++i) {
+        if (s->ev_main[i]) (void)hipEventDestroy(s->ev_main[i]);
+        if (s->ev_head[i]) (void)hipEventDestroy(s->ev_head[i]);
+    }
+    if (s->head_stream) (void)hipStreamDestroy(s->head_stream);
+    for (hipEvent_t x : s->prof_ev) (void)hipEventDestroy(x);
+    s->prof_ev.clear();
 }
 
 double now_ms() {
@@ -652,14 +712,24 @@ int32_t sb_new_session(sb_model* m, void* kv_pool, size_t kv_bytes, void* worksp
     s->prof_mask = 0;
     s->prof_used = 0;
     s->prof_every = 1;
+    s->head_stream = nullptr;
+    s->ev_i = 0;
+    s->head_pending = false;
+    s->head_pending_ev = 0;
+    for (int i = 0; i < 4; ++i) { s->ev_main[i] = nullptr; s->ev_head[i] = nullptr; }
     s->h_round = nullptr;
     reset_session(s);
     hipError_t e = hipHostMalloc((void**)&s->h_round, sizeof(DevRound), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&s->head_stream, hipStreamNonBlocking);  // default priority
+    for (int i = 0; i < 4 && e == hipSuccess; ++i) {
+        e = hipEventCreateWithFlags(&s->ev_main[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_head[i], hipEventDisableTiming);
+    }
     if (e == hipSuccess) e = hipMemcpyAsync(wsp<int32_t>(s, L.table), table.data(), (size_t)L.n_pages * 4, hipMemcpyHostToDevice, m->stream);
     if (e == hipSuccess) e = launch_fill_u32(reinterpret_cast<uint32_t*>(s->d_round), sizeof(DevRound) / 4, 0u, m->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
     if (e != hipSuccess) {
-        if (s->h_round) (void)hipHostFree(s->h_round);
+        free_session_resources(s);
         delete s;
         return fail(SB_EDEVICE, "new_session: %s", hipGetErrorString(e));
     }
@@ -670,9 +740,8 @@ int32_t sb_new_session(sb_model* m, void* kv_pool, size_t kv_bytes, void* worksp
 
 void sb_free_session(sb_session* s) {
     if (!s) return;
-    (void)hipStreamSynchronize(s->m->stream);
-    if (s->h_round) (void)hipHostFree(s->h_round);
-    for (hipEvent_t x : s->prof_ev) (void)hipEventDestroy(x);
+    (void)sync_all(s);
+    free_session_resources(s);
     delete s;
 }
 
@@ -736,7 +805,7 @@ int32_t sb_rewind(sb_session* s, int32_t n_keep, int32_t pending_token, int64_t 
     if (n_keep < 1 || n_keep > s->c) return fail(SB_EINVAL, "rewind: n_keep must be in 1..%d", s->c);
     if (pending_token < 0 || pending_token >= s->m->cfg.vocab) return fail(SB_EINVAL, "rewind: token id out of range");
     if (draft_counter < 0) return fail(SB_EINVAL, "rewind: draft_counter < 0");
-    HIP_TRY(hipStreamSynchronize(s->m->stream));
+    HIP_TRY(sync_all(s));
     reset_session(s);
     s->c = n_keep;
     s->pending = pending_token;
@@ -773,7 +842,7 @@ int32_t sb_profile_end(sb_session* s, int64_t* launches, double* total_ms, int64
     if (!s || !launches || !total_ms || !bytes) return fail(SB_EINVAL, "profile_end: NULL argument");
     if (s->prof_ev.empty()) return fail(SB_ESTATE, "profile_end: timing is not running");
     s->prof_mask = 0;
-    hipError_t e = hipStreamSynchronize(s->m->stream);
+    hipError_t e = sync_all(s);
     for (int k = 0; k < SB_K_COUNT; ++k) { launches[k] = 0; total_ms[k] = 0.0; bytes[k] = 0; }
     for (size_t i = 0; i < s->prof_used && e == hipSuccess; ++i) {
         float ms = 0.f;
@@ -816,7 +885,7 @@ int32_t sb_debug_logits(sb_session* s, int32_t layer, int32_t row, float* out, i
         if (layer < 1 || layer > c.n_exit_heads) return fail(SB_EINVAL, "debug_logits: layer out of range");
         src = wsp<float>(s, s->L.logits_exit) + (size_t)(layer - 1) * c.vocab;
     }
-    HIP_TRY(hipStreamSynchronize(s->m->stream));
+    HIP_TRY(sync_all(s));
     HIP_TRY(hipMemcpy(out, src, (size_t)c.vocab * 4, hipMemcpyDeviceToHost));
     return SB_OK;
 }
@@ -825,7 +894,7 @@ int32_t sb_debug_hidden(sb_session* s, int32_t slot, float* out, int32_t cap) {
     if (!s || !out) return fail(SB_EINVAL, "debug_hidden: NULL argument");
     const sb_config& c = s->m->cfg;
     if (slot < 0 || slot >= SB_MAX_W || cap < c.d_model) return fail(SB_EINVAL, "debug_hidden: bad slot / cap");
-    HIP_TRY(hipStreamSynchronize(s->m->stream));
+    HIP_TRY(sync_all(s));
     HIP_TRY(hipMemcpy(out, wsp<float>(s, s->L.H) + (size_t)slot * c.d_model, (size_t)c.d_model * 4, hipMemcpyDeviceToHost));
     return SB_OK;
 }
@@ -835,7 +904,7 @@ int32_t sb_debug_kv(sb_session* s, int32_t layer, int32_t pos, float* k_out, flo
     const sb_config& c = s->m->cfg;
     const int w = c.n_kv_heads * c.head_dim;
     if (layer < 0 || layer >= c.n_layers || pos < 0 || pos >= c.max_seq || cap < w) return fail(SB_EINVAL, "debug_kv: out of range");
-    HIP_TRY(hipStreamSynchronize(s->m->stream));
+    HIP_TRY(sync_all(s));
     std::vector<int32_t> table(s->L.n_pages);
     HIP_TRY(hipMemcpy(table.data(), s->kv.table, table.size() * 4, hipMemcpyDeviceToHost));
     const size_t es = esize(c.kv_dtype);
