@@ -17,6 +17,10 @@ import time
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes fetched per launch of the gate/up projection at the C2 shape, from
+# rocprofv3 --pmc FETCH_SIZE scaled by the same counter's reading on the plain copy
+# kernel (2.000 KiB per count); summary in profiles/c2_projection_hbm_traffic.txt
+MEASURED_TRAFFIC = {"C2": 88849.6 * 2.0 * 1024}
 
 
 def log(*a):
@@ -33,6 +37,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-table", action="store_true")
     ap.add_argument("--proj", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run the plain copy kernel on 1 GiB (a yardstick of known traffic for "
+                         "calibrating profiler counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (the decode path is one sequence at batch 1); "
@@ -44,6 +51,9 @@ def main():
     import sb_inputs as si
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.copy_probe:
+        copy_probe(torch, sb)
+        return
     wl = si.CONFIGS[args.config]
     shape = wl.shape
     gen_len = args.gen or wl.gen_len
@@ -118,7 +128,10 @@ def main():
     gu_bytes = gu["bytes"] / gu["launches"]
     roofline = {"bound": "hbm", "kernel": "gate_up projection + SwiGLU (gemv_mfma_kernel<2,SWIGLU>)",
                 "achieved": round(gu_bytes / gu_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(gu_bytes / gu_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(gu_bytes / gu_us / 1e3 / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC.get(args.config) if not args.gen else None,
+                "traffic_note": "HBM read bytes per launch (FETCH_SIZE, calibrated on a copy kernel); "
+                                "the kernel writes < 0.4 MB",
                 "bytes_per_launch": int(gu_bytes), "avg_us": round(gu_us, 2), "timed_launches": gu["launches"],
                 "timing": "HIP events around every 16th launch inside the timed steps"}
 
@@ -157,6 +170,24 @@ def main():
         "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
+
+
+def copy_probe(torch, sb):
+    n = 1 << 30
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        sb.op_copy(dst, src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        sb.op_copy(dst, src)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / 5
+    print(json.dumps({"kernel": "copy_kernel", "bytes_read": n, "bytes_written": n, "avg_us": round(us, 1),
+                      "GB/s": round(2 * n / us / 1e3, 1)}), flush=True)
 
 
 def cpu_baseline(shape, weights, prompt, wl):
