@@ -230,8 +230,11 @@ enum { SB_K_RMSNORM = 0, SB_K_QKV, SB_K_ATTN, SB_K_WO, SB_K_GATEUP, SB_K_DOWN, S
 int32_t sb_profile_begin(sb_session *s, uint32_t class_mask, int32_t max_launches, int32_t sample_every);
 /* Synchronises, then per class: timed launches, their summed duration in ms and
  * their summed algorithmic bytes (weights + activations in/out for projections,
- * K/V read for attention).  Arrays of SB_K_COUNT, host.  Ends the timing. */
-int32_t sb_profile_end(sb_session *s, int64_t *launches, double *total_ms, int64_t *bytes);
+ * K/V read for attention).  Arrays of SB_K_COUNT, host.  empty_pair_ms (nullable)
+ * receives the average time between the two events of a pair with no kernel in
+ * between, measured when the timing began: what a bracket adds to a kernel's own
+ * duration.  Ends the timing. */
+int32_t sb_profile_end(sb_session *s, int64_t *launches, double *total_ms, int64_t *bytes, double *empty_pair_ms);
 
 /* ---- single kernels, for parity tests and roofline measurement ---------- */
 /* All pointers are device memory; stream as above; calls do not synchronise.

@@ -115,7 +115,7 @@ def lib() -> C.CDLL:
         L.sb_decode.argtypes = [vp, i32, C.POINTER(sb_params), vp, i32, C.POINTER(i32), C.POINTER(sb_stats)]
         L.sb_rewind.argtypes = [vp, i32, i32, C.c_int64]
         L.sb_profile_begin.argtypes = [vp, C.c_uint32, i32, i32]
-        L.sb_profile_end.argtypes = [vp, vp, vp, vp]
+        L.sb_profile_end.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_double)]
         L.sb_get_stats.argtypes = [vp, C.POINTER(sb_stats)]
         L.sb_committed_len.argtypes = [vp]
         L.sb_debug_enable.argtypes = [vp, i32]
@@ -330,7 +330,10 @@ class Session:
         launches = np.zeros(n, dtype=np.int64)
         ms = np.zeros(n, dtype=np.float64)
         nbytes = np.zeros(n, dtype=np.int64)
-        check(lib().sb_profile_end(self.h, launches.ctypes.data, ms.ctypes.data, nbytes.ctypes.data))
+        empty = C.c_double()
+        check(lib().sb_profile_end(self.h, launches.ctypes.data, ms.ctypes.data, nbytes.ctypes.data,
+                                   C.byref(empty)))
+        self.empty_pair_ms = empty.value
         return {k: dict(launches=int(launches[i]), total_ms=float(ms[i]), bytes=int(nbytes[i]))
                 for i, k in enumerate(KERNEL_CLASSES) if launches[i]}
 

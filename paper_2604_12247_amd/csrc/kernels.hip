@@ -47,11 +47,32 @@ __device__ __forceinline__ void split_store(uint16_t* xs, int ld, int m, int i, 
     xs[(size_t)(8 + m) * ld + i] = lo;
 }
 
+__device__ __forceinline__ void unpack8(uint4 v, float (&w)[8]) {
+    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
+    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
+    w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
+    w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+__device__ __forceinline__ void load8(const uint16_t* p, float (&w)[8]) {
+    uint4 v = *reinterpret_cast<const uint4*>(p);
+    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
+    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
+    w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
+    w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+__device__ __forceinline__ void load8(const float* p, float (&w)[8]) {
+    float4 a = *reinterpret_cast<const float4*>(p);
+    float4 b = *reinterpret_cast<const float4*>(p + 4);
+    w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+    w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+}
+
 // ---------------------------------------------------------------- embedding
 template <typename WT>
 __global__ __launch_bounds__(256) void embed_kernel(const WT* __restrict__ E, int vocab, int d, float* __restrict__ H,
                                                     RowToks toks, const int32_t* __restrict__ slot_tok,
                                                     int32_t* clear_flag, EmbedNorm en) {
+    constexpr int VMAX = 4;  // 8-element groups a thread keeps in registers (covers d <= 8192)
     __shared__ float red[4];
     int r = blockIdx.x, tid = threadIdx.x;
     int tok = toks.tok[r];
@@ -59,12 +80,37 @@ __global__ __launch_bounds__(256) void embed_kernel(const WT* __restrict__ E, in
     if (tok < 0 || tok >= vocab) tok = 0;  // never index outside the table
     if (clear_flag && r == 0 && tid == 0) *clear_flag = 0;
     const WT* e = E + (size_t)tok * d;
+    const int ngrp = d >> 3;
+    float v[VMAX][8], gn[VMAX][8];
+#pragma unroll
+    for (int j = 0; j < VMAX; ++j) {
+        const int gi = tid + j * 256;
+        if (gi < ngrp) {
+            load8(e + gi * 8, v[j]);
+            if (en.nx) load8(en.gain + gi * 8, gn[j]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[j][k] = 0.f;
+        }
+    }
     float ss = 0.f;
-    for (int i = tid; i < d; i += 256) {
-        float v = ldf(e + i);
-        H[(size_t)r * d + i] = v;
-        ss += v * v;
-        if (en.nx) split_store(en.nx, d, r, i, v * en.gain[i]);
+#pragma unroll
+    for (int j = 0; j < VMAX; ++j) {
+        const int gi = tid + j * 256;
+        if (gi < ngrp) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                H[(size_t)r * d + gi * 8 + k] = v[j][k];
+                ss += v[j][k] * v[j][k];
+                if (en.nx) split_store(en.nx, d, r, gi * 8 + k, v[j][k] * gn[j][k]);
+            }
+        }
+    }
+    for (int i = VMAX * 2048 + tid; i < d; i += 256) {  // d > 8192
+        float x = ldf(e + i);
+        H[(size_t)r * d + i] = x;
+        ss += x * x;
+        if (en.nx) split_store(en.nx, d, r, i, x * en.gain[i]);
     }
     if (en.ssq_out) {  // the row's sum of squares, as a single partial
         ss = wave_sum(ss);
@@ -321,26 +367,6 @@ __device__ __forceinline__ void head_partial(const HeadArgs& h, float (*zs)[SB_M
 // loads), partial sums are combined with a fixed shuffle tree.  x is staged in
 // LDS in chunks.  The order in which a row's products are added is a function of
 // K alone.
-__device__ __forceinline__ void unpack8(uint4 v, float (&w)[8]) {
-    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
-    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
-    w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
-    w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
-}
-__device__ __forceinline__ void load8(const uint16_t* p, float (&w)[8]) {
-    uint4 v = *reinterpret_cast<const uint4*>(p);
-    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
-    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
-    w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
-    w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
-}
-__device__ __forceinline__ void load8(const float* p, float (&w)[8]) {
-    float4 a = *reinterpret_cast<const float4*>(p);
-    float4 b = *reinterpret_cast<const float4*>(p + 4);
-    w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
-    w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
-}
-
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + expf(-g)) * u; }
 
 template <typename WT, int M, int EPI>
@@ -516,8 +542,12 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
 #pragma unroll
     for (int t = 0; t < RT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // two register buffers, named apart so that neither is indexed dynamically
-    uint4 wA[RT][4], bA[4], wB[RT][4], bB[4];
+    // Ring of DEPTH register buffers, DEPTH - 1 k blocks in flight per wave.  The
+    // stage loop is fully unrolled, so every buffer index is a compile-time constant.
+    // One tile per wave needs the deeper ring: with few waves per CU (narrow outputs)
+    // the bytes in flight, not the HBM rate, would otherwise bound the kernel.
+    constexpr int DEPTH = (RT == 1) ? 4 : 2;
+    uint4 wbuf[DEPTH][RT][4], bbuf[DEPTH][4];
     auto load_block = [&](uint4 (&wr)[RT][4], uint4 (&br)[4], int kb) {
         const size_t off = (size_t)kb * 128;
 #pragma unroll
@@ -539,7 +569,9 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
         }
     };
     int kb = wave;
-    if (kb < KB) load_block(wA, bA, kb);
+#pragma unroll
+    for (int s = 0; s < DEPTH - 1; ++s)
+        if (kb + s * WPB < KB) load_block(wbuf[s], bbuf[s], kb + s * WPB);
     // RMSNorm scale of each row from the partial sums of squares its producer left
     // (added in index order; the first weight loads are already in flight)
     if (a.ssq_in) {
@@ -552,16 +584,14 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     } else if (tid < SB_MAX_W) {
         s_inv[tid] = 1.0f;
     }
-    if (kb < KB) {
-        while (true) {
-            if (kb + WPB < KB) load_block(wB, bB, kb + WPB);
-            mma_block(wA, bA);
+    for (bool more = kb < KB; more;) {
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) {
+            if (kb >= KB) { more = false; break; }
+            const int nxt = kb + (DEPTH - 1) * WPB;
+            if (nxt < KB) load_block(wbuf[(s + DEPTH - 1) % DEPTH], bbuf[(s + DEPTH - 1) % DEPTH], nxt);
+            mma_block(wbuf[s], bbuf[s]);
             kb += WPB;
-            if (kb >= KB) break;
-            if (kb + WPB < KB) load_block(wA, bA, kb + WPB);
-            mma_block(wB, bB);
-            kb += WPB;
-            if (kb >= KB) break;
         }
     }
 #pragma unroll
@@ -725,20 +755,32 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         pages[pg] = kb < n_total ? a.kv.table[kb / SB_KV_BLOCK] : 0;
     }
 
-    // rotated queries
-    for (int i = tid; i < QG * HALF; i += 256) {
-        int qi = i / HALF, j = i - qi * HALF;
-        float x = 0.f, y = 0.f;
-        if (qi < nq) {
-            int qq = q0 + qi, r = qq / G, gi = qq - r * G;
-            const float* qp = a.q + (size_t)r * a.qkv_rows + (size_t)(g * G + gi) * HD;
-            float qx = qp[j], qy = qp[j + HALF];
-            float c = a.rope_cos[(size_t)(a.pos0 + r) * HALF + j], sn = a.rope_sin[(size_t)(a.pos0 + r) * HALF + j];
-            x = qx * c - qy * sn;
-            y = qy * c + qx * sn;
+    // rotated queries: all loads first, then the arithmetic (one memory round trip)
+    {
+        constexpr int QIT = QG * HALF / 256;
+        float qx[QIT], qy[QIT], qc[QIT], qsn[QIT];
+#pragma unroll
+        for (int it = 0; it < QIT; ++it) {
+            const int i = tid + it * 256;
+            const int qi = i / HALF, j = i - qi * HALF;
+            qx[it] = qy[it] = qsn[it] = 0.f;
+            qc[it] = 1.f;
+            if (qi < nq) {
+                int qq = q0 + qi, r = qq / G, gi = qq - r * G;
+                const float* qp = a.q + (size_t)r * a.qkv_rows + (size_t)(g * G + gi) * HD;
+                qx[it] = qp[j];
+                qy[it] = qp[j + HALF];
+                qc[it] = a.rope_cos[(size_t)(a.pos0 + r) * HALF + j];
+                qsn[it] = a.rope_sin[(size_t)(a.pos0 + r) * HALF + j];
+            }
         }
-        qs[qi * HD + j] = x;
-        qs[qi * HD + j + HALF] = y;
+#pragma unroll
+        for (int it = 0; it < QIT; ++it) {
+            const int i = tid + it * 256;
+            const int qi = i / HALF, j = i - qi * HALF;
+            qs[qi * HD + j] = qx[it] * qc[it] - qy[it] * qsn[it];
+            qs[qi * HD + j + HALF] = qy[it] * qc[it] + qx[it] * qsn[it];
+        }
     }
 
     // One tile = CH keys x HD values of K (which = 0) or V (which = 1).  Old keys

@@ -159,6 +159,7 @@ struct sb_session {
     int prof_every;                    // time every n-th launch of a class
     int64_t prof_seen[SB_K_COUNT];
     std::vector<hipEvent_t> prof_ev;   // pairs
+    std::vector<hipEvent_t> prof_cal;  // empty pairs (calibration)
     std::vector<int> prof_cls;
     std::vector<int64_t> prof_bytes;
     size_t prof_used;                  // pairs used
@@ -560,6 +561,8 @@ void free_session_resources(sb_session* s) {
     if (s->head_stream) (void)hipStreamDestroy(s->head_stream);
     for (hipEvent_t x : s->prof_ev) (void)hipEventDestroy(x);
     s->prof_ev.clear();
+    for (hipEvent_t x : s->prof_cal) (void)hipEventDestroy(x);
+    s->prof_cal.clear();
 }
 
 double now_ms() {
@@ -834,11 +837,22 @@ int32_t sb_profile_begin(sb_session* s, uint32_t class_mask, int32_t max_launche
     s->prof_used = 0;
     s->prof_every = sample_every;
     for (int k = 0; k < SB_K_COUNT; ++k) s->prof_seen[k] = 0;
+    // calibration: a few event pairs with nothing between them
+    s->prof_cal.clear();
+    for (int i = 0; i < 2 * 16; ++i) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) break;
+        s->prof_cal.push_back(e);
+    }
+    for (size_t i = 0; i + 1 < s->prof_cal.size(); i += 2) {
+        (void)hipEventRecord(s->prof_cal[i], s->m->stream);
+        (void)hipEventRecord(s->prof_cal[i + 1], s->m->stream);
+    }
     s->prof_mask = class_mask;
     return SB_OK;
 }
 
-int32_t sb_profile_end(sb_session* s, int64_t* launches, double* total_ms, int64_t* bytes) {
+int32_t sb_profile_end(sb_session* s, int64_t* launches, double* total_ms, int64_t* bytes, double* empty_pair_ms) {
     if (!s || !launches || !total_ms || !bytes) return fail(SB_EINVAL, "profile_end: NULL argument");
     if (s->prof_ev.empty()) return fail(SB_ESTATE, "profile_end: timing is not running");
     s->prof_mask = 0;
@@ -851,6 +865,15 @@ int32_t sb_profile_end(sb_session* s, int64_t* launches, double* total_ms, int64
         total_ms[s->prof_cls[i]] += ms;
         bytes[s->prof_cls[i]] += s->prof_bytes[i];
     }
+    double cal = 0.0;
+    int ncal = 0;
+    for (size_t i = 0; i + 1 < s->prof_cal.size() && e == hipSuccess; i += 2) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, s->prof_cal[i], s->prof_cal[i + 1]) == hipSuccess && i >= 4) { cal += ms; ++ncal; }
+    }
+    if (empty_pair_ms) *empty_pair_ms = ncal ? cal / ncal : 0.0;
+    for (hipEvent_t x : s->prof_cal) (void)hipEventDestroy(x);
+    s->prof_cal.clear();
     for (hipEvent_t x : s->prof_ev) (void)hipEventDestroy(x);
     s->prof_ev.clear();
     s->prof_used = 0;
