@@ -92,7 +92,7 @@ def lib() -> C.CDLL:
     """Load libspecbound.so (building it first only if no built library exists)."""
     global _lib
     if _lib is None:
-        path = _build.lib_path()
+        path = os.environ.get("SPECBOUND_LIB") or _build.lib_path()
         if not os.path.exists(path):
             _build.build()
         L = C.CDLL(path)

@@ -508,11 +508,16 @@ hipError_t launch_gemv_valu(const GemvArgs& a, hipStream_t st) {
 // bf16 weights only.  The M <= 8 activation rows are given as two bf16 parts each
 // (x ~= hi + lo, 16 bits of mantissa), laid out as the 16 columns of one
 // 16x16x32 MFMA B operand: columns 0-7 high parts, 8-15 low parts.  A 16-row
-// tile of W is the A operand, read straight from HBM with 128-bit loads: lane
-// (i = l%16, q = l/16) reads 64 contiguous bytes of row i per 128-wide k block.
+// tile of W is the A operand, read straight from HBM with 128-bit loads: the four
+// lanes (i, q = 0..3) of row i read 64 contiguous bytes per instruction, 256 bytes
+// per 128-wide k block.
 // The four waves of a block take k blocks round-robin and are summed through LDS
 // in wave order.  Products of bf16 values are exact in fp32, so the only rounding
 // is fp32 accumulation.  Columns never mix, hence row results do not depend on M.
+// Element offset of lane group lq's share of MFMA step u inside a 128-wide k block:
+// one load instruction then covers 64 contiguous bytes of each of the 16 rows (the
+// k order inside a block is free as long as A and B use the same one).
+#define SB_KOFF(lq, u) ((u) * 32 + (lq) * 8)
 template <int RT, int EPI, int WPB>
 __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     constexpr int NT = 64 * WPB;
@@ -533,10 +538,15 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
         int row = (EPI == EPI_SWIGLU) ? (t == 0 ? n0 + li : N + n0 + li) : (n0 + t * 16 + li);
         int total = (EPI == EPI_SWIGLU) ? 2 * N : N;
         if (row > total - 1) row = total - 1;
-        wp[t] = W + (size_t)row * K + lq * 32;
+        wp[t] = W + (size_t)row * K;
     }
+    // B operand through buffer loads: lanes whose column is a row that is not there
+    // (m >= M) carry an offset beyond the descriptor's range, for which the hardware
+    // returns zeros without touching memory.  Every load is thus unconditional (the
+    // compiler can count outstanding loads exactly) and costs traffic only for live rows.
+    // lanes whose column is a row that is not there (m >= M) load nothing
     const bool bact = (li & 7) < M;
-    const uint16_t* bp = a.xs + (size_t)li * K + lq * 32;
+    const uint16_t* bp = a.xs + (size_t)li * K;
 
     f32x4 acc[RT];
 #pragma unroll
@@ -544,19 +554,20 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
 
     // Ring of DEPTH register buffers, DEPTH - 1 k blocks in flight per wave.  The
     // stage loop is fully unrolled, so every buffer index is a compile-time constant.
-    // One tile per wave needs the deeper ring: with few waves per CU (narrow outputs)
-    // the bytes in flight, not the HBM rate, would otherwise bound the kernel.
-    constexpr int DEPTH = (RT == 1) ? 4 : 2;
+    constexpr int DEPTH = (RT == 1) ? 3 : 2;  // measured: deeper rings lose occupancy for nothing
     uint4 wbuf[DEPTH][RT][4], bbuf[DEPTH][4];
+    // k block index is clamped instead of tested: loads past the end re-read the last
+    // block (unused), which keeps the steady-state loop free of bounds tests.
     auto load_block = [&](uint4 (&wr)[RT][4], uint4 (&br)[4], int kb) {
-        const size_t off = (size_t)kb * 128;
+        const int kc = kb < KB ? kb : KB - 1;
+        const size_t off = (size_t)kc * 128;
 #pragma unroll
         for (int t = 0; t < RT; ++t)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) wr[t][u] = *reinterpret_cast<const uint4*>(wp[t] + off + u * 8);
+            for (int u = 0; u < 4; ++u) wr[t][u] = *reinterpret_cast<const uint4*>(wp[t] + off + SB_KOFF(lq, u));
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-            br[u] = bact ? *reinterpret_cast<const uint4*>(bp + off + u * 8) : make_uint4(0, 0, 0, 0);
+            br[u] = bact ? *reinterpret_cast<const uint4*>(bp + off + SB_KOFF(lq, u)) : make_uint4(0, 0, 0, 0);
     };
     auto mma_block = [&](const uint4 (&wr)[RT][4], const uint4 (&br)[4]) {
 #pragma unroll
@@ -568,10 +579,10 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
                                                                  0, 0, 0);
         }
     };
-    int kb = wave;
+    const int kb0 = wave;
+    const int nkb = KB > wave ? (KB - wave + WPB - 1) / WPB : 0;  // k blocks of this wave
 #pragma unroll
-    for (int s = 0; s < DEPTH - 1; ++s)
-        if (kb + s * WPB < KB) load_block(wbuf[s], bbuf[s], kb + s * WPB);
+    for (int s = 0; s < DEPTH - 1; ++s) load_block(wbuf[s], bbuf[s], kb0 + s * WPB);
     // RMSNorm scale of each row from the partial sums of squares its producer left
     // (added in index order; the first weight loads are already in flight)
     if (a.ssq_in) {
@@ -584,16 +595,17 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     } else if (tid < SB_MAX_W) {
         s_inv[tid] = 1.0f;
     }
-    for (bool more = kb < KB; more;) {
+    int it = 0;
+    for (; it + DEPTH <= nkb; it += DEPTH) {  // steady state: before it, buf[s] holds block it + s (s < DEPTH-1)
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
-            if (kb >= KB) { more = false; break; }
-            const int nxt = kb + (DEPTH - 1) * WPB;
-            if (nxt < KB) load_block(wbuf[(s + DEPTH - 1) % DEPTH], bbuf[(s + DEPTH - 1) % DEPTH], nxt);
+            load_block(wbuf[(s + DEPTH - 1) % DEPTH], bbuf[(s + DEPTH - 1) % DEPTH], kb0 + (it + s + DEPTH - 1) * WPB);
             mma_block(wbuf[s], bbuf[s]);
-            kb += WPB;
         }
     }
+#pragma unroll
+    for (int s = 0; s < DEPTH - 1; ++s)  // the last nkb - it < DEPTH blocks are already in the ring
+        if (it + s < nkb) mma_block(wbuf[s], bbuf[s]);
 #pragma unroll
     for (int t = 0; t < RT; ++t) *reinterpret_cast<f32x4*>(&red[wave][t][lane][0]) = acc[t];
     __syncthreads();
