@@ -706,19 +706,30 @@ hipError_t launch_gemv_mfma(const GemvArgs& a, hipStream_t st) {
 // M causal query rows at positions pos0..pos0+M-1 against keys 0..pos of the
 // paged cache.  qkv holds the rows' raw projections (q heads, k heads, v heads).
 // The key range is cut into fixed chunks of absolute positions; one block handles
-// one (kv head, chunk, group of <= 16 queries): it rotates its queries (half-split
-// pairing, table built on the host in double and held in float), stages the
-// chunk's K then V pages in LDS -- each page read once for all rows and all query
-// heads of the group -- and writes a partial (max, sum, weighted V) per query.
+// one (kv head, chunk, group of <= 16 queries) and writes a partial (max, sum,
+// weighted V) per query; a second kernel merges the chunks in ascending order.
+//
+// The work inside a block is latency, not bandwidth, so everything is laid out for
+// few dependent steps: K and V go from the cache straight into registers (no LDS
+// tile), each in the mapping its consumer needs, all loads issued up front.
+//   scores   thread = (key, slice of head_dim): partial dot products, slices added in order
+//   softmax  wave per query over the chunk's keys
+//   values   thread = (16-byte group of dims, key slot): a few keys each, then a fixed
+//            shuffle tree over the key slots of a wave and the four waves in order
 // Keys that belong to the new rows are not read from the cache: the block rotates
-// and rounds them from qkv exactly as they are stored, and the block of query
-// group 0 also writes them into the cache (KV append).  A second kernel merges the
-// chunks in ascending order.  A row's result depends on its own position and keys
-// only.
+// (half-split pairing, table built on the host in double and held in float) and
+// rounds them from qkv exactly as they are stored, and the block of query group 0
+// also writes them into the cache (KV append).  A row's result depends on its own
+// position and keys only.
 template <typename KVT> struct KvVec;
 template <> struct KvVec<uint16_t> {
     static constexpr int EPV = 8;
-    static __device__ __forceinline__ void load8(const uint16_t* p, float (&f)[8]) { sb::load8(p, f); }
+    static __device__ __forceinline__ void unpack(uint4 v, float* f) {
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
     static __device__ __forceinline__ uint4 pack(const float* f) {
         return make_uint4((uint32_t)f2bf(f[0]) | ((uint32_t)f2bf(f[1]) << 16), (uint32_t)f2bf(f[2]) | ((uint32_t)f2bf(f[3]) << 16),
                           (uint32_t)f2bf(f[4]) | ((uint32_t)f2bf(f[5]) << 16), (uint32_t)f2bf(f[6]) | ((uint32_t)f2bf(f[7]) << 16));
@@ -726,7 +737,9 @@ template <> struct KvVec<uint16_t> {
 };
 template <> struct KvVec<float> {
     static constexpr int EPV = 4;
-    static __device__ __forceinline__ void load8(const float* p, float (&f)[8]) { sb::load8(p, f); }
+    static __device__ __forceinline__ void unpack(uint4 v, float* f) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    }
     static __device__ __forceinline__ uint4 pack(const float* f) {
         return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
     }
@@ -736,18 +749,20 @@ template <typename KVT, int HD>
 __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     constexpr int CH = (HD * sizeof(KVT) <= 256) ? 128 : 64;  // keys per chunk
     constexpr int EPV = KvVec<KVT>::EPV;                      // elements per 16 bytes
-    constexpr int LDT = HD + EPV;                             // padded tile row
     constexpr int QG = 16;                                    // queries per block
-    constexpr int QSPLIT = 256 / CH, QPT = QG / QSPLIT;
-    constexpr int NS = 256 / HD, KPS = CH / NS;
     constexpr int HALF = HD / 2;
-    constexpr int UPK = HD / EPV;                             // 16-byte units per key
-    constexpr int NIT = CH * UPK / 256;                       // units per thread per tile
-    constexpr int NPG = CH / SB_KV_BLOCK;
-    static_assert(CH * LDT * sizeof(KVT) >= NS * QG * HD * sizeof(float), "tile reused for the split combine");
-    __shared__ __attribute__((aligned(16))) KVT tile[CH * LDT];
+    constexpr int DSPLIT = 256 / CH;                          // score threads per key
+    constexpr int DPT = HD / DSPLIT;                          // dims per score thread
+    constexpr int NKV = DPT / EPV;                            // 16-byte loads per score thread
+    constexpr int DG = HD / EPV;                              // dim groups (value threads per key)
+    constexpr int KS = 256 / DG;                              // key slots
+    constexpr int KPT = CH / KS;                              // keys per value thread
+    constexpr int KSW = 64 / DG;                              // key slots inside one wave
+    static_assert(DPT <= HALF && HALF % DPT == 0, "a score thread's dims lie in one rotary half");
+    static_assert(KSW >= 1 && KS * KPT == CH, "value mapping");
     __shared__ __attribute__((aligned(16))) float qs[QG * HD];
-    __shared__ __attribute__((aligned(16))) float sp[QG * CH];
+    __shared__ __attribute__((aligned(16))) float sp[DSPLIT * QG * CH];  // partial scores, then probabilities
+    __shared__ __attribute__((aligned(16))) float comb[4 * QG * HD];     // per-wave weighted values
     __shared__ float s_m[QG], s_l[QG];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -758,183 +773,176 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     const int key0 = chunk * CH, n_total = a.pos0 + a.M;
     const float scale = 1.0f / sqrtf((float)HD);
     const size_t page_elems = (size_t)Hkv * SB_KV_BLOCK * HD;
+    KVT* const kbase = reinterpret_cast<KVT*>(a.kv.pool) + (size_t)(a.layer * 2 + 0) * a.kv.n_pages * page_elems;
+    KVT* const vbase = reinterpret_cast<KVT*>(a.kv.pool) + (size_t)(a.layer * 2 + 1) * a.kv.n_pages * page_elems;
 
-    // physical pages of this chunk (uniform across the block)
-    int pages[NPG];
+    // ---- issue every global load first: q (+ its rotary factors), K, V
+    constexpr int QIT = QG * HALF / 256;
+    float qx[QIT], qy[QIT], qc[QIT], qsn[QIT];
 #pragma unroll
-    for (int pg = 0; pg < NPG; ++pg) {
-        int kb = key0 + pg * SB_KV_BLOCK;
-        pages[pg] = kb < n_total ? a.kv.table[kb / SB_KV_BLOCK] : 0;
+    for (int it = 0; it < QIT; ++it) {
+        const int i = tid + it * 256;
+        const int qi = i / HALF, j = i - qi * HALF;
+        qx[it] = qy[it] = qsn[it] = 0.f;
+        qc[it] = 1.f;
+        if (qi < nq) {
+            int qq = q0 + qi, r = qq / G, gi = qq - r * G;
+            const float* qp = a.q + (size_t)r * a.qkv_rows + (size_t)(g * G + gi) * HD;
+            qx[it] = qp[j];
+            qy[it] = qp[j + HALF];
+            qc[it] = a.rope_cos[(size_t)(a.pos0 + r) * HALF + j];
+            qsn[it] = a.rope_sin[(size_t)(a.pos0 + r) * HALF + j];
+        }
+    }
+    // scores mapping: key kt, dims [kd0, kd0 + DPT)
+    const int kt = tid % CH, kd0 = (tid / CH) * DPT;
+    const int kkey = key0 + kt;
+    uint4 kreg[NKV];
+    size_t kaddr = 0;  // element offset of this thread's K slice inside the K pool of the layer
+    if (kkey < n_total) kaddr = (size_t)a.kv.table[kkey / SB_KV_BLOCK] * page_elems + ((size_t)g * SB_KV_BLOCK + (kkey % SB_KV_BLOCK)) * HD + kd0;
+#pragma unroll
+    for (int i = 0; i < NKV; ++i) {
+        kreg[i] = make_uint4(0, 0, 0, 0);
+        if (kkey < a.pos0) kreg[i] = *reinterpret_cast<const uint4*>(kbase + kaddr + i * EPV);
+    }
+    // values mapping: dims [vd0, vd0 + EPV), keys vks + KS * i
+    const int vd0 = (tid % DG) * EPV, vks = tid / DG;
+    uint4 vreg[KPT];
+    size_t vaddr[KPT];
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+        const int key = key0 + vks + KS * i;
+        vreg[i] = make_uint4(0, 0, 0, 0);
+        vaddr[i] = 0;
+        if (key < n_total) vaddr[i] = (size_t)a.kv.table[key / SB_KV_BLOCK] * page_elems + ((size_t)g * SB_KV_BLOCK + (key % SB_KV_BLOCK)) * HD + vd0;
+        if (key < a.pos0) vreg[i] = *reinterpret_cast<const uint4*>(vbase + vaddr[i]);
     }
 
-    // rotated queries: all loads first, then the arithmetic (one memory round trip)
+    // ---- rotated queries -> LDS
+#pragma unroll
+    for (int it = 0; it < QIT; ++it) {
+        const int i = tid + it * 256;
+        const int qi = i / HALF, j = i - qi * HALF;
+        qs[qi * HD + j] = qx[it] * qc[it] - qy[it] * qsn[it];
+        qs[qi * HD + j + HALF] = qy[it] * qc[it] + qx[it] * qsn[it];
+    }
+    // ---- keys and values of the new rows: built from qkv, appended by query group 0
+    if (kkey >= a.pos0 && kkey < n_total) {
+        const int r = kkey - a.pos0;
+        const float* kp = a.q + (size_t)r * a.qkv_rows + (size_t)(Hq + g) * HD;
+        const bool lo = kd0 < HALF;
+        const int dj = lo ? kd0 : kd0 - HALF;
+#pragma unroll
+        for (int i = 0; i < NKV; ++i) {
+            float f[EPV];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                const int j = dj + i * EPV + e;
+                float c = a.rope_cos[(size_t)kkey * HALF + j], sn = a.rope_sin[(size_t)kkey * HALF + j];
+                float x = kp[j], y = kp[j + HALF];
+                f[e] = lo ? (x * c - y * sn) : (y * c + x * sn);
+            }
+            kreg[i] = KvVec<KVT>::pack(f);
+            if (qg == 0) *reinterpret_cast<uint4*>(kbase + kaddr + i * EPV) = kreg[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+        const int key = key0 + vks + KS * i;
+        if (key >= a.pos0 && key < n_total) {
+            const float* vp = a.q + (size_t)(key - a.pos0) * a.qkv_rows + (size_t)(Hq + Hkv + g) * HD + vd0;
+            float f[EPV];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) f[e] = vp[e];
+            vreg[i] = KvVec<KVT>::pack(f);
+            if (qg == 0) *reinterpret_cast<uint4*>(vbase + vaddr[i]) = vreg[i];
+        }
+    }
+    __syncthreads();
+
+    // ---- partial scores: this thread's DPT dims of key kt against every live query
     {
-        constexpr int QIT = QG * HALF / 256;
-        float qx[QIT], qy[QIT], qc[QIT], qsn[QIT];
+        float kf[NKV][EPV];
 #pragma unroll
-        for (int it = 0; it < QIT; ++it) {
-            const int i = tid + it * 256;
-            const int qi = i / HALF, j = i - qi * HALF;
-            qx[it] = qy[it] = qsn[it] = 0.f;
-            qc[it] = 1.f;
-            if (qi < nq) {
-                int qq = q0 + qi, r = qq / G, gi = qq - r * G;
-                const float* qp = a.q + (size_t)r * a.qkv_rows + (size_t)(g * G + gi) * HD;
-                qx[it] = qp[j];
-                qy[it] = qp[j + HALF];
-                qc[it] = a.rope_cos[(size_t)(a.pos0 + r) * HALF + j];
-                qsn[it] = a.rope_sin[(size_t)(a.pos0 + r) * HALF + j];
-            }
-        }
+        for (int i = 0; i < NKV; ++i) KvVec<KVT>::unpack(kreg[i], kf[i]);
+        for (int qi = 0; qi < nq; ++qi) {
+            const float* qp = &qs[qi * HD + kd0];
+            float s = 0.f;
 #pragma unroll
-        for (int it = 0; it < QIT; ++it) {
-            const int i = tid + it * 256;
-            const int qi = i / HALF, j = i - qi * HALF;
-            qs[qi * HD + j] = qx[it] * qc[it] - qy[it] * qsn[it];
-            qs[qi * HD + j + HALF] = qy[it] * qc[it] + qx[it] * qsn[it];
-        }
-    }
-
-    // One tile = CH keys x HD values of K (which = 0) or V (which = 1).  Old keys
-    // come from the cache; keys of the new rows are built from qkv.  fetch() only
-    // issues loads into registers, so both tiles' memory round trips overlap with
-    // each other and with the score computation; commit() puts a tile into LDS.
-    auto tile_base = [&](int which) {
-        return reinterpret_cast<KVT*>(a.kv.pool) + (size_t)(a.layer * 2 + which) * a.kv.n_pages * page_elems;
-    };
-    auto fetch = [&](int which, uint4 (&v)[NIT]) {
-        const KVT* base = tile_base(which);
+            for (int i = 0; i < NKV; ++i)
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int u = tid + it * 256;
-            const int t = u / UPK, d = (u - t * UPK) * EPV;
-            const int key = key0 + t;
-            v[it] = make_uint4(0, 0, 0, 0);
-            if (key < a.pos0) {
-                v[it] = *reinterpret_cast<const uint4*>(base + (size_t)pages[t / SB_KV_BLOCK] * page_elems +
-                                                        ((size_t)g * SB_KV_BLOCK + (t % SB_KV_BLOCK)) * HD + d);
-            } else if (key < n_total) {
-                const int r = key - a.pos0;
-                float f[EPV];
-                if (which == 0) {
-                    const float* kp = a.q + (size_t)r * a.qkv_rows + (size_t)(Hq + g) * HD;
-                    const int dj = d < HALF ? d : d - HALF;
-#pragma unroll
-                    for (int e = 0; e < EPV; ++e) {
-                        float c = a.rope_cos[(size_t)key * HALF + dj + e], sn = a.rope_sin[(size_t)key * HALF + dj + e];
-                        float x = kp[dj + e], y = kp[dj + e + HALF];
-                        f[e] = d < HALF ? (x * c - y * sn) : (y * c + x * sn);
-                    }
-                } else {
-                    const float* vp = a.q + (size_t)r * a.qkv_rows + (size_t)(Hq + Hkv + g) * HD;
-#pragma unroll
-                    for (int e = 0; e < EPV; ++e) f[e] = vp[d + e];
+                for (int e = 0; e < EPV; e += 4) {
+                    float4 qv = *reinterpret_cast<const float4*>(qp + i * EPV + e);
+                    s = fmaf(qv.x, kf[i][e], s); s = fmaf(qv.y, kf[i][e + 1], s);
+                    s = fmaf(qv.z, kf[i][e + 2], s); s = fmaf(qv.w, kf[i][e + 3], s);
                 }
-                v[it] = KvVec<KVT>::pack(f);
-            }
-        }
-    };
-    auto commit = [&](int which, const uint4 (&v)[NIT]) {
-        KVT* base = tile_base(which);
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int u = tid + it * 256;
-            const int t = u / UPK, d = (u - t * UPK) * EPV;
-            const int key = key0 + t;
-            if (qg == 0 && key >= a.pos0 && key < n_total)  // KV append: exactly one block per (kv head, key)
-                *reinterpret_cast<uint4*>(base + (size_t)pages[t / SB_KV_BLOCK] * page_elems +
-                                          ((size_t)g * SB_KV_BLOCK + (t % SB_KV_BLOCK)) * HD + d) = v[it];
-            *reinterpret_cast<uint4*>(&tile[t * LDT + d]) = v[it];
-        }
-    };
-    uint4 kreg[NIT], vreg[NIT];
-    fetch(0, kreg);
-    fetch(1, vreg);
-    commit(0, kreg);
-    __syncthreads();
-
-    {   // scores: thread = (key t, query subset qh)
-        const int t = tid % CH, qh = tid / CH;
-        float acc[QPT];
-#pragma unroll
-        for (int j = 0; j < QPT; ++j) acc[j] = 0.f;
-#pragma unroll 2
-        for (int d = 0; d < HD; d += 8) {
-            float kf[8];
-            KvVec<KVT>::load8(&tile[t * LDT + d], kf);
-#pragma unroll
-            for (int j = 0; j < QPT; ++j) {
-                if (qh + j * QSPLIT >= nq) continue;  // uniform per wave
-                const float* qp = &qs[(qh + j * QSPLIT) * HD + d];
-                float4 qa = *reinterpret_cast<const float4*>(qp);
-                float4 qb = *reinterpret_cast<const float4*>(qp + 4);
-                float s = acc[j];
-                s = fmaf(qa.x, kf[0], s); s = fmaf(qa.y, kf[1], s); s = fmaf(qa.z, kf[2], s); s = fmaf(qa.w, kf[3], s);
-                s = fmaf(qb.x, kf[4], s); s = fmaf(qb.y, kf[5], s); s = fmaf(qb.z, kf[6], s); s = fmaf(qb.w, kf[7], s);
-                acc[j] = s;
-            }
-        }
-        const int key = key0 + t;
-#pragma unroll
-        for (int j = 0; j < QPT; ++j) {
-            int qi = qh + j * QSPLIT;
-            int r = (q0 + qi) / G;
-            bool valid = qi < nq && key <= a.pos0 + r;
-            sp[qi * CH + t] = valid ? acc[j] * scale : -SB_INF;
+            sp[((tid / CH) * QG + qi) * CH + kt] = s;
         }
     }
     __syncthreads();
+    // ---- softmax partial of each live query over the chunk (one wave per query)
     for (int qi = wave; qi < nq; qi += 4) {
-        float s0 = sp[qi * CH + lane];
-        float s1 = (CH == 128) ? sp[qi * CH + 64 + lane] : -SB_INF;
-        float mx = wave_max(fmaxf(s0, s1));
-        float p0 = (mx == -SB_INF) ? 0.f : expf(s0 - mx);
-        float p1 = (mx == -SB_INF) ? 0.f : expf(s1 - mx);
-        float l = wave_sum(p0 + p1);
-        sp[qi * CH + lane] = p0;
-        if (CH == 128) sp[qi * CH + 64 + lane] = p1;
+        const int r = (q0 + qi) / G;
+        float sc[CH / 64];
+        float mx = -SB_INF;
+#pragma unroll
+        for (int h = 0; h < CH / 64; ++h) {
+            const int t = lane + 64 * h;
+            float s = sp[qi * CH + t];
+#pragma unroll
+            for (int ds = 1; ds < DSPLIT; ++ds) s += sp[(ds * QG + qi) * CH + t];
+            sc[h] = (key0 + t <= a.pos0 + r) ? s * scale : -SB_INF;
+            mx = fmaxf(mx, sc[h]);
+        }
+        mx = wave_max(mx);
+        float l = 0.f;
+#pragma unroll
+        for (int h = 0; h < CH / 64; ++h) {
+            float p = (mx == -SB_INF) ? 0.f : expf(sc[h] - mx);
+            sc[h] = p;
+            l += p;
+        }
+        l = wave_sum(l);
+#pragma unroll
+        for (int h = 0; h < CH / 64; ++h) sp[qi * CH + lane + 64 * h] = sc[h];
         if (lane == 0) { s_m[qi] = mx; s_l[qi] = l; }
     }
     __syncthreads();
-    commit(1, vreg);
-    __syncthreads();
-
-    float o[QG];
-    {   // weighted values: thread = (dim d, key split ks)
-        const int d = tid % HD, ks = tid / HD;
+    // ---- weighted values
+    {
+        float vf[KPT][EPV];
 #pragma unroll
-        for (int qi = 0; qi < QG; ++qi) o[qi] = 0.f;
-#pragma unroll 2
-        for (int tt = 0; tt < KPS; tt += 4) {
-            const int t = ks * KPS + tt;
-            float v0 = ldf(&tile[(t + 0) * LDT + d]), v1 = ldf(&tile[(t + 1) * LDT + d]);
-            float v2 = ldf(&tile[(t + 2) * LDT + d]), v3 = ldf(&tile[(t + 3) * LDT + d]);
+        for (int i = 0; i < KPT; ++i) KvVec<KVT>::unpack(vreg[i], vf[i]);
+        for (int qi = 0; qi < nq; ++qi) {
+            float o[EPV];
 #pragma unroll
-            for (int qi = 0; qi < QG; ++qi) {
-                if (qi >= nq) continue;
-                float4 p = *reinterpret_cast<const float4*>(&sp[qi * CH + t]);
-                float s = o[qi];
-                s = fmaf(p.x, v0, s); s = fmaf(p.y, v1, s); s = fmaf(p.z, v2, s); s = fmaf(p.w, v3, s);
-                o[qi] = s;
+            for (int e = 0; e < EPV; ++e) o[e] = 0.f;
+#pragma unroll
+            for (int i = 0; i < KPT; ++i) {
+                const float p = sp[qi * CH + vks + KS * i];
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) o[e] = fmaf(p, vf[i][e], o[e]);
+            }
+            // key slots of this wave, fixed tree
+#pragma unroll
+            for (int off = DG; off < 64; off <<= 1)
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) o[e] += __shfl_xor(o[e], off, 64);
+            if (lane < DG) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) comb[(wave * QG + qi) * HD + vd0 + e] = o[e];
             }
         }
-        __syncthreads();
-        float* comb = reinterpret_cast<float*>(tile);
-#pragma unroll
-        for (int qi = 0; qi < QG; ++qi) comb[(ks * QG + qi) * HD + d] = o[qi];
     }
     __syncthreads();
     {
-        const float* comb = reinterpret_cast<const float*>(tile);
         const int stride = HD + 2;
-        for (int i = tid; i < QG * HD; i += 256) {
-            int qi = i / HD, d = i - qi * HD;
-            if (qi >= nq) continue;
-            int qq = q0 + qi, r = qq / G, gi = qq - r * G;
+        for (int i = tid; i < nq * HD; i += 256) {
+            const int qi = i / HD, d = i - qi * HD;
+            const int qq = q0 + qi, r = qq / G, gi = qq - r * G;
             if (key0 > a.pos0 + r) continue;  // no key of this chunk is visible to the row
-            float v = comb[qi * HD + d];
-#pragma unroll
-            for (int s = 1; s < NS; ++s) v += comb[(s * QG + qi) * HD + d];
+            float v = ((comb[(0 * QG + qi) * HD + d] + comb[(1 * QG + qi) * HD + d]) + comb[(2 * QG + qi) * HD + d]) +
+                      comb[(3 * QG + qi) * HD + d];
             float* p = a.partials + ((size_t)(r * Hq + g * G + gi) * a.max_chunks + chunk) * stride;
             p[2 + d] = v;
             if (d == 0) { p[0] = s_m[qi]; p[1] = s_l[qi]; }
