@@ -18,7 +18,10 @@
  *  - "device" pointers are HIP device memory on the model's GPU; "host" pointers
  *    are ordinary memory.  Nothing the caller passes is freed by the library.
  *  - Weights are BORROWED: the device buffers named in sb_weights must outlive
- *    the model.  The host arrays of pointers are copied at load time.
+ *    the model.  The host arrays of pointers are copied at load time.  With
+ *    SB_PROJ_MFMA_PACKED sb_load_model also allocates a tile-packed copy of every
+ *    projection matrix (same size) on the device; the embedding table and the norm
+ *    gains are still read from the caller's buffers.
  *  - The KV pool and the workspace are caller-owned device memory, borrowed for
  *    the session's lifetime.  sb_query_sizes() says how large they must be.
  *  - All kernels are enqueued on the stream given to sb_load_model (a
@@ -45,8 +48,10 @@ enum { SB_OK = 0, SB_EINVAL = -1, SB_ENOMEM = -2, SB_ECAPACITY = -3, SB_ESTATE =
 enum { SB_FP32 = 0, SB_BF16 = 1 };
 /* status of a draft step */
 enum { SB_EXITED = 1, SB_WIDTH_BOUND = 2, SB_DEPTH_BOUND = 3 };
-/* projection kernels: plain vector-ALU dot products, or MFMA tiles (bf16 weights only) */
-enum { SB_PROJ_AUTO = 0, SB_PROJ_VALU = 1, SB_PROJ_MFMA = 2 };
+/* projection kernels: plain vector-ALU dot products, MFMA tiles reading the caller's
+ * row-major weights, or MFMA tiles reading a tile-packed copy of the weights that
+ * sb_load_model makes (bf16 weights only; results identical to SB_PROJ_MFMA) */
+enum { SB_PROJ_AUTO = 0, SB_PROJ_VALU = 1, SB_PROJ_MFMA = 2, SB_PROJ_MFMA_PACKED = 3 };
 
 /* LLaMA-style pre-norm decoder: RMSNorm, rotary embedding (half-split pairing,
  * theta_i = rope_base^(-2i/head_dim)), multi-head or grouped-query causal
@@ -60,7 +65,7 @@ typedef struct sb_config {
     int32_t kv_dtype;      /* SB_FP32 or SB_BF16: K and V are rounded to this on cache store */
     int32_t n_exit_heads;
     int32_t max_seq;       /* capacity in tokens, a multiple of SB_KV_BLOCK */
-    int32_t proj_kernel;   /* SB_PROJ_*; AUTO = MFMA for bf16 weights, VALU for fp32 */
+    int32_t proj_kernel;   /* SB_PROJ_*; AUTO = MFMA_PACKED for bf16 weights, VALU for fp32 */
 } sb_config;
 
 /* Device pointers.  Matrices are row-major [out][in] in weight_dtype; norm gains
@@ -244,11 +249,15 @@ int32_t sb_profile_end(sb_session *s, int64_t *launches, double *total_ms, int64
 int32_t sb_op_rmsnorm(const float *x, const float *gain, float *out, int32_t M, int32_t d, float eps,
                       void *stream);
 /* y[m][n] = sum_k W[n][k] x[m][k]; W [N][K] in w_dtype, x [M][K], y [M][N] float.
- * kernel: SB_PROJ_VALU or SB_PROJ_MFMA (bf16 only; K % 128 == 0, N % 16 == 0).
+ * kernel: SB_PROJ_VALU, SB_PROJ_MFMA or SB_PROJ_MFMA_PACKED (bf16 only; K % 128 == 0,
+ * N % 16 == 0; PACKED: W is the output of sb_op_repack).
  * scratch: device, sb_op_gemv_scratch_bytes(M, K) bytes (MFMA operand staging). */
 int32_t sb_op_gemv(const void *W, int32_t w_dtype, int32_t N, int32_t K, const float *x, float *y,
                    int32_t M, int32_t kernel, void *scratch, void *stream);
 size_t sb_op_gemv_scratch_bytes(int32_t M, int32_t K);
+/* Tile-packed copy of a bf16 matrix W [N][K] (N % 16 == 0, K % 128 == 0) for
+ * kernel = SB_PROJ_MFMA_PACKED of sb_op_gemv / sb_op_head: packed, N*K*2 bytes. */
+int32_t sb_op_repack(const void *W, int32_t N, int32_t K, void *packed, void *stream);
 /* Exit-head evaluation on already normalised rows x [M][K]: z = W x (never
  * written unless logits != NULL, [M][N] float), arg max (lowest index on ties) and
  * confidence p = 1 / sum_j exp((z_j - z_max)/T) (Eq. 2).  argmax_out [M] int32,

@@ -18,7 +18,7 @@ SB_MAX_EXIT_LAYERS = 64
 OK, EINVAL, ENOMEM, ECAPACITY, ESTATE, EDEVICE = 0, -1, -2, -3, -4, -5
 FP32, BF16 = 0, 1
 EXITED, WIDTH_BOUND, DEPTH_BOUND = 1, 2, 3
-PROJ_AUTO, PROJ_VALU, PROJ_MFMA = 0, 1, 2
+PROJ_AUTO, PROJ_VALU, PROJ_MFMA, PROJ_MFMA_PACKED = 0, 1, 2, 3
 
 
 class SbError(RuntimeError):
@@ -80,7 +80,7 @@ SYMBOLS = ["sb_last_error", "sb_temperature_schedule", "sb_query_sizes", "sb_loa
            "sb_debug_kv", "sb_op_rmsnorm", "sb_op_gemv", "sb_op_gemv_scratch_bytes", "sb_op_head",
            "sb_op_head_scratch_bytes", "sb_rope_table_host", "sb_op_attention",
            "sb_op_attention_scratch_bytes", "sb_decode", "sb_rewind", "sb_profile_begin", "sb_profile_end", "sb_op_copy",
-           "sb_op_read"]
+           "sb_op_read", "sb_op_repack"]
 
 KERNEL_CLASSES = ["rmsnorm", "qkv", "attention", "wo", "gate_up", "down", "exit_head",
                   "final_head"]
@@ -129,6 +129,7 @@ def lib() -> C.CDLL:
         L.sb_op_head.argtypes = [vp, i32, i32, i32, vp, i32, f32, i32, vp, vp, vp, vp, vp]
         L.sb_op_head_scratch_bytes.argtypes = [i32, i32, i32]
         L.sb_op_head_scratch_bytes.restype = sz
+        L.sb_op_repack.argtypes = [vp, i32, i32, vp, vp]
         L.sb_op_copy.argtypes = [vp, vp, sz, vp]
         L.sb_op_read.argtypes = [vp, sz, vp, vp]
         L.sb_rope_table_host.argtypes = [i32, f32, i32, vp, vp]
@@ -389,8 +390,18 @@ def _wdtype(W):
     raise TypeError(f"weights must be float32, or bf16 bits as int16 / bfloat16, not {W.dtype}")
 
 
+def op_repack(W):
+    """Tile-packed copy of a bf16 matrix (int16 / bfloat16 tensor [N, K]) for PROJ_MFMA_PACKED."""
+    import torch
+    N, K = W.shape
+    P = torch.empty_like(W)
+    check(lib().sb_op_repack(W.data_ptr(), N, K, P.data_ptr(), _stream_ptr(torch, W.device)))
+    return P
+
+
 def op_gemv(W, x, kernel: int = PROJ_VALU):
-    """W [N, K] (float32, or bf16 as int16/bfloat16), x [M, K] float32 -> y [M, N] float32."""
+    """W [N, K] (float32, or bf16 as int16/bfloat16), x [M, K] float32 -> y [M, N] float32.
+    For PROJ_MFMA_PACKED, W is the output of op_repack."""
     import torch
     N, K = W.shape
     M = x.shape[0]

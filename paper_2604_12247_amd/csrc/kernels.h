@@ -46,7 +46,8 @@ struct HeadArgs {
 };
 
 struct GemvArgs {
-    const void* W;     // [rows][K] row-major, bf16 bits or float
+    const void* W;     // [rows][K] row-major, bf16 bits or float; or the packed tile layout (MFMA path)
+    int32_t packed;    // W is in the packed tile layout written by launch_repack
     int32_t w_dtype;   // SB_FP32 / SB_BF16
     int32_t N;         // outputs per row of x (EPI_SWIGLU: d_ffn, W has 2N rows)
     int32_t K;
@@ -85,6 +86,8 @@ hipError_t launch_rmsnorm(const float* x, const float* gain, float* out, uint16_
                           int32_t M, int32_t d, float eps, hipStream_t st);
 hipError_t launch_gemv_valu(const GemvArgs& a, hipStream_t st);
 hipError_t launch_gemv_mfma(const GemvArgs& a, hipStream_t st);
+// bf16 W [N][K] row-major -> packed MFMA tile layout (N % 16 == 0, K % 128 == 0), same size
+hipError_t launch_repack(const void* W, void* P, int32_t N, int32_t K, hipStream_t st);
 hipError_t launch_split(const float* x, uint16_t* xs, int32_t M, int32_t K, hipStream_t st);
 
 struct KvLayout {

@@ -514,11 +514,53 @@ hipError_t launch_gemv_valu(const GemvArgs& a, hipStream_t st) {
 // The four waves of a block take k blocks round-robin and are summed through LDS
 // in wave order.  Products of bf16 values are exact in fp32, so the only rounding
 // is fp32 accumulation.  Columns never mix, hence row results do not depend on M.
+//
+// PACKED: the weights were re-laid out once (repack_kernel) so that what a wave
+// loads is contiguous: per 16-row tile and 128-wide k block one 4 KB unit, in it
+// 1 KB per MFMA step holding lane l's 16 bytes at l * 16.  Every load instruction
+// then reads 1 KB of consecutive memory (whole cache lines, so a streaming hint is
+// safe) and a block walks one contiguous slab.  Same values in the same MFMA slots
+// as the row-major path: results are bit-identical.
 // Element offset of lane group lq's share of MFMA step u inside a 128-wide k block:
 // one load instruction then covers 64 contiguous bytes of each of the 16 rows (the
 // k order inside a block is free as long as A and B use the same one).
 #define SB_KOFF(lq, u) ((u) * 32 + (lq) * 8)
-template <int RT, int EPI, int WPB>
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+#ifndef SB_PACKED_NT
+#define SB_PACKED_NT 1
+#endif
+__device__ __forceinline__ uint4 ld_weights_packed(const uint16_t* p) {
+#if SB_PACKED_NT
+    u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+#else
+    return *reinterpret_cast<const uint4*>(p);
+#endif
+}
+
+// W [N][K] row-major -> packed tiles (N % 16 == 0, K % 128 == 0); one thread moves 16 bytes.
+__global__ __launch_bounds__(256) void repack_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ P, int N,
+                                                     int K) {
+    const int KB = K >> 7;
+    const size_t unit = (size_t)blockIdx.x * 256 + threadIdx.x;  // 16-byte unit of the packed array
+    const size_t n_units = (size_t)N * K / 8;
+    if (unit >= n_units) return;
+    const int l = (int)(unit & 63), u = (int)((unit >> 6) & 3);
+    const size_t blk = unit >> 8;  // (tile, k block)
+    const int kb = (int)(blk % KB);
+    const size_t tile = blk / KB;
+    const int i = l & 15, q = l >> 4;
+    const uint4 v = *reinterpret_cast<const uint4*>(W + (tile * 16 + i) * (size_t)K + (size_t)kb * 128 + SB_KOFF(q, u));
+    *reinterpret_cast<uint4*>(P + unit * 8) = v;
+}
+hipError_t launch_repack(const void* W, void* P, int32_t N, int32_t K, hipStream_t st) {
+    if (N % 16 || K % 128 || N < 16 || K < 128) return hipErrorInvalidValue;
+    const size_t n_units = (size_t)N * K / 8;
+    repack_kernel<<<(unsigned)((n_units + 255) / 256), 256, 0, st>>>((const uint16_t*)W, (uint16_t*)P, N, K);
+    return hipGetLastError();
+}
+
+template <int RT, int EPI, int WPB, bool PACKED>
 __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     constexpr int NT = 64 * WPB;
     __shared__ __attribute__((aligned(16))) float red[WPB][RT][64][4];
@@ -535,15 +577,17 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     const uint16_t* wp[RT];
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        int row = (EPI == EPI_SWIGLU) ? (t == 0 ? n0 + li : N + n0 + li) : (n0 + t * 16 + li);
+        int row0 = (EPI == EPI_SWIGLU) ? (t == 0 ? n0 : N + n0) : (n0 + t * 16);  // first row of the tile
         int total = (EPI == EPI_SWIGLU) ? 2 * N : N;
-        if (row > total - 1) row = total - 1;
-        wp[t] = W + (size_t)row * K;
+        if (PACKED) {
+            if (row0 > total - 16) row0 = total - 16;
+            wp[t] = W + (size_t)(row0 >> 4) * KB * 2048 + lane * 8;
+        } else {
+            int row = row0 + li;
+            if (row > total - 1) row = total - 1;
+            wp[t] = W + (size_t)row * K;
+        }
     }
-    // B operand through buffer loads: lanes whose column is a row that is not there
-    // (m >= M) carry an offset beyond the descriptor's range, for which the hardware
-    // returns zeros without touching memory.  Every load is thus unconditional (the
-    // compiler can count outstanding loads exactly) and costs traffic only for live rows.
     // lanes whose column is a row that is not there (m >= M) load nothing
     const bool bact = (li & 7) < M;
     const uint16_t* bp = a.xs + (size_t)li * K;
@@ -564,7 +608,9 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
 #pragma unroll
         for (int t = 0; t < RT; ++t)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) wr[t][u] = *reinterpret_cast<const uint4*>(wp[t] + off + SB_KOFF(lq, u));
+            for (int u = 0; u < 4; ++u)
+                wr[t][u] = PACKED ? ld_weights_packed(wp[t] + (size_t)kc * 2048 + u * 512)
+                                  : *reinterpret_cast<const uint4*>(wp[t] + off + SB_KOFF(lq, u));
 #pragma unroll
         for (int u = 0; u < 4; ++u)
             br[u] = bact ? *reinterpret_cast<const uint4*>(bp + off + SB_KOFF(lq, u)) : make_uint4(0, 0, 0, 0);
@@ -677,23 +723,27 @@ static int mfma_row_tiles(int32_t N) { return N >= 16384 ? 2 : 1; }
 static int mfma_waves(int32_t N) { return N <= 8192 ? 8 : 4; }
 int head_blocks_mfma(int32_t N) { return (N + 16 * mfma_row_tiles(N) - 1) / (16 * mfma_row_tiles(N)); }
 
-template <int EPI>
+template <int EPI, bool PACKED>
 static void launch_gemv_mfma_e(const GemvArgs& a, hipStream_t st) {
-    const int rt = mfma_row_tiles(a.N), wpb = mfma_waves(a.N);
-    if (rt == 2) gemv_mfma_kernel<2, EPI, 4><<<(a.N + 31) / 32, 256, 0, st>>>(a);
-    else if (wpb == 8) gemv_mfma_kernel<1, EPI, 8><<<a.N / 16, 512, 0, st>>>(a);
-    else gemv_mfma_kernel<1, EPI, 4><<<a.N / 16, 256, 0, st>>>(a);
+    if constexpr (EPI == EPI_SWIGLU) {
+        gemv_mfma_kernel<2, EPI, 4, PACKED><<<a.N / 16, 256, 0, st>>>(a);
+    } else {
+        const int rt = mfma_row_tiles(a.N), wpb = mfma_waves(a.N);
+        if (rt == 2) gemv_mfma_kernel<2, EPI, 4, PACKED><<<(a.N + 31) / 32, 256, 0, st>>>(a);
+        else if (wpb == 8) gemv_mfma_kernel<1, EPI, 8, PACKED><<<a.N / 16, 512, 0, st>>>(a);
+        else gemv_mfma_kernel<1, EPI, 4, PACKED><<<a.N / 16, 256, 0, st>>>(a);
+    }
 }
 
 hipError_t launch_gemv_mfma(const GemvArgs& a, hipStream_t st) {
     if (a.w_dtype != SB_BF16 || a.K % 128 != 0 || a.N % 16 != 0 || a.M < 1 || a.M > 8 || !a.xs)
         return hipErrorInvalidValue;
     switch (a.epi) {
-        case EPI_STORE: launch_gemv_mfma_e<EPI_STORE>(a, st); break;
-        case EPI_RESID: launch_gemv_mfma_e<EPI_RESID>(a, st); break;
-        case EPI_SWIGLU: gemv_mfma_kernel<2, EPI_SWIGLU, 4><<<a.N / 16, 256, 0, st>>>(a); break;
+        case EPI_STORE: a.packed ? launch_gemv_mfma_e<EPI_STORE, true>(a, st) : launch_gemv_mfma_e<EPI_STORE, false>(a, st); break;
+        case EPI_RESID: a.packed ? launch_gemv_mfma_e<EPI_RESID, true>(a, st) : launch_gemv_mfma_e<EPI_RESID, false>(a, st); break;
+        case EPI_SWIGLU: a.packed ? launch_gemv_mfma_e<EPI_SWIGLU, true>(a, st) : launch_gemv_mfma_e<EPI_SWIGLU, false>(a, st); break;
         case EPI_HEAD: {
-            launch_gemv_mfma_e<EPI_HEAD>(a, st);
+            a.packed ? launch_gemv_mfma_e<EPI_HEAD, true>(a, st) : launch_gemv_mfma_e<EPI_HEAD, false>(a, st);
             hipError_t e = hipGetLastError();
             return e != hipSuccess ? e : launch_head_merge(a.head, a.M, head_blocks_mfma(a.N), st);
         }

@@ -53,10 +53,10 @@ int check_config(const sb_config* c) {
     if (c->d_model % 8 || c->d_ffn % 8 || (c->n_heads * c->head_dim) % 8)
         return fail(SB_EINVAL, "config: d_model, d_ffn and n_heads*head_dim must be multiples of 8");
     if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return fail(SB_EINVAL, "config: rms_eps / rope_base");
-    if (c->proj_kernel < SB_PROJ_AUTO || c->proj_kernel > SB_PROJ_MFMA) return fail(SB_EINVAL, "config: proj_kernel");
-    if (c->proj_kernel == SB_PROJ_MFMA) {
+    if (c->proj_kernel < SB_PROJ_AUTO || c->proj_kernel > SB_PROJ_MFMA_PACKED) return fail(SB_EINVAL, "config: proj_kernel");
+    if (c->proj_kernel == SB_PROJ_MFMA || c->proj_kernel == SB_PROJ_MFMA_PACKED) {
         if (c->weight_dtype != SB_BF16) return fail(SB_EINVAL, "config: the MFMA projection path needs bf16 weights");
-        if (c->d_model % 128 || c->d_ffn % 128 || (c->n_heads * c->head_dim) % 128 || c->vocab % 16)
+        if (c->d_model % 128 || c->d_ffn % 128 || (c->n_heads * c->head_dim) % 128 || c->vocab % 16 || c->d_ffn % 16)
             return fail(SB_EINVAL, "config: the MFMA path needs K %% 128 == 0 and N %% 16 == 0");
     }
     return SB_OK;
@@ -66,7 +66,7 @@ int resolve_proj(const sb_config* c) {
     if (c->proj_kernel != SB_PROJ_AUTO) return c->proj_kernel;
     bool ok = c->weight_dtype == SB_BF16 && c->d_model % 128 == 0 && c->d_ffn % 128 == 0 &&
               (c->n_heads * c->head_dim) % 128 == 0 && c->vocab % 16 == 0;
-    return ok ? SB_PROJ_MFMA : SB_PROJ_VALU;
+    return ok ? SB_PROJ_MFMA_PACKED : SB_PROJ_VALU;
 }
 
 struct WsLayout {
@@ -126,7 +126,9 @@ struct sb_model {
     std::vector<const void*> w_qkv, w_o, w_gate_up, w_down, exit_head;
     hipStream_t stream;
     float *rope_cos, *rope_sin;
-    int proj;
+    int proj;      // SB_PROJ_VALU or SB_PROJ_MFMA (row-major or packed, see `packed`)
+    bool packed;   // the projection pointers below name tile-packed copies owned by the model
+    std::vector<void*> owned;  // device allocations to free
     int64_t layer_bytes, head_bytes;
 };
 
@@ -226,6 +228,7 @@ int64_t gemv_bytes(const GemvArgs& a) {
 }
 
 int gemv(sb_session* s, GemvArgs& a, int cls, hipStream_t st) {
+    a.packed = s->m->packed ? 1 : 0;
     ProfScope ps(s, cls, gemv_bytes(a), st);
     hipError_t e = s->m->proj == SB_PROJ_MFMA ? launch_gemv_mfma(a, st) : launch_gemv_valu(a, st);
     if (e != hipSuccess) return fail(SB_EDEVICE, "projection launch (N=%d K=%d M=%d epi=%d): %s", a.N, a.K, a.M, a.epi,
@@ -649,6 +652,8 @@ int32_t sb_load_model(const sb_config* cfg, const sb_weights* w, void* stream, s
     }
     m->stream = (hipStream_t)stream;
     m->proj = resolve_proj(cfg);
+    m->packed = m->proj == SB_PROJ_MFMA_PACKED;
+    if (m->packed) m->proj = SB_PROJ_MFMA;
     const int64_t es = (int64_t)esize(cfg->weight_dtype), d = cfg->d_model, f = cfg->d_ffn;
     const int64_t qkv_rows = (int64_t)(cfg->n_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
     m->layer_bytes = es * (qkv_rows * d + d * (int64_t)cfg->n_heads * cfg->head_dim + 3 * f * d);
@@ -668,11 +673,34 @@ int32_t sb_load_model(const sb_config* cfg, const sb_weights* w, void* stream, s
     if (e == hipSuccess) e = hipMalloc((void**)&m->rope_sin, hs.size() * 4);
     if (e == hipSuccess) e = hipMemcpy(m->rope_cos, hc.data(), hc.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(m->rope_sin, hs.data(), hs.size() * 4, hipMemcpyHostToDevice);
+    // tile-packed copies of the projection matrices
+    if (e == hipSuccess && m->packed) {
+        const int d = cfg->d_model, f = cfg->d_ffn, hq = cfg->n_heads * cfg->head_dim, V = cfg->vocab;
+        auto pack = [&](const void*& W, int N, int K) {
+            if (e != hipSuccess) return;
+            void* P = nullptr;
+            e = hipMalloc(&P, (size_t)N * K * 2);
+            if (e != hipSuccess) return;
+            m->owned.push_back(P);
+            e = launch_repack(W, P, N, K, m->stream);
+            W = P;
+        };
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            pack(m->w_qkv[l], (int)qkv_rows, d);
+            pack(m->w_o[l], d, hq);
+            pack(m->w_gate_up[l], 2 * f, d);
+            pack(m->w_down[l], d, f);
+        }
+        for (int l = 0; l < cfg->n_exit_heads; ++l) pack(m->exit_head[l], V, d);
+        pack(m->lm_head, V, d);
+        if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+    }
     if (e != hipSuccess) {
         if (m->rope_cos) (void)hipFree(m->rope_cos);
         if (m->rope_sin) (void)hipFree(m->rope_sin);
+        for (void* p : m->owned) (void)hipFree(p);
         delete m;
-        return fail(e == hipErrorOutOfMemory ? SB_ENOMEM : SB_EDEVICE, "load_model: rotary table: %s", hipGetErrorString(e));
+        return fail(e == hipErrorOutOfMemory ? SB_ENOMEM : SB_EDEVICE, "load_model: %s", hipGetErrorString(e));
     }
     *out = m;
     return SB_OK;
@@ -682,6 +710,7 @@ void sb_free_model(sb_model* m) {
     if (!m) return;
     (void)hipFree(m->rope_cos);
     (void)hipFree(m->rope_sin);
+    for (void* p : m->owned) (void)hipFree(p);
     delete m;
 }
 
@@ -963,8 +992,9 @@ static int op_check(const void* W, int32_t w_dtype, int32_t N, int32_t K, const 
     if (!W || !x) return fail(SB_EINVAL, "op: NULL operand");
     if (w_dtype != SB_FP32 && w_dtype != SB_BF16) return fail(SB_EINVAL, "op: w_dtype");
     if (N < 1 || K < 8 || K % 8 || M < 1 || M > SB_MAX_W) return fail(SB_EINVAL, "op: need N >= 1, K %% 8 == 0, 1 <= M <= %d", SB_MAX_W);
-    if (kernel != SB_PROJ_VALU && kernel != SB_PROJ_MFMA) return fail(SB_EINVAL, "op: kernel must be VALU or MFMA");
-    if (kernel == SB_PROJ_MFMA && (w_dtype != SB_BF16 || K % 128 || N % 16))
+    if (kernel != SB_PROJ_VALU && kernel != SB_PROJ_MFMA && kernel != SB_PROJ_MFMA_PACKED)
+        return fail(SB_EINVAL, "op: kernel must be VALU, MFMA or MFMA_PACKED");
+    if (kernel != SB_PROJ_VALU && (w_dtype != SB_BF16 || K % 128 || N % 16))
         return fail(SB_EINVAL, "op: MFMA path needs bf16 weights, K %% 128 == 0, N %% 16 == 0");
     if (((uintptr_t)W & 15) || ((uintptr_t)x & 15)) return fail(SB_EINVAL, "op: operands must be 16-byte aligned");
     return SB_OK;
@@ -977,7 +1007,8 @@ int32_t sb_op_gemv(const void* W, int32_t w_dtype, int32_t N, int32_t K, const f
     if (!y) return fail(SB_EINVAL, "op_gemv: y is NULL");
     GemvArgs g{};
     g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.y = y; g.ldy = N; g.M = M; g.epi = EPI_STORE;
-    if (kernel == SB_PROJ_MFMA) {
+    g.packed = kernel == SB_PROJ_MFMA_PACKED;
+    if (kernel != SB_PROJ_VALU) {
         if (!scratch || ((uintptr_t)scratch & 15)) return fail(SB_EINVAL, "op_gemv: MFMA path needs aligned scratch");
         g.xs = (uint16_t*)scratch;
         HIP_TRY(launch_split(x, (uint16_t*)scratch, M, K, (hipStream_t)stream));
@@ -985,6 +1016,13 @@ int32_t sb_op_gemv(const void* W, int32_t w_dtype, int32_t N, int32_t K, const f
     } else {
         HIP_TRY(launch_gemv_valu(g, (hipStream_t)stream));
     }
+    return SB_OK;
+}
+
+int32_t sb_op_repack(const void* W, int32_t N, int32_t K, void* packed, void* stream) {
+    if (!W || !packed || ((uintptr_t)W & 15) || ((uintptr_t)packed & 15)) return fail(SB_EINVAL, "op_repack: NULL / misaligned operand");
+    if (N < 16 || N % 16 || K < 128 || K % 128) return fail(SB_EINVAL, "op_repack: need N %% 16 == 0 and K %% 128 == 0");
+    HIP_TRY(launch_repack(W, packed, N, K, (hipStream_t)stream));
     return SB_OK;
 }
 
@@ -1006,7 +1044,8 @@ int32_t sb_op_head(const void* W, int32_t w_dtype, int32_t N, int32_t K, const f
     g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.M = M; g.epi = EPI_HEAD;
     g.head.T = T; g.head.partials = (float*)(sc + 256);
     g.head.logits = logits; g.head.argmax_out = argmax_out; g.head.conf_out = conf_out; g.head.post = POST_NONE;
-    if (kernel == SB_PROJ_MFMA) {
+    g.packed = kernel == SB_PROJ_MFMA_PACKED;
+    if (kernel != SB_PROJ_VALU) {
         g.xs = (uint16_t*)(sc + 256 + align_up((size_t)SB_MAX_W * nb * 16, 256));
         HIP_TRY(launch_split(x, const_cast<uint16_t*>(g.xs), M, K, (hipStream_t)stream));
         HIP_TRY(launch_gemv_mfma(g, (hipStream_t)stream));

@@ -29,12 +29,13 @@ def _variants(sb):
         "c1-fp32": (dict(), sb.PROJ_AUTO),
         "bf16-valu": (dict(weight_dtype=B, kv_dtype=B, d_ffn=768), sb.PROJ_VALU),
         "bf16-mfma": (dict(weight_dtype=B, kv_dtype=B, d_ffn=768), sb.PROJ_MFMA),
+        "bf16-mfma-packed": (dict(weight_dtype=B, kv_dtype=B, d_ffn=768), sb.PROJ_MFMA_PACKED),
         "bf16-mfma-gqa": (dict(weight_dtype=B, kv_dtype=B, d_ffn=768, n_kv_heads=2, rope_base=500000.0), sb.PROJ_AUTO),
         "fp32-gqa-bf16kv": (dict(n_kv_heads=1, kv_dtype=B), sb.PROJ_AUTO),
     }
 
 
-VARIANT_NAMES = ["c1-fp32", "bf16-valu", "bf16-mfma", "bf16-mfma-gqa", "fp32-gqa-bf16kv"]
+VARIANT_NAMES = ["c1-fp32", "bf16-valu", "bf16-mfma", "bf16-mfma-packed", "bf16-mfma-gqa", "fp32-gqa-bf16kv"]
 
 
 def _build(sb, name, n_layers=4, n_exit=2, seed=1001, max_seq=160):
@@ -291,3 +292,17 @@ def test_rewind_decode_and_kernel_timing(sb):
     assert prof["gate_up"]["bytes"] // prof["gate_up"]["launches"] >= 2 * shape.d_ffn * shape.d_model * es
     with pytest.raises(sb.SbError):
         s.profile_end()
+
+
+def test_packed_and_row_major_weights_give_identical_output(sb):
+    """The tile-packed copy only changes where the weights lie in memory."""
+    _, _, _, gm_a = _build(sb, "bf16-mfma", n_layers=4, n_exit=2, seed=41)
+    shape, w, om, gm_b = _build(sb, "bf16-mfma-packed", n_layers=4, n_exit=2, seed=41)
+    prompt = si.make_prompt(shape.vocab, 23, 51)
+    p = gpu_params(2, 4, 0.5, forced_exit=si.forced_exit_schedule(5, 300, 1, 2))
+    sa, sb_ = gm_a.session(), gm_b.session()
+    sa.debug_enable(True); sb_.debug_enable(True)
+    a, _ = sa.generate(prompt, 40, p)
+    b, _ = sb_.generate(prompt, 40, p)
+    assert a.tolist() == b.tolist()
+    assert np.array_equal(sa.debug_logits(0, 0), sb_.debug_logits(0, 0))

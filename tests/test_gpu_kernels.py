@@ -71,20 +71,26 @@ def test_gemv_mfma(T, N, K, M):
     g = np.random.default_rng(N + K + M + 1)
     W = _rand_w(g, N, K, True)
     x = g.standard_normal((M, K)).astype(np.float32)
-    y = sb.op_gemv(_dev(T, W), _dev(T, x), sb.PROJ_MFMA).cpu().numpy()
+    Wd = _dev(T, W)
+    y = sb.op_gemv(Wd, _dev(T, x), sb.PROJ_MFMA).cpu().numpy()
     ref = _oracle_rows(W, x)
     # activations carry 16 mantissa bits (two bf16 parts): error ~ 2^-17 per term
     assert np.max(np.abs(y - ref)) <= 3e-5 * np.max(np.abs(ref)) + 1e-7
+    # the tile-packed copy of the weights gives the same bits
+    yp = sb.op_gemv(sb.op_repack(Wd), _dev(T, x), sb.PROJ_MFMA_PACKED).cpu().numpy()
+    assert np.array_equal(yp, y)
 
 
-@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+@pytest.mark.parametrize("kernel", ["valu", "mfma", "mfma_packed"])
 def test_gemv_row_result_does_not_depend_on_m(T, kernel):
     """A row's output is bit-identical whether it is computed alone or with others."""
     import paper_2604_12247_amd as sb
-    k = sb.PROJ_VALU if kernel == "valu" else sb.PROJ_MFMA
+    k = {"valu": sb.PROJ_VALU, "mfma": sb.PROJ_MFMA, "mfma_packed": sb.PROJ_MFMA_PACKED}[kernel]
     g = np.random.default_rng(5)
     for N, K in ((4096, 4096), (1024, 11008), (32000, 256)):
         W = _dev(T, _rand_w(g, N, K, True))
+        if kernel == "mfma_packed":
+            W = sb.op_repack(W)
         x = g.standard_normal((8, K)).astype(np.float32)
         y8 = sb.op_gemv(W, _dev(T, x), k).cpu().numpy()
         for M in (1, 2, 5):
@@ -95,16 +101,17 @@ def test_gemv_row_result_does_not_depend_on_m(T, kernel):
         assert np.array_equal(y1[0], y8[3])
 
 
-@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+@pytest.mark.parametrize("kernel", ["valu", "mfma", "mfma_packed"])
 @pytest.mark.parametrize("N,K,M", [(1024, 256, 1), (32000, 4096, 1), (32000, 4096, 6), (128256, 512, 2)])
 def test_head_argmax_and_confidence(T, kernel, N, K, M):
     import paper_2604_12247_amd as sb
-    k = sb.PROJ_VALU if kernel == "valu" else sb.PROJ_MFMA
+    k = {"valu": sb.PROJ_VALU, "mfma": sb.PROJ_MFMA, "mfma_packed": sb.PROJ_MFMA_PACKED}[kernel]
     g = np.random.default_rng(N + K + M)
     W = _rand_w(g, N, K, True, std=0.05)
     x = g.standard_normal((M, K)).astype(np.float32)
+    Wd = sb.op_repack(_dev(T, W)) if kernel == "mfma_packed" else _dev(T, W)
     for Tl in (2.0, 1.0):
-        am, cf, z = sb.op_head(_dev(T, W), _dev(T, x), Tl, k, want_logits=True)
+        am, cf, z = sb.op_head(Wd, _dev(T, x), Tl, k, want_logits=True)
         am, cf, z = am.cpu().numpy(), cf.cpu().numpy(), z.cpu().numpy()
         ref = _oracle_rows(W, x)
         assert np.max(np.abs(z - ref)) <= 2e-2 * np.max(np.abs(ref))
@@ -130,8 +137,9 @@ def test_head_ties_take_lowest_index(T):
         W2 = W.copy()
         for r in rows:
             W2[r] = row
-        for k in (sb.PROJ_VALU, sb.PROJ_MFMA):
-            am, cf, _ = sb.op_head(_dev(T, W2), _dev(T, x), 1.0, k)
+        for k in (sb.PROJ_VALU, sb.PROJ_MFMA, sb.PROJ_MFMA_PACKED):
+            Wd = sb.op_repack(_dev(T, W2)) if k == sb.PROJ_MFMA_PACKED else _dev(T, W2)
+            am, cf, _ = sb.op_head(Wd, _dev(T, x), 1.0, k)
             assert int(am.cpu()[0]) == min(rows)
 
 
