@@ -526,16 +526,10 @@ hipError_t launch_gemv_valu(const GemvArgs& a, hipStream_t st) {
 // k order inside a block is free as long as A and B use the same one).
 #define SB_KOFF(lq, u) ((u) * 32 + (lq) * 8)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-#ifndef SB_PACKED_NT
-#define SB_PACKED_NT 1
-#endif
+// streaming (non-temporal) 128-bit load: weights are read once per launch
 __device__ __forceinline__ uint4 ld_weights_packed(const uint16_t* p) {
-#if SB_PACKED_NT
     u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
-#else
-    return *reinterpret_cast<const uint4*>(p);
-#endif
 }
 
 // W [N][K] row-major -> packed tiles (N % 16 == 0, K % 128 == 0); one thread moves 16 bytes.
@@ -598,7 +592,9 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
 
     // Ring of DEPTH register buffers, DEPTH - 1 k blocks in flight per wave.  The
     // stage loop is fully unrolled, so every buffer index is a compile-time constant.
-    constexpr int DEPTH = (RT == 1) ? 3 : 2;  // measured: deeper rings lose occupancy for nothing
+    // chosen by measurement: three buffers, but two for the eight-wave blocks of the
+    // narrow projections (a deeper ring there only costs occupancy)
+    constexpr int DEPTH = (RT == 1 && WPB == 8) ? 2 : 3;
     uint4 wbuf[DEPTH][RT][4], bbuf[DEPTH][4];
     // k block index is clamped instead of tested: loads past the end re-read the last
     // block (unused), which keeps the steady-state loop free of bounds tests.
