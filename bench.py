@@ -20,7 +20,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes fetched per launch of the gate/up projection at the C2 shape, from
 # rocprofv3 --pmc FETCH_SIZE scaled by the same counter's reading on the plain copy
 # kernel (2.000 KiB per count); summary in profiles/c2_projection_hbm_traffic.txt
-MEASURED_TRAFFIC = {"C2": 88849.6 * 2.0 * 1024}
+MEASURED_TRAFFIC = {"C2": 88385.6 * 2.0 * 1024}
 
 
 def log(*a):
@@ -130,7 +130,7 @@ def main():
     gu_raw_us = gu["total_ms"] * 1e3 / gu["launches"]
     gu_us = gu_raw_us - pair_us
     gu_bytes = gu["bytes"] / gu["launches"]
-    roofline = {"bound": "hbm", "kernel": "gate_up projection + SwiGLU (gemv_mfma_kernel<2,SWIGLU>)",
+    roofline = {"bound": "hbm", "kernel": "gate_up projection + SwiGLU (gemv_mfma_kernel<2,SWIGLU,4,packed>)",
                 "achieved": round(gu_bytes / gu_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gu_bytes / gu_us / 1e3 / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC.get(args.config) if not args.gen else None,
