@@ -800,15 +800,15 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     constexpr int DSPLIT = 256 / CH;                          // score threads per key
     constexpr int DPT = HD / DSPLIT;                          // dims per score thread
     constexpr int NKV = DPT / EPV;                            // 16-byte loads per score thread
-    constexpr int DG = HD / EPV;                              // dim groups (value threads per key)
-    constexpr int KS = 256 / DG;                              // key slots
+    // values mapping: each wave owns HD/4 dims and sees every key of the chunk, so the
+    // sum over keys ends inside the wave (no cross-wave stage, no LDS buffer for it)
+    constexpr int DGW = HD / 4 / EPV;                         // 16-byte dim groups per wave
+    constexpr int KS = 64 / DGW;                              // key slots (lanes per dim group)
     constexpr int KPT = CH / KS;                              // keys per value thread
-    constexpr int KSW = 64 / DG;                              // key slots inside one wave
     static_assert(DPT <= HALF && HALF % DPT == 0, "a score thread's dims lie in one rotary half");
-    static_assert(KSW >= 1 && KS * KPT == CH, "value mapping");
+    static_assert(DGW >= 1 && KS * KPT == CH, "value mapping");
     __shared__ __attribute__((aligned(16))) float qs[QG * HD];
     __shared__ __attribute__((aligned(16))) float sp[DSPLIT * QG * CH];  // partial scores, then probabilities
-    __shared__ __attribute__((aligned(16))) float comb[4 * QG * HD];     // per-wave weighted values
     __shared__ float s_m[QG], s_l[QG];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -852,7 +852,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         if (kkey < a.pos0) kreg[i] = *reinterpret_cast<const uint4*>(kbase + kaddr + i * EPV);
     }
     // values mapping: dims [vd0, vd0 + EPV), keys vks + KS * i
-    const int vd0 = (tid % DG) * EPV, vks = tid / DG;
+    const int vd0 = wave * (HD / 4) + (lane % DGW) * EPV, vks = lane / DGW;
     uint4 vreg[KPT];
     size_t vaddr[KPT];
 #pragma unroll
@@ -969,29 +969,18 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
 #pragma unroll
                 for (int e = 0; e < EPV; ++e) o[e] = fmaf(p, vf[i][e], o[e]);
             }
-            // key slots of this wave, fixed tree
+            // sum over the key slots: fixed shuffle tree inside the wave
 #pragma unroll
-            for (int off = DG; off < 64; off <<= 1)
+            for (int off = DGW; off < 64; off <<= 1)
 #pragma unroll
                 for (int e = 0; e < EPV; ++e) o[e] += __shfl_xor(o[e], off, 64);
-            if (lane < DG) {
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) comb[(wave * QG + qi) * HD + vd0 + e] = o[e];
-            }
-        }
-    }
-    __syncthreads();
-    {
-        const int stride = HD + 2;
-        for (int i = tid; i < nq * HD; i += 256) {
-            const int qi = i / HD, d = i - qi * HD;
             const int qq = q0 + qi, r = qq / G, gi = qq - r * G;
-            if (key0 > a.pos0 + r) continue;  // no key of this chunk is visible to the row
-            float v = ((comb[(0 * QG + qi) * HD + d] + comb[(1 * QG + qi) * HD + d]) + comb[(2 * QG + qi) * HD + d]) +
-                      comb[(3 * QG + qi) * HD + d];
-            float* p = a.partials + ((size_t)(r * Hq + g * G + gi) * a.max_chunks + chunk) * stride;
-            p[2 + d] = v;
-            if (d == 0) { p[0] = s_m[qi]; p[1] = s_l[qi]; }
+            if (lane < DGW && key0 <= a.pos0 + r) {  // (a chunk with no visible key leaves no partial)
+                float* p = a.partials + ((size_t)(r * Hq + g * G + gi) * a.max_chunks + chunk) * (HD + 2);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) p[2 + vd0 + e] = o[e];
+                if (tid == 0) { p[0] = s_m[qi]; p[1] = s_l[qi]; }
+            }
         }
     }
 }

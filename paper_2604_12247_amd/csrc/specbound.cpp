@@ -147,7 +147,6 @@ struct sb_session {
     bool round_closed;
     int64_t draft_counter;
     bool debug;
-    bool final_logits_valid;
     sb_stats st;
     // Exit heads run on a second stream next to the following layer when the exit
     // layer is known in advance (forced schedules): events order the two streams.
@@ -363,7 +362,7 @@ EmbedNorm embed_norm(sb_session* s, int slot0) {
 
 void reset_session(sb_session* s) {
     s->c = 0; s->has_pending = false; s->n_slots = 0; s->n_drafts = 0; s->round_closed = false;
-    s->draft_counter = 0; s->final_logits_valid = false;
+    s->draft_counter = 0;
     memset(&s->st, 0, sizeof s->st);
 }
 
@@ -404,7 +403,6 @@ int prefill_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first
     if (rc) return rc;
     s->st.final_head_sweeps++;
     if ((rc = readback(s))) return rc;
-    s->final_logits_valid = s->debug;
     s->pending = s->h_round->g[0];
     s->has_pending = true;
     *first_token = s->pending;
@@ -532,7 +530,6 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     if ((rc = run_head(s, m->lm_head, m->final_norm, 0, M, h, m->stream))) return rc;
     s->st.final_head_sweeps++;
     if ((rc = readback(s))) return rc;
-    s->final_logits_valid = s->debug;
     const DevRound& R = *s->h_round;
     if (R.n_emit < 1 || R.n_emit > M) return fail(SB_EDEVICE, "verify: device returned n_emit = %d", R.n_emit);
     sb_verify_result res{};

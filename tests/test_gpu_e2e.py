@@ -306,3 +306,59 @@ def test_packed_and_row_major_weights_give_identical_output(sb):
     b, _ = sb_.generate(prompt, 40, p)
     assert a.tolist() == b.tolist()
     assert np.array_equal(sa.debug_logits(0, 0), sb_.debug_logits(0, 0))
+
+
+@pytest.mark.parametrize("name", ["c1-fp32", "bf16-mfma-packed"])
+def test_computed_exits_that_fire_match_the_oracle(sb, name):
+    """Exit heads with peaked logits (norm gains scaled up), so that the confidence test of
+    Eq. 2 really decides: exits at different layers, depth bounds and width bounds all occur.
+    Exit layers, statuses and accept lengths must equal the oracle's; a step whose oracle
+    confidence lies within 1e-3 of the threshold (or whose draft is a near-tie) may legitimately
+    differ, and the comparison stops there."""
+    kw, proj = _variants(sb)[name]
+    shape = si.tiny_shape(n_layers=6, n_exit_heads=3, **kw)
+    w = si.make_weights(shape, 43, gain_jitter=0.1)
+    for l in range(3):
+        w[f"exit_norm.{l}"] = (w[f"exit_norm.{l}"] * 12.0).astype(np.float32)
+    om, gm = Oracle(shape, w, 160), gpu_model(shape, w, 160, proj)
+    prompt = si.make_prompt(shape.vocab, 15, 53)
+    T = sb.temperature_schedule(1.0, 3, 3)          # Eq. 1 with alpha = 1 over the three head layers
+    assert np.allclose(T, orc.temperature_schedule(1.0, 3, 3))
+    tau = 0.35
+    po, pg = orc.OrcParams(3, 4, T, tau), sb.Params(3, 4, T, tau)
+    osn, gsn = om.session(), gm.session()
+    assert osn.prefill(prompt) == gsn.prefill(prompt)
+    exits, statuses, steps = set(), set(), 0
+    diverged = False
+    for rnd in range(14):
+        while True:
+            ro, rg = osn.draft_step(po), gsn.draft_step(pg)
+            steps += 1
+            near_thr = abs(ro["confidence"] - tau) <= 1e-3
+            if (ro["status"], ro["exit_layer"]) != (rg["status"], rg["exit_layer"]):
+                assert near_thr, (rnd, ro, rg)
+                diverged = True
+                break
+            assert abs(ro["confidence"] - rg["confidence"]) <= 1e-3
+            if ro["token"] != rg["token"]:
+                srt = np.sort(osn.head_logits())
+                assert srt[-1] - srt[-2] < 1e-2, (rnd, ro, rg)
+                diverged = True
+                break
+            exits.add(ro["exit_layer"]); statuses.add(ro["status"])
+            if ro["status"] != orc.EXITED:
+                break
+        if diverged:
+            break
+        vo, vg = osn.verify(po), gsn.verify(pg)
+        if vo["tokens"][: vo["n_emit"]] != vg["tokens"][: vg["n_emit"]]:
+            break                                   # near-tie in a final head: sequences part ways
+        for k in ("n_rows", "n_drafts", "n_matched", "n_emit", "align_layer"):
+            assert vo[k] == vg[k], (rnd, k, vo, vg)
+    assert steps >= 12
+    assert len(exits - {0}) >= 2 and 0 in exits, exits          # exits at several layers and depth bounds
+    # free-running generation with the same parameters stays greedy
+    ar, _ = gm.session().generate(prompt, 40, gpu_params(0, 1))
+    out, st = gm.session().generate(prompt, 40, pg)
+    assert out.tolist() == ar.tolist()
+    assert st["drafts"] > 0 and st["exit_hist"][0] > 0
