@@ -281,8 +281,10 @@ int32_t sb_rope_table_host(int32_t head_dim, float base, int32_t n_pos, float *c
  * pos0..pos0+M-1.  qkv [M][(n_heads + 2 n_kv_heads) head_dim] float holds the
  * rows' raw projections (q heads, k heads, v heads).  Rotated k and v of the new
  * rows are written (rounded to kv_dtype) into the paged pool
- * [layer][2][n_pages][n_kv_heads][SB_KV_BLOCK][head_dim]; table [n_pages] maps
- * logical to physical pages; rope_cos/sin: device tables with at least pos0+M
+ * [layer][2 (k, v)][n_pages][n_kv_heads][SB_KV_BLOCK][head_dim] (in a bf16 pool
+ * the v slabs are held transposed, [head_dim][SB_KV_BLOCK]: the layout is the
+ * library's own, read it back with sb_debug_kv); table [n_pages] maps logical
+ * to physical pages; rope_cos/sin: device tables with at least pos0+M
  * rows.  Each row attends to keys 0..its own position (scale 1/sqrt(head_dim));
  * out [M][n_heads head_dim] float.  scratch: sb_op_attention_scratch_bytes(). */
 int32_t sb_op_attention(const float *qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,

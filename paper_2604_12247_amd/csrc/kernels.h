@@ -91,7 +91,8 @@ hipError_t launch_repack(const void* W, void* P, int32_t N, int32_t K, hipStream
 hipError_t launch_split(const float* x, uint16_t* xs, int32_t M, int32_t K, hipStream_t st);
 
 struct KvLayout {
-    void* pool;            // [layer][2][n_pages][n_kv_heads][SB_KV_BLOCK][head_dim]
+    void* pool;            // [layer][2][n_pages][n_kv_heads][SB_KV_BLOCK][head_dim]; V slabs of a bf16
+                           // pool are transposed: [head_dim][SB_KV_BLOCK]
     const int32_t* table;  // logical page -> physical page (device)
     int32_t n_pages, n_kv_heads, head_dim, kv_dtype;
 };

@@ -985,43 +985,312 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     }
 }
 
+// The same step for a bf16 cache, with both contractions on the matrix cores.
+//   scores   S = Q K^T: A operand = rotated queries (16 rows; fp32 carried as a bf16
+//            hi + lo pair, two MFMAs), B operand = keys straight from the cache (a lane's
+//            8 consecutive dims of one key are one 16-byte load); a wave takes 32 keys
+//   softmax  wave per query over the chunk's keys, probabilities left in LDS as hi + lo
+//   values   O = P V: A operand = probabilities, B operand = values.  A lane needs 8
+//            consecutive keys of one dim, so the V pages of a bf16 cache are stored
+//            transposed, [kv head][dim][16 keys]: the operand is again one 16-byte load
+//            and a wave's loads cover whole pages.  A wave owns HD/4 output dims.
+// Every output row of an MFMA depends on its own operand row only, so a query's
+// partial does not depend on which other queries share the block.
+template <int HD>
+__global__ __launch_bounds__(256, 4) void attn_mfma_kernel(AttnArgs a) {
+    constexpr int CH = 128, QG = 16, HALF = HD / 2;
+    constexpr int KSQ = HD / 32;      // k steps (of 32 dims) of the score product
+    constexpr int KSV = CH / 32;      // k steps (of 32 keys) of the value product
+    constexpr int DT = HD / 64;       // 16-dim output tiles per wave
+    constexpr int QS = HD + 8;        // padded LDS row strides (bf16 elements / floats)
+    constexpr int PS = CH + 8;
+    constexpr int SS = CH + 4;
+    __shared__ __attribute__((aligned(16))) uint16_t q_hi[QG * QS], q_lo[QG * QS];
+    __shared__ __attribute__((aligned(16))) uint16_t p_hi[QG * PS], p_lo[QG * PS];
+    __shared__ __attribute__((aligned(16))) float s_s[QG * SS];
+    __shared__ float s_m[QG], s_l[QG];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15, lq = lane >> 4;
+    const int g = blockIdx.x, chunk = blockIdx.y, qg = blockIdx.z;
+    const int Hq = a.n_heads, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
+    const int nq_total = a.M * G, q0 = qg * QG;
+    const int nq = (nq_total - q0 < QG) ? (nq_total - q0) : QG;
+    const int key0 = chunk * CH, n_total = a.pos0 + a.M;
+    const float scale = 1.0f / sqrtf((float)HD);
+    const size_t page_elems = (size_t)Hkv * SB_KV_BLOCK * HD;
+    uint16_t* const kbase = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 0) * a.kv.n_pages * page_elems;
+    uint16_t* const vbase = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 1) * a.kv.n_pages * page_elems;
+    const bool has_new = key0 + CH > a.pos0;  // the chunk holds keys of the new rows
+
+    // ---- issue every global load first: q (+ its rotary factors), K, V
+    constexpr int QIT = QG * HALF / 256;
+    float qx[QIT], qy[QIT], qc[QIT], qsn[QIT];
+#pragma unroll
+    for (int it = 0; it < QIT; ++it) {
+        const int i = tid + it * 256;
+        const int qi = i / HALF, j = i - qi * HALF;
+        qx[it] = qy[it] = qsn[it] = 0.f;
+        qc[it] = 1.f;
+        if (qi < nq) {
+            int qq = q0 + qi, r = qq / G, gi = qq - r * G;
+            const float* qp = a.q + (size_t)r * a.qkv_rows + (size_t)(g * G + gi) * HD;
+            qx[it] = qp[j];
+            qy[it] = qp[j + HALF];
+            qc[it] = a.rope_cos[(size_t)(a.pos0 + r) * HALF + j];
+            qsn[it] = a.rope_sin[(size_t)(a.pos0 + r) * HALF + j];
+        }
+    }
+    // K operands: tile t of this wave = keys key0 + wave*32 + t*16 + li (one page), dims ks*32 + lq*8 ..
+    uint4 kreg[2][KSQ];
+    size_t kaddr[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int key = key0 + wave * 32 + t * 16 + li;
+        kaddr[t] = 0;
+        if (key < n_total) kaddr[t] = (size_t)a.kv.table[key / SB_KV_BLOCK] * page_elems + ((size_t)g * SB_KV_BLOCK + li) * HD + lq * 8;
+#pragma unroll
+        for (int ks = 0; ks < KSQ; ++ks) {
+            kreg[t][ks] = make_uint4(0, 0, 0, 0);
+            if (key < a.pos0) kreg[t][ks] = *reinterpret_cast<const uint4*>(kbase + kaddr[t] + ks * 32);
+        }
+    }
+    // V operands: dim (wave*DT + dt)*16 + li, keys key0 + ks*32 + lq*8 .. +8 (half a page row)
+    uint4 vreg[DT][KSV];
+    size_t vaddr[KSV];
+#pragma unroll
+    for (int ks = 0; ks < KSV; ++ks) {
+        const int kf = key0 + ks * 32 + lq * 8;  // first key of this lane's 8
+        vaddr[ks] = 0;
+        if (kf < n_total) vaddr[ks] = (size_t)a.kv.table[kf / SB_KV_BLOCK] * page_elems + ((size_t)g * HD + wave * DT * 16 + li) * SB_KV_BLOCK + (lq & 1) * 8;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            vreg[dt][ks] = make_uint4(0, 0, 0, 0);
+            if (kf < a.pos0) vreg[dt][ks] = *reinterpret_cast<const uint4*>(vbase + vaddr[ks] + dt * 16 * SB_KV_BLOCK);
+        }
+    }
+
+    // ---- rotated queries -> LDS as hi + lo
+#pragma unroll
+    for (int it = 0; it < QIT; ++it) {
+        const int i = tid + it * 256;
+        const int qi = i / HALF, j = i - qi * HALF;
+        const float u = qx[it] * qc[it] - qy[it] * qsn[it], v = qy[it] * qc[it] + qx[it] * qsn[it];
+        const uint16_t uh = f2bf(u), vh = f2bf(v);
+        q_hi[qi * QS + j] = uh;
+        q_lo[qi * QS + j] = f2bf(u - bf2f(uh));
+        q_hi[qi * QS + j + HALF] = vh;
+        q_lo[qi * QS + j + HALF] = f2bf(v - bf2f(vh));
+    }
+    // ---- keys and values of the new rows: built from qkv, appended by query group 0
+    if (has_new) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int key = key0 + wave * 32 + t * 16 + li;
+            if (key >= a.pos0 && key < n_total) {
+                const float* kp = a.q + (size_t)(key - a.pos0) * a.qkv_rows + (size_t)(Hq + g) * HD;
+#pragma unroll
+                for (int ks = 0; ks < KSQ; ++ks) {
+                    const int d0 = ks * 32 + lq * 8;
+                    const bool lo = d0 < HALF;
+                    const int dj = lo ? d0 : d0 - HALF;
+                    float f[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int j = dj + e;
+                        float c = a.rope_cos[(size_t)key * HALF + j], sn = a.rope_sin[(size_t)key * HALF + j];
+                        float x = kp[j], y = kp[j + HALF];
+                        f[e] = lo ? (x * c - y * sn) : (y * c + x * sn);
+                    }
+                    kreg[t][ks] = KvVec<uint16_t>::pack(f);
+                    if (qg == 0) *reinterpret_cast<uint4*>(kbase + kaddr[t] + ks * 32) = kreg[t][ks];
+                }
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < KSV; ++ks) {
+            const int kf = key0 + ks * 32 + lq * 8;
+            if (kf + 8 > a.pos0 && kf < n_total) {  // some of the 8 keys are new
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const int d = (wave * DT + dt) * 16 + li;
+                    uint32_t w[4] = {vreg[dt][ks].x, vreg[dt][ks].y, vreg[dt][ks].z, vreg[dt][ks].w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int key = kf + e;
+                        if (key >= a.pos0) {  // new row, or past the end: zero
+                            uint32_t h = 0;
+                            if (key < n_total) h = f2bf(a.q[(size_t)(key - a.pos0) * a.qkv_rows + (size_t)(Hq + Hkv + g) * HD + d]);
+                            w[e >> 1] = (e & 1) ? ((w[e >> 1] & 0x0000ffffu) | (h << 16)) : ((w[e >> 1] & 0xffff0000u) | h);
+                        }
+                    }
+                    vreg[dt][ks] = make_uint4(w[0], w[1], w[2], w[3]);
+                    if (qg == 0) *reinterpret_cast<uint4*>(vbase + vaddr[ks] + dt * 16 * SB_KV_BLOCK) = vreg[dt][ks];
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- scores of this wave's 32 keys against the 16 query rows
+    {
+        f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int ks = 0; ks < KSQ; ++ks) {
+            const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&q_hi[li * QS + ks * 32 + lq * 8]));
+            const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&q_lo[li * QS + ks * 32 + lq * 8]));
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const bf16x8 kb = __builtin_bit_cast(bf16x8, kreg[t][ks]);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, kb, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, kb, acc[t], 0, 0, 0);
+            }
+        }
+        // result register r of lane (li, lq): query 4*lq + r, key li of the tile
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s_s[(4 * lq + r) * SS + wave * 32 + t * 16 + li] = acc[t][r];
+    }
+    __syncthreads();
+    // ---- softmax partial of each query over the chunk (one wave per query)
+    for (int qi = wave; qi < QG; qi += 4) {
+        if (qi >= nq) {  // unused operand rows: defined values
+            p_hi[qi * PS + lane] = p_hi[qi * PS + lane + 64] = 0;
+            p_lo[qi * PS + lane] = p_lo[qi * PS + lane + 64] = 0;
+            continue;
+        }
+        const int r = (q0 + qi) / G;
+        float sc[2];
+        float mx = -SB_INF;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int t = lane + 64 * h;
+            sc[h] = (key0 + t <= a.pos0 + r) ? s_s[qi * SS + t] * scale : -SB_INF;
+            mx = fmaxf(mx, sc[h]);
+        }
+        mx = wave_max(mx);
+        float l = 0.f;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float p = (mx == -SB_INF) ? 0.f : expf(sc[h] - mx);
+            const uint16_t ph = f2bf(p);
+            p_hi[qi * PS + lane + 64 * h] = ph;
+            p_lo[qi * PS + lane + 64 * h] = f2bf(p - bf2f(ph));
+            l += p;
+        }
+        l = wave_sum(l);
+        if (lane == 0) { s_m[qi] = mx; s_l[qi] = l; }
+    }
+    __syncthreads();
+    // ---- weighted values: this wave's DT tiles of 16 dims, all keys of the chunk
+    {
+        f32x4 o[DT];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KSV; ++ks) {
+            const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&p_hi[li * PS + ks * 32 + lq * 8]));
+            const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&p_lo[li * PS + ks * 32 + lq * 8]));
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const bf16x8 vb = __builtin_bit_cast(bf16x8, vreg[dt][ks]);
+                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, vb, o[dt], 0, 0, 0);
+                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, vb, o[dt], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int qi = 4 * lq + r;
+            if (qi >= nq) continue;
+            const int qq = q0 + qi, rr = qq / G, gi = qq - rr * G;
+            if (key0 > a.pos0 + rr) continue;  // (a chunk with no visible key leaves no partial)
+            float* p = a.partials + ((size_t)(rr * Hq + g * G + gi) * a.max_chunks + chunk) * (HD + 2);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) p[2 + (wave * DT + dt) * 16 + li] = o[dt][r];
+            if (wave == 0 && li == 0) { p[0] = s_m[qi]; p[1] = s_l[qi]; }
+        }
+    }
+}
+
 // Second stage: one block per (row, query head) merges that row's chunk partials
-// in ascending chunk order (online-softmax rule).
+// (online-softmax rule against the row's overall maximum).  A thread owns two dims;
+// the chunks are dealt round-robin to the block's thread groups so that all loads
+// of a short context are in flight at once, each group adds its chunks in ascending
+// order and the groups are added in index order.  The order depends on the row's
+// position only.
 template <int HD, int CH>
-__global__ void attn_merge_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     constexpr int MAXC = 512;
+    constexpr int TPG = HD / 2;       // threads per group
+    constexpr int NG = 256 / TPG;     // chunk groups
+    constexpr int U = 8;              // loads in flight per thread
     __shared__ float sm[MAXC], sl[MAXC];
-    const int r = blockIdx.y, hq = blockIdx.x, d = threadIdx.x;
+    __shared__ float red[4];
+    __shared__ __attribute__((aligned(8))) float go[NG][HD];
+    __shared__ float gl[NG];
+    const int r = blockIdx.y, hq = blockIdx.x, tid = threadIdx.x;
+    const int grp = tid / TPG, dp = tid % TPG;
     const int Hq = a.n_heads, stride = HD + 2;
     const int nc = (a.pos0 + r) / CH + 1;
     const float* p = a.partials + (size_t)(r * Hq + hq) * a.max_chunks * stride;
-    for (int c = d; c < nc; c += HD) {
-        sm[c] = p[c * stride];
-        sl[c] = p[c * stride + 1];
+    // this thread's first U chunks' values are requested before anything else
+    float2 av[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int c = grp + NG * u;
+        av[u] = make_float2(0.f, 0.f);
+        if (c < nc) av[u] = *reinterpret_cast<const float2*>(p + (size_t)c * stride + 2 + 2 * dp);
     }
-    __syncthreads();
     float mx = -SB_INF;
-    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, sm[c]);
-    float L = 0.f, O = 0.f;
-    int c = 0;
-    for (; c + 4 <= nc; c += 4) {  // four independent loads in flight
-        float a0 = p[(c + 0) * stride + 2 + d], a1 = p[(c + 1) * stride + 2 + d];
-        float a2 = p[(c + 2) * stride + 2 + d], a3 = p[(c + 3) * stride + 2 + d];
-        float w0 = expf(sm[c] - mx), w1 = expf(sm[c + 1] - mx), w2 = expf(sm[c + 2] - mx), w3 = expf(sm[c + 3] - mx);
-        L += sl[c] * w0; O += a0 * w0;
-        L += sl[c + 1] * w1; O += a1 * w1;
-        L += sl[c + 2] * w2; O += a2 * w2;
-        L += sl[c + 3] * w3; O += a3 * w3;
+    for (int c = tid; c < nc; c += 256) {
+        const float2 ml = *reinterpret_cast<const float2*>(p + (size_t)c * stride);
+        sm[c] = ml.x;
+        sl[c] = ml.y;
+        mx = fmaxf(mx, ml.x);
     }
-    for (; c < nc; ++c) {
-        float w = expf(sm[c] - mx);
-        L += sl[c] * w;
-        O += p[c * stride + 2 + d] * w;
+    mx = wave_max(mx);
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float L = 0.f, O0 = 0.f, O1 = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int c = grp + NG * u;
+        if (c < nc) {
+            const float w = expf(sm[c] - mx);
+            L += sl[c] * w; O0 += av[u].x * w; O1 += av[u].y * w;
+        }
     }
-    float v = O / L;
-    size_t col = (size_t)hq * HD + d;
-    if (a.out) a.out[(size_t)r * Hq * HD + col] = v;
-    if (a.out_split) split_store(a.out_split, Hq * HD, r, (int)col, v);
+    for (int c0 = grp + NG * U; c0 < nc; c0 += NG * U) {  // long contexts: further rounds of U loads
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + NG * u;
+            av[u] = make_float2(0.f, 0.f);
+            if (c < nc) av[u] = *reinterpret_cast<const float2*>(p + (size_t)c * stride + 2 + 2 * dp);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + NG * u;
+            if (c < nc) {
+                const float w = expf(sm[c] - mx);
+                L += sl[c] * w; O0 += av[u].x * w; O1 += av[u].y * w;
+            }
+        }
+    }
+    go[grp][2 * dp] = O0;
+    go[grp][2 * dp + 1] = O1;
+    if (dp == 0) gl[grp] = L;
+    __syncthreads();
+    if (tid < HD) {
+        float Ls = 0.f, Os = 0.f;
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) { Ls += gl[gi]; Os += go[gi][tid]; }
+        const float v = Os / Ls;
+        const size_t col = (size_t)hq * HD + tid;
+        if (a.out) a.out[(size_t)r * Hq * HD + col] = v;
+        if (a.out_split) split_store(a.out_split, Hq * HD, r, (int)col, v);
+    }
 }
 
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype) {
@@ -1039,11 +1308,11 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     if (!a.rope_cos || !a.rope_sin) return hipErrorInvalidValue;
     dim3 mgrid(a.n_heads, a.M);
     if (a.kv.kv_dtype == SB_BF16) {
-        if (hd == 128) { attn_kernel<uint16_t, 128><<<grid, 256, 0, st>>>(a); attn_merge_kernel<128, 128><<<mgrid, 128, 0, st>>>(a); }
-        else { attn_kernel<uint16_t, 64><<<grid, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 64, 0, st>>>(a); }
+        if (hd == 128) { attn_mfma_kernel<128><<<grid, 256, 0, st>>>(a); attn_merge_kernel<128, 128><<<mgrid, 256, 0, st>>>(a); }
+        else { attn_mfma_kernel<64><<<grid, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }
     } else {
-        if (hd == 128) { attn_kernel<float, 128><<<grid, 256, 0, st>>>(a); attn_merge_kernel<128, 64><<<mgrid, 128, 0, st>>>(a); }
-        else { attn_kernel<float, 64><<<grid, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 64, 0, st>>>(a); }
+        if (hd == 128) { attn_kernel<float, 128><<<grid, 256, 0, st>>>(a); attn_merge_kernel<128, 64><<<mgrid, 256, 0, st>>>(a); }
+        else { attn_kernel<float, 64><<<grid, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }
     }
     return hipGetLastError();
 }

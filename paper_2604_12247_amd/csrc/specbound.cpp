@@ -958,18 +958,21 @@ int32_t sb_debug_kv(sb_session* s, int32_t layer, int32_t pos, float* k_out, flo
     HIP_TRY(hipMemcpy(table.data(), s->kv.table, table.size() * 4, hipMemcpyDeviceToHost));
     const size_t es = esize(c.kv_dtype);
     const int page = table[pos / SB_KV_BLOCK], t = pos % SB_KV_BLOCK;
-    std::vector<char> tmp((size_t)c.head_dim * es);
+    // one kv head's slab of a page: K [16 keys][head_dim]; V the same for an fp32 cache and
+    // transposed, [head_dim][16 keys], for a bf16 cache
+    std::vector<char> slab((size_t)SB_KV_BLOCK * c.head_dim * es);
     for (int which = 0; which < 2; ++which)
         for (int h = 0; h < c.n_kv_heads; ++h) {
-            size_t off = ((((size_t)(layer * 2 + which) * s->L.n_pages + page) * c.n_kv_heads + h) * SB_KV_BLOCK + t) * c.head_dim;
-            HIP_TRY(hipMemcpy(tmp.data(), (const char*)s->kv.pool + off * es, tmp.size(), hipMemcpyDeviceToHost));
+            size_t off = (((size_t)(layer * 2 + which) * s->L.n_pages + page) * c.n_kv_heads + h) * SB_KV_BLOCK * c.head_dim;
+            HIP_TRY(hipMemcpy(slab.data(), (const char*)s->kv.pool + off * es, slab.size(), hipMemcpyDeviceToHost));
             float* dst = (which == 0 ? k_out : v_out) + (size_t)h * c.head_dim;
             for (int i = 0; i < c.head_dim; ++i) {
                 if (c.kv_dtype == SB_BF16) {
-                    uint32_t u = (uint32_t)((const uint16_t*)tmp.data())[i] << 16;
+                    const size_t e = which == 0 ? (size_t)t * c.head_dim + i : (size_t)i * SB_KV_BLOCK + t;
+                    uint32_t u = (uint32_t)((const uint16_t*)slab.data())[e] << 16;
                     memcpy(&dst[i], &u, 4);
                 } else {
-                    dst[i] = ((const float*)tmp.data())[i];
+                    dst[i] = ((const float*)slab.data())[(size_t)t * c.head_dim + i];
                 }
             }
         }
