@@ -274,6 +274,14 @@ int32_t sb_op_copy(void *dst, const void *src, size_t nbytes, void *stream);
 /* Plain streaming read of nbytes (sum-reduced into *sink, 4 bytes, device). */
 int32_t sb_op_read(const void *src, size_t nbytes, float *sink, void *stream);
 
+/* The projection of the prompt passes (prefill is the base model's, Sec. 3.1): y [M][N] =
+ * x [M][K] W^T for 1 <= M <= 64 rows against tile-packed bf16 weights (sb_op_repack),
+ * N % 16 == 0, K % 128 == 0.  x is used as a bf16 high + low pair per element, products
+ * accumulate in fp32 over k splits that are added in index order.  x, y, Wp, scratch:
+ * device; scratch of sb_op_gemm_scratch_bytes(N, K) bytes, 256-byte aligned. */
+int32_t sb_op_gemm(const void *Wp, int32_t N, int32_t K, const float *x, float *y, int32_t M, void *scratch,
+                   void *stream);
+size_t sb_op_gemm_scratch_bytes(int32_t N, int32_t K);
 /* Rotary table as the library builds it: cos/sin of pos * base^(-2i/head_dim),
  * evaluated in double and rounded to float; [n_pos][head_dim/2] each, host. */
 int32_t sb_rope_table_host(int32_t head_dim, float base, int32_t n_pos, float *cos_out, float *sin_out);

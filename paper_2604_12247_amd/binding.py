@@ -80,7 +80,7 @@ SYMBOLS = ["sb_last_error", "sb_temperature_schedule", "sb_query_sizes", "sb_loa
            "sb_debug_kv", "sb_op_rmsnorm", "sb_op_gemv", "sb_op_gemv_scratch_bytes", "sb_op_head",
            "sb_op_head_scratch_bytes", "sb_rope_table_host", "sb_op_attention",
            "sb_op_attention_scratch_bytes", "sb_decode", "sb_rewind", "sb_profile_begin", "sb_profile_end", "sb_op_copy",
-           "sb_op_read", "sb_op_repack"]
+           "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes"]
 
 KERNEL_CLASSES = ["rmsnorm", "qkv", "attention", "wo", "gate_up", "down", "exit_head",
                   "final_head"]
@@ -130,6 +130,9 @@ def lib() -> C.CDLL:
         L.sb_op_head_scratch_bytes.argtypes = [i32, i32, i32]
         L.sb_op_head_scratch_bytes.restype = sz
         L.sb_op_repack.argtypes = [vp, i32, i32, vp, vp]
+        L.sb_op_gemm.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp]
+        L.sb_op_gemm_scratch_bytes.argtypes = [i32, i32]
+        L.sb_op_gemm_scratch_bytes.restype = sz
         L.sb_op_copy.argtypes = [vp, vp, sz, vp]
         L.sb_op_read.argtypes = [vp, sz, vp, vp]
         L.sb_rope_table_host.argtypes = [i32, f32, i32, vp, vp]
@@ -397,6 +400,19 @@ def op_repack(W):
     P = torch.empty_like(W)
     check(lib().sb_op_repack(W.data_ptr(), N, K, P.data_ptr(), _stream_ptr(torch, W.device)))
     return P
+
+
+def op_gemm(Wp, x, scratch=None):
+    """Prompt-pass projection: Wp = op_repack(W) of a bf16 W [N, K], x [M <= 64, K] float32 -> y [M, N]."""
+    import torch
+    N, K = Wp.shape
+    M = x.shape[0]
+    y = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    if scratch is None:
+        scratch = torch.empty(max(lib().sb_op_gemm_scratch_bytes(N, K), 256), dtype=torch.uint8, device=x.device)
+    check(lib().sb_op_gemm(Wp.data_ptr(), N, K, x.data_ptr(), y.data_ptr(), M, scratch.data_ptr(),
+                           _stream_ptr(torch, x.device)))
+    return y
 
 
 def op_gemv(W, x, kernel: int = PROJ_VALU):

@@ -9,6 +9,9 @@
 
 namespace sb {
 
+// rows of one prompt pass (the decode passes have at most SB_MAX_W)
+#define SB_PREFILL_ROWS 64
+
 // ---- device-resident record of the current round (read back once per sync) ----
 struct DevRound {
     int32_t slot_tok[SB_MAX_W + 1];  // input token of each row (row 0: pending token)
@@ -107,10 +110,51 @@ struct AttnArgs {
     float* partials;     // [M*n_heads][max_chunks][head_dim + 2]
     int32_t max_chunks;
     float* out;          // [M][n_heads*head_dim]
-    uint16_t* out_split; // optional split-bf16 copy [16][n_heads*head_dim]
+    uint16_t* out_split; // optional bf16 hi/lo copy: rows 0.. high parts, rows split_rows.. low parts
+    int32_t split_rows;  // 8 for decode passes, SB_PREFILL_ROWS for prompt passes
 };
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
+
+// ---- prompt passes: up to SB_PREFILL_ROWS rows against tile-packed bf16 weights ----
+// Activations come as bf16 planes xs [2 * SB_PREFILL_ROWS][K] (high parts, then low
+// parts); the product is left as k-split partial sums part [S][SB_PREFILL_ROWS][rows]
+// for the epilogue that follows.
+struct GemmArgs {
+    const void* Wp;      // packed weights [rows][K]
+    int32_t rows, K;
+    const uint16_t* xs;
+    int32_t M;           // live rows
+    float* part;
+    int32_t S;           // k splits, from gemm_splits()
+};
+int gemm_splits(int32_t rows, int32_t K);
+hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st);
+
+// Sums the k splits in order, applies the RMSNorm scale of the input row (from the
+// partial sums of squares its producer left; nullable) and finishes the projection.
+struct GemmEpiArgs {
+    const float* part;
+    int32_t S, rows;
+    int32_t N, M;          // output columns (rows, or rows / 2 for the gate/up pair), live rows
+    int32_t epi;           // EPI_STORE, EPI_RESID, EPI_SWIGLU
+    const float* ssq_in;   // [SB_PREFILL_ROWS][ssq_ld] partial sums of squares of the input rows
+    int32_t ssq_nb, ssq_ld, K;
+    float eps;
+    float* y;              // STORE: y = v; RESID: y += v        [M][ldy]
+    int32_t ldy;
+    const float* gain;     // RESID: nx = bf16 planes of gain * y (nullable)
+    uint16_t* nx;
+    float* ssq_out;        // RESID: partial sums of squares of y per 256 columns
+    uint16_t* ys;          // SWIGLU: bf16 planes of silu(gate) * up
+};
+hipError_t launch_prefill_epilogue(const GemmEpiArgs& a, hipStream_t st);
+// Embedding rows of tokens[0..M) (device ids): H [M][d], bf16 planes of gain * h, sums of squares.
+hipError_t launch_prefill_embed(const void* E, int32_t w_dtype, int32_t vocab, int32_t d, const int32_t* tokens,
+                                int32_t M, float* H, const float* gain, uint16_t* nx, float* ssq_out, int32_t ssq_ld,
+                                hipStream_t st);
+// x [M][K] float -> bf16 planes (M <= SB_PREFILL_ROWS)
+hipError_t launch_prefill_split(const float* x, uint16_t* xs, int32_t M, int32_t K, hipStream_t st);
 
 hipError_t launch_copy(void* dst, const void* src, size_t nbytes, hipStream_t st);
 hipError_t launch_read(const void* src, size_t nbytes, float* sink, hipStream_t st);

@@ -7,65 +7,11 @@
 // and hence speculative output identical to greedy decoding by the same library
 // (the exactness property of Sec. 3.3).
 #include "kernels.h"
+#include "device_utils.h"
 
 #include <math.h>
 
 namespace sb {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-
-#define SB_INF __builtin_inff()
-
-__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-// float -> bf16, round to nearest even (finite inputs)
-__device__ __forceinline__ uint16_t f2bf(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ float ldf(const float* p) { return *p; }
-__device__ __forceinline__ float ldf(const uint16_t* p) { return bf2f(*p); }
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-
-// value v of row m, column i -> the two bf16 parts used by the MFMA path:
-// rows 0..7 hold the high parts, rows 8..15 the low parts (v ~= hi + lo).
-__device__ __forceinline__ void split_store(uint16_t* xs, int ld, int m, int i, float v) {
-    uint16_t hi = f2bf(v);
-    uint16_t lo = f2bf(v - bf2f(hi));
-    xs[(size_t)m * ld + i] = hi;
-    xs[(size_t)(8 + m) * ld + i] = lo;
-}
-
-__device__ __forceinline__ void unpack8(uint4 v, float (&w)[8]) {
-    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
-    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
-    w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
-    w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
-}
-__device__ __forceinline__ void load8(const uint16_t* p, float (&w)[8]) {
-    uint4 v = *reinterpret_cast<const uint4*>(p);
-    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
-    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
-    w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
-    w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
-}
-__device__ __forceinline__ void load8(const float* p, float (&w)[8]) {
-    float4 a = *reinterpret_cast<const float4*>(p);
-    float4 b = *reinterpret_cast<const float4*>(p + 4);
-    w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
-    w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
-}
 
 // ---------------------------------------------------------------- embedding
 template <typename WT>
@@ -367,7 +313,6 @@ __device__ __forceinline__ void head_partial(const HeadArgs& h, float (*zs)[SB_M
 // loads), partial sums are combined with a fixed shuffle tree.  x is staged in
 // LDS in chunks.  The order in which a row's products are added is a function of
 // K alone.
-__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + expf(-g)) * u; }
 
 template <typename WT, int M, int EPI>
 __global__ __launch_bounds__(256) void gemv_valu_kernel(GemvArgs a) {
@@ -525,13 +470,6 @@ hipError_t launch_gemv_valu(const GemvArgs& a, hipStream_t st) {
 // one load instruction then covers 64 contiguous bytes of each of the 16 rows (the
 // k order inside a block is free as long as A and B use the same one).
 #define SB_KOFF(lq, u) ((u) * 32 + (lq) * 8)
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-// streaming (non-temporal) 128-bit load: weights are read once per launch
-__device__ __forceinline__ uint4 ld_weights_packed(const uint16_t* p) {
-    u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
 // W [N][K] row-major -> packed tiles (N % 16 == 0, K % 128 == 0); one thread moves 16 bytes.
 __global__ __launch_bounds__(256) void repack_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ P, int N,
                                                      int K) {
@@ -1289,7 +1227,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
         const float v = Os / Ls;
         const size_t col = (size_t)hq * HD + tid;
         if (a.out) a.out[(size_t)r * Hq * HD + col] = v;
-        if (a.out_split) split_store(a.out_split, Hq * HD, r, (int)col, v);
+        if (a.out_split) split_store_rows(a.out_split, Hq * HD, a.split_rows, r, (int)col, v);
     }
 }
 
@@ -1299,7 +1237,8 @@ int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype) {
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     const int hd = a.kv.head_dim;
-    if ((hd != 64 && hd != 128) || a.M < 1 || a.M > SB_MAX_W || a.n_heads % a.kv.n_kv_heads) return hipErrorInvalidValue;
+    if ((hd != 64 && hd != 128) || a.M < 1 || a.M > SB_PREFILL_ROWS || a.n_heads % a.kv.n_kv_heads) return hipErrorInvalidValue;
+    if (a.out_split && a.split_rows < a.M) return hipErrorInvalidValue;
     const int ch = attn_chunk_keys(hd, a.kv.kv_dtype);
     const int n_chunks = (a.pos0 + a.M + ch - 1) / ch;
     if (n_chunks > a.max_chunks || n_chunks > 512) return hipErrorInvalidValue;

@@ -73,6 +73,10 @@ struct WsLayout {
     size_t H, xn, xs_attn, xs_ffn, xs_exit, ssq_attn, ssq_ffn, qkv, att, atts, u, us, attn_part, head_part,
         logits_exit, logits_final, round, table, total;
     int max_chunks, head_blocks, n_pages, ssq_ld;
+    // prompt passes of SB_PREFILL_ROWS rows (packed bf16 weights only)
+    bool prefill_gemm;
+    size_t p_tok, p_H, p_xs, p_ssq, p_qkv, p_atts, p_us, p_part, p_attn_part;
+    int p_ssq_ld;
 };
 
 WsLayout ws_layout(const sb_config* c) {
@@ -107,6 +111,26 @@ WsLayout ws_layout(const sb_config* c) {
     L.logits_final = take((size_t)SB_MAX_W * V * 4);
     L.round = take(sizeof(DevRound));
     L.table = take((size_t)L.n_pages * 4);
+    L.prefill_gemm = resolve_proj(c) == SB_PROJ_MFMA_PACKED;
+    if (L.prefill_gemm) {
+        const size_t PM = SB_PREFILL_ROWS;
+        L.p_ssq_ld = (int)((d + 255) / 256);
+        L.p_tok = take((size_t)c->max_seq * 4);
+        L.p_H = take(PM * d * 4);
+        L.p_xs = take(2 * PM * d * 2);
+        L.p_ssq = take(PM * L.p_ssq_ld * 4);
+        L.p_qkv = take(PM * qkv_rows * 4);
+        L.p_atts = take(2 * PM * hq * 2);
+        L.p_us = take(2 * PM * f * 2);
+        size_t pe = 0;  // largest k-split partial of the four projections
+        const size_t shapes[4][2] = {{qkv_rows, d}, {d, hq}, {2 * f, d}, {d, f}};
+        for (auto& sh : shapes) {
+            size_t e = (size_t)gemm_splits((int32_t)sh[0], (int32_t)sh[1]) * PM * sh[0];
+            if (e > pe) pe = e;
+        }
+        L.p_part = take(pe * 4);
+        L.p_attn_part = take(PM * c->n_heads * L.max_chunks * (c->head_dim + 2) * 4);
+    }
     L.total = off;
     return L;
 }
@@ -279,7 +303,7 @@ int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
     a.q = qkv; a.rope_cos = m->rope_cos; a.rope_sin = m->rope_sin; a.qkv_rows = qkv_rows; a.n_heads = c.n_heads;
     a.kv = s->kv; a.layer = l; a.pos0 = pos0; a.M = M;
     a.partials = wsp<float>(s, s->L.attn_part); a.max_chunks = s->L.max_chunks;
-    a.out = mf ? nullptr : att; a.out_split = mf ? atts : nullptr;
+    a.out = mf ? nullptr : att; a.out_split = mf ? atts : nullptr; a.split_rows = 8;
     const int64_t kv_read = (int64_t)(pos0 + M) * 2 * c.n_kv_heads * c.head_dim * (int64_t)esize(c.kv_dtype);
     {
         ProfScope ps(s, SB_K_ATTN, kv_read, st);
@@ -322,7 +346,8 @@ int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
 // Head projection + arg max / confidence for the M rows starting at slot `slot0`.
 // VALU path: RMSNorm kernel first.  MFMA path: the last W_down already left
 // gain * h and the sums of squares for these slots (run_layer's head_gain).
-int run_head(sb_session* s, const void* W, const float* gain, int slot0, int M, HeadArgs h, hipStream_t st) {
+int run_head(sb_session* s, const void* W, const float* gain, int slot0, int M, HeadArgs h, hipStream_t st,
+             bool prenormed = false) {
     sb_model* m = s->m;
     const sb_config& c = m->cfg;
     const bool mf = m->proj == SB_PROJ_MFMA;
@@ -337,7 +362,7 @@ int run_head(sb_session* s, const void* W, const float* gain, int slot0, int M, 
     GemvArgs g{};
     g.W = W; g.w_dtype = c.weight_dtype; g.N = c.vocab; g.K = c.d_model; g.x = xn; g.M = M;
     g.xs = wsp<uint16_t>(s, s->L.xs_exit) + (size_t)slot0 * c.d_model;
-    if (mf) {
+    if (mf && !prenormed) {  // (prenormed: xs already holds the normalised rows)
         g.ssq_in = wsp<float>(s, s->L.ssq_attn) + (size_t)slot0 * s->L.ssq_ld;
         g.ssq_nb = c.d_model / 16; g.ssq_ld = s->L.ssq_ld; g.eps = c.rms_eps;
     }
@@ -366,6 +391,99 @@ void reset_session(sb_session* s) {
     memset(&s->st, 0, sizeof s->st);
 }
 
+// One projection of a prompt pass: k-split GEMM, then its epilogue.
+int prefill_proj(sb_session* s, const void* Wp, int rows, int K, const uint16_t* xs, int M, GemmEpiArgs e, int cls) {
+    hipStream_t st = s->m->stream;
+    GemmArgs g{};
+    g.Wp = Wp; g.rows = rows; g.K = K; g.xs = xs; g.M = M;
+    g.part = wsp<float>(s, s->L.p_part); g.S = gemm_splits(rows, K);
+    e.part = g.part; e.S = g.S; e.rows = rows; e.M = M; e.K = K; e.eps = s->m->cfg.rms_eps; e.ssq_ld = s->L.p_ssq_ld;
+    ProfScope ps(s, cls, (int64_t)rows * K * 2 + (int64_t)M * K * 4 + (int64_t)M * rows * 4, st);
+    hipError_t err = launch_prefill_gemm(g, st);
+    if (err == hipSuccess) err = launch_prefill_epilogue(e, st);
+    if (err != hipSuccess) return fail(SB_EDEVICE, "prompt projection launch (rows=%d K=%d M=%d): %s", rows, K, M,
+                                       hipGetErrorString(err));
+    return SB_OK;
+}
+
+// Prompt passes of up to SB_PREFILL_ROWS rows through all layers (packed bf16 weights).
+// Same layer as run_layer; the hidden rows and their bf16 planes live in the p_* buffers.
+int prefill_gemm_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first_token) {
+    sb_model* m = s->m;
+    const sb_config& c = m->cfg;
+    hipStream_t st = m->stream;
+    const int d = c.d_model, f = c.d_ffn, hq = c.n_heads * c.head_dim;
+    const int qkv_rows = (c.n_heads + 2 * c.n_kv_heads) * c.head_dim;
+    const int nb_d = (d + 255) / 256;
+    int32_t* toks = wsp<int32_t>(s, s->L.p_tok);
+    float* H = wsp<float>(s, s->L.p_H);
+    uint16_t* xs = wsp<uint16_t>(s, s->L.p_xs);
+    float* ssq = wsp<float>(s, s->L.p_ssq);
+    float* qkv = wsp<float>(s, s->L.p_qkv);
+    uint16_t* atts = wsp<uint16_t>(s, s->L.p_atts);
+    uint16_t* us = wsp<uint16_t>(s, s->L.p_us);
+    HIP_TRY(hipMemcpyAsync(toks, prompt, (size_t)n * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));  // the caller's buffer is pageable: do not return while it is being read
+    int rc, M = 0;
+    for (int i0 = 0; i0 < n; i0 += SB_PREFILL_ROWS) {
+        M = n - i0 < SB_PREFILL_ROWS ? n - i0 : SB_PREFILL_ROWS;
+        HIP_TRY(launch_prefill_embed(m->embed, c.weight_dtype, c.vocab, d, toks + i0, M, H, m->attn_norm[0], xs, ssq,
+                                     s->L.p_ssq_ld, st));
+        for (int l = 0; l < c.n_layers; ++l) {
+            GemmEpiArgs e{};
+            e.N = qkv_rows; e.epi = EPI_STORE; e.ssq_in = ssq; e.ssq_nb = nb_d; e.y = qkv; e.ldy = qkv_rows;
+            if ((rc = prefill_proj(s, m->w_qkv[l], qkv_rows, d, xs, M, e, SB_K_QKV))) return rc;
+
+            AttnArgs a{};
+            a.q = qkv; a.rope_cos = m->rope_cos; a.rope_sin = m->rope_sin; a.qkv_rows = qkv_rows; a.n_heads = c.n_heads;
+            a.kv = s->kv; a.layer = l; a.pos0 = s->c; a.M = M;
+            a.partials = wsp<float>(s, s->L.p_attn_part); a.max_chunks = s->L.max_chunks;
+            a.out = nullptr; a.out_split = atts; a.split_rows = SB_PREFILL_ROWS;
+            const int64_t kv_read = (int64_t)(s->c + M) * 2 * c.n_kv_heads * c.head_dim * (int64_t)esize(c.kv_dtype);
+            {
+                ProfScope ps(s, SB_K_ATTN, kv_read, st);
+                HIP_TRY(launch_attention(a, st));
+            }
+
+            e = GemmEpiArgs{};
+            e.N = d; e.epi = EPI_RESID; e.y = H; e.ldy = d; e.gain = m->ffn_norm[l]; e.nx = xs; e.ssq_out = ssq;
+            if ((rc = prefill_proj(s, m->w_o[l], d, hq, atts, M, e, SB_K_WO))) return rc;
+
+            e = GemmEpiArgs{};
+            e.N = f; e.epi = EPI_SWIGLU; e.ssq_in = ssq; e.ssq_nb = nb_d; e.ys = us;
+            if ((rc = prefill_proj(s, m->w_gate_up[l], 2 * f, d, xs, M, e, SB_K_GATEUP))) return rc;
+
+            e = GemmEpiArgs{};
+            e.N = d; e.epi = EPI_RESID; e.y = H; e.ldy = d; e.ssq_out = ssq;
+            if (l + 1 < c.n_layers) { e.gain = m->attn_norm[l + 1]; e.nx = xs; }
+            if ((rc = prefill_proj(s, m->w_down[l], d, f, us, M, e, SB_K_DOWN))) return rc;
+
+            s->st.layer_sweeps += 1;
+            s->st.row_layers += M;
+            s->st.weight_bytes += m->layer_bytes;
+            s->st.kv_bytes += kv_read;
+        }
+        s->c += M;
+    }
+    // final head on the last prompt row: normalise it into slot 0's projection input
+    {
+        ProfScope ps(s, SB_K_RMSNORM, (int64_t)d * 8, st);
+        HIP_TRY(launch_rmsnorm(H + (size_t)(M - 1) * d, m->final_norm, wsp<float>(s, s->L.xn),
+                               wsp<uint16_t>(s, s->L.xs_exit), d, 1, d, c.rms_eps, st));
+    }
+    HeadArgs h{};
+    h.T = 1.0f; h.post = POST_NONE;
+    h.argmax_out = s->d_round->g; h.conf_out = s->d_round->gconf;
+    h.logits = s->debug ? wsp<float>(s, s->L.logits_final) : nullptr;
+    if ((rc = run_head(s, m->lm_head, m->final_norm, 0, 1, h, st, true))) return rc;
+    s->st.final_head_sweeps++;
+    if ((rc = readback(s))) return rc;
+    s->pending = s->h_round->g[0];
+    s->has_pending = true;
+    *first_token = s->pending;
+    return SB_OK;
+}
+
 int prefill_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first_token) {
     sb_model* m = s->m;
     const sb_config& c = m->cfg;
@@ -379,6 +497,7 @@ int prefill_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first
         if (jrc) return jrc;
     }
     reset_session(s);
+    if (s->L.prefill_gemm && m->packed) return prefill_gemm_impl(s, prompt, n, first_token);
     float* H = wsp<float>(s, s->L.H);
     int last_rows = 0;
     for (int i0 = 0; i0 < n; i0 += SB_MAX_W) {
@@ -1026,6 +1145,29 @@ int32_t sb_op_repack(const void* W, int32_t N, int32_t K, void* packed, void* st
     return SB_OK;
 }
 
+size_t sb_op_gemm_scratch_bytes(int32_t N, int32_t K) {
+    if (N < 16 || K < 128 || N % 16 || K % 128) return 0;
+    return align_up((size_t)2 * SB_PREFILL_ROWS * K * 2, 256) + (size_t)gemm_splits(N, K) * SB_PREFILL_ROWS * N * 4;
+}
+
+int32_t sb_op_gemm(const void* Wp, int32_t N, int32_t K, const float* x, float* y, int32_t M, void* scratch,
+                   void* stream) {
+    if (!Wp || !x || !y || !scratch) return fail(SB_EINVAL, "op_gemm: NULL argument");
+    if (N < 16 || K < 128 || N % 16 || K % 128 || M < 1 || M > SB_PREFILL_ROWS)
+        return fail(SB_EINVAL, "op_gemm: need N %% 16 == 0, K %% 128 == 0, 1 <= M <= %d", SB_PREFILL_ROWS);
+    hipStream_t st = (hipStream_t)stream;
+    uint16_t* xs = (uint16_t*)scratch;
+    float* part = (float*)((char*)scratch + align_up((size_t)2 * SB_PREFILL_ROWS * K * 2, 256));
+    HIP_TRY(launch_prefill_split(x, xs, M, K, st));
+    GemmArgs g{};
+    g.Wp = Wp; g.rows = N; g.K = K; g.xs = xs; g.M = M; g.part = part; g.S = gemm_splits(N, K);
+    HIP_TRY(launch_prefill_gemm(g, st));
+    GemmEpiArgs e{};
+    e.part = part; e.S = g.S; e.rows = N; e.N = N; e.M = M; e.epi = EPI_STORE; e.K = K; e.y = y; e.ldy = N;
+    HIP_TRY(launch_prefill_epilogue(e, st));
+    return SB_OK;
+}
+
 size_t sb_op_head_scratch_bytes(int32_t M, int32_t N, int32_t K) {
     if (N < 1 || K < 1) return 0;
     int nb = head_blocks_valu(N);
@@ -1116,7 +1258,7 @@ int32_t sb_op_attention(const float* qkv, int32_t n_heads, int32_t n_kv_heads, i
     a.layer = layer; a.pos0 = pos0; a.M = M;
     a.partials = (float*)scratch;
     a.max_chunks = (n_pages * SB_KV_BLOCK + ch - 1) / ch;
-    a.out = out; a.out_split = nullptr;
+    a.out = out; a.out_split = nullptr; a.split_rows = 8;
     HIP_TRY(launch_attention(a, (hipStream_t)stream));
     return SB_OK;
 }

@@ -294,8 +294,10 @@ def test_rewind_decode_and_kernel_timing(sb):
         s.profile_end()
 
 
-def test_packed_and_row_major_weights_give_identical_output(sb):
-    """The tile-packed copy only changes where the weights lie in memory."""
+def test_packed_and_row_major_weights_give_the_same_output(sb):
+    """The tile-packed copy only changes where the weights lie in memory: the decode kernels give
+    the same bits on both (checked kernel by kernel elsewhere).  The prompt, though, goes through
+    the 64-row passes only with packed weights, so the cached keys differ in the last bits."""
     _, _, _, gm_a = _build(sb, "bf16-mfma", n_layers=4, n_exit=2, seed=41)
     shape, w, om, gm_b = _build(sb, "bf16-mfma-packed", n_layers=4, n_exit=2, seed=41)
     prompt = si.make_prompt(shape.vocab, 23, 51)
@@ -305,7 +307,8 @@ def test_packed_and_row_major_weights_give_identical_output(sb):
     a, _ = sa.generate(prompt, 40, p)
     b, _ = sb_.generate(prompt, 40, p)
     assert a.tolist() == b.tolist()
-    assert np.array_equal(sa.debug_logits(0, 0), sb_.debug_logits(0, 0))
+    za, zb = sa.debug_logits(0, 0), sb_.debug_logits(0, 0)
+    assert np.max(np.abs(za - zb)) <= 2e-4 * np.max(np.abs(za))
 
 
 @pytest.mark.parametrize("name", ["c1-fp32", "bf16-mfma-packed"])
@@ -362,3 +365,39 @@ def test_computed_exits_that_fire_match_the_oracle(sb, name):
     out, st = gm.session().generate(prompt, 40, pg)
     assert out.tolist() == ar.tolist()
     assert st["drafts"] > 0 and st["exit_hist"][0] > 0
+
+
+@pytest.mark.parametrize("name,n_prompt", [("bf16-mfma-packed", 150), ("bf16-mfma-gqa", 64), ("bf16-mfma-gqa", 193),
+                                           ("bf16-mfma-packed", 65)])
+def test_long_prompt_goes_through_64_row_passes(sb, name, n_prompt):
+    """Prompts longer than one pass (full passes plus a ragged tail): first token, final logits
+    and the cached K/V of prompt positions against the oracle; decoding continues from that
+    cache exactly as greedy decoding does."""
+    shape, w, om, gm = _build(sb, name, n_layers=4, n_exit=2, seed=61, max_seq=288)
+    prompt = si.make_prompt(shape.vocab, n_prompt, 71)
+    osn, gsn = om.session(), gm.session()
+    gsn.debug_enable(True)
+    t_o, t_g = osn.prefill(prompt), gsn.prefill(prompt)
+    z_o, z_g = osn.verify_logits(0), gsn.debug_logits(0, 0)
+    assert np.max(np.abs(z_g - z_o)) <= 2e-2 * np.max(np.abs(z_o))
+    srt = np.sort(z_o)
+    if srt[-1] - srt[-2] >= 1e-2:
+        assert t_o == t_g
+    assert gsn.committed_len() == n_prompt
+    for layer in (0, shape.n_layers - 1):
+        for pos in sorted({0, 1, 15, 16, 63, 64 % n_prompt, n_prompt // 2, n_prompt - 1}):
+            ko, vo = osn.kv_read(layer, pos)
+            kg, vg = gsn.debug_kv(layer, pos)
+            lim = 2.0 ** -7 * max(1.0, np.max(np.abs(ko)))
+            assert np.max(np.abs(kg - ko)) <= lim and np.max(np.abs(vg - vo)) <= lim, (layer, pos)
+    if t_o != t_g:
+        return
+    # speculative decoding from the prefilled cache equals the library's own greedy decoding,
+    # and the greedy continuation follows the oracle's up to near-ties
+    ar, _ = gm.session().generate(prompt, 24, gpu_params(0, 1))
+    spec, st = gm.session().generate(prompt, 24, gpu_params(2, 4, 0.5, forced_exit=si.forced_exit_schedule(9, 200, 1, 2)))
+    assert spec.tolist() == ar.tolist()
+    teacher_forced_check(om, prompt, ar.tolist())
+    pst = gm.session()
+    pst.prefill(prompt)
+    assert pst.stats()["layer_sweeps"] == shape.n_layers * ((n_prompt + 63) // 64)

@@ -81,6 +81,31 @@ def test_gemv_mfma(T, N, K, M):
     assert np.array_equal(yp, y)
 
 
+GEMM_CASES = [(16, 128, 1), (48, 384, 5), (4096, 4096, 64), (12288, 4096, 37), (4096, 11008, 64), (22016, 4096, 64),
+              (4112, 256, 17), (8192 + 80, 512, 33)]
+
+
+@pytest.mark.parametrize("N,K,M", GEMM_CASES)
+def test_prompt_pass_gemm(T, N, K, M):
+    """The projection of the prompt passes (up to 64 rows, k splits added in order) against the
+    double-precision product of the same bf16 weights; unwritten rows of the scratch hold NaN."""
+    import paper_2604_12247_amd as sb
+    g = np.random.default_rng(N + K + M + 2)
+    W = _rand_w(g, N, K, True)
+    x = g.standard_normal((M, K)).astype(np.float32)
+    Wp = sb.op_repack(_dev(T, W))
+    scratch = T.empty(sb.lib().sb_op_gemm_scratch_bytes(N, K), dtype=T.uint8, device="cuda")
+    scratch.fill_(0xFF)
+    y = sb.op_gemm(Wp, _dev(T, x), scratch).cpu().numpy()
+    ref = _oracle_rows(W, x)
+    assert np.all(np.isfinite(y))
+    assert np.max(np.abs(y - ref)) <= 3e-5 * np.max(np.abs(ref)) + 1e-7
+    # a row's result does not depend on the rows beside it
+    if M > 3:
+        y3 = sb.op_gemm(Wp, _dev(T, x[:3]), scratch).cpu().numpy()
+        assert np.array_equal(y3, y[:3])
+
+
 @pytest.mark.parametrize("kernel", ["valu", "mfma", "mfma_packed"])
 def test_gemv_row_result_does_not_depend_on_m(T, kernel):
     """A row's output is bit-identical whether it is computed alone or with others."""
