@@ -8,9 +8,10 @@
 // the rows' activations, which every wave of the block needs and which are therefore
 // staged through LDS (B operand; bf16 high and low parts, two MFMAs per weight tile,
 // so a product keeps about 16 bits of the activation's mantissa as in the decode
-// path).  The k range is split across blocks to fill the chip; each split leaves a
-// partial sum.  prefill_epilogue_kernel adds the splits in index order, applies the
-// RMSNorm scale and the projection's tail (store, residual + next input, SwiGLU).
+// path).  The work is cut evenly across thread blocks, also along k, so a row of the
+// result is left as a few partial sums.  prefill_epilogue_kernel adds them in index
+// order, applies the RMSNorm scale and the projection's tail (store, residual + next
+// input, SwiGLU).
 #include "kernels.h"
 #include "device_utils.h"
 
@@ -20,134 +21,199 @@ namespace {
 constexpr int PM = SB_PREFILL_ROWS;
 constexpr int ROWB = 272;                  // LDS bytes per staged row: 128 bf16 + 16 bytes of padding
 constexpr int STAGE = 2 * PM * ROWB;       // one k block of both planes
+constexpr int WPB = 4;                     // waves per thread block
+constexpr int DEPTH = 2;                   // weight register stages per wave (deeper rings cost occupancy, measured no gain)
 }  // namespace
 
-// grid (ceil(rows / (64 RT)), S); 256 threads = 4 waves, each RT 16-row weight tiles
-template <int RT>
-__global__ __launch_bounds__(256) void prefill_gemm_kernel(GemmArgs a) {
-    constexpr int CT = PM / 16;  // 16-row column tiles of the activations
-    extern __shared__ __attribute__((aligned(16))) unsigned char bt[];  // [2][STAGE]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int li = lane & 15, lq = lane >> 4;
-    const int K = a.K, KB = K >> 7;
-    const int KBS = (KB + a.S - 1) / a.S;
-    const int kb0 = blockIdx.y * KBS, kb1 = (kb0 + KBS < KB) ? kb0 + KBS : KB;
-    if (kb0 >= kb1) return;
-    const int n_tiles = a.rows >> 4;
-    const int ctl = (a.M + 15) >> 4;  // live column tiles
+// Work decomposition: the (row block, k block) pairs are numbered row block first and
+// cut into equal contiguous ranges, one per thread block, so that every block streams
+// the same number of weight bytes whatever the shape (a plain k split leaves a ragged
+// last round of blocks on 256 CUs).  A range may end in the middle of a row block: each
+// thread block that touches a row block leaves one partial sum for it, in slot
+// (thread block index - first thread block of that row block).
+struct GemmPlan {
+    int rt;      // 16-row weight tiles per wave (row block = 64 rt rows)
+    int nb;      // row blocks
+    int q;       // (row block, k block) pairs per thread block
+    int grid;    // thread blocks
+    int smax;    // most partial sums a row block can get
+};
+static GemmPlan gemm_plan(int32_t rows, int32_t K) {
+    GemmPlan p;
+    const int KB = K >> 7;
+    p.rt = rows >= 8192 ? 2 : 1;
+    p.nb = (rows + 16 * WPB * p.rt - 1) / (16 * WPB * p.rt);
+    const long total = (long)p.nb * KB;
+    const int slots = (p.rt == 2 ? 512 : 768) * 4 / WPB;  // resident thread blocks on 256 CUs at this kernel's register use
+    p.q = (int)((total + slots - 1) / slots);
+    if (p.q < 2 && KB >= 2) p.q = 2;          // (never one partial per k block)
+    p.grid = (int)((total + p.q - 1) / p.q);
+    p.smax = (KB + p.q - 1) / p.q + 1;
+    if (p.smax > KB) p.smax = KB;
+    return p;
+}
+int gemm_splits(int32_t rows, int32_t K) { return gemm_plan(rows, K).smax; }
 
-    const uint16_t* wp[RT];
-    int rt[RT];
+// ---- pieces of the GEMM kernel (all inlined; register arrays are passed by reference) ----
+struct GemmCtx {
+    const uint16_t* W;      // packed weights + this lane's 16 bytes
+    const uint16_t* bsrc0;  // this thread's first staging unit in the activation planes
+    int bdst0;              // ... and in an LDS stage
+    int K, KB, n_tiles, it1, wave, li, lq;
+};
+
+// weights of pair `it` (clamped to the block's range: a re-read of the last pair keeps the
+// steady-state loop free of conditional loads, whose completion could only be waited for
+// conservatively)
+template <int RT>
+__device__ __forceinline__ void gemm_load_a(uint4 (&ar)[RT][4], const GemmCtx& c, int it_) {
+    const int it = it_ < c.it1 ? it_ : c.it1 - 1;
+    const int b = it / c.KB, kb = it - b * c.KB;
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        rt[t] = (blockIdx.x * 4 + wave) * RT + t;
-        const int c = rt[t] < n_tiles ? rt[t] : n_tiles - 1;  // a tile past the end re-reads the last one (not stored)
-        wp[t] = reinterpret_cast<const uint16_t*>(a.Wp) + (size_t)c * KB * 2048 + lane * 8;
-    }
-    // staging map: 2 planes x 64 rows x 16 segments of 16 bytes, 8 per thread
-    const uint16_t* bsrc[8];
-    int bdst[8];
-    bool bact[8];
+        int tile = (b * WPB + c.wave) * RT + t;
+        if (tile > c.n_tiles - 1) tile = c.n_tiles - 1;  // a tile past the end re-reads the last one (not stored)
+        const uint16_t* wp = c.W + ((size_t)tile * c.KB + kb) * 2048;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int unit = tid + 256 * i;
-        const int plane = unit >> 10, row = (unit >> 4) & 63, seg = unit & 15;
-        bact[i] = row < a.M;
-        bsrc[i] = a.xs + (size_t)(plane * PM + row) * K + seg * 8;
-        bdst[i] = (plane * PM + row) * ROWB + seg * 16;
+        for (int u = 0; u < 4; ++u) ar[t][u] = ld_weights_packed(wp + u * 512);
     }
+}
+// Staging map: 2 planes x 64 rows x 16 segments of 16 bytes, NBU per thread; unit i of a
+// thread lies RPI rows below unit i - 1 (same segment), running on into the low plane.
+// Rows past M are read too, from the planes' unused rows: whatever they hold only reaches
+// result columns that are never stored.
+constexpr int NBU = 2048 / (64 * WPB);
+constexpr int RPI = 4 * WPB;
+__device__ __forceinline__ void gemm_load_b(u32x4 (&br)[NBU], const GemmCtx& c, int it_) {
+    const int it = it_ < c.it1 ? it_ : c.it1 - 1;
+    const int kb = it % c.KB;
+#pragma unroll
+    for (int i = 0; i < NBU; ++i)
+        br[i] = *reinterpret_cast<const u32x4*>(c.bsrc0 + (size_t)(i * RPI) * c.K + (size_t)kb * 128);
+}
+__device__ __forceinline__ void gemm_store_b(unsigned char* dst, const u32x4 (&br)[NBU], const GemmCtx& c) {
+#pragma unroll
+    for (int i = 0; i < NBU; ++i) *reinterpret_cast<u32x4*>(dst + c.bdst0 + i * RPI * ROWB) = br[i];
+}
+// All four column tiles are always multiplied: the block of LDS reads and MFMAs stays free
+// of branches.
+template <int RT>
+__device__ __forceinline__ void gemm_mma(f32x4 (&acc)[RT][PM / 16], const uint4 (&ar)[RT][4], const unsigned char* src,
+                                         const GemmCtx& c) {
+    constexpr int CT = PM / 16;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        bf16x8 bh[CT], bl[CT];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const unsigned char* rp = src + (ct * 16 + c.li) * ROWB + u * 64 + c.lq * 16;
+            bh[ct] = *reinterpret_cast<const bf16x8*>(rp);
+            bl[ct] = *reinterpret_cast<const bf16x8*>(rp + PM * ROWB);
+        }
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ar[t][u]), bh[ct],
+                                                                     acc[t][ct], 0, 0, 0);
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ar[t][u]), bl[ct],
+                                                                     acc[t][ct], 0, 0, 0);
+    }
+}
+// Partial sum of row block b (C layout: lane (j = li, g = lq), register r -> weight row 4g + r
+// of the tile, activation row j), then zero for the next row block.
+template <int RT>
+__device__ __forceinline__ void gemm_flush(f32x4 (&acc)[RT][PM / 16], const GemmArgs& a, const GemmCtx& c, int b, int q) {
+    constexpr int CT = PM / 16;
+    const int slot = (int)blockIdx.x - (b * c.KB) / q;
+    float* part = a.part + (size_t)slot * PM * a.rows;
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        const int tile = (b * WPB + c.wave) * RT + t;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const int m = ct * 16 + c.li;
+            if (tile < c.n_tiles && m < a.M)
+                *reinterpret_cast<f32x4*>(part + (size_t)m * a.rows + tile * 16 + 4 * c.lq) = acc[t][ct];
+            acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+}
+
+// One pair: request the next activations and the weights D - 1 pairs ahead, multiply the
+// current pair, leave the row block's partial sum if it ends here, publish the next
+// activations (the stage they go to was last read before the barrier that ended the
+// previous pair).
+template <int RT>
+__device__ __forceinline__ void gemm_step(f32x4 (&acc)[RT][PM / 16], const uint4 (&acur)[RT][4], uint4 (&afar)[RT][4],
+                                          u32x4 (&breg)[NBU], unsigned char* bt, int& buf, const GemmArgs& a,
+                                          const GemmCtx& c, int cur, int q) {
+    gemm_load_b(breg, c, cur + 1);
+    gemm_load_a<RT>(afar, c, cur + DEPTH - 1);
+    gemm_mma<RT>(acc, acur, bt + buf * STAGE, c);
+    const int b = cur / c.KB;
+    if (cur + 1 >= c.it1 || (cur + 1) / c.KB != b) gemm_flush<RT>(acc, a, c, b, q);
+    buf ^= 1;
+    gemm_store_b(bt + buf * STAGE, breg, c);
+    __syncthreads();
+}
+
+// 64 WPB threads, each wave RT 16-row weight tiles of the block's 16 WPB RT rows.
+// Weights: a ring of D register stages, D - 1 pairs requested ahead; activations: one
+// pair ahead through LDS (they come from L2).  Loads complete
+// in issue order, so the activations are requested before the weights: waiting for them at
+// the end of the step leaves the weight loads in flight.
+template <int RT>
+__global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int q) {
+    constexpr int CT = PM / 16;  // 16-row column tiles of the activations
+    constexpr int D = DEPTH;
+    extern __shared__ __attribute__((aligned(16))) unsigned char bt[];  // [2][STAGE]
+    const int tid = threadIdx.x, lane = tid & 63;
+    GemmCtx c;
+    c.wave = tid >> 6; c.li = lane & 15; c.lq = lane >> 4;
+    c.K = a.K; c.KB = a.K >> 7; c.n_tiles = a.rows >> 4;
+    const int nb = (c.n_tiles + WPB * RT - 1) / (WPB * RT);
+    const int total = nb * c.KB;  // (checked on the host to fit an int)
+    const int it0 = blockIdx.x * q;
+    c.it1 = it0 + q < total ? it0 + q : total;
+    if (it0 >= c.it1) return;
+    c.W = reinterpret_cast<const uint16_t*>(a.Wp) + lane * 8;
+    c.bsrc0 = a.xs + (size_t)(tid >> 4) * a.K + (tid & 15) * 8;
+    c.bdst0 = (tid >> 4) * ROWB + (tid & 15) * 16;
 
     f32x4 acc[RT][CT];
 #pragma unroll
     for (int t = 0; t < RT; ++t)
 #pragma unroll
-        for (int c = 0; c < CT; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int ct = 0; ct < CT; ++ct) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint4 aw[D][RT][4];  // ring of weight stages
+    u32x4 breg[NBU];     // (a native vector type: the compiler keeps such an array in registers)
 
-    uint4 abuf[2][RT][4], breg[8];
-    auto load_a = [&](uint4 (&ar)[RT][4], int kb) {
+    gemm_load_b(breg, c, it0);
 #pragma unroll
-        for (int t = 0; t < RT; ++t)
-#pragma unroll
-            for (int u = 0; u < 4; ++u) ar[t][u] = ld_weights_packed(wp[t] + (size_t)kb * 2048 + u * 512);
-    };
-    auto load_b = [&](int kb) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            breg[i] = bact[i] ? *reinterpret_cast<const uint4*>(bsrc[i] + (size_t)kb * 128) : make_uint4(0, 0, 0, 0);
-    };
-    auto store_b = [&](unsigned char* dst) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(dst + bdst[i]) = breg[i];
-    };
-    auto mma = [&](const uint4 (&ar)[RT][4], const unsigned char* src) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-#pragma unroll
-            for (int c = 0; c < CT; ++c) {
-                if (c < ctl) {
-                    const unsigned char* rp = src + (c * 16 + li) * ROWB + u * 64 + lq * 16;
-                    const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(rp));
-                    const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(rp + PM * ROWB));
-#pragma unroll
-                    for (int t = 0; t < RT; ++t) {
-                        const bf16x8 av = __builtin_bit_cast(bf16x8, ar[t][u]);
-                        acc[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh, acc[t][c], 0, 0, 0);
-                        acc[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl, acc[t][c], 0, 0, 0);
-                    }
-                }
-            }
-        }
-    };
-    // one k block: request the next block's operands, multiply the current one, then
-    // publish the next activations (the buffer they go to was last read before the
-    // barrier that ended the previous block)
-    auto step = [&](const uint4 (&acur)[RT][4], uint4 (&anxt)[RT][4], unsigned char* bcur, unsigned char* bnxt, int kb) {
-        const bool more = kb + 1 < kb1;
-        if (more) { load_a(anxt, kb + 1); load_b(kb + 1); }
-        mma(acur, bcur);
-        if (more) store_b(bnxt);
-        __syncthreads();
-    };
-
-    load_a(abuf[0], kb0);
-    load_b(kb0);
-    store_b(bt);
+    for (int s = 0; s < D - 1; ++s) gemm_load_a<RT>(aw[s], c, it0 + s);
+    gemm_store_b(bt, breg, c);
     __syncthreads();
-    for (int kb = kb0; kb < kb1; kb += 2) {
-        step(abuf[0], abuf[1], bt, bt + STAGE, kb);
-        if (kb + 1 < kb1) step(abuf[1], abuf[0], bt + STAGE, bt, kb + 1);
-    }
-
-    // C layout: lane (j = li, g = lq), register r -> weight row 4g + r of the tile, activation row j
-    float* part = a.part + (size_t)blockIdx.y * PM * a.rows;
+    int buf = 0;  // LDS stage that holds the current pair's activations
+    int it = it0;
+    for (; it + D <= c.it1; it += D) {  // steady state, fully unrolled: every stage index is a constant
 #pragma unroll
-    for (int t = 0; t < RT; ++t) {
-        if (rt[t] >= n_tiles) continue;
-#pragma unroll
-        for (int c = 0; c < CT; ++c) {
-            const int m = c * 16 + li;
-            if (m < a.M) *reinterpret_cast<f32x4*>(part + (size_t)m * a.rows + rt[t] * 16 + 4 * lq) = acc[t][c];
-        }
+        for (int s = 0; s < D; ++s)
+            gemm_step<RT>(acc, aw[s], aw[(s + D - 1) % D], breg, bt, buf, a, c, it + s, q);
     }
-}
-
-static int gemm_row_tiles(int32_t rows) { return rows >= 8192 ? 2 : 1; }
-
-// k splits: enough blocks for the chip, never an empty split
-int gemm_splits(int32_t rows, int32_t K) {
-    const int KB = K >> 7;
-    const int nb = (rows + 64 * gemm_row_tiles(rows) - 1) / (64 * gemm_row_tiles(rows));
-    int S = (640 + nb - 1) / nb;
-    if (S > 16) S = 16;
-    if (S > KB) S = KB;
-    if (S < 1) S = 1;
-    const int KBS = (KB + S - 1) / S;
-    return (KB + KBS - 1) / KBS;
+#pragma unroll
+    for (int s = 0; s < D - 1; ++s)
+        if (it + s < c.it1) gemm_step<RT>(acc, aw[s], aw[(s + D - 1) % D], breg, bt, buf, a, c, it + s, q);
 }
 
 hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
-    if (a.rows < 16 || a.rows % 16 || a.K < 128 || a.K % 128 || a.M < 1 || a.M > PM || a.S < 1 || a.S > (a.K >> 7))
-        return hipErrorInvalidValue;
+    if (a.rows < 16 || a.rows % 16 || a.K < 128 || a.K % 128 || a.M < 1 || a.M > PM) return hipErrorInvalidValue;
+    const GemmPlan p = gemm_plan(a.rows, a.K);
+    if (a.S != p.smax || (long)p.nb * (a.K >> 7) > 0x3fffffffL) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_gemm_kernel<1>),
@@ -158,16 +224,22 @@ hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int rtl = gemm_row_tiles(a.rows);
-    dim3 grid((a.rows + 64 * rtl - 1) / (64 * rtl), a.S);
-    if (rtl == 2) prefill_gemm_kernel<2><<<grid, 256, 2 * STAGE, st>>>(a);
-    else prefill_gemm_kernel<1><<<grid, 256, 2 * STAGE, st>>>(a);
+    if (p.rt == 2) prefill_gemm_kernel<2><<<p.grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+    else prefill_gemm_kernel<1><<<p.grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
     return hipGetLastError();
+}
+
+// Partial sums that row block b received: thread blocks first..last of the plan.
+struct GemmSplitMap { int rows_per_block, KB, q; };
+__device__ __forceinline__ int splits_of(const GemmSplitMap& mp, int n) {
+    const int b = n / mp.rows_per_block;
+    const int first = (int)(((long)b * mp.KB) / mp.q), last = (int)(((long)(b + 1) * mp.KB - 1) / mp.q);
+    return last - first + 1;
 }
 
 // grid (ceil(N / 256), M): thread = one output element
 template <int EPI>
-__global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a) {
+__global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a, GemmSplitMap mp) {
     __shared__ float red[4];
     const int tid = threadIdx.x, m = blockIdx.y, n = blockIdx.x * 256 + tid;
     float inv = 1.0f;
@@ -182,11 +254,14 @@ __global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a) {
     if (n < a.N) {
         if (EPI == EPI_SWIGLU) {
             float g = 0.f, u = 0.f;
-            for (int s = 0; s < a.S; ++s) { g += p[s * plane + n]; u += p[s * plane + a.N + n]; }
+            const int sg = splits_of(mp, n), su = splits_of(mp, a.N + n);
+            for (int s = 0; s < sg; ++s) g += p[s * plane + n];
+            for (int s = 0; s < su; ++s) u += p[s * plane + a.N + n];
             split_store_rows(a.ys, a.N, PM, m, n, silu_mul(g * inv, u * inv));
         } else {
             float v = 0.f;
-            for (int s = 0; s < a.S; ++s) v += p[s * plane + n];
+            const int sn = splits_of(mp, n);
+            for (int s = 0; s < sn; ++s) v += p[s * plane + n];
             v *= inv;
             float* yp = a.y + (size_t)m * a.ldy + n;
             if (EPI == EPI_RESID) {
@@ -210,10 +285,13 @@ hipError_t launch_prefill_epilogue(const GemmEpiArgs& a, hipStream_t st) {
     if (a.epi == EPI_SWIGLU ? (!a.ys || a.rows != 2 * a.N) : (!a.y || a.rows != a.N)) return hipErrorInvalidValue;
     if (a.ssq_out && (a.N + 255) / 256 > a.ssq_ld) return hipErrorInvalidValue;
     dim3 grid((a.N + 255) / 256, a.M);
+    const GemmPlan pl = gemm_plan(a.rows, a.K);
+    if (a.S != pl.smax) return hipErrorInvalidValue;
+    const GemmSplitMap mp{16 * WPB * pl.rt, a.K >> 7, pl.q};
     switch (a.epi) {
-        case EPI_STORE: prefill_epilogue_kernel<EPI_STORE><<<grid, 256, 0, st>>>(a); break;
-        case EPI_RESID: prefill_epilogue_kernel<EPI_RESID><<<grid, 256, 0, st>>>(a); break;
-        case EPI_SWIGLU: prefill_epilogue_kernel<EPI_SWIGLU><<<grid, 256, 0, st>>>(a); break;
+        case EPI_STORE: prefill_epilogue_kernel<EPI_STORE><<<grid, 256, 0, st>>>(a, mp); break;
+        case EPI_RESID: prefill_epilogue_kernel<EPI_RESID><<<grid, 256, 0, st>>>(a, mp); break;
+        case EPI_SWIGLU: prefill_epilogue_kernel<EPI_SWIGLU><<<grid, 256, 0, st>>>(a, mp); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
