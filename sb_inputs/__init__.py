@@ -6,12 +6,12 @@ the speculation algorithm's arithmetic, and imports neither the oracle nor the
 HIP library.
 """
 from .configs import ModelShape, Workload, CONFIGS, tiny_shape
-from .weights import make_weights, round_to_bf16, bf16_to_f32, tensor_specs
+from .weights import make_weights, round_to_bf16, bf16_to_f32, tensor_specs, easy_token_weights
 from .schedules import (make_prompt, forced_exit_schedule, accept_schedule,
                         injection_schedule)
 
 __all__ = [
     "ModelShape", "Workload", "CONFIGS", "tiny_shape", "make_weights",
-    "round_to_bf16", "bf16_to_f32", "tensor_specs", "make_prompt",
+    "round_to_bf16", "bf16_to_f32", "tensor_specs", "easy_token_weights", "make_prompt",
     "forced_exit_schedule", "accept_schedule", "injection_schedule",
 ]

@@ -94,3 +94,29 @@ def make_weights(shape: ModelShape, seed: int, gain_jitter: float = 0.0,
             g = bf16_to_f32(round_to_bf16(g)) if bf16 else g
         out[name] = g
     return out
+
+
+def easy_token_weights(shape: ModelShape, weights: Dict[str, np.ndarray], decay: float = 0.5,
+                       head_scale: float = 20.0, ramp: float = 0.0) -> Dict[str, np.ndarray]:
+    """A structured variant of `weights` on which computed exits fire and drafts are often
+    right (random heads never agree with the final head): the output projections of layer l
+    (0-based) are scaled by decay**l, so deeper layers refine the hidden state less and less;
+    every exit head is the final head (same matrix), with the final norm's gains times
+    head_scale so that the soft-max is peaked enough for a confidence test to decide.
+    ramp in [0, 1] makes shallow heads less peaked than deep ones (head l of n gets
+    head_scale * (1 - ramp * (1 - l / n)), l = 1..n), which spreads the exits over the layers.
+    A power-of-two decay keeps bf16 weights exact.  Returns a new dict (shares the untouched
+    arrays)."""
+    bf16 = shape.weight_dtype == BF16
+    out = dict(weights)
+    for l in range(shape.n_layers):
+        s = np.float32(decay ** l)
+        for name in (f"w_o.{l}", f"w_down.{l}"):
+            a = bf16_to_f32(weights[name]) if bf16 else weights[name]
+            a = a * s
+            out[name] = round_to_bf16(a) if bf16 else a.astype(np.float32)
+    for l in range(shape.n_exit_heads):
+        out[f"exit_head.{l}"] = weights["lm_head"]
+        hs = head_scale * (1.0 - ramp * (1.0 - (l + 1) / shape.n_exit_heads))
+        out[f"exit_norm.{l}"] = (weights["final_norm"] * np.float32(hs)).astype(np.float32)
+    return out

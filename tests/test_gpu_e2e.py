@@ -401,3 +401,52 @@ def test_long_prompt_goes_through_64_row_passes(sb, name, n_prompt):
     pst = gm.session()
     pst.prefill(prompt)
     assert pst.stats()["layer_sweeps"] == shape.n_layers * ((n_prompt + 63) // 64)
+
+
+@pytest.mark.parametrize("tau", [0.3, 0.7])
+def test_easy_token_fixture_accepts_computed_drafts_like_the_oracle(sb, tau):
+    """The structured fixture (aliased, peaked heads; deep layers fading out): computed exits
+    fire and many drafts are accepted, so rounds of every accept length occur.  Step by step
+    against the oracle as above; at the end both have emitted the same tokens."""
+    kw, proj = _variants(sb)["bf16-mfma-packed"]
+    shape = si.tiny_shape(n_layers=12, n_exit_heads=8, **kw)
+    w = si.easy_token_weights(shape, si.make_weights(shape, 77), decay=0.5, head_scale=20.0)
+    om, gm = Oracle(shape, w, 256), gpu_model(shape, w, 256, proj)
+    prompt = si.make_prompt(shape.vocab, 24, 5)
+    T = sb.temperature_schedule(0.2, 8, 8)
+    po, pg = orc.OrcParams(8, 6, T, tau), sb.Params(8, 6, T, tau)
+    osn, gsn = om.session(), gm.session()
+    assert osn.prefill(prompt) == gsn.prefill(prompt)
+    accept_lengths, emitted_o, emitted_g = set(), [], []
+    diverged = False
+    for rnd in range(16):
+        while True:
+            ro, rg = osn.draft_step(po), gsn.draft_step(pg)
+            if (ro["status"], ro["exit_layer"]) != (rg["status"], rg["exit_layer"]):
+                assert abs(ro["confidence"] - tau) <= 1e-3, (rnd, ro, rg)
+                diverged = True
+                break
+            assert abs(ro["confidence"] - rg["confidence"]) <= 1e-3
+            if ro["token"] != rg["token"]:
+                srt = np.sort(osn.head_logits())
+                assert srt[-1] - srt[-2] < 1e-2, (rnd, ro, rg)
+                diverged = True
+                break
+            if ro["status"] != orc.EXITED:
+                break
+        if diverged:
+            break
+        vo, vg = osn.verify(po), gsn.verify(pg)
+        if vo["tokens"][: vo["n_emit"]] != vg["tokens"][: vg["n_emit"]]:
+            break
+        for k in ("n_rows", "n_drafts", "n_matched", "n_emit", "align_layer"):
+            assert vo[k] == vg[k], (rnd, k, vo, vg)
+        accept_lengths.add(vo["n_matched"])
+        emitted_o += vo["tokens"][: vo["n_emit"]]
+        emitted_g += vg["tokens"][: vg["n_emit"]]
+    assert emitted_o == emitted_g and len(emitted_g) >= 12
+    assert len(accept_lengths) >= 3 and max(accept_lengths) >= 3, accept_lengths
+    ar, _ = gm.session().generate(prompt, 64, gpu_params(0, 1))
+    out, st = gm.session().generate(prompt, 64, pg)
+    assert out.tolist() == ar.tolist()
+    assert st["emitted"] / st["rounds"] > 1.5

@@ -253,3 +253,29 @@ def test_max_new_truncation_eos_and_errors(model6):
     assert s.verify(params(2, 2), check=False) == -4              # nothing to verify
     s2 = m.session()
     assert s2.draft_step(params(2, 2), check=False) == -4         # no prefill yet
+
+
+def test_easy_token_fixture_has_a_threshold_optimum():
+    """On the structured fixture (aliased peaked heads, deep layers fading out) the threshold
+    trades draft count against acceptance as in the paper's ablation (Sec. 4.3): a very low
+    threshold lets every token exit at layer 1 with poor acceptance, a very high one suppresses
+    exits; in between the tokens per round peak and the layer sweeps bottom out.  Output is the
+    greedy one at every setting."""
+    shape = si.tiny_shape(n_layers=12, n_exit_heads=8, weight_dtype=si.configs.BF16, kv_dtype=si.configs.BF16, d_ffn=768)
+    w = si.easy_token_weights(shape, si.make_weights(shape, 77), decay=0.5, head_scale=20.0)
+    om = Oracle(shape, w, 256)
+    prompt = si.make_prompt(shape.vocab, 24, 5)
+    T = orc.temperature_schedule(0.2, 8, 8)
+    s = om.session()
+    greedy = s.generate(prompt, 64, orc.OrcParams(0, 1, [], 0.5))
+    res = {}
+    for tau in (0.1, 0.3, 0.9):
+        s = om.session()
+        out = s.generate(prompt, 64, orc.OrcParams(8, 6, T, tau))
+        assert list(out) == list(greedy)
+        st = s.stats()
+        res[tau] = (st["emitted"] / st["rounds"], st["layer_sweeps"], st["drafts"], st["exit_hist"])
+    assert res[0.1][3][1] == res[0.1][2]                      # lowest threshold: every draft exits at layer 1
+    assert res[0.1][2] > res[0.3][2] > res[0.9][2]            # fewer drafts as the threshold rises
+    assert res[0.3][0] > res[0.1][0] and res[0.3][0] > res[0.9][0]   # tokens per round peak in between
+    assert res[0.3][1] < res[0.1][1] and res[0.3][1] < res[0.9][1]   # and the weight sweeps bottom out
