@@ -89,3 +89,17 @@ def test_null_and_invalid_arguments_are_rejected_on_the_host():
     assert L.sb_op_gemv(x.ctypes.data, 0, 16, 128, x.ctypes.data, x.ctypes.data, 1, sb.PROJ_MFMA, None, None) == sb.EINVAL
     assert L.sb_op_attention(x.ctypes.data, 4, 4, 64, 0, x.ctypes.data, x.ctypes.data, 2, 0, x.ctypes.data,
                              x.ctypes.data, 30, 4, x.ctypes.data, x.ctypes.data, None) == sb.ECAPACITY
+    # the newer entry points reject NULL handles and bad shapes the same way
+    assert L.sb_decode(None, 1, None, None, 0, None, None) == sb.EINVAL
+    assert L.sb_rewind(None, 0, 0, 0) == sb.EINVAL
+    assert L.sb_profile_begin(None, 0, 0, 1) == sb.EINVAL
+    assert L.sb_profile_end(None, None, None, None, None) == sb.EINVAL
+    assert L.sb_op_repack(None, 16, 128, None, None) == sb.EINVAL
+    assert L.sb_op_repack(x.ctypes.data, 24, 128, x.ctypes.data, None) == sb.EINVAL     # N % 16
+    assert L.sb_op_gemm(None, 16, 128, None, None, 1, None, None) == sb.EINVAL
+    p = x.ctypes.data
+    assert L.sb_op_gemm(p, 16, 128, p, p, 65, p, None) == sb.EINVAL                     # more than 64 rows
+    assert L.sb_op_gemm(p, 16, 64, p, p, 1, p, None) == sb.EINVAL                       # K % 128
+    assert L.sb_op_gemm(p, 20, 128, p, p, 1, p, None) == sb.EINVAL                      # N % 16
+    assert L.sb_op_gemm_scratch_bytes(20, 128) == 0
+    assert L.sb_op_gemm_scratch_bytes(4096, 4096) >= 2 * 64 * 4096 * 2 + 64 * 4096 * 4
