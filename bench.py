@@ -20,7 +20,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes fetched per launch of the gate/up projection at the C2 shape, from
 # rocprofv3 --pmc FETCH_SIZE scaled by the same counter's reading on the plain copy
 # kernel (2.000 KiB per count); summary in profiles/c2_projection_hbm_traffic.txt
-MEASURED_TRAFFIC = {"C2": 88385.6 * 2.0 * 1024}
+MEASURED_TRAFFIC = {"C2": 88201.1 * 2.0 * 1024}
 
 
 def log(*a):
