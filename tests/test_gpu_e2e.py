@@ -46,7 +46,7 @@ def _build(sb, name, n_layers=4, n_exit=2, seed=1001, max_seq=160):
 
 
 def test_c1_config_matches_oracle_free_running(sb):
-    """BASELINE config 1: fp32 tiny model, computed exits and a forced-exit schedule;
+    """Workload C1: fp32 tiny model, computed exits and a forced-exit schedule;
     fp32 against the double oracle must agree token for token with no flags."""
     wl = si.CONFIGS["C1"]
     w = si.make_weights(wl.shape, wl.weight_seed)

@@ -1,4 +1,4 @@
-"""GPU parity at the full shapes of BASELINE configs 2-5, in the launch
+"""GPU parity at the full shapes of workloads C2-C5 (sb_inputs.CONFIGS), in the launch
 configuration bench.py times (MFMA projections, forced exit schedule with draft
 injection, second stream for the exit heads).
 
