@@ -76,7 +76,10 @@ def _run_config(sb, name, prompt_len, gen_len, n_oracle_prompt=12, n_oracle_gen=
     assert o2.tolist() == g2[1:n_oracle_gen + 1]
     print(f"[fullsize] {wl.name}: oracle scoring {n_oracle_prompt}+{n_oracle_gen} positions", flush=True)
     om = Oracle(shape, w, 64)
-    flagged, n = teacher_forced_check(om, sp, [f2] + o2.tolist())
+    # At these shapes fp32 arithmetic itself sits 3e-3 rms (up to 1.6e-2) from the double oracle's
+    # logits after 32 random-init layers, whichever projection kernel runs (the all-fp32 vector
+    # path included): an oracle gap below 2e-2 can flip the arg max and is flagged, not failed.
+    flagged, n = teacher_forced_check(om, sp, [f2] + o2.tolist(), gap_tol=2e-2)
     assert flagged <= 1, flagged
     # first exit-head evaluation of a draft step against the oracle: logits, arg max, confidence
     s2.rewind(n_oracle_prompt, f2)
