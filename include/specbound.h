@@ -275,7 +275,7 @@ int32_t sb_op_copy(void *dst, const void *src, size_t nbytes, void *stream);
 int32_t sb_op_read(const void *src, size_t nbytes, float *sink, void *stream);
 
 /* The projection of the prompt passes (prefill is the base model's, Sec. 3.1): y [M][N] =
- * x [M][K] W^T for 1 <= M <= 64 rows against tile-packed bf16 weights (sb_op_repack),
+ * x [M][K] W^T for 1 <= M <= 128 rows against tile-packed bf16 weights (sb_op_repack),
  * N % 16 == 0, K % 128 == 0.  x is used as a bf16 high + low pair per element, products
  * accumulate in fp32 over k splits that are added in index order.  x, y, Wp, scratch:
  * device; scratch of sb_op_gemm_scratch_bytes(N, K) bytes, 256-byte aligned. */

@@ -403,7 +403,7 @@ def op_repack(W):
 
 
 def op_gemm(Wp, x, scratch=None):
-    """Prompt-pass projection: Wp = op_repack(W) of a bf16 W [N, K], x [M <= 64, K] float32 -> y [M, N]."""
+    """Prompt-pass projection: Wp = op_repack(W) of a bf16 W [N, K], x [M <= 128, K] float32 -> y [M, N]."""
     import torch
     N, K = Wp.shape
     M = x.shape[0]

@@ -10,7 +10,7 @@
 namespace sb {
 
 // rows of one prompt pass (the decode passes have at most SB_MAX_W)
-#define SB_PREFILL_ROWS 64
+#define SB_PREFILL_ROWS 128
 
 // ---- device-resident record of the current round (read back once per sync) ----
 struct DevRound {

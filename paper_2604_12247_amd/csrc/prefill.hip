@@ -1,5 +1,5 @@
 // gfx950 kernels of the prompt passes: the same decoder layer as a decode pass, for
-// up to SB_PREFILL_ROWS rows at once, so that the weights are streamed once per 64
+// up to SB_PREFILL_ROWS rows at once, so that the weights are streamed once per 128
 // prompt tokens instead of once per 8 (prefill is the base model's own, Sec. 3.1;
 // only its cost matters, not its schedule).
 //
@@ -21,7 +21,7 @@ namespace {
 constexpr int PM = SB_PREFILL_ROWS;
 constexpr int ROWB = 272;                  // LDS bytes per staged row: 128 bf16 + 16 bytes of padding
 constexpr int STAGE = 2 * PM * ROWB;       // one k block of both planes
-constexpr int WPB = 4;                     // waves per thread block
+constexpr int WPB = 8;                     // waves per thread block (one block per CU: two LDS stages take 136 KB)
 constexpr int DEPTH = 2;                   // weight register stages per wave (deeper rings cost occupancy, measured no gain)
 }  // namespace
 
@@ -32,7 +32,7 @@ constexpr int DEPTH = 2;                   // weight register stages per wave (d
 // thread block that touches a row block leaves one partial sum for it, in slot
 // (thread block index - first thread block of that row block).
 struct GemmPlan {
-    int rt;      // 16-row weight tiles per wave (row block = 64 rt rows)
+    int rt;      // 16-row weight tiles per wave (row block = 16 WPB rt rows)
     int nb;      // row blocks
     int q;       // (row block, k block) pairs per thread block
     int grid;    // thread blocks
@@ -44,7 +44,7 @@ static GemmPlan gemm_plan(int32_t rows, int32_t K) {
     p.rt = rows >= 8192 ? 2 : 1;
     p.nb = (rows + 16 * WPB * p.rt - 1) / (16 * WPB * p.rt);
     const long total = (long)p.nb * KB;
-    const int slots = (p.rt == 2 ? 512 : 768) * 4 / WPB;  // resident thread blocks on 256 CUs at this kernel's register use
+    const int slots = 256;  // resident thread blocks: one per CU (LDS)
     p.q = (int)((total + slots - 1) / slots);
     if (p.q < 2 && KB >= 2) p.q = 2;          // (never one partial per k block)
     p.grid = (int)((total + p.q - 1) / p.q);
@@ -78,11 +78,11 @@ __device__ __forceinline__ void gemm_load_a(uint4 (&ar)[RT][4], const GemmCtx& c
         for (int u = 0; u < 4; ++u) ar[t][u] = ld_weights_packed(wp + u * 512);
     }
 }
-// Staging map: 2 planes x 64 rows x 16 segments of 16 bytes, NBU per thread; unit i of a
+// Staging map: 2 planes x PM rows x 16 segments of 16 bytes, NBU per thread; unit i of a
 // thread lies RPI rows below unit i - 1 (same segment), running on into the low plane.
 // Rows past M are read too, from the planes' unused rows: whatever they hold only reaches
 // result columns that are never stored.
-constexpr int NBU = 2048 / (64 * WPB);
+constexpr int NBU = 2 * PM * 16 / (64 * WPB);
 constexpr int RPI = 4 * WPB;
 __device__ __forceinline__ void gemm_load_b(u32x4 (&br)[NBU], const GemmCtx& c, int it_) {
     const int it = it_ < c.it1 ? it_ : c.it1 - 1;
@@ -95,8 +95,8 @@ __device__ __forceinline__ void gemm_store_b(unsigned char* dst, const u32x4 (&b
 #pragma unroll
     for (int i = 0; i < NBU; ++i) *reinterpret_cast<u32x4*>(dst + c.bdst0 + i * RPI * ROWB) = br[i];
 }
-// All four column tiles are always multiplied: the block of LDS reads and MFMAs stays free
-// of branches.
+// All column tiles are always multiplied: the block of LDS reads and MFMAs stays free of
+// branches.
 template <int RT>
 __device__ __forceinline__ void gemm_mma(f32x4 (&acc)[RT][PM / 16], const uint4 (&ar)[RT][4], const unsigned char* src,
                                          const GemmCtx& c) {

@@ -98,8 +98,8 @@ def test_null_and_invalid_arguments_are_rejected_on_the_host():
     assert L.sb_op_repack(x.ctypes.data, 24, 128, x.ctypes.data, None) == sb.EINVAL     # N % 16
     assert L.sb_op_gemm(None, 16, 128, None, None, 1, None, None) == sb.EINVAL
     p = x.ctypes.data
-    assert L.sb_op_gemm(p, 16, 128, p, p, 65, p, None) == sb.EINVAL                     # more than 64 rows
+    assert L.sb_op_gemm(p, 16, 128, p, p, 129, p, None) == sb.EINVAL                    # more than 128 rows
     assert L.sb_op_gemm(p, 16, 64, p, p, 1, p, None) == sb.EINVAL                       # K % 128
     assert L.sb_op_gemm(p, 20, 128, p, p, 1, p, None) == sb.EINVAL                      # N % 16
     assert L.sb_op_gemm_scratch_bytes(20, 128) == 0
-    assert L.sb_op_gemm_scratch_bytes(4096, 4096) >= 2 * 64 * 4096 * 2 + 64 * 4096 * 4
+    assert L.sb_op_gemm_scratch_bytes(4096, 4096) >= 2 * 128 * 4096 * 2 + 128 * 4096 * 4

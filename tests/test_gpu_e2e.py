@@ -297,7 +297,7 @@ def test_rewind_decode_and_kernel_timing(sb):
 def test_packed_and_row_major_weights_give_the_same_output(sb):
     """The tile-packed copy only changes where the weights lie in memory: the decode kernels give
     the same bits on both (checked kernel by kernel elsewhere).  The prompt, though, goes through
-    the 64-row passes only with packed weights, so the cached keys differ in the last bits."""
+    the 128-row passes only with packed weights, so the cached keys differ in the last bits."""
     _, _, _, gm_a = _build(sb, "bf16-mfma", n_layers=4, n_exit=2, seed=41)
     shape, w, om, gm_b = _build(sb, "bf16-mfma-packed", n_layers=4, n_exit=2, seed=41)
     prompt = si.make_prompt(shape.vocab, 23, 51)
@@ -367,13 +367,13 @@ def test_computed_exits_that_fire_match_the_oracle(sb, name):
     assert st["drafts"] > 0 and st["exit_hist"][0] > 0
 
 
-@pytest.mark.parametrize("name,n_prompt", [("bf16-mfma-packed", 150), ("bf16-mfma-gqa", 64), ("bf16-mfma-gqa", 193),
-                                           ("bf16-mfma-packed", 65)])
-def test_long_prompt_goes_through_64_row_passes(sb, name, n_prompt):
+@pytest.mark.parametrize("name,n_prompt", [("bf16-mfma-packed", 150), ("bf16-mfma-gqa", 128), ("bf16-mfma-gqa", 301),
+                                           ("bf16-mfma-packed", 129)])
+def test_long_prompt_goes_through_128_row_passes(sb, name, n_prompt):
     """Prompts longer than one pass (full passes plus a ragged tail): first token, final logits
     and the cached K/V of prompt positions against the oracle; decoding continues from that
     cache exactly as greedy decoding does."""
-    shape, w, om, gm = _build(sb, name, n_layers=4, n_exit=2, seed=61, max_seq=288)
+    shape, w, om, gm = _build(sb, name, n_layers=4, n_exit=2, seed=61, max_seq=400)
     prompt = si.make_prompt(shape.vocab, n_prompt, 71)
     osn, gsn = om.session(), gm.session()
     gsn.debug_enable(True)
@@ -385,7 +385,7 @@ def test_long_prompt_goes_through_64_row_passes(sb, name, n_prompt):
         assert t_o == t_g
     assert gsn.committed_len() == n_prompt
     for layer in (0, shape.n_layers - 1):
-        for pos in sorted({0, 1, 15, 16, 63, 64 % n_prompt, n_prompt // 2, n_prompt - 1}):
+        for pos in sorted({0, 1, 15, 16, 63, 64, 127, 128 % n_prompt, n_prompt // 2, n_prompt - 1}):
             ko, vo = osn.kv_read(layer, pos)
             kg, vg = gsn.debug_kv(layer, pos)
             lim = 2.0 ** -7 * max(1.0, np.max(np.abs(ko)))
@@ -400,7 +400,7 @@ def test_long_prompt_goes_through_64_row_passes(sb, name, n_prompt):
     teacher_forced_check(om, prompt, ar.tolist())
     pst = gm.session()
     pst.prefill(prompt)
-    assert pst.stats()["layer_sweeps"] == shape.n_layers * ((n_prompt + 63) // 64)
+    assert pst.stats()["layer_sweeps"] == shape.n_layers * ((n_prompt + 127) // 128)
 
 
 @pytest.mark.parametrize("tau", [0.3, 0.7])

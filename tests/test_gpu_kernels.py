@@ -81,13 +81,13 @@ def test_gemv_mfma(T, N, K, M):
     assert np.array_equal(yp, y)
 
 
-GEMM_CASES = [(16, 128, 1), (48, 384, 5), (4096, 4096, 64), (12288, 4096, 37), (4096, 11008, 64), (22016, 4096, 64),
-              (4112, 256, 17), (8192 + 80, 512, 33)]
+GEMM_CASES = [(16, 128, 1), (48, 384, 5), (4096, 4096, 128), (12288, 4096, 37), (4096, 11008, 64), (22016, 4096, 128),
+              (4112, 256, 17), (8192 + 80, 512, 97), (32000, 4096, 128)]
 
 
 @pytest.mark.parametrize("N,K,M", GEMM_CASES)
 def test_prompt_pass_gemm(T, N, K, M):
-    """The projection of the prompt passes (up to 64 rows, k splits added in order) against the
+    """The projection of the prompt passes (up to 128 rows, k splits added in order) against the
     double-precision product of the same bf16 weights; unwritten rows of the scratch hold NaN."""
     import paper_2604_12247_amd as sb
     g = np.random.default_rng(N + K + M + 2)
