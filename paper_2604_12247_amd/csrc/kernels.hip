@@ -985,8 +985,11 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         const int key = key0 + wave * 32 + t * 16 + li;
+        // a tile is one page: its table entry is wave-uniform, read through the scalar cache
+        const int kpage = __builtin_amdgcn_readfirstlane((key0 + wave * 32 + t * 16) / SB_KV_BLOCK);
         kaddr[t] = 0;
-        if (key < n_total) kaddr[t] = (size_t)a.kv.table[key / SB_KV_BLOCK] * page_elems + ((size_t)g * SB_KV_BLOCK + li) * HD + lq * 8;
+        if (kpage * SB_KV_BLOCK < n_total)
+            kaddr[t] = (size_t)a.kv.table[kpage] * page_elems + ((size_t)g * SB_KV_BLOCK + li) * HD + lq * 8;
 #pragma unroll
         for (int ks = 0; ks < KSQ; ++ks) {
             kreg[t][ks] = make_uint4(0, 0, 0, 0);
@@ -999,8 +1002,12 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
     for (int ks = 0; ks < KSV; ++ks) {
         const int kf = key0 + ks * 32 + lq * 8;  // first key of this lane's 8
+        // the 32 keys of a step lie in two pages (lq 0-1, lq 2-3): two wave-uniform table entries
+        const int vpage = (key0 + ks * 32) / SB_KV_BLOCK;
+        const int pg0 = vpage * SB_KV_BLOCK < n_total ? a.kv.table[vpage] : 0;
+        const int pg1 = (vpage + 1) * SB_KV_BLOCK < n_total ? a.kv.table[vpage + 1] : 0;
         vaddr[ks] = 0;
-        if (kf < n_total) vaddr[ks] = (size_t)a.kv.table[kf / SB_KV_BLOCK] * page_elems + ((size_t)g * HD + wave * DT * 16 + li) * SB_KV_BLOCK + (lq & 1) * 8;
+        if (kf < n_total) vaddr[ks] = (size_t)(lq < 2 ? pg0 : pg1) * page_elems + ((size_t)g * HD + wave * DT * 16 + li) * SB_KV_BLOCK + (lq & 1) * 8;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             vreg[dt][ks] = make_uint4(0, 0, 0, 0);
