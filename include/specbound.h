@@ -101,7 +101,12 @@ typedef struct sb_weights {
  *             in 1..d_max makes step k exit exactly there, 0 makes it never exit;
  *             forced_draft[k] >= 0 replaces the drafted token id, -1 keeps the
  *             head's arg max.  Exit heads of all layers up to the exit layer are
- *             still evaluated.  Steps past n_forced use the computed test. */
+ *             still evaluated.  Steps past n_forced use the computed test.
+ *  head_mask  0: an exit head is evaluated after every layer 1..d_max, the
+ *             paper's rule (Sec. 3.2).  Otherwise bit l-1 set means layer l has
+ *             its head evaluated; the other layers are passed without a test, so
+ *             a token can only exit at a layer of the mask (a cheaper variant, not
+ *             the paper's rule; forced_exit must then name layers of the mask). */
 typedef struct sb_params {
     int32_t d_max, w_max;
     const float *T;
@@ -110,6 +115,7 @@ typedef struct sb_params {
     const int32_t *forced_exit;
     const int32_t *forced_draft;
     int64_t n_forced;
+    uint32_t head_mask;
 } sb_params;
 
 typedef struct sb_draft_result {

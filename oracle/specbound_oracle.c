@@ -70,6 +70,9 @@ typedef struct {
     const int32_t *forced_exit;  /* per draft step: 1..d_max, 0 = never exit; NULL = computed */
     const int32_t *forced_draft; /* per draft step: token override, -1 = head argmax; NULL */
     int64_t n_forced;
+    uint32_t head_mask;          /* 0: an exit head after every layer 1..d_max (Sec. 3.2); else bit l-1
+                                    set = layer l has its head evaluated, the others are passed without a
+                                    test (a variant, not the paper's rule) */
 } orc_params;
 
 typedef struct { int32_t token, exit_layer, status; float confidence; } orc_draft_result;
@@ -525,6 +528,7 @@ int32_t orc_draft_step(orc_session *s, const orc_params *p, orc_draft_result *re
     int32_t forced = (p->forced_exit && k < p->n_forced) ? p->forced_exit[k] : -1;
     int32_t override = (p->forced_draft && k < p->n_forced) ? p->forced_draft[k] : -1;
     if (forced > p->d_max || override >= c->vocab) return ORC_EINVAL;
+    if (forced >= 1 && p->head_mask && !((p->head_mask >> (forced - 1)) & 1u)) return ORC_EINVAL;
     s->draft_counter++;
     s->st.draft_steps++;
 
@@ -538,6 +542,7 @@ int32_t orc_draft_step(orc_session *s, const orc_params *p, orc_draft_result *re
     res->token = -1; res->exit_layer = 0; res->status = ORC_DEPTH_BOUND; res->confidence = 0;
     for (int32_t l = 1; l <= p->d_max; ++l) {
         advance_rows(s, l, ORC_PH_DRAFT);
+        if (p->head_mask && !((p->head_mask >> (l - 1)) & 1u)) continue;   /* no head at this layer */
         orc_rmsnorm(sl->h, s->m->w.exit_norm[l - 1], c->d_model, c->rms_eps, s->xn);
         orc_matvec(s->m->w.exit_head[l - 1], c->weight_dtype, c->vocab, c->d_model, s->xn, s->head_logits);
         orc_act(s->head_logits, c->vocab, (real)p->T[l - 1], &s->last_argmax, &s->last_conf);

@@ -47,7 +47,7 @@ class sb_params(C.Structure):
     _fields_ = [("d_max", C.c_int32), ("w_max", C.c_int32), ("T", C.POINTER(C.c_float)),
                 ("threshold", C.c_float), ("eos_id", C.c_int32),
                 ("forced_exit", C.POINTER(C.c_int32)), ("forced_draft", C.POINTER(C.c_int32)),
-                ("n_forced", C.c_int64)]
+                ("n_forced", C.c_int64), ("head_mask", C.c_uint32)]
 
 
 class sb_draft_result(C.Structure):
@@ -172,7 +172,7 @@ class Params:
 
     def __init__(self, d_max: int, w_max: int, T: Sequence[float], threshold: float,
                  forced_exit: Optional[Sequence[int]] = None, forced_draft: Optional[Sequence[int]] = None,
-                 eos_id: int = -1):
+                 eos_id: int = -1, head_mask: int = 0):
         self.T = np.ascontiguousarray(T, dtype=np.float32)
         self.fe = None if forced_exit is None else np.ascontiguousarray(forced_exit, dtype=np.int32)
         self.fd = None if forced_draft is None else np.ascontiguousarray(forced_draft, dtype=np.int32)
@@ -186,7 +186,7 @@ class Params:
                            threshold, eos_id,
                            None if self.fe is None else self.fe.ctypes.data_as(C.POINTER(C.c_int32)),
                            None if self.fd is None else self.fd.ctypes.data_as(C.POINTER(C.c_int32)),
-                           n_forced)
+                           n_forced, head_mask)
 
 
 def _stats_dict(st: sb_stats) -> dict:

@@ -543,6 +543,8 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
     int forced = (p->forced_exit && k < p->n_forced) ? p->forced_exit[k] : -1;
     int over = (p->forced_draft && k < p->n_forced) ? p->forced_draft[k] : -1;
     if (forced > p->d_max) return fail(SB_EINVAL, "forced_exit[%lld] = %d exceeds d_max", (long long)k, forced);
+    if (forced >= 1 && p->head_mask && !((p->head_mask >> (forced - 1)) & 1u))
+        return fail(SB_EINVAL, "forced_exit[%lld] = %d names a layer outside head_mask", (long long)k, forced);
     if (over >= c.vocab) return fail(SB_EINVAL, "forced_draft[%lld] = %d out of range", (long long)k, over);
     if (forced < -1) forced = -1;
     if (over < -1) over = -1;
@@ -565,12 +567,15 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
     s->exit_layer[idx] = 0;
     s->draft_host[idx] = -1;
 
-    int exit_at = 0;
+    int exit_at = 0, n_heads_run = 0;
     for (int l = 1; l <= p->d_max; ++l) {
         int j0 = idx;
         while (j0 > 0 && s->reached[j0 - 1] == l - 1) --j0;
-        if ((rc = run_layer(s, l - 1, j0, idx - j0 + 1, m->exit_norm[l - 1]))) return rc;
+        const bool has_head = !p->head_mask || ((p->head_mask >> (l - 1)) & 1u);
+        if ((rc = run_layer(s, l - 1, j0, idx - j0 + 1, has_head ? m->exit_norm[l - 1] : nullptr))) return rc;
         for (int j = j0; j <= idx; ++j) s->reached[j] = l;
+        if (!has_head) continue;  // (variant: no exit test at this layer)
+        ++n_heads_run;
         HeadArgs h{};
         h.T = p->T[l - 1]; h.post = POST_EXIT; h.slot = idx; h.layer = l; h.forced_exit = forced; h.forced_draft = over;
         h.threshold = p->threshold;
@@ -596,9 +601,9 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
             break;
         }
     }
-    if (!computed && sync && p->d_max > 0)
+    if (!computed && sync && n_heads_run > 0)
         if ((rc = readback(s))) return rc;
-    const bool have = (computed || sync) && p->d_max > 0;
+    const bool have = (computed || sync) && n_heads_run > 0;
 
     sb_draft_result res{-1, 0, SB_DEPTH_BOUND, 0.f};
     if (have) res.confidence = s->h_round->conf[idx];

@@ -450,3 +450,51 @@ def test_easy_token_fixture_accepts_computed_drafts_like_the_oracle(sb, tau):
     out, st = gm.session().generate(prompt, 64, pg)
     assert out.tolist() == ar.tolist()
     assert st["emitted"] / st["rounds"] > 1.5
+
+
+@pytest.mark.parametrize("mask", [0b101, 0b010])
+def test_head_subset_variant_matches_the_oracle(sb, mask):
+    """Exit heads only at the layers of a mask (a variant of the every-layer rule of Sec. 3.2):
+    step by step against the oracle with a forced schedule on the mask's layers, then computed
+    exits on the easy-token fixture; output stays the library's own greedy one."""
+    shape, w, om, gm = _build(sb, "bf16-mfma-packed", n_layers=6, n_exit=3, seed=35)
+    prompt = si.make_prompt(shape.vocab, 19, 45)
+    allowed = [l for l in (1, 2, 3) if (mask >> (l - 1)) & 1]
+    fe = [allowed[i % len(allowed)] if i % 5 else 0 for i in range(40)]
+    T = linear_T(3)
+    po = orc.OrcParams(3, 4, T, 0.5, forced_exit=fe, head_mask=mask)
+    pg = sb.Params(3, 4, T, 0.5, forced_exit=fe, head_mask=mask)
+    osn, gsn = om.session(), gm.session()
+    assert osn.prefill(prompt) == gsn.prefill(prompt)
+    for rnd in range(4):
+        while True:
+            ro, rg = osn.draft_step(po), gsn.draft_step(pg)
+            assert (ro["status"], ro["exit_layer"]) == (rg["status"], rg["exit_layer"])
+            assert abs(ro["confidence"] - rg["confidence"]) <= 1e-3
+            if ro["token"] != rg["token"]:
+                srt = np.sort(osn.head_logits())
+                assert srt[-1] - srt[-2] < 1e-2
+                return
+            if ro["status"] != orc.EXITED:
+                break
+        vo, vg = osn.verify(po), gsn.verify(pg)
+        if vo["tokens"][: vo["n_emit"]] != vg["tokens"][: vg["n_emit"]]:
+            return
+        for k in ("n_rows", "n_drafts", "n_matched", "n_emit", "align_layer"):
+            assert vo[k] == vg[k], (rnd, k, vo, vg)
+    so, sg = osn.stats(), gsn.stats()
+    assert so["head_evals"] == sg["head_evals"] and so["exit_hist"][:4] == sg["exit_hist"][:4]
+    with pytest.raises(sb.SbError):
+        bad = [l for l in (1, 2, 3) if l not in allowed][0]
+        gm.session().generate(prompt, 4, sb.Params(3, 4, T, 0.5, forced_exit=[bad], head_mask=mask))
+    # computed exits on the structured fixture
+    kw, proj = _variants(sb)["bf16-mfma-packed"]
+    shape2 = si.tiny_shape(n_layers=12, n_exit_heads=8, **kw)
+    w2 = si.easy_token_weights(shape2, si.make_weights(shape2, 77), decay=0.5, head_scale=20.0)
+    gm2 = gpu_model(shape2, w2, 256, proj)
+    p2 = si.make_prompt(shape2.vocab, 24, 5)
+    ar, _ = gm2.session().generate(p2, 48, gpu_params(0, 1))
+    T8 = sb.temperature_schedule(0.2, 8, 8)
+    out, st = gm2.session().generate(p2, 48, sb.Params(8, 6, T8, 0.3, head_mask=0b10101010))
+    assert out.tolist() == ar.tolist()
+    assert st["drafts"] > 0 and all(st["exit_hist"][l] == 0 for l in (1, 3, 5, 7))

@@ -279,3 +279,33 @@ def test_easy_token_fixture_has_a_threshold_optimum():
     assert res[0.1][2] > res[0.3][2] > res[0.9][2]            # fewer drafts as the threshold rises
     assert res[0.3][0] > res[0.1][0] and res[0.3][0] > res[0.9][0]   # tokens per round peak in between
     assert res[0.3][1] < res[0.1][1] and res[0.3][1] < res[0.9][1]   # and the weight sweeps bottom out
+
+
+def test_head_subset_variant_stays_greedy_and_skips_heads(model6):
+    """Variant of Sec. 3.2's every-layer rule: exit heads only at the layers of a mask.  Output
+    is still the brute-force greedy one; exits happen only at layers of the mask; the head
+    count is one per evaluated layer; mask 0 and the full mask are the paper's rule."""
+    shape, w, m = model6
+    prompt = si.make_prompt(shape.vocab, 8, 104)
+    bf = m.greedy_nocache(prompt, 20).tolist()
+    thr = 2.0 / shape.vocab
+    base = None
+    for mask in (0, 0b111, 0b101, 0b010, 0b100):
+        s = m.session()
+        p = orc.OrcParams(3, 4, [1.0, 1.0, 1.0], thr, head_mask=mask)
+        out = s.generate(prompt, 20, p).tolist()
+        assert out == bf, mask
+        st = s.stats()
+        allowed = [l for l in (1, 2, 3) if mask == 0 or (mask >> (l - 1)) & 1]
+        assert all(st["exit_hist"][l] == 0 for l in (1, 2, 3) if l not in allowed), (mask, st["exit_hist"])
+        if mask in (0, 0b111):
+            if base is None:
+                base = (st["head_evals"], st["exit_hist"])
+            assert (st["head_evals"], st["exit_hist"]) == base
+        if mask == 0b100:      # a single head at layer 3: one evaluation per draft step
+            assert st["head_evals"] == st["draft_steps"]
+    # a forced exit must name a layer of the mask
+    s = m.session()
+    s.prefill(prompt)
+    with pytest.raises(Exception):
+        s.draft_step(orc.OrcParams(3, 4, [1.0, 1.0, 1.0], 0.5, forced_exit=[2], head_mask=0b101))
