@@ -112,6 +112,7 @@ struct AttnArgs {
     float* out;          // [M][n_heads*head_dim]
     uint16_t* out_split; // optional bf16 hi/lo copy: rows 0.. high parts, rows split_rows.. low parts
     int32_t split_rows;  // 8 for decode passes, SB_PREFILL_ROWS for prompt passes
+    int32_t qg_per_block;  // set by launch_attention
 };
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);

@@ -935,7 +935,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
 // Every output row of an MFMA depends on its own operand row only, so a query's
 // partial does not depend on which other queries share the block.
 template <int HD>
-__global__ __launch_bounds__(256, 4) void attn_mfma_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, 3) void attn_mfma_kernel(AttnArgs a) {
     constexpr int CH = 128, QG = 16, HALF = HD / 2;
     constexpr int KSQ = HD / 32;      // k steps (of 32 dims) of the score product
     constexpr int KSV = CH / 32;      // k steps (of 32 keys) of the value product
@@ -950,10 +950,14 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_kernel(AttnArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lq = lane >> 4;
-    const int g = blockIdx.x, chunk = blockIdx.y, qg = blockIdx.z;
+    const int g = blockIdx.x, chunk = blockIdx.y;
     const int Hq = a.n_heads, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
-    const int nq_total = a.M * G, q0 = qg * QG;
-    const int nq = (nq_total - q0 < QG) ? (nq_total - q0) : QG;
+    const int nq_total = a.M * G;
+    // this block's query groups (16 queries each), handled one after the other with the
+    // chunk's K and V held in registers
+    const int n_qg = (nq_total + QG - 1) / QG;
+    const int qg_first = blockIdx.z * a.qg_per_block;
+    const int qg_last = (qg_first + a.qg_per_block < n_qg) ? qg_first + a.qg_per_block : n_qg;
     const int key0 = chunk * CH, n_total = a.pos0 + a.M;
     const float scale = 1.0f / sqrtf((float)HD);
     const size_t page_elems = (size_t)Hkv * SB_KV_BLOCK * HD;
@@ -961,24 +965,29 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_kernel(AttnArgs a) {
     uint16_t* const vbase = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 1) * a.kv.n_pages * page_elems;
     const bool has_new = key0 + CH > a.pos0;  // the chunk holds keys of the new rows
 
-    // ---- issue every global load first: q (+ its rotary factors), K, V
+    // ---- issue every global load first: q (+ its rotary factors) of the first group, K, V
     constexpr int QIT = QG * HALF / 256;
     float qx[QIT], qy[QIT], qc[QIT], qsn[QIT];
+    auto load_q = [&](int qg) {
+        const int q0 = qg * QG;
+        const int nq = (nq_total - q0 < QG) ? (nq_total - q0) : QG;
 #pragma unroll
-    for (int it = 0; it < QIT; ++it) {
-        const int i = tid + it * 256;
-        const int qi = i / HALF, j = i - qi * HALF;
-        qx[it] = qy[it] = qsn[it] = 0.f;
-        qc[it] = 1.f;
-        if (qi < nq) {
-            int qq = q0 + qi, r = qq / G, gi = qq - r * G;
-            const float* qp = a.q + (size_t)r * a.qkv_rows + (size_t)(g * G + gi) * HD;
-            qx[it] = qp[j];
-            qy[it] = qp[j + HALF];
-            qc[it] = a.rope_cos[(size_t)(a.pos0 + r) * HALF + j];
-            qsn[it] = a.rope_sin[(size_t)(a.pos0 + r) * HALF + j];
+        for (int it = 0; it < QIT; ++it) {
+            const int i = tid + it * 256;
+            const int qi = i / HALF, j = i - qi * HALF;
+            qx[it] = qy[it] = qsn[it] = 0.f;
+            qc[it] = 1.f;
+            if (qi < nq) {
+                int qq = q0 + qi, r = qq / G, gi = qq - r * G;
+                const float* qp = a.q + (size_t)r * a.qkv_rows + (size_t)(g * G + gi) * HD;
+                qx[it] = qp[j];
+                qy[it] = qp[j + HALF];
+                qc[it] = a.rope_cos[(size_t)(a.pos0 + r) * HALF + j];
+                qsn[it] = a.rope_sin[(size_t)(a.pos0 + r) * HALF + j];
+            }
         }
-    }
+    };
+    load_q(qg_first);
     // K operands: tile t of this wave = keys key0 + wave*32 + t*16 + li (one page), dims ks*32 + lq*8 ..
     uint4 kreg[2][KSQ];
     size_t kaddr[2];
@@ -1015,18 +1024,6 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_kernel(AttnArgs a) {
         }
     }
 
-    // ---- rotated queries -> LDS as hi + lo
-#pragma unroll
-    for (int it = 0; it < QIT; ++it) {
-        const int i = tid + it * 256;
-        const int qi = i / HALF, j = i - qi * HALF;
-        const float u = qx[it] * qc[it] - qy[it] * qsn[it], v = qy[it] * qc[it] + qx[it] * qsn[it];
-        const uint16_t uh = f2bf(u), vh = f2bf(v);
-        q_hi[qi * QS + j] = uh;
-        q_lo[qi * QS + j] = f2bf(u - bf2f(uh));
-        q_hi[qi * QS + j + HALF] = vh;
-        q_lo[qi * QS + j + HALF] = f2bf(v - bf2f(vh));
-    }
     // ---- keys and values of the new rows: built from qkv, appended by query group 0
     if (has_new) {
 #pragma unroll
@@ -1048,7 +1045,7 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_kernel(AttnArgs a) {
                         f[e] = lo ? (x * c - y * sn) : (y * c + x * sn);
                     }
                     kreg[t][ks] = KvVec<uint16_t>::pack(f);
-                    if (qg == 0) *reinterpret_cast<uint4*>(kbase + kaddr[t] + ks * 32) = kreg[t][ks];
+                    if (blockIdx.z == 0) *reinterpret_cast<uint4*>(kbase + kaddr[t] + ks * 32) = kreg[t][ks];
                 }
             }
         }
@@ -1070,11 +1067,27 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_kernel(AttnArgs a) {
                         }
                     }
                     vreg[dt][ks] = make_uint4(w[0], w[1], w[2], w[3]);
-                    if (qg == 0) *reinterpret_cast<uint4*>(vbase + vaddr[ks] + dt * 16 * SB_KV_BLOCK) = vreg[dt][ks];
+                    if (blockIdx.z == 0) *reinterpret_cast<uint4*>(vbase + vaddr[ks] + dt * 16 * SB_KV_BLOCK) = vreg[dt][ks];
                 }
             }
         }
     }
+    for (int qg = qg_first; qg < qg_last; ++qg) {
+    const int q0 = qg * QG;
+    const int nq = (nq_total - q0 < QG) ? (nq_total - q0) : QG;
+    // ---- rotated queries -> LDS as hi + lo
+#pragma unroll
+    for (int it = 0; it < QIT; ++it) {
+        const int i = tid + it * 256;
+        const int qi = i / HALF, j = i - qi * HALF;
+        const float u = qx[it] * qc[it] - qy[it] * qsn[it], v = qy[it] * qc[it] + qx[it] * qsn[it];
+        const uint16_t uh = f2bf(u), vh = f2bf(v);
+        q_hi[qi * QS + j] = uh;
+        q_lo[qi * QS + j] = f2bf(u - bf2f(uh));
+        q_hi[qi * QS + j + HALF] = vh;
+        q_lo[qi * QS + j + HALF] = f2bf(v - bf2f(vh));
+    }
+    if (qg + 1 < qg_last) load_q(qg + 1);  // (in flight during this group's products)
     __syncthreads();
 
     // ---- scores of this wave's 32 keys against the 16 query rows
@@ -1155,6 +1168,8 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_kernel(AttnArgs a) {
             for (int dt = 0; dt < DT; ++dt) p[2 + (wave * DT + dt) * 16 + li] = o[dt][r];
             if (wave == 0 && li == 0) { p[0] = s_m[qi]; p[1] = s_l[qi]; }
         }
+    }
+    __syncthreads();  // the next group overwrites the LDS arrays
     }
 }
 
@@ -1250,15 +1265,24 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     const int n_chunks = (a.pos0 + a.M + ch - 1) / ch;
     if (n_chunks > a.max_chunks || n_chunks > 512) return hipErrorInvalidValue;
     const int G = a.n_heads / a.kv.n_kv_heads;
-    dim3 grid(a.kv.n_kv_heads, n_chunks, (a.M * G + 15) / 16);
+    // Query groups of 16: one block each while the launch is small; in a large launch (a prompt
+    // pass over a long context) a block takes several groups in turn on one load of its K/V
+    // chunk.  A query's result does not depend on the grouping.
+    const int n_qg = (a.M * G + 15) / 16;
+    int qpb = (int)(((long)a.kv.n_kv_heads * n_chunks * n_qg + 1023) / 1024);
+    if (qpb > n_qg) qpb = n_qg;
+    AttnArgs b = a;
+    b.qg_per_block = qpb;
+    dim3 grid(a.kv.n_kv_heads, n_chunks, (n_qg + qpb - 1) / qpb);
+    dim3 grid1(a.kv.n_kv_heads, n_chunks, n_qg);
     if (!a.rope_cos || !a.rope_sin) return hipErrorInvalidValue;
     dim3 mgrid(a.n_heads, a.M);
     if (a.kv.kv_dtype == SB_BF16) {
-        if (hd == 128) { attn_mfma_kernel<128><<<grid, 256, 0, st>>>(a); attn_merge_kernel<128, 128><<<mgrid, 256, 0, st>>>(a); }
-        else { attn_mfma_kernel<64><<<grid, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }
+        if (hd == 128) { attn_mfma_kernel<128><<<grid, 256, 0, st>>>(b); attn_merge_kernel<128, 128><<<mgrid, 256, 0, st>>>(a); }
+        else { attn_mfma_kernel<64><<<grid, 256, 0, st>>>(b); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }
     } else {
-        if (hd == 128) { attn_kernel<float, 128><<<grid, 256, 0, st>>>(a); attn_merge_kernel<128, 64><<<mgrid, 256, 0, st>>>(a); }
-        else { attn_kernel<float, 64><<<grid, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }
+        if (hd == 128) { attn_kernel<float, 128><<<grid1, 256, 0, st>>>(a); attn_merge_kernel<128, 64><<<mgrid, 256, 0, st>>>(a); }
+        else { attn_kernel<float, 64><<<grid1, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }
     }
     return hipGetLastError();
 }
