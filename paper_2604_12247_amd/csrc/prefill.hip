@@ -238,14 +238,33 @@ __device__ __forceinline__ int splits_of(const GemmSplitMap& mp, int n) {
 }
 
 // grid (ceil(N / 256), M): thread = one output element
+// Partial sums of one element, added in slot order; eight loads are in flight at a time.
+__device__ __forceinline__ float sum_splits(const float* p, size_t plane, int n_splits) {
+    float v = 0.f;
+    for (int s0 = 0; s0 < n_splits; s0 += 8) {
+        float t[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = s0 + i < n_splits ? p[(size_t)(s0 + i) * plane] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v += t[i];
+    }
+    return v;
+}
+
 template <int EPI>
 __global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a, GemmSplitMap mp) {
     __shared__ float red[4];
     const int tid = threadIdx.x, m = blockIdx.y, n = blockIdx.x * 256 + tid;
     float inv = 1.0f;
-    if (a.ssq_in) {
+    if (a.ssq_in) {  // (added in index order; sixteen loads in flight at a time)
         float t = 0.f;
-        for (int b = 0; b < a.ssq_nb; ++b) t += a.ssq_in[(size_t)m * a.ssq_ld + b];
+        for (int b0 = 0; b0 < a.ssq_nb; b0 += 16) {
+            float q[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) q[i] = b0 + i < a.ssq_nb ? a.ssq_in[(size_t)m * a.ssq_ld + b0 + i] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t += q[i];
+        }
         inv = 1.0f / sqrtf(t / (float)a.K + a.eps);
     }
     const size_t plane = (size_t)PM * a.rows;
@@ -253,15 +272,11 @@ __global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a, Ge
     float sq = 0.f;
     if (n < a.N) {
         if (EPI == EPI_SWIGLU) {
-            float g = 0.f, u = 0.f;
-            const int sg = splits_of(mp, n), su = splits_of(mp, a.N + n);
-            for (int s = 0; s < sg; ++s) g += p[s * plane + n];
-            for (int s = 0; s < su; ++s) u += p[s * plane + a.N + n];
+            const float g = sum_splits(p + n, plane, splits_of(mp, n));
+            const float u = sum_splits(p + a.N + n, plane, splits_of(mp, a.N + n));
             split_store_rows(a.ys, a.N, PM, m, n, silu_mul(g * inv, u * inv));
         } else {
-            float v = 0.f;
-            const int sn = splits_of(mp, n);
-            for (int s = 0; s < sn; ++s) v += p[s * plane + n];
+            float v = sum_splits(p + n, plane, splits_of(mp, n));
             v *= inv;
             float* yp = a.y + (size_t)m * a.ldy + n;
             if (EPI == EPI_RESID) {
