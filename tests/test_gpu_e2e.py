@@ -32,6 +32,8 @@ def _variants(sb):
         "bf16-mfma-packed": (dict(weight_dtype=B, kv_dtype=B, d_ffn=768), sb.PROJ_MFMA_PACKED),
         "bf16-mfma-gqa": (dict(weight_dtype=B, kv_dtype=B, d_ffn=768, n_kv_heads=2, rope_base=500000.0), sb.PROJ_AUTO),
         "fp32-gqa-bf16kv": (dict(n_kv_heads=1, kv_dtype=B), sb.PROJ_AUTO),
+        # many heads: a long prompt's attention launch is large enough for blocks to take several query groups
+        "bf16-many-heads": (dict(weight_dtype=B, kv_dtype=B, d_ffn=768, n_heads=32, n_kv_heads=32, head_dim=64), sb.PROJ_AUTO),
     }
 
 
@@ -368,12 +370,12 @@ def test_computed_exits_that_fire_match_the_oracle(sb, name):
 
 
 @pytest.mark.parametrize("name,n_prompt", [("bf16-mfma-packed", 150), ("bf16-mfma-gqa", 128), ("bf16-mfma-gqa", 301),
-                                           ("bf16-mfma-packed", 129)])
+                                           ("bf16-mfma-packed", 129), ("bf16-many-heads", 700)])
 def test_long_prompt_goes_through_128_row_passes(sb, name, n_prompt):
     """Prompts longer than one pass (full passes plus a ragged tail): first token, final logits
     and the cached K/V of prompt positions against the oracle; decoding continues from that
     cache exactly as greedy decoding does."""
-    shape, w, om, gm = _build(sb, name, n_layers=4, n_exit=2, seed=61, max_seq=400)
+    shape, w, om, gm = _build(sb, name, n_layers=4, n_exit=2, seed=61, max_seq=max(400, (n_prompt + 127) // 16 * 16))
     prompt = si.make_prompt(shape.vocab, n_prompt, 71)
     osn, gsn = om.session(), gm.session()
     gsn.debug_enable(True)
