@@ -173,7 +173,9 @@ def main():
         "metric": "batch1_generated_tokens_per_s", "value": round(tok_s, 2), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights, f32 accumulate" if shape.weight_dtype == si.configs.BF16 else "f32",
+        "dtype": "bf16" if shape.weight_dtype == si.configs.BF16 else "f32",
+        "arithmetic": ("bf16 weights x activations carried as bf16 high + low parts on the matrix cores, fp32 accumulation, "
+                       "bf16 KV cache" if shape.weight_dtype == si.configs.BF16 else "fp32 on the vector ALUs"),
         "data": "synthetic",
         "config": {"workload": wl.name, "prompt_len": P, "gen_len": gen_len, "d_max": wl.d_max,
                    "w_max": wl.w_max, "threshold": wl.threshold, "T": [round(t, 4) for t in T],
