@@ -117,29 +117,36 @@ struct AttnArgs {
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
 
-// ---- prompt passes: up to SB_PREFILL_ROWS rows against tile-packed bf16 weights ----
-// Activations come as bf16 planes xs [2 * SB_PREFILL_ROWS][K] (high parts, then low
-// parts); the product is left as k-split partial sums part [S][SB_PREFILL_ROWS][rows]
-// for the epilogue that follows.
+// ---- prompt passes: SB_PREFILL_ROWS rows each, against tile-packed bf16 weights ----
+// Up to SB_PREFILL_PASSES passes of one layer go into one launch (a "super-pass"), so
+// that the passes' thread blocks meet on the same weights in the caches.  Activations
+// come as bf16 planes xs [2][plane_rows][K] (high parts, then low parts; row r of pass p
+// is row p * SB_PREFILL_ROWS + r); the product is left as k-split partial sums
+// part [n_pass][S][SB_PREFILL_ROWS][rows] for the epilogue that follows.
+#define SB_PREFILL_PASSES 16
 struct GemmArgs {
     const void* Wp;      // packed weights [rows][K]
     int32_t rows, K;
     const uint16_t* xs;
-    int32_t M;           // live rows
+    int32_t plane_rows;
+    int32_t M;           // live rows over all passes
+    int32_t n_pass;      // ceil(M / SB_PREFILL_ROWS)
     float* part;
-    int32_t S;           // k splits, from gemm_splits()
+    int32_t S;           // partial-sum slots per row block, from gemm_splits()
 };
-int gemm_splits(int32_t rows, int32_t K);
+int gemm_splits(int32_t rows, int32_t K, int32_t n_pass);
 hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st);
 
 // Sums the k splits in order, applies the RMSNorm scale of the input row (from the
 // partial sums of squares its producer left; nullable) and finishes the projection.
+// Rows are indexed over the whole super-pass.
 struct GemmEpiArgs {
     const float* part;
     int32_t S, rows;
-    int32_t N, M;          // output columns (rows, or rows / 2 for the gate/up pair), live rows
+    int32_t N, M, n_pass;  // output columns (rows, or rows / 2 for the gate/up pair), live rows, passes
+    int32_t plane_rows;    // rows between the high and the low plane of nx / ys
     int32_t epi;           // EPI_STORE, EPI_RESID, EPI_SWIGLU
-    const float* ssq_in;   // [SB_PREFILL_ROWS][ssq_ld] partial sums of squares of the input rows
+    const float* ssq_in;   // [M][ssq_ld] partial sums of squares of the input rows
     int32_t ssq_nb, ssq_ld, K;
     float eps;
     float* y;              // STORE: y = v; RESID: y += v        [M][ldy]
@@ -152,10 +159,10 @@ struct GemmEpiArgs {
 hipError_t launch_prefill_epilogue(const GemmEpiArgs& a, hipStream_t st);
 // Embedding rows of tokens[0..M) (device ids): H [M][d], bf16 planes of gain * h, sums of squares.
 hipError_t launch_prefill_embed(const void* E, int32_t w_dtype, int32_t vocab, int32_t d, const int32_t* tokens,
-                                int32_t M, float* H, const float* gain, uint16_t* nx, float* ssq_out, int32_t ssq_ld,
-                                hipStream_t st);
-// x [M][K] float -> bf16 planes (M <= SB_PREFILL_ROWS)
-hipError_t launch_prefill_split(const float* x, uint16_t* xs, int32_t M, int32_t K, hipStream_t st);
+                                int32_t M, float* H, const float* gain, uint16_t* nx, int32_t plane_rows,
+                                float* ssq_out, int32_t ssq_ld, hipStream_t st);
+// x [M][K] float -> bf16 planes [2][plane_rows][K]
+hipError_t launch_prefill_split(const float* x, uint16_t* xs, int32_t plane_rows, int32_t M, int32_t K, hipStream_t st);
 
 hipError_t launch_copy(void* dst, const void* src, size_t nbytes, hipStream_t st);
 hipError_t launch_read(const void* src, size_t nbytes, float* sink, hipStream_t st);

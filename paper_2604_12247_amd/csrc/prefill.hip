@@ -30,7 +30,7 @@ constexpr int DEPTH = 2;                   // weight register stages per wave (d
 // the same number of weight bytes whatever the shape (a plain k split leaves a ragged
 // last round of blocks on 256 CUs).  A range may end in the middle of a row block: each
 // thread block that touches a row block leaves one partial sum for it, in slot
-// (thread block index - first thread block of that row block).
+// (range index - first range of that row block).
 struct GemmPlan {
     int rt;      // 16-row weight tiles per wave (row block = 16 WPB rt rows)
     int nb;      // row blocks
@@ -38,21 +38,25 @@ struct GemmPlan {
     int grid;    // thread blocks
     int smax;    // most partial sums a row block can get
 };
-static GemmPlan gemm_plan(int32_t rows, int32_t K) {
+static GemmPlan gemm_plan(int32_t rows, int32_t K, int32_t n_pass) {
     GemmPlan p;
     const int KB = K >> 7;
     p.rt = rows >= 8192 ? 2 : 1;
     p.nb = (rows + 16 * WPB * p.rt - 1) / (16 * WPB * p.rt);
     const long total = (long)p.nb * KB;
-    const int slots = 256;  // resident thread blocks: one per CU (LDS)
+    // resident thread blocks: one per CU (LDS), shared out among the passes of the launch --
+    // every pass gets the same cut, so the blocks of different passes that work on the same
+    // weights are neighbours in the grid and run at the same time
+    int slots = 256 / n_pass;
+    if (slots < 1) slots = 1;
     p.q = (int)((total + slots - 1) / slots);
     if (p.q < 2 && KB >= 2) p.q = 2;          // (never one partial per k block)
-    p.grid = (int)((total + p.q - 1) / p.q);
+    p.grid = (int)((total + p.q - 1) / p.q);  // per pass
     p.smax = (KB + p.q - 1) / p.q + 1;
     if (p.smax > KB) p.smax = KB;
     return p;
 }
-int gemm_splits(int32_t rows, int32_t K) { return gemm_plan(rows, K).smax; }
+int gemm_splits(int32_t rows, int32_t K, int32_t n_pass) { return gemm_plan(rows, K, n_pass).smax; }
 
 // ---- pieces of the GEMM kernel (all inlined; register arrays are passed by reference) ----
 struct GemmCtx {
@@ -60,6 +64,8 @@ struct GemmCtx {
     const uint16_t* bsrc0;  // this thread's first staging unit in the activation planes
     int bdst0;              // ... and in an LDS stage
     int K, KB, n_tiles, it1, wave, li, lq;
+    int lo_off;             // rows from a high-plane row to its low-plane row
+    int Mp, cid, pass;      // live rows of this pass, range index, pass
 };
 
 // weights of pair `it` (clamped to the block's range: a re-read of the last pair keeps the
@@ -79,17 +85,19 @@ __device__ __forceinline__ void gemm_load_a(uint4 (&ar)[RT][4], const GemmCtx& c
     }
 }
 // Staging map: 2 planes x PM rows x 16 segments of 16 bytes, NBU per thread; unit i of a
-// thread lies RPI rows below unit i - 1 (same segment), running on into the low plane.
-// Rows past M are read too, from the planes' unused rows: whatever they hold only reaches
-// result columns that are never stored.
+// thread lies RPI rows below unit i - 1 (same segment), first in the high plane, then in
+// the low plane.  Rows past the live ones are read too, from the planes' unused rows:
+// whatever they hold only reaches result columns that are never stored.
 constexpr int NBU = 2 * PM * 16 / (64 * WPB);
 constexpr int RPI = 4 * WPB;
 __device__ __forceinline__ void gemm_load_b(u32x4 (&br)[NBU], const GemmCtx& c, int it_) {
     const int it = it_ < c.it1 ? it_ : c.it1 - 1;
     const int kb = it % c.KB;
 #pragma unroll
-    for (int i = 0; i < NBU; ++i)
-        br[i] = *reinterpret_cast<const u32x4*>(c.bsrc0 + (size_t)(i * RPI) * c.K + (size_t)kb * 128);
+    for (int i = 0; i < NBU; ++i) {
+        const int row = i * RPI < PM ? i * RPI : c.lo_off + i * RPI - PM;  // high plane, then low plane
+        br[i] = *reinterpret_cast<const u32x4*>(c.bsrc0 + (size_t)row * c.K + (size_t)kb * 128);
+    }
 }
 __device__ __forceinline__ void gemm_store_b(unsigned char* dst, const u32x4 (&br)[NBU], const GemmCtx& c) {
 #pragma unroll
@@ -129,15 +137,15 @@ __device__ __forceinline__ void gemm_mma(f32x4 (&acc)[RT][PM / 16], const uint4 
 template <int RT>
 __device__ __forceinline__ void gemm_flush(f32x4 (&acc)[RT][PM / 16], const GemmArgs& a, const GemmCtx& c, int b, int q) {
     constexpr int CT = PM / 16;
-    const int slot = (int)blockIdx.x - (b * c.KB) / q;
-    float* part = a.part + (size_t)slot * PM * a.rows;
+    const int slot = c.cid - (b * c.KB) / q;
+    float* part = a.part + (size_t)(c.pass * a.S + slot) * PM * a.rows;
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
         const int tile = (b * WPB + c.wave) * RT + t;
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
             const int m = ct * 16 + c.li;
-            if (tile < c.n_tiles && m < a.M)
+            if (tile < c.n_tiles && m < c.Mp)
                 *reinterpret_cast<f32x4*>(part + (size_t)m * a.rows + tile * 16 + 4 * c.lq) = acc[t][ct];
             acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
@@ -178,11 +186,15 @@ __global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int 
     c.K = a.K; c.KB = a.K >> 7; c.n_tiles = a.rows >> 4;
     const int nb = (c.n_tiles + WPB * RT - 1) / (WPB * RT);
     const int total = nb * c.KB;  // (checked on the host to fit an int)
-    const int it0 = blockIdx.x * q;
+    c.pass = blockIdx.x % a.n_pass;  // neighbours in the grid: same weights, different passes
+    c.cid = blockIdx.x / a.n_pass;
+    c.Mp = a.M - c.pass * PM < PM ? a.M - c.pass * PM : PM;
+    c.lo_off = a.plane_rows;
+    const int it0 = c.cid * q;
     c.it1 = it0 + q < total ? it0 + q : total;
     if (it0 >= c.it1) return;
     c.W = reinterpret_cast<const uint16_t*>(a.Wp) + lane * 8;
-    c.bsrc0 = a.xs + (size_t)(tid >> 4) * a.K + (tid & 15) * 8;
+    c.bsrc0 = a.xs + (size_t)(c.pass * PM + (tid >> 4)) * a.K + (tid & 15) * 8;
     c.bdst0 = (tid >> 4) * ROWB + (tid & 15) * 16;
 
     f32x4 acc[RT][CT];
@@ -211,8 +223,10 @@ __global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int 
 }
 
 hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
-    if (a.rows < 16 || a.rows % 16 || a.K < 128 || a.K % 128 || a.M < 1 || a.M > PM) return hipErrorInvalidValue;
-    const GemmPlan p = gemm_plan(a.rows, a.K);
+    if (a.rows < 16 || a.rows % 16 || a.K < 128 || a.K % 128 || a.M < 1 || a.n_pass < 1 || a.n_pass > SB_PREFILL_PASSES ||
+        a.n_pass != (a.M + PM - 1) / PM || a.plane_rows < a.n_pass * PM)
+        return hipErrorInvalidValue;
+    const GemmPlan p = gemm_plan(a.rows, a.K, a.n_pass);
     if (a.S != p.smax || (long)p.nb * (a.K >> 7) > 0x3fffffffL) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
@@ -224,8 +238,9 @@ hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    if (p.rt == 2) prefill_gemm_kernel<2><<<p.grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
-    else prefill_gemm_kernel<1><<<p.grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+    const int grid = p.grid * a.n_pass;
+    if (p.rt == 2) prefill_gemm_kernel<2><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+    else prefill_gemm_kernel<1><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
     return hipGetLastError();
 }
 
@@ -254,7 +269,7 @@ __device__ __forceinline__ float sum_splits(const float* p, size_t plane, int n_
 template <int EPI>
 __global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a, GemmSplitMap mp) {
     __shared__ float red[4];
-    const int tid = threadIdx.x, m = blockIdx.y, n = blockIdx.x * 256 + tid;
+    const int tid = threadIdx.x, m = blockIdx.y, n = blockIdx.x * 256 + tid;  // m: row of the super-pass
     float inv = 1.0f;
     if (a.ssq_in) {  // (added in index order; sixteen loads in flight at a time)
         float t = 0.f;
@@ -268,20 +283,20 @@ __global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a, Ge
         inv = 1.0f / sqrtf(t / (float)a.K + a.eps);
     }
     const size_t plane = (size_t)PM * a.rows;
-    const float* p = a.part + (size_t)m * a.rows;
+    const float* p = a.part + ((size_t)(m / PM) * a.S * PM + m % PM) * a.rows;
     float sq = 0.f;
     if (n < a.N) {
         if (EPI == EPI_SWIGLU) {
             const float g = sum_splits(p + n, plane, splits_of(mp, n));
             const float u = sum_splits(p + a.N + n, plane, splits_of(mp, a.N + n));
-            split_store_rows(a.ys, a.N, PM, m, n, silu_mul(g * inv, u * inv));
+            split_store_rows(a.ys, a.N, a.plane_rows, m, n, silu_mul(g * inv, u * inv));
         } else {
             float v = sum_splits(p + n, plane, splits_of(mp, n));
             v *= inv;
             float* yp = a.y + (size_t)m * a.ldy + n;
             if (EPI == EPI_RESID) {
                 v += *yp;
-                if (a.nx) split_store_rows(a.nx, a.N, PM, m, n, v * a.gain[n]);
+                if (a.nx) split_store_rows(a.nx, a.N, a.plane_rows, m, n, v * a.gain[n]);
                 sq = v * v;
             }
             *yp = v;
@@ -296,11 +311,11 @@ __global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a, Ge
 }
 
 hipError_t launch_prefill_epilogue(const GemmEpiArgs& a, hipStream_t st) {
-    if (a.M < 1 || a.M > PM || a.N < 1 || a.S < 1) return hipErrorInvalidValue;
+    if (a.M < 1 || a.N < 1 || a.S < 1 || a.n_pass != (a.M + PM - 1) / PM || a.plane_rows < a.M) return hipErrorInvalidValue;
     if (a.epi == EPI_SWIGLU ? (!a.ys || a.rows != 2 * a.N) : (!a.y || a.rows != a.N)) return hipErrorInvalidValue;
     if (a.ssq_out && (a.N + 255) / 256 > a.ssq_ld) return hipErrorInvalidValue;
     dim3 grid((a.N + 255) / 256, a.M);
-    const GemmPlan pl = gemm_plan(a.rows, a.K);
+    const GemmPlan pl = gemm_plan(a.rows, a.K, a.n_pass);
     if (a.S != pl.smax) return hipErrorInvalidValue;
     const GemmSplitMap mp{16 * WPB * pl.rt, a.K >> 7, pl.q};
     switch (a.epi) {
@@ -317,7 +332,7 @@ template <typename WT>
 __global__ __launch_bounds__(256) void prefill_embed_kernel(const WT* __restrict__ E, int vocab, int d,
                                                             const int32_t* __restrict__ tokens, float* __restrict__ H,
                                                             const float* __restrict__ gain, uint16_t* __restrict__ nx,
-                                                            float* __restrict__ ssq_out, int ssq_ld) {
+                                                            int plane_rows, float* __restrict__ ssq_out, int ssq_ld) {
     __shared__ float red[4];
     const int tid = threadIdx.x, m = blockIdx.y, n = blockIdx.x * 256 + tid;
     int tok = tokens[m];
@@ -326,7 +341,7 @@ __global__ __launch_bounds__(256) void prefill_embed_kernel(const WT* __restrict
     if (n < d) {
         const float x = ldf(E + (size_t)tok * d + n);
         H[(size_t)m * d + n] = x;
-        if (nx) split_store_rows(nx, d, PM, m, n, x * gain[n]);
+        if (nx) split_store_rows(nx, d, plane_rows, m, n, x * gain[n]);
         sq = x * x;
     }
     if (ssq_out) {
@@ -338,24 +353,26 @@ __global__ __launch_bounds__(256) void prefill_embed_kernel(const WT* __restrict
 }
 
 hipError_t launch_prefill_embed(const void* E, int32_t w_dtype, int32_t vocab, int32_t d, const int32_t* tokens,
-                                int32_t M, float* H, const float* gain, uint16_t* nx, float* ssq_out, int32_t ssq_ld,
-                                hipStream_t st) {
-    if (M < 1 || M > PM || (ssq_out && (d + 255) / 256 > ssq_ld)) return hipErrorInvalidValue;
+                                int32_t M, float* H, const float* gain, uint16_t* nx, int32_t plane_rows,
+                                float* ssq_out, int32_t ssq_ld, hipStream_t st) {
+    if (M < 1 || plane_rows < M || (ssq_out && (d + 255) / 256 > ssq_ld)) return hipErrorInvalidValue;
     dim3 grid((d + 255) / 256, M);
     if (w_dtype == SB_BF16)
-        prefill_embed_kernel<uint16_t><<<grid, 256, 0, st>>>((const uint16_t*)E, vocab, d, tokens, H, gain, nx, ssq_out, ssq_ld);
+        prefill_embed_kernel<uint16_t><<<grid, 256, 0, st>>>((const uint16_t*)E, vocab, d, tokens, H, gain, nx, plane_rows,
+                                                              ssq_out, ssq_ld);
     else
-        prefill_embed_kernel<float><<<grid, 256, 0, st>>>((const float*)E, vocab, d, tokens, H, gain, nx, ssq_out, ssq_ld);
+        prefill_embed_kernel<float><<<grid, 256, 0, st>>>((const float*)E, vocab, d, tokens, H, gain, nx, plane_rows,
+                                                           ssq_out, ssq_ld);
     return hipGetLastError();
 }
 
-__global__ void prefill_split_kernel(const float* __restrict__ x, uint16_t* __restrict__ xs, int K) {
+__global__ void prefill_split_kernel(const float* __restrict__ x, uint16_t* __restrict__ xs, int plane_rows, int K) {
     const int m = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
-    if (i < K) split_store_rows(xs, K, PM, m, i, x[(size_t)m * K + i]);
+    if (i < K) split_store_rows(xs, K, plane_rows, m, i, x[(size_t)m * K + i]);
 }
-hipError_t launch_prefill_split(const float* x, uint16_t* xs, int32_t M, int32_t K, hipStream_t st) {
-    if (M < 1 || M > PM) return hipErrorInvalidValue;
-    prefill_split_kernel<<<dim3((K + 255) / 256, M), 256, 0, st>>>(x, xs, K);
+hipError_t launch_prefill_split(const float* x, uint16_t* xs, int32_t plane_rows, int32_t M, int32_t K, hipStream_t st) {
+    if (M < 1 || plane_rows < M) return hipErrorInvalidValue;
+    prefill_split_kernel<<<dim3((K + 255) / 256, M), 256, 0, st>>>(x, xs, plane_rows, K);
     return hipGetLastError();
 }
 

@@ -76,7 +76,7 @@ struct WsLayout {
     // prompt passes of SB_PREFILL_ROWS rows (packed bf16 weights only)
     bool prefill_gemm;
     size_t p_tok, p_H, p_xs, p_ssq, p_qkv, p_atts, p_us, p_part, p_attn_part;
-    int p_ssq_ld;
+    int p_ssq_ld, p_rows;
 };
 
 WsLayout ws_layout(const sb_config* c) {
@@ -113,21 +113,26 @@ WsLayout ws_layout(const sb_config* c) {
     L.table = take((size_t)L.n_pages * 4);
     L.prefill_gemm = resolve_proj(c) == SB_PROJ_MFMA_PACKED;
     if (L.prefill_gemm) {
+        // a super-pass: up to SB_PREFILL_PASSES passes of SB_PREFILL_ROWS rows per launch
         const size_t PM = SB_PREFILL_ROWS;
+        size_t RS = (size_t)(c->max_seq + PM - 1) / PM * PM;
+        if (RS > PM * SB_PREFILL_PASSES) RS = PM * SB_PREFILL_PASSES;
+        L.p_rows = (int)RS;
         L.p_ssq_ld = (int)((d + 255) / 256);
         L.p_tok = take((size_t)c->max_seq * 4);
-        L.p_H = take(PM * d * 4);
-        L.p_xs = take(2 * PM * d * 2);
-        L.p_ssq = take(PM * L.p_ssq_ld * 4);
-        L.p_qkv = take(PM * qkv_rows * 4);
-        L.p_atts = take(2 * PM * hq * 2);
-        L.p_us = take(2 * PM * f * 2);
-        size_t pe = 0;  // largest k-split partial of the four projections
+        L.p_H = take(RS * d * 4);
+        L.p_xs = take(2 * RS * d * 2);
+        L.p_ssq = take(RS * L.p_ssq_ld * 4);
+        L.p_qkv = take(RS * qkv_rows * 4);
+        L.p_atts = take(2 * RS * hq * 2);
+        L.p_us = take(2 * RS * f * 2);
+        size_t pe = 0;  // largest set of k-split partials: any projection, any number of passes
         const size_t shapes[4][2] = {{qkv_rows, d}, {d, hq}, {2 * f, d}, {d, f}};
-        for (auto& sh : shapes) {
-            size_t e = (size_t)gemm_splits((int32_t)sh[0], (int32_t)sh[1]) * PM * sh[0];
-            if (e > pe) pe = e;
-        }
+        for (auto& sh : shapes)
+            for (int np = 1; np <= (int)(RS / PM); ++np) {
+                size_t e = (size_t)np * gemm_splits((int32_t)sh[0], (int32_t)sh[1], np) * PM * sh[0];
+                if (e > pe) pe = e;
+            }
         L.p_part = take(pe * 4);
         L.p_attn_part = take(PM * c->n_heads * L.max_chunks * (c->head_dim + 2) * 4);
     }
@@ -391,30 +396,34 @@ void reset_session(sb_session* s) {
     memset(&s->st, 0, sizeof s->st);
 }
 
-// One projection of a prompt pass: k-split GEMM, then its epilogue.
-int prefill_proj(sb_session* s, const void* Wp, int rows, int K, const uint16_t* xs, int M, GemmEpiArgs e, int cls) {
+// One projection of a super-pass (R rows = several prompt passes): k-split GEMM, then its epilogue.
+int prefill_proj(sb_session* s, const void* Wp, int rows, int K, const uint16_t* xs, int R, GemmEpiArgs e, int cls) {
     hipStream_t st = s->m->stream;
     GemmArgs g{};
-    g.Wp = Wp; g.rows = rows; g.K = K; g.xs = xs; g.M = M;
-    g.part = wsp<float>(s, s->L.p_part); g.S = gemm_splits(rows, K);
-    e.part = g.part; e.S = g.S; e.rows = rows; e.M = M; e.K = K; e.eps = s->m->cfg.rms_eps; e.ssq_ld = s->L.p_ssq_ld;
-    ProfScope ps(s, cls, (int64_t)rows * K * 2 + (int64_t)M * K * 4 + (int64_t)M * rows * 4, st);
+    g.Wp = Wp; g.rows = rows; g.K = K; g.xs = xs; g.plane_rows = s->L.p_rows; g.M = R;
+    g.n_pass = (R + SB_PREFILL_ROWS - 1) / SB_PREFILL_ROWS;
+    g.part = wsp<float>(s, s->L.p_part); g.S = gemm_splits(rows, K, g.n_pass);
+    e.part = g.part; e.S = g.S; e.rows = rows; e.M = R; e.n_pass = g.n_pass; e.plane_rows = s->L.p_rows;
+    e.K = K; e.eps = s->m->cfg.rms_eps; e.ssq_ld = s->L.p_ssq_ld;
+    ProfScope ps(s, cls, (int64_t)rows * K * 2 + (int64_t)R * K * 4 + (int64_t)R * rows * 4, st);
     hipError_t err = launch_prefill_gemm(g, st);
     if (err == hipSuccess) err = launch_prefill_epilogue(e, st);
-    if (err != hipSuccess) return fail(SB_EDEVICE, "prompt projection launch (rows=%d K=%d M=%d): %s", rows, K, M,
+    if (err != hipSuccess) return fail(SB_EDEVICE, "prompt projection launch (rows=%d K=%d R=%d): %s", rows, K, R,
                                        hipGetErrorString(err));
     return SB_OK;
 }
 
-// Prompt passes of up to SB_PREFILL_ROWS rows through all layers (packed bf16 weights).
-// Same layer as run_layer; the hidden rows and their bf16 planes live in the p_* buffers.
+// The prompt through all layers, a super-pass (up to SB_PREFILL_PASSES passes of
+// SB_PREFILL_ROWS rows) at a time: per layer one launch per projection over all its rows,
+// and one attention launch per pass, in order (a pass attends to the keys of the passes
+// before it).  Same layer as run_layer; hidden rows and bf16 planes live in the p_* buffers.
 int prefill_gemm_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* first_token) {
     sb_model* m = s->m;
     const sb_config& c = m->cfg;
     hipStream_t st = m->stream;
     const int d = c.d_model, f = c.d_ffn, hq = c.n_heads * c.head_dim;
     const int qkv_rows = (c.n_heads + 2 * c.n_kv_heads) * c.head_dim;
-    const int nb_d = (d + 255) / 256;
+    const int nb_d = (d + 255) / 256, PM = SB_PREFILL_ROWS, RS = s->L.p_rows;
     int32_t* toks = wsp<int32_t>(s, s->L.p_tok);
     float* H = wsp<float>(s, s->L.p_H);
     uint16_t* xs = wsp<uint16_t>(s, s->L.p_xs);
@@ -424,51 +433,54 @@ int prefill_gemm_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* 
     uint16_t* us = wsp<uint16_t>(s, s->L.p_us);
     HIP_TRY(hipMemcpyAsync(toks, prompt, (size_t)n * 4, hipMemcpyHostToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));  // the caller's buffer is pageable: do not return while it is being read
-    int rc, M = 0;
-    for (int i0 = 0; i0 < n; i0 += SB_PREFILL_ROWS) {
-        M = n - i0 < SB_PREFILL_ROWS ? n - i0 : SB_PREFILL_ROWS;
-        HIP_TRY(launch_prefill_embed(m->embed, c.weight_dtype, c.vocab, d, toks + i0, M, H, m->attn_norm[0], xs, ssq,
+    int rc, R = 0;
+    for (int r0 = 0; r0 < n; r0 += RS) {
+        R = n - r0 < RS ? n - r0 : RS;
+        HIP_TRY(launch_prefill_embed(m->embed, c.weight_dtype, c.vocab, d, toks + r0, R, H, m->attn_norm[0], xs, RS, ssq,
                                      s->L.p_ssq_ld, st));
         for (int l = 0; l < c.n_layers; ++l) {
             GemmEpiArgs e{};
             e.N = qkv_rows; e.epi = EPI_STORE; e.ssq_in = ssq; e.ssq_nb = nb_d; e.y = qkv; e.ldy = qkv_rows;
-            if ((rc = prefill_proj(s, m->w_qkv[l], qkv_rows, d, xs, M, e, SB_K_QKV))) return rc;
+            if ((rc = prefill_proj(s, m->w_qkv[l], qkv_rows, d, xs, R, e, SB_K_QKV))) return rc;
 
-            AttnArgs a{};
-            a.q = qkv; a.rope_cos = m->rope_cos; a.rope_sin = m->rope_sin; a.qkv_rows = qkv_rows; a.n_heads = c.n_heads;
-            a.kv = s->kv; a.layer = l; a.pos0 = s->c; a.M = M;
-            a.partials = wsp<float>(s, s->L.p_attn_part); a.max_chunks = s->L.max_chunks;
-            a.out = nullptr; a.out_split = atts; a.split_rows = SB_PREFILL_ROWS;
-            const int64_t kv_read = (int64_t)(s->c + M) * 2 * c.n_kv_heads * c.head_dim * (int64_t)esize(c.kv_dtype);
-            {
-                ProfScope ps(s, SB_K_ATTN, kv_read, st);
+            int64_t kv_read = 0;
+            for (int p0 = 0; p0 < R; p0 += PM) {
+                AttnArgs a{};
+                a.q = qkv + (size_t)p0 * qkv_rows; a.rope_cos = m->rope_cos; a.rope_sin = m->rope_sin;
+                a.qkv_rows = qkv_rows; a.n_heads = c.n_heads;
+                a.kv = s->kv; a.layer = l; a.pos0 = s->c + p0; a.M = R - p0 < PM ? R - p0 : PM;
+                a.partials = wsp<float>(s, s->L.p_attn_part); a.max_chunks = s->L.max_chunks;
+                a.out = nullptr; a.out_split = atts + (size_t)p0 * hq; a.split_rows = RS;
+                const int64_t kvb = (int64_t)(a.pos0 + a.M) * 2 * c.n_kv_heads * c.head_dim * (int64_t)esize(c.kv_dtype);
+                kv_read += kvb;
+                ProfScope ps(s, SB_K_ATTN, kvb, st);
                 HIP_TRY(launch_attention(a, st));
             }
 
             e = GemmEpiArgs{};
             e.N = d; e.epi = EPI_RESID; e.y = H; e.ldy = d; e.gain = m->ffn_norm[l]; e.nx = xs; e.ssq_out = ssq;
-            if ((rc = prefill_proj(s, m->w_o[l], d, hq, atts, M, e, SB_K_WO))) return rc;
+            if ((rc = prefill_proj(s, m->w_o[l], d, hq, atts, R, e, SB_K_WO))) return rc;
 
             e = GemmEpiArgs{};
             e.N = f; e.epi = EPI_SWIGLU; e.ssq_in = ssq; e.ssq_nb = nb_d; e.ys = us;
-            if ((rc = prefill_proj(s, m->w_gate_up[l], 2 * f, d, xs, M, e, SB_K_GATEUP))) return rc;
+            if ((rc = prefill_proj(s, m->w_gate_up[l], 2 * f, d, xs, R, e, SB_K_GATEUP))) return rc;
 
             e = GemmEpiArgs{};
             e.N = d; e.epi = EPI_RESID; e.y = H; e.ldy = d; e.ssq_out = ssq;
             if (l + 1 < c.n_layers) { e.gain = m->attn_norm[l + 1]; e.nx = xs; }
-            if ((rc = prefill_proj(s, m->w_down[l], d, f, us, M, e, SB_K_DOWN))) return rc;
+            if ((rc = prefill_proj(s, m->w_down[l], d, f, us, R, e, SB_K_DOWN))) return rc;
 
             s->st.layer_sweeps += 1;
-            s->st.row_layers += M;
+            s->st.row_layers += R;
             s->st.weight_bytes += m->layer_bytes;
             s->st.kv_bytes += kv_read;
         }
-        s->c += M;
+        s->c += R;
     }
     // final head on the last prompt row: normalise it into slot 0's projection input
     {
         ProfScope ps(s, SB_K_RMSNORM, (int64_t)d * 8, st);
-        HIP_TRY(launch_rmsnorm(H + (size_t)(M - 1) * d, m->final_norm, wsp<float>(s, s->L.xn),
+        HIP_TRY(launch_rmsnorm(H + (size_t)(R - 1) * d, m->final_norm, wsp<float>(s, s->L.xn),
                                wsp<uint16_t>(s, s->L.xs_exit), d, 1, d, c.rms_eps, st));
     }
     HeadArgs h{};
@@ -1152,7 +1164,7 @@ int32_t sb_op_repack(const void* W, int32_t N, int32_t K, void* packed, void* st
 
 size_t sb_op_gemm_scratch_bytes(int32_t N, int32_t K) {
     if (N < 16 || K < 128 || N % 16 || K % 128) return 0;
-    return align_up((size_t)2 * SB_PREFILL_ROWS * K * 2, 256) + (size_t)gemm_splits(N, K) * SB_PREFILL_ROWS * N * 4;
+    return align_up((size_t)2 * SB_PREFILL_ROWS * K * 2, 256) + (size_t)gemm_splits(N, K, 1) * SB_PREFILL_ROWS * N * 4;
 }
 
 int32_t sb_op_gemm(const void* Wp, int32_t N, int32_t K, const float* x, float* y, int32_t M, void* scratch,
@@ -1163,12 +1175,14 @@ int32_t sb_op_gemm(const void* Wp, int32_t N, int32_t K, const float* x, float* 
     hipStream_t st = (hipStream_t)stream;
     uint16_t* xs = (uint16_t*)scratch;
     float* part = (float*)((char*)scratch + align_up((size_t)2 * SB_PREFILL_ROWS * K * 2, 256));
-    HIP_TRY(launch_prefill_split(x, xs, M, K, st));
+    HIP_TRY(launch_prefill_split(x, xs, SB_PREFILL_ROWS, M, K, st));
     GemmArgs g{};
-    g.Wp = Wp; g.rows = N; g.K = K; g.xs = xs; g.M = M; g.part = part; g.S = gemm_splits(N, K);
+    g.Wp = Wp; g.rows = N; g.K = K; g.xs = xs; g.plane_rows = SB_PREFILL_ROWS; g.M = M; g.n_pass = 1;
+    g.part = part; g.S = gemm_splits(N, K, 1);
     HIP_TRY(launch_prefill_gemm(g, st));
     GemmEpiArgs e{};
-    e.part = part; e.S = g.S; e.rows = N; e.N = N; e.M = M; e.epi = EPI_STORE; e.K = K; e.y = y; e.ldy = N;
+    e.part = part; e.S = g.S; e.rows = N; e.N = N; e.M = M; e.n_pass = 1; e.plane_rows = SB_PREFILL_ROWS;
+    e.epi = EPI_STORE; e.K = K; e.y = y; e.ldy = N;
     HIP_TRY(launch_prefill_epilogue(e, st));
     return SB_OK;
 }
