@@ -22,7 +22,6 @@ constexpr int PM = SB_PREFILL_ROWS;
 constexpr int ROWB = 272;                  // LDS bytes per staged row: 128 bf16 + 16 bytes of padding
 constexpr int STAGE = 2 * PM * ROWB;       // one k block of both planes
 constexpr int WPB = 8;                     // waves per thread block (one block per CU: two LDS stages take 136 KB)
-constexpr int DEPTH = 2;                   // weight register stages per wave (deeper rings cost occupancy, measured no gain)
 }  // namespace
 
 // Work decomposition: the (row block, k block) pairs are numbered row block first and
@@ -32,7 +31,7 @@ constexpr int DEPTH = 2;                   // weight register stages per wave (d
 // thread block that touches a row block leaves one partial sum for it, in slot
 // (range index - first range of that row block).
 struct GemmPlan {
-    int rt;      // 16-row weight tiles per wave (row block = 16 WPB rt rows)
+    int rt;      // row block = 128 rt weight rows (2 rt tiles per wave)
     int nb;      // row blocks
     int q;       // (row block, k block) pairs per thread block
     int grid;    // thread blocks
@@ -63,25 +62,29 @@ struct GemmCtx {
     const uint16_t* W;      // packed weights + this lane's 16 bytes
     const uint16_t* bsrc0;  // this thread's first staging unit in the activation planes
     int bdst0;              // ... and in an LDS stage
-    int K, KB, n_tiles, it1, wave, li, lq;
+    int K, KB, n_tiles, it1, wr, wt, li, lq;  // wr: the wave's row group (0-3), wt: its token half (0-1)
     int lo_off;             // rows from a high-plane row to its low-plane row
     int Mp, cid, pass;      // live rows of this pass, range index, pass
 };
 
-// weights of pair `it` (clamped to the block's range: a re-read of the last pair keeps the
-// steady-state loop free of conditional loads, whose completion could only be waited for
-// conservatively)
-template <int RT>
-__device__ __forceinline__ void gemm_load_a(uint4 (&ar)[RT][4], const GemmCtx& c, int it_) {
-    const int it = it_ < c.it1 ? it_ : c.it1 - 1;
-    const int b = it / c.KB, kb = it - b * c.KB;
+// Weights of half a pair: half-step h = 2 * pair + (0 | 1) covers MFMA steps 2 (h & 1) and
+// 2 (h & 1) + 1 of the pair's k block.  (Clamped to the block's range: a re-read of the last
+// half keeps the steady-state loop free of conditional loads, whose completion could only be
+// waited for conservatively.)  STREAM: the weights are read once by this launch (a single
+// pass), so the loads carry the streaming hint; with several passes the other passes' blocks
+// read the same lines and they are left to the caches.
+template <int RT, bool STREAM>
+__device__ __forceinline__ void gemm_load_a(uint4 (&ar)[RT][2], const GemmCtx& c, int h_) {
+    const int h = h_ < 2 * c.it1 ? h_ : 2 * c.it1 - 1;
+    const int it = h >> 1, b = it / c.KB, kb = it - b * c.KB;
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        int tile = (b * WPB + c.wave) * RT + t;
+        int tile = (b * 4 + c.wr) * RT + t;
         if (tile > c.n_tiles - 1) tile = c.n_tiles - 1;  // a tile past the end re-reads the last one (not stored)
-        const uint16_t* wp = c.W + ((size_t)tile * c.KB + kb) * 2048;
+        const uint16_t* wp = c.W + ((size_t)tile * c.KB + kb) * 2048 + (h & 1) * 1024;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) ar[t][u] = ld_weights_packed(wp + u * 512);
+        for (int u = 0; u < 2; ++u)
+            ar[t][u] = STREAM ? ld_weights_packed(wp + u * 512) : *reinterpret_cast<const uint4*>(wp + u * 512);
     }
 }
 // Staging map: 2 planes x PM rows x 16 segments of 16 bytes, NBU per thread; unit i of a
@@ -103,48 +106,43 @@ __device__ __forceinline__ void gemm_store_b(unsigned char* dst, const u32x4 (&b
 #pragma unroll
     for (int i = 0; i < NBU; ++i) *reinterpret_cast<u32x4*>(dst + c.bdst0 + i * RPI * ROWB) = br[i];
 }
-// All column tiles are always multiplied: the block of LDS reads and MFMAs stays free of
-// branches.
+// A wave multiplies its RT weight tiles with the four column tiles (64 rows) of its token
+// half: one LDS operand read serves RT MFMAs.  All column tiles are always multiplied, so
+// the block of LDS reads and MFMAs stays free of branches.
+constexpr int CTW = PM / 32;  // column tiles per wave
 template <int RT>
-__device__ __forceinline__ void gemm_mma(f32x4 (&acc)[RT][PM / 16], const uint4 (&ar)[RT][4], const unsigned char* src,
-                                         const GemmCtx& c) {
-    constexpr int CT = PM / 16;
+__device__ __forceinline__ void gemm_mma(f32x4 (&acc)[RT][CTW], const uint4 (&ar)[RT][2], const unsigned char* src,
+                                         const GemmCtx& c, int uhalf) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        bf16x8 bh[CT], bl[CT];
+    for (int uu = 0; uu < 2; ++uu) {
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            const unsigned char* rp = src + (ct * 16 + c.li) * ROWB + u * 64 + c.lq * 16;
-            bh[ct] = *reinterpret_cast<const bf16x8*>(rp);
-            bl[ct] = *reinterpret_cast<const bf16x8*>(rp + PM * ROWB);
+        for (int ct = 0; ct < CTW; ++ct) {
+            const unsigned char* rp = src + ((c.wt * CTW + ct) * 16 + c.li) * ROWB + (uhalf * 2 + uu) * 64 + c.lq * 16;
+            const bf16x8 bh = *reinterpret_cast<const bf16x8*>(rp);
+            const bf16x8 bl = *reinterpret_cast<const bf16x8*>(rp + PM * ROWB);
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ar[t][uu]), bh, acc[t][ct],
+                                                                     0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ar[t][uu]), bl, acc[t][ct],
+                                                                     0, 0, 0);
         }
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-            for (int t = 0; t < RT; ++t)
-                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ar[t][u]), bh[ct],
-                                                                     acc[t][ct], 0, 0, 0);
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-            for (int t = 0; t < RT; ++t)
-                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ar[t][u]), bl[ct],
-                                                                     acc[t][ct], 0, 0, 0);
     }
 }
 // Partial sum of row block b (C layout: lane (j = li, g = lq), register r -> weight row 4g + r
 // of the tile, activation row j), then zero for the next row block.
 template <int RT>
-__device__ __forceinline__ void gemm_flush(f32x4 (&acc)[RT][PM / 16], const GemmArgs& a, const GemmCtx& c, int b, int q) {
-    constexpr int CT = PM / 16;
+__device__ __forceinline__ void gemm_flush(f32x4 (&acc)[RT][CTW], const GemmArgs& a, const GemmCtx& c, int b, int q) {
     const int slot = c.cid - (b * c.KB) / q;
     float* part = a.part + (size_t)(c.pass * a.S + slot) * PM * a.rows;
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        const int tile = (b * WPB + c.wave) * RT + t;
+        const int tile = (b * 4 + c.wr) * RT + t;
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            const int m = ct * 16 + c.li;
+        for (int ct = 0; ct < CTW; ++ct) {
+            const int m = (c.wt * CTW + ct) * 16 + c.li;
             if (tile < c.n_tiles && m < c.Mp)
                 *reinterpret_cast<f32x4*>(part + (size_t)m * a.rows + tile * 16 + 4 * c.lq) = acc[t][ct];
             acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -152,39 +150,42 @@ __device__ __forceinline__ void gemm_flush(f32x4 (&acc)[RT][PM / 16], const Gemm
     }
 }
 
-// One pair: request the next activations and the weights D - 1 pairs ahead, multiply the
-// current pair, leave the row block's partial sum if it ends here, publish the next
-// activations (the stage they go to was last read before the barrier that ended the
-// previous pair).
-template <int RT>
-__device__ __forceinline__ void gemm_step(f32x4 (&acc)[RT][PM / 16], const uint4 (&acur)[RT][4], uint4 (&afar)[RT][4],
+// Half a pair.  First half (P = 0): request the next pair's activations; both halves: request
+// the weights two half-steps ahead, multiply the current half; second half (P = 1): leave the
+// row block's partial sum if it ends here and publish the next activations (the stage they go
+// to was last read before the barrier that ended the previous pair).  Loads complete in issue
+// order and the activations are requested before the weights of the same half-step, so
+// waiting for them leaves the newest weight loads in flight.
+template <int RT, bool STREAM, int P>
+__device__ __forceinline__ void gemm_half(f32x4 (&acc)[RT][CTW], const uint4 (&acur)[RT][2], uint4 (&afar)[RT][2],
                                           u32x4 (&breg)[NBU], unsigned char* bt, int& buf, const GemmArgs& a,
-                                          const GemmCtx& c, int cur, int q) {
-    gemm_load_b(breg, c, cur + 1);
-    gemm_load_a<RT>(afar, c, cur + DEPTH - 1);
-    gemm_mma<RT>(acc, acur, bt + buf * STAGE, c);
-    const int b = cur / c.KB;
-    if (cur + 1 >= c.it1 || (cur + 1) / c.KB != b) gemm_flush<RT>(acc, a, c, b, q);
-    buf ^= 1;
-    gemm_store_b(bt + buf * STAGE, breg, c);
-    __syncthreads();
+                                          const GemmCtx& c, int h, int q) {
+    const int cur = h >> 1;
+    if (P == 0) gemm_load_b(breg, c, cur + 1);
+    gemm_load_a<RT, STREAM>(afar, c, h + 2);
+    gemm_mma<RT>(acc, acur, bt + buf * STAGE, c, P);
+    if (P == 1) {
+        const int b = cur / c.KB;
+        if (cur + 1 >= c.it1 || (cur + 1) / c.KB != b) gemm_flush<RT>(acc, a, c, b, q);
+        buf ^= 1;
+        gemm_store_b(bt + buf * STAGE, breg, c);
+        __syncthreads();
+    }
 }
 
-// 64 WPB threads, each wave RT 16-row weight tiles of the block's 16 WPB RT rows.
-// Weights: a ring of D register stages, D - 1 pairs requested ahead; activations: one
-// pair ahead through LDS (they come from L2).  Loads complete
-// in issue order, so the activations are requested before the weights: waiting for them at
-// the end of the step leaves the weight loads in flight.
-template <int RT>
+// 512 threads: four row groups x two token halves; a wave has RT 16-row weight tiles (of the
+// block's 64 RT rows) and 64 of the pass's 128 rows, i.e. up to a 64 x 64 tile of the result.
+// Weights: a ring of three register half-stages, requested two half-steps (one pair) ahead;
+// activations: one pair ahead through LDS.
+template <int RT, bool STREAM>
 __global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int q) {
-    constexpr int CT = PM / 16;  // 16-row column tiles of the activations
-    constexpr int D = DEPTH;
+    static_assert(WPB == 8, "four row groups x two token halves");
     extern __shared__ __attribute__((aligned(16))) unsigned char bt[];  // [2][STAGE]
     const int tid = threadIdx.x, lane = tid & 63;
     GemmCtx c;
-    c.wave = tid >> 6; c.li = lane & 15; c.lq = lane >> 4;
+    c.wr = (tid >> 6) & 3; c.wt = tid >> 8; c.li = lane & 15; c.lq = lane >> 4;
     c.K = a.K; c.KB = a.K >> 7; c.n_tiles = a.rows >> 4;
-    const int nb = (c.n_tiles + WPB * RT - 1) / (WPB * RT);
+    const int nb = (c.n_tiles + 4 * RT - 1) / (4 * RT);
     const int total = nb * c.KB;  // (checked on the host to fit an int)
     c.pass = blockIdx.x % a.n_pass;  // neighbours in the grid: same weights, different passes
     c.cid = blockIdx.x / a.n_pass;
@@ -197,29 +198,38 @@ __global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int 
     c.bsrc0 = a.xs + (size_t)(c.pass * PM + (tid >> 4)) * a.K + (tid & 15) * 8;
     c.bdst0 = (tid >> 4) * ROWB + (tid & 15) * 16;
 
-    f32x4 acc[RT][CT];
+    f32x4 acc[RT][CTW];
 #pragma unroll
     for (int t = 0; t < RT; ++t)
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-    uint4 aw[D][RT][4];  // ring of weight stages
+        for (int ct = 0; ct < CTW; ++ct) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint4 ah[3][RT][2];  // ring of weight half-stages
     u32x4 breg[NBU];     // (a native vector type: the compiler keeps such an array in registers)
 
     gemm_load_b(breg, c, it0);
-#pragma unroll
-    for (int s = 0; s < D - 1; ++s) gemm_load_a<RT>(aw[s], c, it0 + s);
+    gemm_load_a<RT, STREAM>(ah[0], c, 2 * it0);
+    gemm_load_a<RT, STREAM>(ah[1], c, 2 * it0 + 1);
     gemm_store_b(bt, breg, c);
     __syncthreads();
     int buf = 0;  // LDS stage that holds the current pair's activations
     int it = it0;
-    for (; it + D <= c.it1; it += D) {  // steady state, fully unrolled: every stage index is a constant
-#pragma unroll
-        for (int s = 0; s < D; ++s)
-            gemm_step<RT>(acc, aw[s], aw[(s + D - 1) % D], breg, bt, buf, a, c, it + s, q);
+    // steady state: three pairs = six half-steps, every ring index a constant
+    for (; it + 3 <= c.it1; it += 3) {
+        gemm_half<RT, STREAM, 0>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it, q);
+        gemm_half<RT, STREAM, 1>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 1, q);
+        gemm_half<RT, STREAM, 0>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 2, q);
+        gemm_half<RT, STREAM, 1>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it + 3, q);
+        gemm_half<RT, STREAM, 0>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 4, q);
+        gemm_half<RT, STREAM, 1>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 5, q);
     }
-#pragma unroll
-    for (int s = 0; s < D - 1; ++s)
-        if (it + s < c.it1) gemm_step<RT>(acc, aw[s], aw[(s + D - 1) % D], breg, bt, buf, a, c, it + s, q);
+    if (it < c.it1) {
+        gemm_half<RT, STREAM, 0>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it, q);
+        gemm_half<RT, STREAM, 1>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 1, q);
+    }
+    if (it + 1 < c.it1) {
+        gemm_half<RT, STREAM, 0>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 2, q);
+        gemm_half<RT, STREAM, 1>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it + 3, q);
+    }
 }
 
 hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
@@ -230,17 +240,25 @@ hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
     if (a.S != p.smax || (long)p.nb * (a.K >> 7) > 0x3fffffffL) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_gemm_kernel<1>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_gemm_kernel<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
-        if (e != hipSuccess) return e;
+        const void* fns[4] = {reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<4, false>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<4, true>)};
+        for (const void* fn : fns) {
+            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
+            if (e != hipSuccess) return e;
+        }
         attr_set = true;
     }
     const int grid = p.grid * a.n_pass;
-    if (p.rt == 2) prefill_gemm_kernel<2><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
-    else prefill_gemm_kernel<1><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+    const bool stream = a.n_pass == 1;
+    if (p.rt == 2) {
+        if (stream) prefill_gemm_kernel<4, true><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+        else prefill_gemm_kernel<4, false><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+    } else {
+        if (stream) prefill_gemm_kernel<2, true><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+        else prefill_gemm_kernel<2, false><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+    }
     return hipGetLastError();
 }
 
