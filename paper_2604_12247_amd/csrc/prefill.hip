@@ -270,24 +270,36 @@ __device__ __forceinline__ int splits_of(const GemmSplitMap& mp, int n) {
     return last - first + 1;
 }
 
-// grid (ceil(N / 256), M): thread = one output element
-// Partial sums of one element, added in slot order; eight loads are in flight at a time.
-__device__ __forceinline__ float sum_splits(const float* p, size_t plane, int n_splits) {
-    float v = 0.f;
+// Partial sums of four neighbouring elements, added in slot order; eight loads in flight at a time.
+__device__ __forceinline__ float4 sum_splits4(const float* p, size_t plane, int n_splits) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int s0 = 0; s0 < n_splits; s0 += 8) {
-        float t[8];
+        float4 t[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) t[i] = s0 + i < n_splits ? p[(size_t)(s0 + i) * plane] : 0.f;
+        for (int i = 0; i < 8; ++i)
+            t[i] = s0 + i < n_splits ? *reinterpret_cast<const float4*>(p + (size_t)(s0 + i) * plane) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v += t[i];
+        for (int i = 0; i < 8; ++i) { v.x += t[i].x; v.y += t[i].y; v.z += t[i].z; v.w += t[i].w; }
     }
     return v;
 }
+// four values of row m, columns n..n+3 -> the two bf16 planes (8-byte stores)
+__device__ __forceinline__ void split_store4(uint16_t* xs, int ld, int lo_rows, int m, int n, float4 v) {
+    const uint16_t h0 = f2bf(v.x), h1 = f2bf(v.y), h2 = f2bf(v.z), h3 = f2bf(v.w);
+    const uint16_t l0 = f2bf(v.x - bf2f(h0)), l1 = f2bf(v.y - bf2f(h1)), l2 = f2bf(v.z - bf2f(h2)), l3 = f2bf(v.w - bf2f(h3));
+    *reinterpret_cast<uint2*>(xs + (size_t)m * ld + n) = make_uint2((uint32_t)h0 | ((uint32_t)h1 << 16), (uint32_t)h2 | ((uint32_t)h3 << 16));
+    *reinterpret_cast<uint2*>(xs + (size_t)(lo_rows + m) * ld + n) =
+        make_uint2((uint32_t)l0 | ((uint32_t)l1 << 16), (uint32_t)l2 | ((uint32_t)l3 << 16));
+}
 
+// grid (ceil(N / 256), ceil(M / 4)), 256 threads: a wave takes one row and 256 columns, a
+// lane four neighbouring columns (all in one row block, hence with the same partial sums)
 template <int EPI>
 __global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a, GemmSplitMap mp) {
-    __shared__ float red[4];
-    const int tid = threadIdx.x, m = blockIdx.y, n = blockIdx.x * 256 + tid;  // m: row of the super-pass
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.y * 4 + (threadIdx.x >> 6);  // row of the super-pass
+    const int n = blockIdx.x * 256 + lane * 4;
+    if (m >= a.M) return;
     float inv = 1.0f;
     if (a.ssq_in) {  // (added in index order; sixteen loads in flight at a time)
         float t = 0.f;
@@ -305,26 +317,30 @@ __global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a, Ge
     float sq = 0.f;
     if (n < a.N) {
         if (EPI == EPI_SWIGLU) {
-            const float g = sum_splits(p + n, plane, splits_of(mp, n));
-            const float u = sum_splits(p + a.N + n, plane, splits_of(mp, a.N + n));
-            split_store_rows(a.ys, a.N, a.plane_rows, m, n, silu_mul(g * inv, u * inv));
+            const float4 g = sum_splits4(p + n, plane, splits_of(mp, n));
+            const float4 u = sum_splits4(p + a.N + n, plane, splits_of(mp, a.N + n));
+            const float4 v = make_float4(silu_mul(g.x * inv, u.x * inv), silu_mul(g.y * inv, u.y * inv),
+                                         silu_mul(g.z * inv, u.z * inv), silu_mul(g.w * inv, u.w * inv));
+            split_store4(a.ys, a.N, a.plane_rows, m, n, v);
         } else {
-            float v = sum_splits(p + n, plane, splits_of(mp, n));
-            v *= inv;
-            float* yp = a.y + (size_t)m * a.ldy + n;
+            float4 v = sum_splits4(p + n, plane, splits_of(mp, n));
+            v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
+            float4* yp = reinterpret_cast<float4*>(a.y + (size_t)m * a.ldy + n);
             if (EPI == EPI_RESID) {
-                v += *yp;
-                if (a.nx) split_store_rows(a.nx, a.N, a.plane_rows, m, n, v * a.gain[n]);
-                sq = v * v;
+                const float4 y0 = *yp;
+                v.x += y0.x; v.y += y0.y; v.z += y0.z; v.w += y0.w;
+                if (a.nx) {
+                    const float4 gn = *reinterpret_cast<const float4*>(a.gain + n);
+                    split_store4(a.nx, a.N, a.plane_rows, m, n, make_float4(v.x * gn.x, v.y * gn.y, v.z * gn.z, v.w * gn.w));
+                }
+                sq = (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
             }
             *yp = v;
         }
     }
     if (EPI == EPI_RESID && a.ssq_out) {
         sq = wave_sum(sq);
-        if ((tid & 63) == 0) red[tid >> 6] = sq;
-        __syncthreads();
-        if (tid == 0) a.ssq_out[(size_t)m * a.ssq_ld + blockIdx.x] = ((red[0] + red[1]) + red[2]) + red[3];
+        if (lane == 0) a.ssq_out[(size_t)m * a.ssq_ld + blockIdx.x] = sq;
     }
 }
 
@@ -332,7 +348,8 @@ hipError_t launch_prefill_epilogue(const GemmEpiArgs& a, hipStream_t st) {
     if (a.M < 1 || a.N < 1 || a.S < 1 || a.n_pass != (a.M + PM - 1) / PM || a.plane_rows < a.M) return hipErrorInvalidValue;
     if (a.epi == EPI_SWIGLU ? (!a.ys || a.rows != 2 * a.N) : (!a.y || a.rows != a.N)) return hipErrorInvalidValue;
     if (a.ssq_out && (a.N + 255) / 256 > a.ssq_ld) return hipErrorInvalidValue;
-    dim3 grid((a.N + 255) / 256, a.M);
+    if (a.N % 4 || a.ldy % 4) return hipErrorInvalidValue;
+    dim3 grid((a.N + 255) / 256, (a.M + 3) / 4);
     const GemmPlan pl = gemm_plan(a.rows, a.K, a.n_pass);
     if (a.S != pl.smax) return hipErrorInvalidValue;
     const GemmSplitMap mp{16 * WPB * pl.rt, a.K >> 7, pl.q};
