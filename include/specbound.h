@@ -306,6 +306,15 @@ int32_t sb_op_attention(const float *qkv, int32_t n_heads, int32_t n_kv_heads, i
                         const float *rope_sin, int32_t pos0, int32_t M, float *out, void *scratch, void *stream);
 size_t sb_op_attention_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t kv_dtype, int32_t n_pages);
 
+/* The same operation in the form the prompt uses (any number of rows, bf16 pool only):
+ * the k and v of all M rows are appended first, then every row's causal attention is
+ * computed with a running soft-max per query (no scratch).  Arguments, layouts and
+ * errors as sb_op_attention; M >= 1 is limited only by the pool (pos0 + M <= 16 n_pages);
+ * qkv, out and the rope tables 16-byte aligned. */
+int32_t sb_op_prompt_attention(const float *qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, void *pool,
+                               const int32_t *table, int32_t n_pages, int32_t layer, const float *rope_cos,
+                               const float *rope_sin, int32_t pos0, int32_t M, float *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

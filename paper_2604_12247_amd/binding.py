@@ -79,7 +79,7 @@ SYMBOLS = ["sb_last_error", "sb_temperature_schedule", "sb_query_sizes", "sb_loa
            "sb_get_stats", "sb_committed_len", "sb_debug_enable", "sb_debug_logits", "sb_debug_hidden",
            "sb_debug_kv", "sb_op_rmsnorm", "sb_op_gemv", "sb_op_gemv_scratch_bytes", "sb_op_head",
            "sb_op_head_scratch_bytes", "sb_rope_table_host", "sb_op_attention",
-           "sb_op_attention_scratch_bytes", "sb_decode", "sb_rewind", "sb_profile_begin", "sb_profile_end", "sb_op_copy",
+           "sb_op_attention_scratch_bytes", "sb_op_prompt_attention", "sb_decode", "sb_rewind", "sb_profile_begin", "sb_profile_end", "sb_op_copy",
            "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes"]
 
 KERNEL_CLASSES = ["rmsnorm", "qkv", "attention", "wo", "gate_up", "down", "exit_head",
@@ -138,6 +138,7 @@ def lib() -> C.CDLL:
         L.sb_rope_table_host.argtypes = [i32, f32, i32, vp, vp]
         L.sb_op_attention.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp]
         L.sb_op_attention_scratch_bytes.argtypes = [i32, i32, i32, i32]
+        L.sb_op_prompt_attention.argtypes = [vp, i32, i32, i32, vp, vp, i32, i32, vp, vp, i32, i32, vp, vp]
         L.sb_op_attention_scratch_bytes.restype = sz
         _lib = L
     return _lib
@@ -463,6 +464,17 @@ def op_attention(qkv, n_heads, n_kv_heads, head_dim, kv_dtype, pool, table, laye
     check(lib().sb_op_attention(qkv.data_ptr(), n_heads, n_kv_heads, head_dim, kv_dtype, pool.data_ptr(),
                                 table.data_ptr(), table.numel(), layer, rope_cos.data_ptr(), rope_sin.data_ptr(),
                                 pos0, M, out.data_ptr(), scratch.data_ptr(), _stream_ptr(torch, qkv.device)))
+    return out
+
+
+def op_prompt_attention(qkv, n_heads, n_kv_heads, head_dim, pool, table, layer, rope_cos, rope_sin, pos0):
+    """op_attention in the prompt's form: any number of rows, bf16 pool, running soft-max per query."""
+    import torch
+    M = qkv.shape[0]
+    out = torch.empty((M, n_heads * head_dim), dtype=torch.float32, device=qkv.device)
+    check(lib().sb_op_prompt_attention(qkv.data_ptr(), n_heads, n_kv_heads, head_dim, pool.data_ptr(),
+                                       table.data_ptr(), table.numel(), layer, rope_cos.data_ptr(),
+                                       rope_sin.data_ptr(), pos0, M, out.data_ptr(), _stream_ptr(torch, qkv.device)))
     return out
 
 

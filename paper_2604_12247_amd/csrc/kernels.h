@@ -116,6 +116,9 @@ struct AttnArgs {
 };
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
+// The prompt's attention for a bf16 cache: K/V append for all M rows, then every row's attention
+// with a running softmax per query (no partials; `partials` is not used); M is not limited.
+hipError_t launch_prefill_attention(const AttnArgs& a, hipStream_t st);
 
 // ---- prompt passes: SB_PREFILL_ROWS rows each, against tile-packed bf16 weights ----
 // Up to SB_PREFILL_PASSES passes of one layer go into one launch (a "super-pass"), so

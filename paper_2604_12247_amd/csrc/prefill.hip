@@ -12,6 +12,7 @@
 // result is left as a few partial sums.  prefill_epilogue_kernel adds them in index
 // order, applies the RMSNorm scale and the projection's tail (store, residual + next
 // input, SwiGLU).
+#include <type_traits>
 #include "kernels.h"
 #include "device_utils.h"
 
@@ -408,6 +409,361 @@ __global__ void prefill_split_kernel(const float* __restrict__ x, uint16_t* __re
 hipError_t launch_prefill_split(const float* x, uint16_t* xs, int32_t plane_rows, int32_t M, int32_t K, hipStream_t st) {
     if (M < 1 || plane_rows < M) return hipErrorInvalidValue;
     prefill_split_kernel<<<dim3((K + 255) / 256, M), 256, 0, st>>>(x, xs, plane_rows, K);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- prompt attention
+// The prompt's attention for a bf16 cache: first the keys and values of all rows of the
+// super-pass go into the cache (rotary embedding on the keys, both rounded to bf16; V
+// transposed per page, as everywhere), then one launch computes every row's attention with
+// the running-softmax scheme: a block owns 64 queries of one kv head (rows x the heads of
+// its group, 128 in the wide form), walks the 64-key chunks up to its last row's position and
+// keeps the running maximum, the sum and the weighted values of each query in registers -- no
+// per-chunk partials, no merge pass.  Both products run on the matrix cores with hi + lo pairs
+// for the fp32 side (queries, probabilities) like the decode kernel; a query's result depends
+// only on its own column of the accumulators, not on the other queries of the block.
+//
+// grid (pages touched, n_kv_heads), 256 threads: a block writes one head's part of one page --
+// K as 16-byte pieces (8 dims of a key), V transposed as 16-byte pieces (8 keys of a dim);
+// where the rows cover a page only partly, the V pieces go out key by key.
+template <int HD>
+__global__ __launch_bounds__(256) void prefill_kv_append_kernel(AttnArgs a) {
+    constexpr int HALF = HD / 2, PPK = HD / 8;
+    const int g = blockIdx.y, tid = threadIdx.x;
+    const int Hq = a.n_heads, Hkv = a.kv.n_kv_heads;
+    const int n_total = a.pos0 + a.M;
+    const int lpage = a.pos0 / SB_KV_BLOCK + blockIdx.x;
+    const int key_lo = lpage * SB_KV_BLOCK > a.pos0 ? lpage * SB_KV_BLOCK : a.pos0;
+    const int key_hi = (lpage + 1) * SB_KV_BLOCK < n_total ? (lpage + 1) * SB_KV_BLOCK : n_total;  // keys key_lo .. key_hi - 1
+    const size_t page_elems = (size_t)Hkv * SB_KV_BLOCK * HD;
+    const size_t page = (size_t)a.kv.table[lpage] * page_elems;
+    uint16_t* const kdst = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 0) * a.kv.n_pages * page_elems + page + (size_t)g * SB_KV_BLOCK * HD;
+    uint16_t* const vdst = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 1) * a.kv.n_pages * page_elems + page + (size_t)g * SB_KV_BLOCK * HD;
+    for (int idx = tid; idx < SB_KV_BLOCK * PPK; idx += 256) {
+        const int t = idx / PPK, d0 = (idx - t * PPK) * 8;
+        const int key = lpage * SB_KV_BLOCK + t;
+        if (key < key_lo || key >= key_hi) continue;
+        const bool lower = d0 < HALF;
+        const int j0 = lower ? d0 : d0 - HALF;
+        const float* kp = a.q + (size_t)(key - a.pos0) * a.qkv_rows + (size_t)(Hq + g) * HD;
+        const float* cp = a.rope_cos + (size_t)key * HALF + j0;
+        const float* sp = a.rope_sin + (size_t)key * HALF + j0;
+        uint32_t w[4];
+#pragma unroll
+        for (int e4 = 0; e4 < 8; e4 += 4) {
+            const float4 x = *reinterpret_cast<const float4*>(kp + j0 + e4);
+            const float4 y = *reinterpret_cast<const float4*>(kp + j0 + HALF + e4);
+            const float4 c = *reinterpret_cast<const float4*>(cp + e4);
+            const float4 sn = *reinterpret_cast<const float4*>(sp + e4);
+            const float u0 = lower ? x.x * c.x - y.x * sn.x : y.x * c.x + x.x * sn.x;
+            const float u1 = lower ? x.y * c.y - y.y * sn.y : y.y * c.y + x.y * sn.y;
+            const float u2 = lower ? x.z * c.z - y.z * sn.z : y.z * c.z + x.z * sn.z;
+            const float u3 = lower ? x.w * c.w - y.w * sn.w : y.w * c.w + x.w * sn.w;
+            w[e4 / 2] = (uint32_t)f2bf(u0) | ((uint32_t)f2bf(u1) << 16);
+            w[e4 / 2 + 1] = (uint32_t)f2bf(u2) | ((uint32_t)f2bf(u3) << 16);
+        }
+        *reinterpret_cast<uint4*>(kdst + (size_t)t * HD + d0) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    for (int idx = tid; idx < HD * 2; idx += 256) {
+        const int dim = idx >> 1, t0 = (idx & 1) * 8;
+        const int key0 = lpage * SB_KV_BLOCK + t0;
+        const float* vp = a.q + (size_t)(Hq + Hkv + g) * HD + dim;
+        uint16_t b[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int key = key0 + x;
+            b[x] = (key >= key_lo && key < key_hi) ? f2bf(vp[(size_t)(key - a.pos0) * a.qkv_rows]) : (uint16_t)0;
+        }
+        uint16_t* dst = vdst + (size_t)dim * SB_KV_BLOCK + t0;
+        if (key0 >= key_lo && key0 + 8 <= key_hi) {
+            *reinterpret_cast<uint4*>(dst) = make_uint4(b[0] | ((uint32_t)b[1] << 16), b[2] | ((uint32_t)b[3] << 16), b[4] | ((uint32_t)b[5] << 16), b[6] | ((uint32_t)b[7] << 16));
+        } else {
+#pragma unroll
+            for (int x = 0; x < 8; ++x)
+                if (key0 + x >= key_lo && key0 + x < key_hi) dst[x] = b[x];
+        }
+    }
+}
+
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+typedef float f32x2v __attribute__((ext_vector_type(2)));
+// two floats -> a packed bf16 pair, round to nearest even (the hardware's conversion)
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2v{a, b}, bf16x2v));
+}
+
+// grid (n_kv_heads, ceil(M G / (64 QT))), 256 threads.  A wave owns QT tiles of 16 queries and
+// is independent of the other waves but for the K/V chunk (64 keys) the block stages in LDS.
+// Scores are computed transposed, S^T = K Q^T, so a lane holds, for ONE query (its column),
+// the scores of 4 keys per key tile: the running maximum, sum and rescaling are per-lane
+// scalars, and the exponentials -- 4 keys of tile 2s, then 4 of tile 2s+1 -- are already the
+// B operand of O^T += V^T P^T when the 32 keys of a k step are taken in that order, which is
+// the order the A operand is read in from the transposed V page (two 8-byte runs per lane).
+template <int HD, int QT>
+__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(AttnArgs a) {
+    constexpr int CH = 64, KT = CH / 16, HALF = HD / 2;
+    constexpr int KSQ = HD / 32;             // k steps (32 dims) of the score product
+    constexpr int DTN = HD / 16;             // 16-dim tiles of the output
+    constexpr int PPK = HD / 8;              // 16-byte pieces of a key
+    constexpr int SLAB = SB_KV_BLOCK * HD;   // one head's part of a page
+    constexpr int NL = KT * SLAB / (256 * 8);  // 16-byte pieces per thread, operand and chunk
+    // Two chunks in LDS, filled by direct global -> LDS loads (lane l of a wave lands 16 l bytes
+    // after the wave's base).  V pages keep their layout; a K piece (key, p) sits at piece
+    // p ^ f(key) of its key's row, which spreads the 16 keys a score operand reads over all banks.
+    __shared__ __attribute__((aligned(16))) uint16_t k_s[2][CH * HD];
+    __shared__ __attribute__((aligned(16))) uint16_t v_s[2][KT * SLAB];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15, lq = lane >> 4;
+    const int g = blockIdx.x;
+    const int qtile = gridDim.y - 1 - blockIdx.y;  // the longest blocks (last rows) start first
+    const int Hq = a.n_heads, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
+    const int nq_total = a.M * G, q0 = qtile * (64 * QT);
+    const int n_total = a.pos0 + a.M;
+    const int q_last = (q0 + 64 * QT < nq_total ? q0 + 64 * QT : nq_total) - 1;
+    const int n_chunks = (a.pos0 + q_last / G) / CH + 1;  // chunks with a key the block's last row sees
+    const int wq0 = q0 + wave * QT * 16;                   // the wave's queries: wq0 .. wq1
+    const int wq1 = (wq0 + QT * 16 - 1 < nq_total - 1) ? wq0 + QT * 16 - 1 : nq_total - 1;
+    const bool wave_live = wq0 < nq_total;
+    const int wpos_min = a.pos0 + wq0 / G, wpos_max = a.pos0 + wq1 / G;
+    const float c2 = 1.4426950408889634f / sqrtf((float)HD);  // scores in units of log 2
+    const size_t page_elems = (size_t)Hkv * SLAB;
+    const uint16_t* const kbase = reinterpret_cast<const uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 0) * a.kv.n_pages * page_elems;
+    const uint16_t* const vbase = reinterpret_cast<const uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 1) * a.kv.n_pages * page_elems;
+
+    // ---- this wave's rotated queries as hi + lo B operands: lane (li, lq) has query li, dims 32 ks + 8 lq ..
+    bf16x8 qh[QT][KSQ], ql[QT][KSQ];
+    int qpos[QT], qrow[QT], qhead[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int qq = wq0 + qt * 16 + li;
+        const bool valid = qq < nq_total;
+        const int r = valid ? qq / G : 0, gi = valid ? qq - r * G : 0;
+        qrow[qt] = valid ? r : -1;
+        qhead[qt] = g * G + gi;
+        qpos[qt] = valid ? a.pos0 + r : 0x7fffffff;  // (a query past the end: zeros, nothing masked, never stored)
+        const float* qp = a.q + (size_t)r * a.qkv_rows + (size_t)qhead[qt] * HD;
+        const float* cp = a.rope_cos + (size_t)(a.pos0 + r) * HALF;
+        const float* sp = a.rope_sin + (size_t)(a.pos0 + r) * HALF;
+#pragma unroll
+        for (int ks = 0; ks < KSQ; ++ks) {
+            const int d0 = ks * 32 + lq * 8;
+            const bool lower = d0 < HALF;
+            const int j0 = lower ? d0 : d0 - HALF;
+            uint16_t h[8], l[8];
+#pragma unroll
+            for (int e4 = 0; e4 < 8; e4 += 4) {
+                const float4 x = *reinterpret_cast<const float4*>(qp + j0 + e4);
+                const float4 y = *reinterpret_cast<const float4*>(qp + j0 + HALF + e4);
+                const float4 c = *reinterpret_cast<const float4*>(cp + j0 + e4);
+                const float4 sn = *reinterpret_cast<const float4*>(sp + j0 + e4);
+                const float xs4[4] = {x.x, x.y, x.z, x.w}, ys4[4] = {y.x, y.y, y.z, y.w};
+                const float cs4[4] = {c.x, c.y, c.z, c.w}, sn4[4] = {sn.x, sn.y, sn.z, sn.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float u = lower ? xs4[e] * cs4[e] - ys4[e] * sn4[e] : ys4[e] * cs4[e] + xs4[e] * sn4[e];
+                    u = valid ? u * c2 : 0.f;  // scores come out in units of log 2
+                    h[e4 + e] = f2bf(u);
+                    l[e4 + e] = f2bf(u - bf2f(h[e4 + e]));
+                }
+            }
+            const uint4 hv = make_uint4(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16), h[4] | ((uint32_t)h[5] << 16), h[6] | ((uint32_t)h[7] << 16));
+            const uint4 lv = make_uint4(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16), l[4] | ((uint32_t)l[5] << 16), l[6] | ((uint32_t)l[7] << 16));
+            qh[qt][ks] = __builtin_bit_cast(bf16x8, hv);
+            ql[qt][ks] = __builtin_bit_cast(bf16x8, lv);
+        }
+    }
+
+    f32x4 o[QT][DTN];  // O^T: register r of lane (li, lq) is dim 16 dt + 4 lq + r of query li
+    float m_run[QT], l_run[QT];  // running maximum (log-2 units); this lane's part of the running sum
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        m_run[qt] = -__builtin_inff();
+        l_run[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DTN; ++dt) o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // ---- staging of a chunk: thread -> 16-byte pieces of the chunk's 4 pages (K and V slabs of head g)
+    int pg[NL];  // physical pages of the chunk issued next (-1: no key there); read one chunk ahead of the issue
+    auto lookup = [&](int chunk) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int page = chunk * KT + (i * 256 + tid) / (SB_KV_BLOCK * PPK);
+            pg[i] = (page * SB_KV_BLOCK < n_total) ? a.kv.table[page] : -1;
+        }
+    };
+    auto issue = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int slot = i * 256 + tid;             // the piece's place in LDS
+            const int key = slot / PPK, pp = slot - key * PPK;
+            const int piece = pp ^ (PPK == 16 ? (key & 15) : ((key >> 1) & 7));
+            uint16_t* kw = &k_s[buf][(i * 256 + wave * 64) * 8];  // the wave's 64 pieces
+            uint16_t* vw = &v_s[buf][(i * 256 + wave * 64) * 8];
+            if (pg[i] >= 0) {
+                const size_t base = (size_t)pg[i] * page_elems + (size_t)g * SLAB;
+                __builtin_amdgcn_global_load_lds(kbase + base + (key % SB_KV_BLOCK) * HD + piece * 8, kw, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(vbase + base + (slot * 8) % SLAB, vw, 16, 0, 0);
+            } else {  // past the last key: zeros
+                *reinterpret_cast<u32x4*>(kw + lane * 8) = u32x4{0u, 0u, 0u, 0u};
+                *reinterpret_cast<u32x4*>(vw + lane * 8) = u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+    };
+    const int kswz = PPK == 16 ? li : ((li >> 1) & 7);  // f(key) of this lane's key in a score operand
+
+    lookup(0);
+    issue(0);
+    lookup(1);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int chunk = 0; chunk < n_chunks; ++chunk) {
+        const int key0 = chunk * CH, buf = chunk & 1;
+        if (chunk + 1 < n_chunks) {
+            issue(buf ^ 1);
+            lookup(chunk + 2);
+        }
+        if (key0 + CH > n_total) {
+            // The last page has slots past the last key; what V holds there would meet a zero
+            // probability, and 0 x (stale bits that read as NaN) is not 0: zeros instead.  (K needs
+            // nothing: those scores are masked.)  Once per block at most.
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int slot = i * 256 + tid;
+                const int vk = key0 + (slot / (SB_KV_BLOCK * PPK)) * SB_KV_BLOCK + (slot * 8) % SB_KV_BLOCK;  // keys vk .. vk+7 of one dim
+                if (vk < n_total && vk + 8 > n_total) {
+                    u32x4 vv = *reinterpret_cast<u32x4*>(&v_s[buf][slot * 8]);
+#pragma unroll
+                    for (int x = 0; x < 8; ++x)
+                        if (vk + x >= n_total) vv[x >> 1] &= (x & 1) ? 0x0000ffffu : 0xffff0000u;
+                    *reinterpret_cast<u32x4*>(&v_s[buf][slot * 8]) = vv;
+                } else if (vk >= n_total && vk < (n_total + SB_KV_BLOCK - 1) / SB_KV_BLOCK * SB_KV_BLOCK) {
+                    *reinterpret_cast<u32x4*>(&v_s[buf][slot * 8]) = u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+            __syncthreads();
+        }
+        if (wave_live && key0 <= wpos_max) {
+            // ---- S^T = K Q^T for the 4 key tiles
+            f32x4 st[KT][QT];
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) st[kt][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KSQ; ++ks) {
+                    const bf16x8 kop = *reinterpret_cast<const bf16x8*>(&k_s[buf][((kt * 16 + li) * PPK + ((ks * 4 + lq) ^ kswz)) * 8]);
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt) {
+                        st[kt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qh[qt][ks], st[kt][qt], 0, 0, 0);
+                        st[kt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, ql[qt][ks], st[kt][qt], 0, 0, 0);
+                    }
+                }
+            }
+            // ---- running soft-max of each query (register r of tile kt: key key0 + 16 kt + 4 lq + r)
+            bf16x8 ph[QT][KT / 2], pl[QT][KT / 2];
+            auto soft = [&](auto masked) {
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) {
+                    float mx = -__builtin_inff();
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            if (decltype(masked)::value && key0 + kt * 16 + 4 * lq + r > qpos[qt]) st[kt][qt][r] = -__builtin_inff();
+                            mx = fmaxf(mx, st[kt][qt][r]);
+                        }
+                    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                    const float m_new = fmaxf(m_run[qt], mx);  // finite from the first chunk on: key 0 is visible to all
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+                    m_run[qt] = m_new;
+                    float sum = 0.f;
+                    uint32_t hw[KT][2], lw[KT][2];
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                        for (int r = 0; r < 4; r += 2) {
+                            const float p0 = __builtin_amdgcn_exp2f(st[kt][qt][r] - m_new);
+                            const float p1 = __builtin_amdgcn_exp2f(st[kt][qt][r + 1] - m_new);
+                            sum += p0 + p1;
+                            const uint32_t hp = pack_bf16(p0, p1);
+                            hw[kt][r >> 1] = hp;
+                            lw[kt][r >> 1] = pack_bf16(p0 - __uint_as_float(hp << 16), p1 - __uint_as_float(hp & 0xffff0000u));
+                        }
+                    l_run[qt] = l_run[qt] * alpha + sum;
+#pragma unroll
+                    for (int s2 = 0; s2 < KT / 2; ++s2) {
+                        ph[qt][s2] = __builtin_bit_cast(bf16x8, make_uint4(hw[2 * s2][0], hw[2 * s2][1], hw[2 * s2 + 1][0], hw[2 * s2 + 1][1]));
+                        pl[qt][s2] = __builtin_bit_cast(bf16x8, make_uint4(lw[2 * s2][0], lw[2 * s2][1], lw[2 * s2 + 1][0], lw[2 * s2 + 1][1]));
+                    }
+                    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // (no query of the tile has a new maximum: nothing to rescale)
+#pragma unroll
+                        for (int dt = 0; dt < DTN; ++dt)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) o[qt][dt][r] *= alpha;
+                    }
+                }
+            };
+            if (key0 + CH - 1 > wpos_min) soft(std::true_type{});
+            else soft(std::false_type{});
+            // ---- O^T += V^T P^T: k step s2 = keys (tile 2 s2: 4 lq ..+3, tile 2 s2 + 1: 4 lq ..+3) per lane group
+#pragma unroll
+            for (int s2 = 0; s2 < KT / 2; ++s2)
+#pragma unroll
+                for (int dt = 0; dt < DTN; ++dt) {
+                    const uint2 v0 = *reinterpret_cast<const uint2*>(&v_s[buf][(2 * s2) * SLAB + (dt * 16 + li) * SB_KV_BLOCK + 4 * lq]);
+                    const uint2 v1 = *reinterpret_cast<const uint2*>(&v_s[buf][(2 * s2 + 1) * SLAB + (dt * 16 + li) * SB_KV_BLOCK + 4 * lq]);
+                    const bf16x8 vop = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt) {
+                        o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, ph[qt][s2], o[qt][dt], 0, 0, 0);
+                        o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pl[qt][s2], o[qt][dt], 0, 0, 0);
+                    }
+                }
+        }
+        __builtin_amdgcn_s_waitcnt(0);  // this wave's pieces of the next chunk have landed
+        __syncthreads();                // ... and everybody's; every wave is done with this chunk
+    }
+    // ---- normalise; a lane has 4 neighbouring dims per tile of its query
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        float lt = l_run[qt];
+        lt += __shfl_xor(lt, 16, 64);
+        lt += __shfl_xor(lt, 32, 64);
+        if (qrow[qt] < 0) continue;
+        const float inv_l = 1.0f / lt;
+#pragma unroll
+        for (int dt = 0; dt < DTN; ++dt) {
+            const int col = qhead[qt] * HD + dt * 16 + 4 * lq;
+            const float4 val = make_float4(o[qt][dt][0] * inv_l, o[qt][dt][1] * inv_l, o[qt][dt][2] * inv_l, o[qt][dt][3] * inv_l);
+            if (a.out) *reinterpret_cast<float4*>(a.out + (size_t)qrow[qt] * Hq * HD + col) = val;
+            else split_store4(a.out_split, Hq * HD, a.split_rows, qrow[qt], col, val);
+        }
+    }
+}
+
+// M rows at positions pos0.. (bf16 cache): append their K/V, then attention of all rows,
+// output as floats (out) or as bf16 planes (out_split / split_rows as in launch_attention).
+hipError_t launch_prefill_attention(const AttnArgs& a, hipStream_t st) {
+    const int hd = a.kv.head_dim;
+    if ((hd != 64 && hd != 128) || a.kv.kv_dtype != SB_BF16 || a.M < 1 || a.n_heads % a.kv.n_kv_heads ||
+        (!a.out && (!a.out_split || a.split_rows < a.M)) || !a.rope_cos || !a.rope_sin)
+        return hipErrorInvalidValue;
+    const int G = a.n_heads / a.kv.n_kv_heads, nq = a.M * G;
+    // 32 queries per wave halve the LDS reads per product; 16 fill the chip at smaller sizes
+    const bool wide = (int64_t)a.kv.n_kv_heads * ((nq + 127) / 128) >= 512;
+    dim3 agrid((a.pos0 + a.M - 1) / SB_KV_BLOCK - a.pos0 / SB_KV_BLOCK + 1, a.kv.n_kv_heads), grid(a.kv.n_kv_heads, wide ? (nq + 127) / 128 : (nq + 63) / 64);
+    if (hd == 128) {
+        prefill_kv_append_kernel<128><<<agrid, 256, 0, st>>>(a);
+        if (wide) prefill_attn_kernel<128, 2><<<grid, 256, 0, st>>>(a);
+        else prefill_attn_kernel<128, 1><<<grid, 256, 0, st>>>(a);
+    } else {
+        prefill_kv_append_kernel<64><<<agrid, 256, 0, st>>>(a);
+        if (wide) prefill_attn_kernel<64, 2><<<grid, 256, 0, st>>>(a);
+        else prefill_attn_kernel<64, 1><<<grid, 256, 0, st>>>(a);
+    }
     return hipGetLastError();
 }
 

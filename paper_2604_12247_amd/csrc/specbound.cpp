@@ -444,6 +444,20 @@ int prefill_gemm_impl(sb_session* s, const int32_t* prompt, int32_t n, int32_t* 
             if ((rc = prefill_proj(s, m->w_qkv[l], qkv_rows, d, xs, R, e, SB_K_QKV))) return rc;
 
             int64_t kv_read = 0;
+            if (c.kv_dtype == SB_BF16) {  // all rows in one launch, running softmax per query
+                AttnArgs a{};
+                a.q = qkv; a.rope_cos = m->rope_cos; a.rope_sin = m->rope_sin;
+                a.qkv_rows = qkv_rows; a.n_heads = c.n_heads;
+                a.kv = s->kv; a.layer = l; a.pos0 = s->c; a.M = R;
+                a.out = nullptr; a.out_split = atts; a.split_rows = RS;
+                // a block of 64 queries reads the keys and values up to its last row once
+                const int G = c.n_heads / c.n_kv_heads, rows_per_block = 64 / G > 0 ? 64 / G : 1;
+                for (int q0 = 0; q0 < R; q0 += rows_per_block)
+                    kv_read += (int64_t)(s->c + (q0 + rows_per_block < R ? q0 + rows_per_block : R)) * 2 * c.n_kv_heads *
+                               c.head_dim * 2;
+                ProfScope ps(s, SB_K_ATTN, kv_read, st);
+                HIP_TRY(launch_prefill_attention(a, st));
+            } else
             for (int p0 = 0; p0 < R; p0 += PM) {
                 AttnArgs a{};
                 a.q = qkv + (size_t)p0 * qkv_rows; a.rope_cos = m->rope_cos; a.rope_sin = m->rope_sin;
@@ -1279,6 +1293,26 @@ int32_t sb_op_attention(const float* qkv, int32_t n_heads, int32_t n_kv_heads, i
     a.max_chunks = (n_pages * SB_KV_BLOCK + ch - 1) / ch;
     a.out = out; a.out_split = nullptr; a.split_rows = 8;
     HIP_TRY(launch_attention(a, (hipStream_t)stream));
+    return SB_OK;
+}
+
+int32_t sb_op_prompt_attention(const float* qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, void* pool,
+                               const int32_t* table, int32_t n_pages, int32_t layer, const float* rope_cos,
+                               const float* rope_sin, int32_t pos0, int32_t M, float* out, void* stream) {
+    int rc = attn_op_check(n_heads, n_kv_heads, head_dim, SB_BF16, pool, table, n_pages, layer, pos0, 1);
+    if (rc) return rc;
+    if (M < 1 || pos0 + (int64_t)M > (int64_t)n_pages * SB_KV_BLOCK)
+        return fail(SB_ECAPACITY, "op: rows %d..%lld outside the %d-page pool", pos0, (long long)pos0 + M - 1, n_pages);
+    if (!qkv || !out || !rope_cos || !rope_sin) return fail(SB_EINVAL, "op_prompt_attention: NULL operand");
+    if (((uintptr_t)qkv | (uintptr_t)out | (uintptr_t)rope_cos | (uintptr_t)rope_sin) & 15)
+        return fail(SB_EINVAL, "op_prompt_attention: operands must be 16-byte aligned");
+    AttnArgs a{};
+    a.q = qkv; a.rope_cos = rope_cos; a.rope_sin = rope_sin;
+    a.qkv_rows = (n_heads + 2 * n_kv_heads) * head_dim; a.n_heads = n_heads;
+    a.kv = KvLayout{pool, table, n_pages, n_kv_heads, head_dim, SB_BF16};
+    a.layer = layer; a.pos0 = pos0; a.M = M;
+    a.out = out; a.out_split = nullptr; a.split_rows = M;
+    HIP_TRY(launch_prefill_attention(a, (hipStream_t)stream));
     return SB_OK;
 }
 

@@ -102,4 +102,7 @@ def test_null_and_invalid_arguments_are_rejected_on_the_host():
     assert L.sb_op_gemm(p, 16, 64, p, p, 1, p, None) == sb.EINVAL                       # K % 128
     assert L.sb_op_gemm(p, 20, 128, p, p, 1, p, None) == sb.EINVAL                      # N % 16
     assert L.sb_op_gemm_scratch_bytes(20, 128) == 0
+    assert L.sb_op_prompt_attention(p, 4, 4, 64, p, p, 2, 0, p, p, 0, 33, p, None) == sb.ECAPACITY   # 33 rows, 2 pages
+    assert L.sb_op_prompt_attention(p, 4, 4, 32, p, p, 2, 0, p, p, 0, 4, p, None) == sb.EINVAL       # head_dim
+    assert L.sb_op_prompt_attention(p, 4, 4, 64, p, p, 2, 0, p, p, 0, 4, None, None) == sb.EINVAL
     assert L.sb_op_gemm_scratch_bytes(4096, 4096) >= 2 * 128 * 4096 * 2 + 128 * 4096 * 4

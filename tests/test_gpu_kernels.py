@@ -232,6 +232,77 @@ def test_rope_append_attention(T, case):
     assert worst <= 2e-5, worst
 
 
+PROMPT_ATT_CASES = [  # Hq, Hkv, hd, rows already cached, rows of this call, rope base
+    (4, 4, 64, 0, 1, 1e4),          # a single key
+    (4, 4, 64, 0, 70, 1e4),         # two query blocks, one chunk
+    (4, 2, 64, 37, 200, 1e4),       # GQA, a cached prefix, chunk boundary inside a query block
+    (6, 2, 128, 0, 150, 5e5),       # group of 3: query blocks straddle rows
+    (8, 8, 128, 130, 333, 1e4),     # several chunks, ragged last block and last page
+]
+
+
+@pytest.mark.parametrize("case", PROMPT_ATT_CASES)
+def test_prompt_attention(T, case):
+    """All rows of a prompt pass in one call (running soft-max per query): every output row and the
+    cache it leaves against the oracle's attention, rows before pos0 cached by the per-pass kernel."""
+    import paper_2604_12247_amd as sb
+    Hq, Hkv, hd, n_ctx, M, base = case
+    g = np.random.default_rng(5 + sum(int(x) for x in case[:5]))
+    n_tot = n_ctx + M
+    n_pages = (n_tot + 15) // 16 + 1
+    rows = (Hq + 2 * Hkv) * hd
+    qkv = (g.standard_normal((n_tot, rows)) * 1.2).astype(np.float32)
+    pool = T.empty(2 * 2 * n_pages * Hkv * 16 * hd * 2, dtype=T.uint8, device="cuda")
+    pool.fill_(0xFF)
+    table = _dev(T, g.permutation(n_pages).astype(np.int32))
+    c, s = sb.rope_table(hd, base, n_pages * 16)
+    cd, sd = _dev(T, c), _dev(T, s)
+    for pos in range(0, n_ctx, 8):
+        sb.op_attention(_dev(T, qkv[pos:min(pos + 8, n_ctx)]), Hq, Hkv, hd, sb.BF16, pool, table, 1, cd, sd, pos)
+    out = sb.op_prompt_attention(_dev(T, qkv[n_ctx:]), Hq, Hkv, hd, pool, table, 1, cd, sd, n_ctx).cpu().numpy()
+    # a decode-style pass after it reads the cache the call left
+    nxt = (g.standard_normal((1, rows))).astype(np.float32)
+    after = sb.op_attention(_dev(T, nxt), Hq, Hkv, hd, sb.BF16, pool, table, 1, cd, sd, n_tot).cpu().numpy()
+
+    # The cache first.  V is a plain rounding of the input: exact.  K is rounded after the rotation,
+    # which the kernel evaluates in float and the oracle in double: an element within float error of
+    # a rounding boundary may land on the neighbouring bf16 value, so a few elements may differ by
+    # one unit in the last place, none by more.  The attention below is then checked against the
+    # oracle's attention over the keys the cache holds.
+    raw = pool.view(T.int16).cpu().numpy().view(np.uint16).reshape(2, 2, n_pages, Hkv, 16 * hd)
+    tbl = table.cpu().numpy()
+    Kc = np.zeros((n_tot + 1, Hkv, hd), np.uint16); Vc = np.zeros_like(Kc)
+    for t in range(n_tot + 1):
+        pg = tbl[t // 16]
+        for h in range(Hkv):
+            Kc[t, h] = raw[1, 0, pg, h].reshape(16, hd)[t % 16]
+            Vc[t, h] = raw[1, 1, pg, h].reshape(hd, 16)[:, t % 16]
+    allq = np.concatenate([qkv, nxt])
+    Ko = np.zeros_like(Kc); Vo = np.zeros_like(Kc)
+    for t in range(n_tot + 1):
+        for h in range(Hkv):
+            Ko[t, h] = si.round_to_bf16(orc.rope_apply(allq[t, (Hq + h) * hd:(Hq + h + 1) * hd], t, base).astype(np.float32))
+            Vo[t, h] = si.round_to_bf16(allq[t, (Hq + Hkv + h) * hd:(Hq + Hkv + h + 1) * hd])
+    assert np.array_equal(Vc, Vo)
+    dk = np.abs(Kc.astype(np.int32) - Ko.astype(np.int32))
+    assert dk.max() <= 1 and (dk != 0).mean() <= 1e-3, (int(dk.max()), float((dk != 0).mean()))
+    K, V = si.bf16_to_f32(Kc), si.bf16_to_f32(Vc)
+    G = Hq // Hkv
+    worst = 0.0
+    check_rows = range(M) if M <= 80 else sorted(set(list(range(0, M, 7)) + [63, 64, 127, 128, M - 2, M - 1]) & set(range(M)))
+    for r in check_rows:
+        p = n_ctx + r
+        for h in range(Hq):
+            q = orc.rope_apply(qkv[p, h * hd:(h + 1) * hd], p, base)
+            ref = orc.attention_head(q, K[:p + 1, h // G], V[:p + 1, h // G])
+            worst = max(worst, float(np.max(np.abs(out[r, h * hd:(h + 1) * hd] - ref))))
+    assert worst <= 2e-5, worst
+    for h in range(Hq):
+        q = orc.rope_apply(nxt[0, h * hd:(h + 1) * hd], n_tot, base)
+        ref = orc.attention_head(q, K[:, h // G], V[:, h // G])
+        assert np.max(np.abs(after[0, h * hd:(h + 1) * hd] - ref)) <= 2e-5
+
+
 def test_attention_row_result_does_not_depend_on_m(T):
     """The same position gives the same bits alone and inside a pass of 6 rows."""
     args = (8, 8, 128, True)
