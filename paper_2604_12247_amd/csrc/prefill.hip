@@ -20,9 +20,10 @@ namespace sb {
 
 namespace {
 constexpr int PM = SB_PREFILL_ROWS;
-constexpr int ROWB = 272;                  // LDS bytes per staged row: 128 bf16 + 16 bytes of padding
+constexpr int ROWB = 288;                  // LDS bytes per staged row: 128 bf16 + 32 bytes of padding (16-byte operand
+                                           // reads at rows 272 bytes apart measure as 2-way bank conflicts, at 288 as none)
 constexpr int STAGE = 2 * PM * ROWB;       // one k block of both planes
-constexpr int WPB = 8;                     // waves per thread block (one block per CU: two LDS stages take 136 KB)
+constexpr int WPB = 8;                     // waves per thread block (one block per CU: two LDS stages take 144 KB)
 }  // namespace
 
 // Work decomposition: the (row block, k block) pairs are numbered row block first and
@@ -508,8 +509,9 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(AttnArgs a) {
     constexpr int SLAB = SB_KV_BLOCK * HD;   // one head's part of a page
     constexpr int NL = KT * SLAB / (256 * 8);  // 16-byte pieces per thread, operand and chunk
     // Two chunks in LDS, filled by direct global -> LDS loads (lane l of a wave lands 16 l bytes
-    // after the wave's base).  V pages keep their layout; a K piece (key, p) sits at piece
-    // p ^ f(key) of its key's row, which spreads the 16 keys a score operand reads over all banks.
+    // after the wave's base).  Which piece lands where is chosen so that operand reads are free of
+    // bank conflicts (measured): a K piece (key, p) sits at piece p ^ f(key) of its key's row; the two
+    // halves (8 keys each) of a V row change places in every second group of 8 dims.
     __shared__ __attribute__((aligned(16))) uint16_t k_s[2][CH * HD];
     __shared__ __attribute__((aligned(16))) uint16_t v_s[2][KT * SLAB];
 
@@ -604,7 +606,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(AttnArgs a) {
             if (pg[i] >= 0) {
                 const size_t base = (size_t)pg[i] * page_elems + (size_t)g * SLAB;
                 __builtin_amdgcn_global_load_lds(kbase + base + (key % SB_KV_BLOCK) * HD + piece * 8, kw, 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(vbase + base + (slot * 8) % SLAB, vw, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(vbase + base + ((slot ^ ((slot >> 4) & 1)) * 8) % SLAB, vw, 16, 0, 0);
             } else {  // past the last key: zeros
                 *reinterpret_cast<u32x4*>(kw + lane * 8) = u32x4{0u, 0u, 0u, 0u};
                 *reinterpret_cast<u32x4*>(vw + lane * 8) = u32x4{0u, 0u, 0u, 0u};
@@ -612,6 +614,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(AttnArgs a) {
         }
     };
     const int kswz = PPK == 16 ? li : ((li >> 1) & 7);  // f(key) of this lane's key in a score operand
+    const int vq = (((lq >> 1) ^ (li >> 3)) & 1) * 8 + (lq & 1) * 4;  // this lane's 4 keys within a V row in LDS
 
     lookup(0);
     issue(0);
@@ -631,7 +634,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(AttnArgs a) {
 #pragma unroll
             for (int i = 0; i < NL; ++i) {
                 const int slot = i * 256 + tid;
-                const int vk = key0 + (slot / (SB_KV_BLOCK * PPK)) * SB_KV_BLOCK + (slot * 8) % SB_KV_BLOCK;  // keys vk .. vk+7 of one dim
+                const int vk = key0 + (slot / (SB_KV_BLOCK * PPK)) * SB_KV_BLOCK + ((slot ^ (slot >> 4)) & 1) * 8;  // keys vk .. vk+7 of one dim
                 if (vk < n_total && vk + 8 > n_total) {
                     u32x4 vv = *reinterpret_cast<u32x4*>(&v_s[buf][slot * 8]);
 #pragma unroll
@@ -713,8 +716,8 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(AttnArgs a) {
             for (int s2 = 0; s2 < KT / 2; ++s2)
 #pragma unroll
                 for (int dt = 0; dt < DTN; ++dt) {
-                    const uint2 v0 = *reinterpret_cast<const uint2*>(&v_s[buf][(2 * s2) * SLAB + (dt * 16 + li) * SB_KV_BLOCK + 4 * lq]);
-                    const uint2 v1 = *reinterpret_cast<const uint2*>(&v_s[buf][(2 * s2 + 1) * SLAB + (dt * 16 + li) * SB_KV_BLOCK + 4 * lq]);
+                    const uint2 v0 = *reinterpret_cast<const uint2*>(&v_s[buf][(2 * s2) * SLAB + (dt * 16 + li) * SB_KV_BLOCK + vq]);
+                    const uint2 v1 = *reinterpret_cast<const uint2*>(&v_s[buf][(2 * s2 + 1) * SLAB + (dt * 16 + li) * SB_KV_BLOCK + vq]);
                     const bf16x8 vop = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt) {
