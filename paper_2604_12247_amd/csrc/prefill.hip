@@ -486,13 +486,6 @@ __global__ __launch_bounds__(256) void prefill_kv_append_kernel(AttnArgs a) {
     }
 }
 
-typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
-typedef float f32x2v __attribute__((ext_vector_type(2)));
-// two floats -> a packed bf16 pair, round to nearest even (the hardware's conversion)
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2v{a, b}, bf16x2v));
-}
-
 // grid (n_kv_heads, ceil(M G / (64 QT))), 256 threads.  A wave owns QT tiles of 16 queries and
 // is independent of the other waves but for the K/V chunk (64 keys) the block stages in LDS.
 // Scores are computed transposed, S^T = K Q^T, so a lane holds, for ONE query (its column),
