@@ -33,7 +33,7 @@ constexpr int WPB = 8;                     // waves per thread block (one block 
 // thread block that touches a row block leaves one partial sum for it, in slot
 // (range index - first range of that row block).
 struct GemmPlan {
-    int rt;      // row block = 128 rt weight rows (2 rt tiles per wave)
+    int rt;      // row block = 128 rt weight rows
     int nb;      // row blocks
     int q;       // (row block, k block) pairs per thread block
     int grid;    // thread blocks
@@ -64,7 +64,7 @@ struct GemmCtx {
     const uint16_t* W;      // packed weights + this lane's 16 bytes
     const uint16_t* bsrc0;  // this thread's first staging unit in the activation planes
     int bdst0;              // ... and in an LDS stage
-    int K, KB, n_tiles, it1, wr, wt, li, lq;  // wr: the wave's row group (0-3), wt: its token half (0-1)
+    int K, KB, n_tiles, it1, wr, wt, li, lq;  // wr: the wave's row group, wt: its share of the pass's rows
     int lo_off;             // rows from a high-plane row to its low-plane row
     int Mp, cid, pass;      // live rows of this pass, range index, pass
 };
@@ -75,13 +75,13 @@ struct GemmCtx {
 // waited for conservatively.)  STREAM: the weights are read once by this launch (a single
 // pass), so the loads carry the streaming hint; with several passes the other passes' blocks
 // read the same lines and they are left to the caches.
-template <int RT, bool STREAM>
+template <int RT, bool STREAM, int RG>
 __device__ __forceinline__ void gemm_load_a(uint4 (&ar)[RT][2], const GemmCtx& c, int h_) {
     const int h = h_ < 2 * c.it1 ? h_ : 2 * c.it1 - 1;
     const int it = h >> 1, b = it / c.KB, kb = it - b * c.KB;
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        int tile = (b * 4 + c.wr) * RT + t;
+        int tile = (b * RG + c.wr) * RT + t;
         if (tile > c.n_tiles - 1) tile = c.n_tiles - 1;  // a tile past the end re-reads the last one (not stored)
         const uint16_t* wp = c.W + ((size_t)tile * c.KB + kb) * 2048 + (h & 1) * 1024;
 #pragma unroll
@@ -108,11 +108,10 @@ __device__ __forceinline__ void gemm_store_b(unsigned char* dst, const u32x4 (&b
 #pragma unroll
     for (int i = 0; i < NBU; ++i) *reinterpret_cast<u32x4*>(dst + c.bdst0 + i * RPI * ROWB) = br[i];
 }
-// A wave multiplies its RT weight tiles with the four column tiles (64 rows) of its token
-// half: one LDS operand read serves RT MFMAs.  All column tiles are always multiplied, so
+// A wave multiplies its RT weight tiles with the CTW column tiles (16 rows each) of its share of
+// the pass: one LDS operand read serves RT MFMAs.  All column tiles are always multiplied, so
 // the block of LDS reads and MFMAs stays free of branches.
-constexpr int CTW = PM / 32;  // column tiles per wave
-template <int RT>
+template <int RT, int CTW>
 __device__ __forceinline__ void gemm_mma(f32x4 (&acc)[RT][CTW], const uint4 (&ar)[RT][2], const unsigned char* src,
                                          const GemmCtx& c, int uhalf) {
 #pragma unroll
@@ -135,13 +134,13 @@ __device__ __forceinline__ void gemm_mma(f32x4 (&acc)[RT][CTW], const uint4 (&ar
 }
 // Partial sum of row block b (C layout: lane (j = li, g = lq), register r -> weight row 4g + r
 // of the tile, activation row j), then zero for the next row block.
-template <int RT>
+template <int RT, int RG, int CTW>
 __device__ __forceinline__ void gemm_flush(f32x4 (&acc)[RT][CTW], const GemmArgs& a, const GemmCtx& c, int b, int q) {
     const int slot = c.cid - (b * c.KB) / q;
     float* part = a.part + (size_t)(c.pass * a.S + slot) * PM * a.rows;
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        const int tile = (b * 4 + c.wr) * RT + t;
+        const int tile = (b * RG + c.wr) * RT + t;
 #pragma unroll
         for (int ct = 0; ct < CTW; ++ct) {
             const int m = (c.wt * CTW + ct) * 16 + c.li;
@@ -158,36 +157,42 @@ __device__ __forceinline__ void gemm_flush(f32x4 (&acc)[RT][CTW], const GemmArgs
 // to was last read before the barrier that ended the previous pair).  Loads complete in issue
 // order and the activations are requested before the weights of the same half-step, so
 // waiting for them leaves the newest weight loads in flight.
-template <int RT, bool STREAM, int P>
+template <int RT, bool STREAM, int P, int RG, int CTW>
 __device__ __forceinline__ void gemm_half(f32x4 (&acc)[RT][CTW], const uint4 (&acur)[RT][2], uint4 (&afar)[RT][2],
                                           u32x4 (&breg)[NBU], unsigned char* bt, int& buf, const GemmArgs& a,
                                           const GemmCtx& c, int h, int q) {
     const int cur = h >> 1;
     if (P == 0) gemm_load_b(breg, c, cur + 1);
-    gemm_load_a<RT, STREAM>(afar, c, h + 2);
-    gemm_mma<RT>(acc, acur, bt + buf * STAGE, c, P);
+    gemm_load_a<RT, STREAM, RG>(afar, c, h + 2);
+    gemm_mma<RT, CTW>(acc, acur, bt + buf * STAGE, c, P);
     if (P == 1) {
         const int b = cur / c.KB;
-        if (cur + 1 >= c.it1 || (cur + 1) / c.KB != b) gemm_flush<RT>(acc, a, c, b, q);
+        if (cur + 1 >= c.it1 || (cur + 1) / c.KB != b) gemm_flush<RT, RG, CTW>(acc, a, c, b, q);
         buf ^= 1;
         gemm_store_b(bt + buf * STAGE, breg, c);
         __syncthreads();
     }
 }
 
-// 512 threads: four row groups x two token halves; a wave has RT 16-row weight tiles (of the
-// block's 64 RT rows) and 64 of the pass's 128 rows, i.e. up to a 64 x 64 tile of the result.
+// 512 threads = RG row groups x (8 / RG) splits of the pass's 128 rows; a wave has RT 16-row weight
+// tiles (of the block's 16 RG RT weight rows) and 16 RG of the pass's rows.  RG = 4, RT = 2 for the
+// narrow projections (128 weight rows per block: a 32 x 64 tile of the result per wave), RG = 8,
+// RT = 2 for the wide ones (256 weight rows per block: 32 x 128 per wave -- every wave loads weights
+// of its own, which halves the traffic through the vector memory path, busy 64 % of the time with
+// four row groups, at the price of twice the LDS operand reads, which have room: measured 4-5 %
+// faster on the wide projections, 15 % slower on the narrow ones).
 // Weights: a ring of three register half-stages, requested two half-steps (one pair) ahead;
 // activations: one pair ahead through LDS.
-template <int RT, bool STREAM>
+template <int RT, bool STREAM, int RG>
 __global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int q) {
-    static_assert(WPB == 8, "four row groups x two token halves");
+    static_assert(WPB == 8 && (RG == 4 || RG == 8), "row groups x splits of the pass's rows");
+    constexpr int CTW = PM / 16 / (WPB / RG);  // column tiles (16 of the pass's rows) per wave
     extern __shared__ __attribute__((aligned(16))) unsigned char bt[];  // [2][STAGE]
     const int tid = threadIdx.x, lane = tid & 63;
     GemmCtx c;
-    c.wr = (tid >> 6) & 3; c.wt = tid >> 8; c.li = lane & 15; c.lq = lane >> 4;
+    c.wr = (tid >> 6) % RG; c.wt = (tid >> 6) / RG; c.li = lane & 15; c.lq = lane >> 4;
     c.K = a.K; c.KB = a.K >> 7; c.n_tiles = a.rows >> 4;
-    const int nb = (c.n_tiles + 4 * RT - 1) / (4 * RT);
+    const int nb = (c.n_tiles + RG * RT - 1) / (RG * RT);
     const int total = nb * c.KB;  // (checked on the host to fit an int)
     c.pass = blockIdx.x % a.n_pass;  // neighbours in the grid: same weights, different passes
     c.cid = blockIdx.x / a.n_pass;
@@ -209,28 +214,28 @@ __global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int 
     u32x4 breg[NBU];     // (a native vector type: the compiler keeps such an array in registers)
 
     gemm_load_b(breg, c, it0);
-    gemm_load_a<RT, STREAM>(ah[0], c, 2 * it0);
-    gemm_load_a<RT, STREAM>(ah[1], c, 2 * it0 + 1);
+    gemm_load_a<RT, STREAM, RG>(ah[0], c, 2 * it0);
+    gemm_load_a<RT, STREAM, RG>(ah[1], c, 2 * it0 + 1);
     gemm_store_b(bt, breg, c);
     __syncthreads();
     int buf = 0;  // LDS stage that holds the current pair's activations
     int it = it0;
     // steady state: three pairs = six half-steps, every ring index a constant
     for (; it + 3 <= c.it1; it += 3) {
-        gemm_half<RT, STREAM, 0>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it, q);
-        gemm_half<RT, STREAM, 1>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 1, q);
-        gemm_half<RT, STREAM, 0>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 2, q);
-        gemm_half<RT, STREAM, 1>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it + 3, q);
-        gemm_half<RT, STREAM, 0>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 4, q);
-        gemm_half<RT, STREAM, 1>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 5, q);
+        gemm_half<RT, STREAM, 0, RG, CTW>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it, q);
+        gemm_half<RT, STREAM, 1, RG, CTW>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 1, q);
+        gemm_half<RT, STREAM, 0, RG, CTW>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 2, q);
+        gemm_half<RT, STREAM, 1, RG, CTW>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it + 3, q);
+        gemm_half<RT, STREAM, 0, RG, CTW>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 4, q);
+        gemm_half<RT, STREAM, 1, RG, CTW>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 5, q);
     }
     if (it < c.it1) {
-        gemm_half<RT, STREAM, 0>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it, q);
-        gemm_half<RT, STREAM, 1>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 1, q);
+        gemm_half<RT, STREAM, 0, RG, CTW>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it, q);
+        gemm_half<RT, STREAM, 1, RG, CTW>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 1, q);
     }
     if (it + 1 < c.it1) {
-        gemm_half<RT, STREAM, 0>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 2, q);
-        gemm_half<RT, STREAM, 1>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it + 3, q);
+        gemm_half<RT, STREAM, 0, RG, CTW>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 2, q);
+        gemm_half<RT, STREAM, 1, RG, CTW>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it + 3, q);
     }
 }
 
@@ -242,10 +247,10 @@ hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
     if (a.S != p.smax || (long)p.nb * (a.K >> 7) > 0x3fffffffL) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
-        const void* fns[4] = {reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false>),
-                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true>),
-                              reinterpret_cast<const void*>(&prefill_gemm_kernel<4, false>),
-                              reinterpret_cast<const void*>(&prefill_gemm_kernel<4, true>)};
+        const void* fns[4] = {reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false, 4>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true, 4>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false, 8>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true, 8>)};
         for (const void* fn : fns) {
             hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
             if (e != hipSuccess) return e;
@@ -255,11 +260,11 @@ hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
     const int grid = p.grid * a.n_pass;
     const bool stream = a.n_pass == 1;
     if (p.rt == 2) {
-        if (stream) prefill_gemm_kernel<4, true><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
-        else prefill_gemm_kernel<4, false><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+        if (stream) prefill_gemm_kernel<2, true, 8><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+        else prefill_gemm_kernel<2, false, 8><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
     } else {
-        if (stream) prefill_gemm_kernel<2, true><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
-        else prefill_gemm_kernel<2, false><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+        if (stream) prefill_gemm_kernel<2, true, 4><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+        else prefill_gemm_kernel<2, false, 4><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
     }
     return hipGetLastError();
 }
