@@ -131,6 +131,13 @@ __device__ __forceinline__ void gemm_mma(f32x4 (&acc)[RT][CTW], const uint4 (&ar
                                                                      0, 0, 0);
         }
     }
+    // issue order for the compiler's scheduler: two operand reads, 2 RT MFMAs, and so on (1 % faster
+    // than its own choice)
+#pragma unroll
+    for (int i = 0; i < 2 * CTW; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * RT, 0);
+    }
 }
 // Partial sum of row block b (C layout: lane (j = li, g = lq), register r -> weight row 4g + r
 // of the tile, activation row j), then zero for the next row block.
