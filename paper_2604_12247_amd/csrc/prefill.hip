@@ -24,6 +24,7 @@ constexpr int ROWB = 288;                  // LDS bytes per staged row: 128 bf16
                                            // reads at rows 272 bytes apart measure as 2-way bank conflicts, at 288 as none)
 constexpr int STAGE = 2 * PM * ROWB;       // one k block of both planes
 constexpr int WPB = 8;                     // waves per thread block (one block per CU: two LDS stages take 144 KB)
+constexpr int BLOCK_ROWS = 256;            // weight rows of a row block: 8 row groups x 2 tiles of 16
 }  // namespace
 
 // Work decomposition: the (row block, k block) pairs are numbered row block first and
@@ -33,7 +34,6 @@ constexpr int WPB = 8;                     // waves per thread block (one block 
 // thread block that touches a row block leaves one partial sum for it, in slot
 // (range index - first range of that row block).
 struct GemmPlan {
-    int rt;      // row block = 128 rt weight rows
     int nb;      // row blocks
     int q;       // (row block, k block) pairs per thread block
     int grid;    // thread blocks
@@ -42,8 +42,7 @@ struct GemmPlan {
 static GemmPlan gemm_plan(int32_t rows, int32_t K, int32_t n_pass) {
     GemmPlan p;
     const int KB = K >> 7;
-    p.rt = rows >= 8192 ? 2 : 1;
-    p.nb = (rows + 16 * WPB * p.rt - 1) / (16 * WPB * p.rt);
+    p.nb = (rows + BLOCK_ROWS - 1) / BLOCK_ROWS;
     const long total = (long)p.nb * KB;
     // resident thread blocks: one per CU (LDS), shared out among the passes of the launch --
     // every pass gets the same cut, so the blocks of different passes that work on the same
@@ -182,12 +181,11 @@ __device__ __forceinline__ void gemm_half(f32x4 (&acc)[RT][CTW], const uint4 (&a
 }
 
 // 512 threads = RG row groups x (8 / RG) splits of the pass's 128 rows; a wave has RT 16-row weight
-// tiles (of the block's 16 RG RT weight rows) and 16 RG of the pass's rows.  RG = 4, RT = 2 for the
-// narrow projections (128 weight rows per block: a 32 x 64 tile of the result per wave), RG = 8,
-// RT = 2 for the wide ones (256 weight rows per block: 32 x 128 per wave -- every wave loads weights
-// of its own, which halves the traffic through the vector memory path, busy 64 % of the time with
-// four row groups, at the price of twice the LDS operand reads, which have room: measured 4-5 %
-// faster on the wide projections, 15 % slower on the narrow ones).
+// tiles (of the block's 16 RG RT weight rows) and 16 RG of the pass's rows.  Used with RG = 8, RT = 2:
+// 256 weight rows per block, a 32 x 128 tile of the result per wave, every wave loading weights of
+// its own.  (Four row groups x two halves of the pass, a 64 x 64 tile per wave, read every weight
+// tile in two waves: the vector memory path was busy 64 % of the time instead of 46 %, the launches
+// took 4-5 % longer on the wide projections and 20 % longer on the narrow ones at 16 passes.)
 // Weights: a ring of three register half-stages, requested two half-steps (one pair) ahead;
 // activations: one pair ahead through LDS.
 template <int RT, bool STREAM, int RG>
@@ -254,9 +252,7 @@ hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
     if (a.S != p.smax || (long)p.nb * (a.K >> 7) > 0x3fffffffL) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
-        const void* fns[4] = {reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false, 4>),
-                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true, 4>),
-                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false, 8>),
+        const void* fns[2] = {reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false, 8>),
                               reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true, 8>)};
         for (const void* fn : fns) {
             hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
@@ -265,14 +261,8 @@ hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
         attr_set = true;
     }
     const int grid = p.grid * a.n_pass;
-    const bool stream = a.n_pass == 1;
-    if (p.rt == 2) {
-        if (stream) prefill_gemm_kernel<2, true, 8><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
-        else prefill_gemm_kernel<2, false, 8><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
-    } else {
-        if (stream) prefill_gemm_kernel<2, true, 4><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
-        else prefill_gemm_kernel<2, false, 4><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
-    }
+    if (a.n_pass == 1) prefill_gemm_kernel<2, true, 8><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+    else prefill_gemm_kernel<2, false, 8><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
     return hipGetLastError();
 }
 
@@ -366,7 +356,7 @@ hipError_t launch_prefill_epilogue(const GemmEpiArgs& a, hipStream_t st) {
     dim3 grid((a.N + 255) / 256, (a.M + 3) / 4);
     const GemmPlan pl = gemm_plan(a.rows, a.K, a.n_pass);
     if (a.S != pl.smax) return hipErrorInvalidValue;
-    const GemmSplitMap mp{16 * WPB * pl.rt, a.K >> 7, pl.q};
+    const GemmSplitMap mp{BLOCK_ROWS, a.K >> 7, pl.q};
     switch (a.epi) {
         case EPI_STORE: prefill_epilogue_kernel<EPI_STORE><<<grid, 256, 0, st>>>(a, mp); break;
         case EPI_RESID: prefill_epilogue_kernel<EPI_RESID><<<grid, 256, 0, st>>>(a, mp); break;
