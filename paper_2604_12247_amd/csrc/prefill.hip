@@ -189,7 +189,7 @@ __device__ __forceinline__ void gemm_half(f32x4 (&acc)[RT][CTW], const uint4 (&a
 // Weights: a ring of three register half-stages, requested two half-steps (one pair) ahead;
 // activations: one pair ahead through LDS.
 template <int RT, bool STREAM, int RG>
-__global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int q) {
+__global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int q, int xa) {
     static_assert(WPB == 8 && (RG == 4 || RG == 8), "row groups x splits of the pass's rows");
     constexpr int CTW = PM / 16 / (WPB / RG);  // column tiles (16 of the pass's rows) per wave
     extern __shared__ __attribute__((aligned(16))) unsigned char bt[];  // [2][STAGE]
@@ -199,8 +199,17 @@ __global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int 
     c.K = a.K; c.KB = a.K >> 7; c.n_tiles = a.rows >> 4;
     const int nb = (c.n_tiles + RG * RT - 1) / (RG * RT);
     const int total = nb * c.KB;  // (checked on the host to fit an int)
-    c.pass = blockIdx.x % a.n_pass;  // neighbours in the grid: same weights, different passes
-    c.cid = blockIdx.x / a.n_pass;
+    // Thread blocks go to the 8 XCDs round-robin by index.  The blocks that share a range of the
+    // weights (same range index, different passes) are given indices of one residue mod 8, so that
+    // they meet in one L2 and each L2 fetches an eighth of the layer's weights instead of all of them.
+    // Here the 8 XCDs form an xa x (8 / xa) array: range indices are dealt to its rows, passes to its
+    // columns, so the weights of a range are fetched by 8 / xa of the L2s and the activations of a
+    // pass by xa of them (xa is chosen on the host).
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int xb = 8 / xa, npb = (a.n_pass + xb - 1) / xb;
+    c.pass = (j % npb) * xb + xcd / xa;
+    c.cid = (j / npb) * xa + xcd % xa;
+    if (c.pass >= a.n_pass) return;
     c.Mp = a.M - c.pass * PM < PM ? a.M - c.pass * PM : PM;
     c.lo_off = a.plane_rows;
     const int it0 = c.cid * q;
@@ -260,9 +269,14 @@ hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
         }
         attr_set = true;
     }
-    const int grid = p.grid * a.n_pass;
-    if (a.n_pass == 1) prefill_gemm_kernel<2, true, 8><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
-    else prefill_gemm_kernel<2, false, 8><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q);
+    // XCD array shape, by measurement at the 7B shapes: with few passes the weights dominate what the
+    // L2s fetch (one L2 per range: 8 % faster than every L2 fetching everything at 4 passes); with many
+    // passes the activations weigh as much and 2 x 4 is 2 % ahead of both 8 x 1 and 1 x 8
+    const int xa = a.n_pass >= 8 ? 2 : (a.n_pass >= 5 ? 4 : 8);
+    const int xb = 8 / xa;
+    const int grid = 8 * ((a.n_pass + xb - 1) / xb) * ((p.grid + xa - 1) / xa);
+    if (a.n_pass == 1) prefill_gemm_kernel<2, true, 8><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q, xa);
+    else prefill_gemm_kernel<2, false, 8><<<grid, 64 * WPB, 2 * STAGE, st>>>(a, p.q, xa);
     return hipGetLastError();
 }
 
