@@ -56,6 +56,15 @@ __device__ __forceinline__ void split_store_rows(uint16_t* xs, int ld, int lo_ro
     xs[(size_t)(lo_rows + m) * ld + i] = lo;
 }
 
+// four values of row m, columns n..n+3 -> the two bf16 planes (8-byte stores)
+__device__ __forceinline__ void split_store4(uint16_t* xs, int ld, int lo_rows, int m, int n, float4 v) {
+    const uint16_t h0 = f2bf(v.x), h1 = f2bf(v.y), h2 = f2bf(v.z), h3 = f2bf(v.w);
+    const uint16_t l0 = f2bf(v.x - bf2f(h0)), l1 = f2bf(v.y - bf2f(h1)), l2 = f2bf(v.z - bf2f(h2)), l3 = f2bf(v.w - bf2f(h3));
+    *reinterpret_cast<uint2*>(xs + (size_t)m * ld + n) = make_uint2((uint32_t)h0 | ((uint32_t)h1 << 16), (uint32_t)h2 | ((uint32_t)h3 << 16));
+    *reinterpret_cast<uint2*>(xs + (size_t)(lo_rows + m) * ld + n) =
+        make_uint2((uint32_t)l0 | ((uint32_t)l1 << 16), (uint32_t)l2 | ((uint32_t)l3 << 16));
+}
+
 __device__ __forceinline__ void unpack8(uint4 v, float (&w)[8]) {
     w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
     w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
