@@ -136,16 +136,19 @@ struct GemmArgs {
     int32_t n_pass;      // ceil(M / SB_PREFILL_ROWS)
     float* part;
     int32_t S;           // partial-sum slots per row block, from gemm_splits()
-    // gate/up projection (rows = 2 N: N gate rows, then N up rows): a thread block takes matching gate
-    // and up tiles together and, where it owns a row block's whole k range, leaves silu(g) * u of the
-    // normalised inputs as bf16 planes in ys [2][plane_rows][N] itself; the epilogue (which must be
-    // given swiglu_fused = 1 as well) then only finishes the row blocks that were cut along k.
-    int32_t swiglu_fused;
-    int32_t N;           // outputs (swiglu_fused)
-    const float* ssq_in; // partial sums of squares of the input rows (swiglu_fused; as in GemmEpiArgs)
+    // Tail done by the GEMM itself for the row blocks (256 weight rows) whose whole k range one thread
+    // block owns; the epilogue, which must be given the same `fused`, then only finishes the row blocks
+    // that were cut along k.  0: none.  1 + EPI_STORE: y = scale * product.  1 + EPI_SWIGLU (rows = 2 N:
+    // N gate rows, then N up rows; a thread block takes matching gate and up tiles together):
+    // silu(g) * u of the scaled products as bf16 planes ys [2][plane_rows][N].
+    int32_t fused;
+    int32_t N;           // outputs
+    const float* ssq_in; // partial sums of squares of the input rows (nullable: no scale; as in GemmEpiArgs)
     int32_t ssq_nb, ssq_ld;
     float eps;
-    uint16_t* ys;
+    uint16_t* ys;        // SWIGLU
+    float* y;            // STORE: [M][ldy]
+    int32_t ldy;
 };
 int gemm_splits(int32_t rows, int32_t K, int32_t n_pass);
 hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st);
@@ -168,7 +171,7 @@ struct GemmEpiArgs {
     uint16_t* nx;
     float* ssq_out;        // RESID: partial sums of squares of y per 256 columns
     uint16_t* ys;          // SWIGLU: bf16 planes of silu(gate) * up
-    int32_t swiglu_fused;  // SWIGLU: the GEMM ran with swiglu_fused = 1 (row blocks with one partial are done)
+    int32_t fused;         // the GEMM ran with this `fused` (row blocks with one partial are done)
 };
 hipError_t launch_prefill_epilogue(const GemmEpiArgs& a, hipStream_t st);
 // Embedding rows of tokens[0..M) (device ids): H [M][d], bf16 planes of gain * h, sums of squares.

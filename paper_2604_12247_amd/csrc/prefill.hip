@@ -76,24 +76,24 @@ struct GemmCtx {
 // waited for conservatively.)  STREAM: the weights are read once by this launch (a single
 // pass), so the loads carry the streaming hint; with several passes the other passes' blocks
 // read the same lines and they are left to the caches.
-// Weight tile t of this wave in row block b; -1 past the end.  SWI (gate/up with the fused tail): the
+// Weight tile t of this wave in row block b; -1 past the end.  Gate/up with the fused tail: the
 // wave's two tiles are the gate and the up tile of one group of 16 outputs.
-template <int RT, int RG, bool SWI>
+template <int RT, int RG, int FE>
 __device__ __forceinline__ int gemm_tile(const GemmCtx& c, int b, int t) {
-    if (SWI) {
+    if (FE == 1 + EPI_SWIGLU) {
         const int j = b * RG + c.wr;
         return j < c.n_out_tiles ? (t == 0 ? j : c.n_out_tiles + j) : -1;
     }
     const int tile = (b * RG + c.wr) * RT + t;
     return tile < c.n_tiles ? tile : -1;
 }
-template <int RT, bool STREAM, int RG, bool SWI>
+template <int RT, bool STREAM, int RG, int FE>
 __device__ __forceinline__ void gemm_load_a(uint4 (&ar)[RT][2], const GemmCtx& c, int h_) {
     const int h = h_ < 2 * c.it1 ? h_ : 2 * c.it1 - 1;
     const int it = h >> 1, b = it / c.KB, kb = it - b * c.KB;
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        int tile = gemm_tile<RT, RG, SWI>(c, b, t);
+        int tile = gemm_tile<RT, RG, FE>(c, b, t);
         if (tile < 0) tile = c.n_tiles - 1;  // a tile past the end re-reads the last one (not stored)
         const uint16_t* wp = c.W + ((size_t)tile * c.KB + kb) * 2048 + (h & 1) * 1024;
 #pragma unroll
@@ -153,13 +153,30 @@ __device__ __forceinline__ void gemm_mma(f32x4 (&acc)[RT][CTW], const uint4 (&ar
 }
 // Partial sum of row block b (C layout: lane (j = li, g = lq), register r -> weight row 4g + r
 // of the tile, activation row j), then zero for the next row block.
-template <int RT, int RG, int CTW, bool SWI>
+template <int RT, int RG, int CTW, int FE>
 __device__ __forceinline__ void gemm_flush(f32x4 (&acc)[RT][CTW], const GemmArgs& a, const GemmCtx& c, int b, int q,
                                            const float* s_inv) {
     const int first = (b * c.KB) / q;
-    if (SWI && first == ((b + 1) * c.KB - 1) / q) {
-        // the whole k range of the row block was this thread block's: finish it here -- register r of
-        // lane (li, lq): output 16 j + 4 lq + r of row li of the column tile, gate in tile 0, up in tile 1
+    const bool whole = first == ((b + 1) * c.KB - 1) / q;  // the row block's whole k range was this thread block's
+    if (FE == 1 + EPI_STORE && whole) {
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            const int tile = gemm_tile<RT, RG, FE>(c, b, t);
+#pragma unroll
+            for (int ct = 0; ct < CTW; ++ct) {
+                const int m = (c.wt * CTW + ct) * 16 + c.li;
+                if (tile >= 0 && m < c.Mp) {
+                    const float inv = s_inv[m];
+                    *reinterpret_cast<float4*>(a.y + (size_t)(c.pass * PM + m) * a.ldy + tile * 16 + 4 * c.lq) =
+                        make_float4(acc[t][ct][0] * inv, acc[t][ct][1] * inv, acc[t][ct][2] * inv, acc[t][ct][3] * inv);
+                }
+                acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+        return;
+    }
+    if (FE == 1 + EPI_SWIGLU && whole) {
+        // register r of lane (li, lq): output 16 j + 4 lq + r of row li of the column tile, gate in tile 0, up in tile 1
         const int j = b * RG + c.wr;
 #pragma unroll
         for (int ct = 0; ct < CTW; ++ct) {
@@ -179,7 +196,7 @@ __device__ __forceinline__ void gemm_flush(f32x4 (&acc)[RT][CTW], const GemmArgs
     float* part = a.part + (size_t)(c.pass * a.S + slot) * PM * a.rows;
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        const int tile = gemm_tile<RT, RG, SWI>(c, b, t);
+        const int tile = gemm_tile<RT, RG, FE>(c, b, t);
 #pragma unroll
         for (int ct = 0; ct < CTW; ++ct) {
             const int m = (c.wt * CTW + ct) * 16 + c.li;
@@ -196,17 +213,17 @@ __device__ __forceinline__ void gemm_flush(f32x4 (&acc)[RT][CTW], const GemmArgs
 // to was last read before the barrier that ended the previous pair).  Loads complete in issue
 // order and the activations are requested before the weights of the same half-step, so
 // waiting for them leaves the newest weight loads in flight.
-template <int RT, bool STREAM, int P, int RG, int CTW, bool SWI>
+template <int RT, bool STREAM, int P, int RG, int CTW, int FE>
 __device__ __forceinline__ void gemm_half(f32x4 (&acc)[RT][CTW], const uint4 (&acur)[RT][2], uint4 (&afar)[RT][2],
                                           u32x4 (&breg)[NBU], unsigned char* bt, int& buf, const GemmArgs& a,
                                           const GemmCtx& c, int h, int q) {
     const int cur = h >> 1;
     if (P == 0) gemm_load_b(breg, c, cur + 1);
-    gemm_load_a<RT, STREAM, RG, SWI>(afar, c, h + 2);
+    gemm_load_a<RT, STREAM, RG, FE>(afar, c, h + 2);
     gemm_mma<RT, CTW>(acc, acur, bt + buf * STAGE, c, P);
     if (P == 1) {
         const int b = cur / c.KB;
-        if (cur + 1 >= c.it1 || (cur + 1) / c.KB != b) gemm_flush<RT, RG, CTW, SWI>(acc, a, c, b, q, reinterpret_cast<const float*>(bt + 2 * STAGE));
+        if (cur + 1 >= c.it1 || (cur + 1) / c.KB != b) gemm_flush<RT, RG, CTW, FE>(acc, a, c, b, q, reinterpret_cast<const float*>(bt + 2 * STAGE));
         buf ^= 1;
         gemm_store_b(bt + buf * STAGE, breg, c);
         __syncthreads();
@@ -221,15 +238,16 @@ __device__ __forceinline__ void gemm_half(f32x4 (&acc)[RT][CTW], const uint4 (&a
 // took 4-5 % longer on the wide projections and 20 % longer on the narrow ones at 16 passes.)
 // Weights: a ring of three register half-stages, requested two half-steps (one pair) ahead;
 // activations: one pair ahead through LDS.
-template <int RT, bool STREAM, int RG, bool SWI>
+template <int RT, bool STREAM, int RG, int FE>
 __global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int q, int xa) {
     static_assert(WPB == 8 && (RG == 4 || RG == 8), "row groups x splits of the pass's rows");
     constexpr int CTW = PM / 16 / (WPB / RG);  // column tiles (16 of the pass's rows) per wave
-    extern __shared__ __attribute__((aligned(16))) unsigned char bt[];  // [2][STAGE], then PM floats: the rows' RMSNorm scales (SWI)
+    extern __shared__ __attribute__((aligned(16))) unsigned char bt[];  // [2][STAGE], then PM floats: the rows' RMSNorm scales (fused tails)
     const int tid = threadIdx.x, lane = tid & 63;
     GemmCtx c;
     c.wr = (tid >> 6) % RG; c.wt = (tid >> 6) / RG; c.li = lane & 15; c.lq = lane >> 4;
     c.K = a.K; c.KB = a.K >> 7; c.n_tiles = a.rows >> 4;
+    constexpr bool SWI = FE == 1 + EPI_SWIGLU;
     static_assert(!SWI || RT == 2, "a gate and an up tile per wave");
     c.n_out_tiles = SWI ? a.N >> 4 : 0;
     const int nb = SWI ? (c.n_out_tiles + RG - 1) / RG : (c.n_tiles + RG * RT - 1) / (RG * RT);
@@ -263,37 +281,37 @@ __global__ __launch_bounds__(64 * WPB) void prefill_gemm_kernel(GemmArgs a, int 
     u32x4 breg[NBU];     // (a native vector type: the compiler keeps such an array in registers)
 
     gemm_load_b(breg, c, it0);
-    gemm_load_a<RT, STREAM, RG, SWI>(ah[0], c, 2 * it0);
-    gemm_load_a<RT, STREAM, RG, SWI>(ah[1], c, 2 * it0 + 1);
+    gemm_load_a<RT, STREAM, RG, FE>(ah[0], c, 2 * it0);
+    gemm_load_a<RT, STREAM, RG, FE>(ah[1], c, 2 * it0 + 1);
     gemm_store_b(bt, breg, c);
-    if (SWI) {  // 1 / rms of this pass's input rows, from the partial sums of squares their producer left
+    if (FE != 0) {  // 1 / rms of this pass's input rows, from the partial sums of squares their producer left
         const int m = tid >> 2, part = tid & 3;
         float t = 0.f;
-        if (m < c.Mp)
+        if (a.ssq_in && m < c.Mp)
             for (int i = part; i < a.ssq_nb; i += 4) t += a.ssq_in[(size_t)(c.pass * PM + m) * a.ssq_ld + i];
         t += __shfl_xor(t, 1, 64);
         t += __shfl_xor(t, 2, 64);
-        if (part == 0) reinterpret_cast<float*>(bt + 2 * STAGE)[m] = 1.0f / sqrtf(t / (float)a.K + a.eps);
+        if (part == 0) reinterpret_cast<float*>(bt + 2 * STAGE)[m] = a.ssq_in ? 1.0f / sqrtf(t / (float)a.K + a.eps) : 1.0f;
     }
     __syncthreads();
     int buf = 0;  // LDS stage that holds the current pair's activations
     int it = it0;
     // steady state: three pairs = six half-steps, every ring index a constant
     for (; it + 3 <= c.it1; it += 3) {
-        gemm_half<RT, STREAM, 0, RG, CTW, SWI>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it, q);
-        gemm_half<RT, STREAM, 1, RG, CTW, SWI>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 1, q);
-        gemm_half<RT, STREAM, 0, RG, CTW, SWI>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 2, q);
-        gemm_half<RT, STREAM, 1, RG, CTW, SWI>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it + 3, q);
-        gemm_half<RT, STREAM, 0, RG, CTW, SWI>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 4, q);
-        gemm_half<RT, STREAM, 1, RG, CTW, SWI>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 5, q);
+        gemm_half<RT, STREAM, 0, RG, CTW, FE>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it, q);
+        gemm_half<RT, STREAM, 1, RG, CTW, FE>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 1, q);
+        gemm_half<RT, STREAM, 0, RG, CTW, FE>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 2, q);
+        gemm_half<RT, STREAM, 1, RG, CTW, FE>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it + 3, q);
+        gemm_half<RT, STREAM, 0, RG, CTW, FE>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 4, q);
+        gemm_half<RT, STREAM, 1, RG, CTW, FE>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 5, q);
     }
     if (it < c.it1) {
-        gemm_half<RT, STREAM, 0, RG, CTW, SWI>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it, q);
-        gemm_half<RT, STREAM, 1, RG, CTW, SWI>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 1, q);
+        gemm_half<RT, STREAM, 0, RG, CTW, FE>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it, q);
+        gemm_half<RT, STREAM, 1, RG, CTW, FE>(acc, ah[1], ah[0], breg, bt, buf, a, c, 2 * it + 1, q);
     }
     if (it + 1 < c.it1) {
-        gemm_half<RT, STREAM, 0, RG, CTW, SWI>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 2, q);
-        gemm_half<RT, STREAM, 1, RG, CTW, SWI>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it + 3, q);
+        gemm_half<RT, STREAM, 0, RG, CTW, FE>(acc, ah[2], ah[1], breg, bt, buf, a, c, 2 * it + 2, q);
+        gemm_half<RT, STREAM, 1, RG, CTW, FE>(acc, ah[0], ah[2], breg, bt, buf, a, c, 2 * it + 3, q);
     }
 }
 
@@ -303,13 +321,18 @@ hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
         return hipErrorInvalidValue;
     const GemmPlan p = gemm_plan(a.rows, a.K, a.n_pass);
     if (a.S != p.smax || (long)p.nb * (a.K >> 7) > 0x3fffffffL) return hipErrorInvalidValue;
-    if (a.swiglu_fused && (a.rows != 2 * a.N || a.N % 16 || !a.ys || !a.ssq_in || a.ssq_nb < 1)) return hipErrorInvalidValue;
+    if (a.fused != 0 && a.fused != 1 + EPI_STORE && a.fused != 1 + EPI_SWIGLU) return hipErrorInvalidValue;
+    if (a.fused == 1 + EPI_SWIGLU && (a.rows != 2 * a.N || a.N % 16 || !a.ys)) return hipErrorInvalidValue;
+    if (a.fused == 1 + EPI_STORE && (a.rows != a.N || !a.y || a.ldy < a.N || a.ldy % 4)) return hipErrorInvalidValue;
+    if (a.fused && a.ssq_in && (a.ssq_nb < 1 || a.ssq_ld < a.ssq_nb)) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
-        const void* fns[4] = {reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false, 8, false>),
-                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true, 8, false>),
-                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false, 8, true>),
-                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true, 8, true>)};
+        const void* fns[6] = {reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false, 8, 0>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true, 8, 0>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false, 8, 1 + EPI_STORE>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true, 8, 1 + EPI_STORE>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, false, 8, 1 + EPI_SWIGLU>),
+                              reinterpret_cast<const void*>(&prefill_gemm_kernel<2, true, 8, 1 + EPI_SWIGLU>)};
         for (const void* fn : fns) {
             hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
             if (e != hipSuccess) return e;
@@ -323,12 +346,16 @@ hipError_t launch_prefill_gemm(const GemmArgs& a, hipStream_t st) {
     const int xb = 8 / xa;
     const int grid = 8 * ((a.n_pass + xb - 1) / xb) * ((p.grid + xa - 1) / xa);
     const bool stream = a.n_pass == 1;
-    if (a.swiglu_fused) {
-        if (stream) prefill_gemm_kernel<2, true, 8, true><<<grid, 64 * WPB, LDS_BYTES, st>>>(a, p.q, xa);
-        else prefill_gemm_kernel<2, false, 8, true><<<grid, 64 * WPB, LDS_BYTES, st>>>(a, p.q, xa);
+    const dim3 g3(grid), b3(64 * WPB);
+    if (a.fused == 1 + EPI_SWIGLU) {
+        if (stream) prefill_gemm_kernel<2, true, 8, 1 + EPI_SWIGLU><<<g3, b3, LDS_BYTES, st>>>(a, p.q, xa);
+        else prefill_gemm_kernel<2, false, 8, 1 + EPI_SWIGLU><<<g3, b3, LDS_BYTES, st>>>(a, p.q, xa);
+    } else if (a.fused == 1 + EPI_STORE) {
+        if (stream) prefill_gemm_kernel<2, true, 8, 1 + EPI_STORE><<<g3, b3, LDS_BYTES, st>>>(a, p.q, xa);
+        else prefill_gemm_kernel<2, false, 8, 1 + EPI_STORE><<<g3, b3, LDS_BYTES, st>>>(a, p.q, xa);
     } else {
-        if (stream) prefill_gemm_kernel<2, true, 8, false><<<grid, 64 * WPB, LDS_BYTES, st>>>(a, p.q, xa);
-        else prefill_gemm_kernel<2, false, 8, false><<<grid, 64 * WPB, LDS_BYTES, st>>>(a, p.q, xa);
+        if (stream) prefill_gemm_kernel<2, true, 8, 0><<<g3, b3, LDS_BYTES, st>>>(a, p.q, xa);
+        else prefill_gemm_kernel<2, false, 8, 0><<<g3, b3, LDS_BYTES, st>>>(a, p.q, xa);
     }
     return hipGetLastError();
 }
@@ -378,7 +405,7 @@ __global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a, Ge
     const float* p = a.part + ((size_t)(m / PM) * a.S * PM + m % PM) * a.rows;
     float sq = 0.f;
     if (n < a.N) {
-        if (EPI == EPI_SWIGLU && a.swiglu_fused) {
+        if (EPI == EPI_SWIGLU && a.fused) {
             // (row blocks are 128 outputs: gate and up tiles side by side; one partial = finished by the GEMM)
             const int sp = splits_of(mp, n);
             if (sp > 1) {
@@ -394,6 +421,8 @@ __global__ __launch_bounds__(256) void prefill_epilogue_kernel(GemmEpiArgs a, Ge
             const float4 v = make_float4(silu_mul(g.x * inv, u.x * inv), silu_mul(g.y * inv, u.y * inv),
                                          silu_mul(g.z * inv, u.z * inv), silu_mul(g.w * inv, u.w * inv));
             split_store4(a.ys, a.N, a.plane_rows, m, n, v);
+        } else if (EPI == EPI_STORE && a.fused && splits_of(mp, n) == 1) {
+            // (finished by the GEMM)
         } else {
             float4 v = sum_splits4(p + n, plane, splits_of(mp, n));
             v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
@@ -424,7 +453,8 @@ hipError_t launch_prefill_epilogue(const GemmEpiArgs& a, hipStream_t st) {
     dim3 grid((a.N + 255) / 256, (a.M + 3) / 4);
     const GemmPlan pl = gemm_plan(a.rows, a.K, a.n_pass);
     if (a.S != pl.smax) return hipErrorInvalidValue;
-    const GemmSplitMap mp{a.epi == EPI_SWIGLU && a.swiglu_fused ? BLOCK_ROWS / 2 : BLOCK_ROWS, a.K >> 7, pl.q};
+    if (a.fused && a.fused != 1 + a.epi) return hipErrorInvalidValue;
+    const GemmSplitMap mp{a.epi == EPI_SWIGLU && a.fused ? BLOCK_ROWS / 2 : BLOCK_ROWS, a.K >> 7, pl.q};
     switch (a.epi) {
         case EPI_STORE: prefill_epilogue_kernel<EPI_STORE><<<grid, 256, 0, st>>>(a, mp); break;
         case EPI_RESID: prefill_epilogue_kernel<EPI_RESID><<<grid, 256, 0, st>>>(a, mp); break;

@@ -405,9 +405,10 @@ int prefill_proj(sb_session* s, const void* Wp, int rows, int K, const uint16_t*
     g.part = wsp<float>(s, s->L.p_part); g.S = gemm_splits(rows, K, g.n_pass);
     e.part = g.part; e.S = g.S; e.rows = rows; e.M = R; e.n_pass = g.n_pass; e.plane_rows = s->L.p_rows;
     e.K = K; e.eps = s->m->cfg.rms_eps; e.ssq_ld = s->L.p_ssq_ld;
-    if (e.epi == EPI_SWIGLU) {  // the GEMM finishes the row blocks it owns whole
-        g.swiglu_fused = e.swiglu_fused = 1;
-        g.N = e.N; g.ssq_in = e.ssq_in; g.ssq_nb = e.ssq_nb; g.ssq_ld = e.ssq_ld; g.eps = e.eps; g.ys = e.ys;
+    if (e.epi == EPI_SWIGLU || e.epi == EPI_STORE) {  // the GEMM finishes the row blocks it owns whole
+        g.fused = e.fused = 1 + e.epi;
+        g.N = e.N; g.ssq_in = e.ssq_in; g.ssq_nb = e.ssq_nb; g.ssq_ld = e.ssq_ld; g.eps = e.eps;
+        g.ys = e.ys; g.y = e.y; g.ldy = e.ldy;
     }
     ProfScope ps(s, cls, (int64_t)rows * K * 2 + (int64_t)R * K * 4 + (int64_t)R * rows * 4, st);
     hipError_t err = launch_prefill_gemm(g, st);
