@@ -370,7 +370,8 @@ def test_computed_exits_that_fire_match_the_oracle(sb, name):
 
 
 @pytest.mark.parametrize("name,n_prompt", [("bf16-mfma-packed", 150), ("bf16-mfma-gqa", 128), ("bf16-mfma-gqa", 301),
-                                           ("bf16-mfma-packed", 129), ("bf16-many-heads", 700)])
+                                           ("bf16-mfma-packed", 129), ("bf16-many-heads", 700),
+                                           ("bf16-mfma-gqa", 2100)])   # (more than one super-pass of 2048 rows)
 def test_long_prompt_goes_through_128_row_passes(sb, name, n_prompt):
     """Prompts longer than one pass (full passes plus a ragged tail): first token, final logits
     and the cached K/V of prompt positions against the oracle; decoding continues from that
@@ -387,7 +388,8 @@ def test_long_prompt_goes_through_128_row_passes(sb, name, n_prompt):
         assert t_o == t_g
     assert gsn.committed_len() == n_prompt
     for layer in (0, shape.n_layers - 1):
-        for pos in sorted({0, 1, 15, 16, 63, 64, 127, 128 % n_prompt, n_prompt // 2, n_prompt - 1}):
+        for pos in sorted({0, 1, 15, 16, 63, 64, 127, 128 % n_prompt, 2047 % n_prompt, 2048 % n_prompt, n_prompt // 2,
+                           n_prompt - 1}):
             ko, vo = osn.kv_read(layer, pos)
             kg, vg = gsn.debug_kv(layer, pos)
             lim = 2.0 ** -7 * max(1.0, np.max(np.abs(ko)))
