@@ -106,7 +106,8 @@ typedef struct sb_weights {
  *             paper's rule (Sec. 3.2).  Otherwise bit l-1 set means layer l has
  *             its head evaluated; the other layers are passed without a test, so
  *             a token can only exit at a layer of the mask (a cheaper variant, not
- *             the paper's rule; forced_exit must then name layers of the mask). */
+ *             the paper's rule; forced_exit must then name layers of the mask; 32 bits, so a
+ *             nonzero mask needs d_max <= 32, else SB_EINVAL). */
 typedef struct sb_params {
     int32_t d_max, w_max;
     const float *T;

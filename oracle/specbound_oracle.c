@@ -459,6 +459,7 @@ static int check_params(const orc_session *s, const orc_params *p) {
     if (p->d_max > 0 && !p->T) return ORC_EINVAL;
     for (int32_t l = 0; l < p->d_max; ++l)
         if (!(p->T[l] > 0)) return ORC_EINVAL;
+    if (p->head_mask && p->d_max > 32) return ORC_EINVAL;   /* the mask has 32 bits */
     return ORC_OK;
 }
 

@@ -210,6 +210,7 @@ int check_params(const sb_session* s, const sb_params* p) {
     for (int l = 0; l < p->d_max; ++l)
         if (!(p->T[l] > 0.f)) return fail(SB_EINVAL, "T[%d] must be positive", l);
     if (p->n_forced < 0) return fail(SB_EINVAL, "n_forced < 0");
+    if (p->head_mask && p->d_max > 32) return fail(SB_EINVAL, "head_mask has 32 bits: d_max must be <= 32 with it");
     return SB_OK;
 }
 
