@@ -50,22 +50,68 @@ def gpu_params(d_max, w_max, threshold=0.5, forced_exit=None, forced_draft=None,
                      forced_exit=forced_exit, forced_draft=forced_draft, eos_id=eos_id)
 
 
-def teacher_forced_check(oracle_model, prompt, gpu_tokens, gap_tol=1e-2):
+def progress(msg):
+    """A progress line on stdout and, when the run has a gpurun_out/ folder to write to, in
+    gpurun_out/test_progress.log: long full-size tests are then not mistaken for hung ones."""
+    import os, time
+    print(msg, flush=True)
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    try:
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "test_progress.log"), "a") as f:
+            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+    except OSError:
+        pass
+
+
+def teacher_forced_check(oracle_model, prompt, gpu_tokens, gap_tol=1e-2, report=None, every=0):
     """Score the GPU's output with the oracle position by position.  A position
     passes if the GPU token is the oracle's arg max, or the oracle's logit gap
     between its arg max and the GPU token is below gap_tol (flagged near-tie).
-    Returns (n_flagged, n_scored); raises on a real mismatch."""
+    Returns (n_flagged, n_scored); raises on a real mismatch.  report (a dict) receives
+    the flagged gaps and the number of positions whose oracle top-2 gap is below gap_tol."""
     s = oracle_model.session()
     first = s.prefill(prompt)
     z = s.verify_logits(0)
     flagged = 0
+    gaps, close = [], 0
     toks = list(gpu_tokens)
     for i, t in enumerate(toks):
         am = int(np.argmax(z))
+        top2 = np.partition(z, -2)[-2:]
+        close += int(top2[1] - top2[0] < gap_tol)
         if t != am:
-            gap = z[am] - z[t]
+            gap = float(z[am] - z[t])
             assert gap < gap_tol, f"position {i}: gpu token {t}, oracle {am}, logit gap {gap}"
             flagged += 1
+            gaps.append(gap)
+        if every and i % every == 0:
+            progress(f"  oracle scored {i + 1}/{len(toks)} positions, {flagged} flagged")
         if i + 1 < len(toks):
             _, z = s.step(t)
+    if report is not None:
+        report.update(flagged=flagged, scored=len(toks), gaps=gaps, close_positions=close)
     return flagged, len(toks)
+
+
+class NearTies:
+    """Where a GPU-vs-oracle comparison of free-running rounds must end because the two sides
+    chose different tokens, the choice has to be a near-tie FOR THE ORACLE: its logit gap
+    between its own arg max and the GPU's token below `tol`.  Counts such endings."""
+
+    def __init__(self, tol=1e-2):
+        self.tol, self.flags = tol, []
+
+    def flag(self, where, z_oracle, tok_gpu):
+        gap = float(np.max(z_oracle) - z_oracle[tok_gpu])
+        assert gap < self.tol, f"{where}: gpu token {tok_gpu}, oracle {int(np.argmax(z_oracle))}, oracle logit gap {gap}"
+        self.flags.append((where, gap))
+        print(f"near-tie ({where}): oracle gap {gap:.3g}", flush=True)
+
+    def verify_rows(self, where, osn, vo, vg):
+        """Emitted tokens of a verification differ: the first differing row must be a near-tie."""
+        for i, (a, b) in enumerate(zip(vo["tokens"], vg["tokens"])):
+            if a != b:
+                self.flag(f"{where} row {i}", osn.verify_logits(i), b)
+                return
+        raise AssertionError(f"{where}: emitted counts differ with equal tokens: {vo} vs {vg}")

@@ -8,7 +8,7 @@ import pytest
 import oracle as orc
 import sb_inputs as si
 from helpers import (tiny_model, params, gpu_model, gpu_params, teacher_forced_check, all_accept_weights,
-                     linear_T)
+                     linear_T, NearTies)
 from oracle import Oracle
 
 pytestmark = pytest.mark.gpu
@@ -120,6 +120,7 @@ def test_step_by_step_parity_of_rounds(sb, name):
     assert t_o == t_g
     bf16 = shape.weight_dtype == si.configs.BF16
     htol = 2e-3 if bf16 else 2e-5
+    ties, rounds_done = NearTies(), 0
     for rnd in range(5):
         while True:
             ro, rg = osn.draft_step(po), gsn.draft_step(pg)
@@ -128,21 +129,23 @@ def test_step_by_step_parity_of_rounds(sb, name):
             last = rg["exit_layer"] if rg["exit_layer"] else 3
             zo, zg = osn.head_logits(), gsn.debug_logits(last)
             assert np.max(np.abs(zg - zo)) <= 2e-2 * np.max(np.abs(zo))
-            srt = np.sort(zo)
-            if rg["exit_layer"] and srt[-1] - srt[-2] >= 1e-2:
-                assert ro["token"] == rg["token"]
-            if ro["token"] != rg["token"]:
-                pytest.skip("near-tie draft: the two rounds diverge from here")
+            if ro["token"] != rg["token"]:      # only a near-tie of the oracle's may end the comparison
+                ties.flag(f"round {rnd} draft", zo, rg["token"])
+                break
             slot = osn.open_slots() - 1
             ho, hg = osn.slot_hidden(slot), gsn.debug_hidden(slot)
             assert np.max(np.abs(hg - ho)) <= htol * max(1.0, np.max(np.abs(ho)))
             if ro["status"] != orc.EXITED:
                 break
+        if ties.flags:
+            break
         c0 = osn.committed_len()
         vo, vg = osn.verify(po), gsn.verify(pg)
+        if vo["tokens"][: vo["n_emit"]] != vg["tokens"][: vg["n_emit"]]:
+            ties.verify_rows(f"round {rnd} verify", osn, vo, vg)
+            break
         for k in ("n_rows", "n_drafts", "n_matched", "n_emit", "align_layer"):
             assert vo[k] == vg[k], (rnd, k, vo, vg)
-        assert vo["tokens"][: vo["n_emit"]] == vg["tokens"][: vg["n_emit"]]
         for r in range(vo["n_rows"]):
             zo, zg = osn.verify_logits(r), gsn.debug_logits(0, r)
             assert np.max(np.abs(zg - zo)) <= 2e-2 * np.max(np.abs(zo))
@@ -153,6 +156,10 @@ def test_step_by_step_parity_of_rounds(sb, name):
             kg, vg_ = gsn.debug_kv(layer, c0)
             lim = (2.0 ** -7 if shape.kv_dtype == si.configs.BF16 else 1e-4) * max(1.0, np.max(np.abs(ko)))
             assert np.max(np.abs(kg - ko)) <= lim and np.max(np.abs(vg_ - vo_)) <= lim
+        rounds_done += 1
+    # the seeded inputs of this test run all five rounds without a near-tie; should a change of
+    # arithmetic move one in, at least three whole rounds must have been compared before it
+    assert rounds_done >= 3 and len(ties.flags) <= 1, (rounds_done, ties.flags)
 
 
 def test_worked_examples_round_structure(sb, golden):
@@ -334,33 +341,33 @@ def test_computed_exits_that_fire_match_the_oracle(sb, name):
     osn, gsn = om.session(), gm.session()
     assert osn.prefill(prompt) == gsn.prefill(prompt)
     exits, statuses, steps = set(), set(), 0
-    diverged = False
+    ties, near_threshold = NearTies(), 0
     for rnd in range(14):
         while True:
             ro, rg = osn.draft_step(po), gsn.draft_step(pg)
-            steps += 1
-            near_thr = abs(ro["confidence"] - tau) <= 1e-3
             if (ro["status"], ro["exit_layer"]) != (rg["status"], rg["exit_layer"]):
-                assert near_thr, (rnd, ro, rg)
-                diverged = True
+                # only a confidence within the tolerance of the threshold may decide differently
+                assert abs(ro["confidence"] - tau) <= 1e-3 and abs(ro["confidence"] - rg["confidence"]) <= 1e-3, (rnd, ro, rg)
+                near_threshold += 1
                 break
             assert abs(ro["confidence"] - rg["confidence"]) <= 1e-3
             if ro["token"] != rg["token"]:
-                srt = np.sort(osn.head_logits())
-                assert srt[-1] - srt[-2] < 1e-2, (rnd, ro, rg)
-                diverged = True
+                ties.flag(f"round {rnd} draft", osn.head_logits(), rg["token"])
                 break
+            steps += 1
             exits.add(ro["exit_layer"]); statuses.add(ro["status"])
             if ro["status"] != orc.EXITED:
                 break
-        if diverged:
+        if ties.flags or near_threshold:
             break
         vo, vg = osn.verify(po), gsn.verify(pg)
         if vo["tokens"][: vo["n_emit"]] != vg["tokens"][: vg["n_emit"]]:
-            break                                   # near-tie in a final head: sequences part ways
+            ties.verify_rows(f"round {rnd} verify", osn, vo, vg)   # asserts the oracle's gap < 1e-2
+            break
         for k in ("n_rows", "n_drafts", "n_matched", "n_emit", "align_layer"):
             assert vo[k] == vg[k], (rnd, k, vo, vg)
-    assert steps >= 12
+    # at most one flagged ending, and only after at least 12 draft steps agreed in full
+    assert steps >= 12 and len(ties.flags) + near_threshold <= 1, (steps, ties.flags, near_threshold)
     assert len(exits - {0}) >= 2 and 0 in exits, exits          # exits at several layers and depth bounds
     # free-running generation with the same parameters stays greedy
     ar, _ = gm.session().generate(prompt, 40, gpu_params(0, 1))
@@ -394,14 +401,14 @@ def test_long_prompt_goes_through_128_row_passes(sb, name, n_prompt):
             kg, vg = gsn.debug_kv(layer, pos)
             lim = 2.0 ** -7 * max(1.0, np.max(np.abs(ko)))
             assert np.max(np.abs(kg - ko)) <= lim and np.max(np.abs(vg - vo)) <= lim, (layer, pos)
-    if t_o != t_g:
-        return
+    # (a first token that differs is scored below like any other position: near-ties only)
     # speculative decoding from the prefilled cache equals the library's own greedy decoding,
     # and the greedy continuation follows the oracle's up to near-ties
     ar, _ = gm.session().generate(prompt, 24, gpu_params(0, 1))
     spec, st = gm.session().generate(prompt, 24, gpu_params(2, 4, 0.5, forced_exit=si.forced_exit_schedule(9, 200, 1, 2)))
     assert spec.tolist() == ar.tolist()
-    teacher_forced_check(om, prompt, ar.tolist())
+    flagged, _ = teacher_forced_check(om, prompt, ar.tolist())
+    assert flagged <= 2, flagged
     pst = gm.session()
     pst.prefill(prompt)
     # the passes of a layer share one sweep over its weights (up to 16 passes of 128 rows per launch)
@@ -425,26 +432,25 @@ def test_easy_token_fixture_accepts_computed_drafts_like_the_oracle(sb, tau):
     osn, gsn = om.session(), gm.session()
     assert osn.prefill(prompt) == gsn.prefill(prompt)
     accept_lengths, emitted_o, emitted_g = set(), [], []
-    diverged = False
+    ties, near_threshold = NearTies(), 0
     for rnd in range(16):
         while True:
             ro, rg = osn.draft_step(po), gsn.draft_step(pg)
             if (ro["status"], ro["exit_layer"]) != (rg["status"], rg["exit_layer"]):
-                assert abs(ro["confidence"] - tau) <= 1e-3, (rnd, ro, rg)
-                diverged = True
+                assert abs(ro["confidence"] - tau) <= 1e-3 and abs(ro["confidence"] - rg["confidence"]) <= 1e-3, (rnd, ro, rg)
+                near_threshold += 1
                 break
             assert abs(ro["confidence"] - rg["confidence"]) <= 1e-3
             if ro["token"] != rg["token"]:
-                srt = np.sort(osn.head_logits())
-                assert srt[-1] - srt[-2] < 1e-2, (rnd, ro, rg)
-                diverged = True
+                ties.flag(f"round {rnd} draft", osn.head_logits(), rg["token"])
                 break
             if ro["status"] != orc.EXITED:
                 break
-        if diverged:
+        if ties.flags or near_threshold:
             break
         vo, vg = osn.verify(po), gsn.verify(pg)
         if vo["tokens"][: vo["n_emit"]] != vg["tokens"][: vg["n_emit"]]:
+            ties.verify_rows(f"round {rnd} verify", osn, vo, vg)
             break
         for k in ("n_rows", "n_drafts", "n_matched", "n_emit", "align_layer"):
             assert vo[k] == vg[k], (rnd, k, vo, vg)
@@ -452,6 +458,7 @@ def test_easy_token_fixture_accepts_computed_drafts_like_the_oracle(sb, tau):
         emitted_o += vo["tokens"][: vo["n_emit"]]
         emitted_g += vg["tokens"][: vg["n_emit"]]
     assert emitted_o == emitted_g and len(emitted_g) >= 12
+    assert len(ties.flags) + near_threshold <= 1, (ties.flags, near_threshold)
     assert len(accept_lengths) >= 3 and max(accept_lengths) >= 3, accept_lengths
     ar, _ = gm.session().generate(prompt, 64, gpu_params(0, 1))
     out, st = gm.session().generate(prompt, 64, pg)
@@ -473,24 +480,31 @@ def test_head_subset_variant_matches_the_oracle(sb, mask):
     pg = sb.Params(3, 4, T, 0.5, forced_exit=fe, head_mask=mask)
     osn, gsn = om.session(), gm.session()
     assert osn.prefill(prompt) == gsn.prefill(prompt)
+    ties, rounds_done = NearTies(), 0
     for rnd in range(4):
         while True:
             ro, rg = osn.draft_step(po), gsn.draft_step(pg)
             assert (ro["status"], ro["exit_layer"]) == (rg["status"], rg["exit_layer"])
             assert abs(ro["confidence"] - rg["confidence"]) <= 1e-3
             if ro["token"] != rg["token"]:
-                srt = np.sort(osn.head_logits())
-                assert srt[-1] - srt[-2] < 1e-2
-                return
+                ties.flag(f"round {rnd} draft", osn.head_logits(), rg["token"])
+                break
             if ro["status"] != orc.EXITED:
                 break
+        if ties.flags:
+            break
         vo, vg = osn.verify(po), gsn.verify(pg)
         if vo["tokens"][: vo["n_emit"]] != vg["tokens"][: vg["n_emit"]]:
-            return
+            ties.verify_rows(f"round {rnd} verify", osn, vo, vg)
+            break
         for k in ("n_rows", "n_drafts", "n_matched", "n_emit", "align_layer"):
             assert vo[k] == vg[k], (rnd, k, vo, vg)
-    so, sg = osn.stats(), gsn.stats()
-    assert so["head_evals"] == sg["head_evals"] and so["exit_hist"][:4] == sg["exit_hist"][:4]
+        rounds_done += 1
+    # (the part below does not depend on the oracle and always runs)
+    assert rounds_done >= 2 and len(ties.flags) <= 1, (rounds_done, ties.flags)
+    if not ties.flags:
+        so, sg = osn.stats(), gsn.stats()
+        assert so["head_evals"] == sg["head_evals"] and so["exit_hist"][:4] == sg["exit_hist"][:4]
     with pytest.raises(sb.SbError):
         bad = [l for l in (1, 2, 3) if l not in allowed][0]
         gm.session().generate(prompt, 4, sb.Params(3, 4, T, 0.5, forced_exit=[bad], head_mask=mask))

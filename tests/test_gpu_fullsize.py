@@ -2,17 +2,17 @@
 configuration bench.py times (MFMA projections, forced exit schedule with draft
 injection, second stream for the exit heads).
 
-What the oracle can afford at these sizes is a short sequence: it scores the
-library's output position by position (teacher forcing) on a 12-token prompt.  The
-properties that hold at any size are checked at the real lengths: speculative
-output == the library's own greedy output, bit for bit, and the accept schedule is
-realised exactly."""
+The oracle scores the library's output position by position (teacher forcing) on a
+sample it can afford: a prompt of several 128-row passes plus 128 generated positions
+per workload.  The properties that hold at any size are checked at the workloads' own
+prompt lengths: speculative output == the library's own greedy output, bit for bit, and
+the accept schedule is realised exactly."""
 import numpy as np
 import pytest
 
 import oracle as orc
 import sb_inputs as si
-from helpers import teacher_forced_check
+from helpers import teacher_forced_check, progress, NearTies
 from oracle import Oracle
 
 pytestmark = pytest.mark.gpu
@@ -33,18 +33,38 @@ def _spec_params(sb, wl, greedy, n_rounds_hint):
     return sb.Params(wl.d_max, wl.w_max, wl.temperatures(), wl.threshold, forced_exit=fe, forced_draft=fd), accepts
 
 
-def _run_config(sb, name, prompt_len, gen_len, n_oracle_prompt=12, n_oracle_gen=10):
+# Oracle scoring at full size: prompt and generated positions the oracle teacher-forces per
+# workload (the prompts span several 128-row passes plus a ragged tail; C3's spans nine).
+ORACLE_SAMPLE = {"C2": (300, 128), "C3": (1040, 128), "C4": (272, 128), "C5": (272, 128)}
+# positions also scored by the float build of the oracle (same weights; C2 and C3 share theirs)
+ORACLE32_POSITIONS = {"C2": 128}
+GAP_RULE = 1e-2     # an arg-max difference is a flagged near-tie below this oracle gap ...
+GAP_HARD = 2e-2     # ... tolerated (counted as "wide") up to this one, a failure above
+
+
+def _score(om, sp, toks, label):
+    rep = {}
+    teacher_forced_check(om, sp, toks, gap_tol=GAP_HARD, report=rep, every=64)
+    wide = [g for g in rep["gaps"] if g >= GAP_RULE]
+    progress(f"[fullsize] {label}: scored {rep['scored']} positions, {rep['flagged']} flagged "
+             f"(largest gap {max(rep['gaps'], default=0.0):.4g}), {len(wide)} of them at or above {GAP_RULE}, "
+             f"{rep['close_positions']} positions with an oracle top-2 gap below {GAP_HARD}")
+    return rep, wide
+
+
+def _run_config(sb, name, prompt_len, gen_len):
     import torch
     wl = si.CONFIGS[name]
     shape = wl.shape
-    print(f"[fullsize] {wl.name}: generating weights", flush=True)
+    n_oracle_prompt, n_oracle_gen = ORACLE_SAMPLE[name]
+    progress(f"[fullsize] {wl.name}: generating weights")
     w = si.make_weights(shape, wl.weight_seed)
     max_seq = (prompt_len + gen_len + 4 * wl.w_max + 31) // 16 * 16
     gm = sb.Model(shape, w, max_seq)
     prompt = si.make_prompt(shape.vocab, prompt_len, wl.prompt_seed)
     s = gm.session()
     first = s.prefill(prompt)
-    print(f"[fullsize] {wl.name}: prefill of {prompt_len} done", flush=True)
+    progress(f"[fullsize] {wl.name}: prefill of {prompt_len} done")
     n_ar = gen_len + 2 * wl.w_max
     G, st_ar = s.decode(n_ar, sb.Params(0, 1, [], wl.threshold))
     greedy = [first] + G.tolist()
@@ -64,7 +84,8 @@ def _run_config(sb, name, prompt_len, gen_len, n_oracle_prompt=12, n_oracle_gen=
     out2, _ = s.decode(gen_len, p_spec)
     assert out2.tolist() == out.tolist()
     del s
-    # (4) the oracle scores a short sequence produced by the same path
+    # (4) the oracle scores a sequence produced by the same path: a prompt of several 128-row
+    # passes, then speculative decoding with the workload's schedule
     sp = prompt[:n_oracle_prompt]
     s2 = gm.session()
     f2 = s2.prefill(sp)
@@ -72,49 +93,59 @@ def _run_config(sb, name, prompt_len, gen_len, n_oracle_prompt=12, n_oracle_gen=
     g2 = [f2] + G2.tolist()
     p2, _ = _spec_params(sb, wl, g2, 4 * n_oracle_gen)
     s2.rewind(n_oracle_prompt, f2)
-    o2, _ = s2.decode(n_oracle_gen, p2)
+    o2, st2 = s2.decode(n_oracle_gen, p2)
     assert o2.tolist() == g2[1:n_oracle_gen + 1]
-    print(f"[fullsize] {wl.name}: oracle scoring {n_oracle_prompt}+{n_oracle_gen} positions", flush=True)
-    om = Oracle(shape, w, 64)
-    # At these shapes fp32 arithmetic itself sits 3e-3 rms (up to 1.6e-2) from the double oracle's
-    # logits after 32 random-init layers, whichever projection kernel runs (the all-fp32 vector
-    # path included): an oracle gap below 2e-2 can flip the arg max and is flagged, not failed.
-    flagged, n = teacher_forced_check(om, sp, [f2] + o2.tolist(), gap_tol=2e-2)
-    assert flagged <= 1, flagged
+    assert st2["drafts"] == st2["rounds"] * wl.w_max
+    oseq = (n_oracle_prompt + n_oracle_gen + 31) // 16 * 16
+    progress(f"[fullsize] {wl.name}: oracle scoring {n_oracle_prompt}+{n_oracle_gen} positions")
+    om = Oracle(shape, w, oseq)
+    # Rule: the library's token is the oracle's arg max, or the oracle's gap between the two is
+    # below 1e-2 (flagged).  After 32-40 random-init layers fp32 arithmetic itself sits up to
+    # 1.6e-2 from the double oracle's logits (the all-fp32 vector path included), so a gap in
+    # [1e-2, 2e-2) is counted separately and at most one per sequence is tolerated; the counts
+    # and the largest gap are printed.
+    rep, wide = _score(om, sp, [f2] + o2.tolist(), f"{wl.name} vs double oracle")
+    assert len(wide) <= 1 and rep["flagged"] <= max(2, rep["close_positions"]), rep
+    if name in ORACLE32_POSITIONS:
+        n32 = ORACLE32_POSITIONS[name]
+        om32 = Oracle(shape, w, oseq, bits=32)
+        rep32, wide32 = _score(om32, sp, ([f2] + o2.tolist())[:n32], f"{wl.name} vs float oracle")
+        assert len(wide32) <= 1, rep32
+        del om32
     # first exit-head evaluation of a draft step against the oracle: logits, arg max, confidence
-    s2.rewind(n_oracle_prompt, f2)
-    s2.debug_enable(True)
     osn = om.session()
-    osn.prefill(sp)
+    osn.prefill(sp[:12])
+    s3 = gm.session()
+    s3.debug_enable(True)
+    s3.prefill(sp[:12])
     po = orc.OrcParams(wl.d_max, wl.w_max, wl.temperatures(), wl.threshold, forced_exit=[2, 0])
     pg = sb.Params(wl.d_max, wl.w_max, wl.temperatures(), wl.threshold, forced_exit=[2, 0])
-    ro, rg = osn.draft_step(po), s2.draft_step(pg)
+    ro, rg = osn.draft_step(po), s3.draft_step(pg)
     assert (ro["status"], ro["exit_layer"]) == (rg["status"], rg["exit_layer"]) == (sb.EXITED, 2)
-    zo, zg = osn.head_logits(), s2.debug_logits(2)
+    zo, zg = osn.head_logits(), s3.debug_logits(2)
     assert np.max(np.abs(zg - zo)) <= 2e-2 * np.max(np.abs(zo))
     assert abs(ro["confidence"] - rg["confidence"]) <= 1e-3
-    srt = np.sort(zo)
-    if srt[-1] - srt[-2] >= 1e-2:
-        assert ro["token"] == rg["token"]
+    if ro["token"] != rg["token"]:
+        NearTies(GAP_RULE).flag("exit head of a draft step", zo, rg["token"])
     del osn, om
     return st_ar, st
 
 
 def test_c2_7b_full_shape(sb):
-    _run_config(sb, "C2", prompt_len=512, gen_len=192)
+    _run_config(sb, "C2", prompt_len=512, gen_len=512)
 
 
 def test_c3_7b_long_context(sb):
     # 4096-token prompt in the paged cache, w_max = 8: verify attention over > 4100 keys
-    _run_config(sb, "C3", prompt_len=4096, gen_len=96)
+    _run_config(sb, "C3", prompt_len=4096, gen_len=256)
 
 
 def test_c4_13b_full_shape(sb):
-    _run_config(sb, "C4", prompt_len=256, gen_len=96)
+    _run_config(sb, "C4", prompt_len=1024, gen_len=1024)
 
 
 def test_c5_8b_gqa_large_vocab(sb):
-    _run_config(sb, "C5", prompt_len=256, gen_len=96)
+    _run_config(sb, "C5", prompt_len=2048, gen_len=1024)
 
 
 def test_long_context_attention_kernel_against_oracle(sb):
