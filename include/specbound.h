@@ -274,6 +274,20 @@ int32_t sb_op_head(const void *W, int32_t w_dtype, int32_t N, int32_t K, const f
                    void *scratch, void *stream);
 size_t sb_op_head_scratch_bytes(int32_t M, int32_t N, int32_t K);
 
+/* sb_op_head for callers that cannot allocate device memory or carry a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels
+ * and the same results as sb_op_head with logits == NULL, with the scratch area in a static
+ * device array of the library (1.3 MB, held by every GPU the library runs on until the
+ * process ends) instead of a caller's buffer.  The call allocates nothing.  Limits:
+ * N <= SB_STATIC_MAX_N and K <= SB_STATIC_MAX_K, else SB_ECAPACITY; otherwise arguments and
+ * errors as sb_op_head.  All calls on one GPU share the array (its contents are whatever the
+ * last call left; nothing in it needs clearing), so calls that overlap on one GPU -- on
+ * different streams or from different threads -- race: serialise them. */
+#define SB_STATIC_MAX_N 131072
+#define SB_STATIC_MAX_K 8192
+int32_t sb_op_head_static(const void *W, int32_t w_dtype, int32_t N, int32_t K, const float *x, int32_t M,
+                          float T, int32_t kernel, int32_t *argmax_out, float *conf_out, void *stream);
+
 /* Plain device-to-device copy kernel (128-bit loads and stores), nbytes % 16 == 0,
  * both pointers 16-byte aligned.  A bandwidth yardstick of known traffic
  * (nbytes read + nbytes written) for calibrating profiler counters. */

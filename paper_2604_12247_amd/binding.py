@@ -80,7 +80,7 @@ SYMBOLS = ["sb_last_error", "sb_temperature_schedule", "sb_query_sizes", "sb_loa
            "sb_debug_kv", "sb_op_rmsnorm", "sb_op_gemv", "sb_op_gemv_scratch_bytes", "sb_op_head",
            "sb_op_head_scratch_bytes", "sb_rope_table_host", "sb_op_attention",
            "sb_op_attention_scratch_bytes", "sb_op_prompt_attention", "sb_decode", "sb_rewind", "sb_profile_begin", "sb_profile_end", "sb_op_copy",
-           "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes"]
+           "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes", "sb_op_head_static"]
 
 KERNEL_CLASSES = ["rmsnorm", "qkv", "attention", "wo", "gate_up", "down", "exit_head",
                   "final_head"]
@@ -127,6 +127,7 @@ def lib() -> C.CDLL:
         L.sb_op_gemv_scratch_bytes.argtypes = [i32, i32]
         L.sb_op_gemv_scratch_bytes.restype = sz
         L.sb_op_head.argtypes = [vp, i32, i32, i32, vp, i32, f32, i32, vp, vp, vp, vp, vp]
+        L.sb_op_head_static.argtypes = [vp, i32, i32, i32, vp, i32, f32, i32, vp, vp, vp]
         L.sb_op_head_scratch_bytes.argtypes = [i32, i32, i32]
         L.sb_op_head_scratch_bytes.restype = sz
         L.sb_op_repack.argtypes = [vp, i32, i32, vp, vp]
@@ -443,6 +444,15 @@ def op_head(W, x, T: float, kernel: int = PROJ_VALU, want_logits: bool = False):
                            cf.data_ptr(), logits.data_ptr() if want_logits else None, scratch.data_ptr(),
                            _stream_ptr(torch, x.device)))
     return am, cf, logits
+
+
+def op_head_static(W, x, T: float, kernel: int, am, cf):
+    """op_head without a scratch buffer (the library's static device array): writes into the
+    caller's am [M] int32 and cf [M] float32 tensors; allocates nothing."""
+    import torch
+    N, K = W.shape
+    check(lib().sb_op_head_static(W.data_ptr(), _wdtype(W), N, K, x.data_ptr(), x.shape[0], T, kernel,
+                                  am.data_ptr(), cf.data_ptr(), _stream_ptr(torch, x.device)))
 
 
 def rope_table(head_dim: int, base: float, n_pos: int):

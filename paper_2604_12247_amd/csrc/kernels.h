@@ -181,6 +181,11 @@ hipError_t launch_prefill_embed(const void* E, int32_t w_dtype, int32_t vocab, i
 // x [M][K] float -> bf16 planes [2][plane_rows][K]
 hipError_t launch_prefill_split(const float* x, uint16_t* xs, int32_t plane_rows, int32_t M, int32_t K, hipStream_t st);
 
+// Device memory that belongs to the library itself (a file-scope device array, one copy per
+// GPU): *out receives its address on the current device.  No allocation takes place.
+#define SB_STATIC_SCRATCH_BYTES (256 + SB_MAX_W * (SB_STATIC_MAX_N / 16) * 16 + 16 * SB_STATIC_MAX_K * 2)
+hipError_t static_scratch(void** out);
+
 hipError_t launch_copy(void* dst, const void* src, size_t nbytes, hipStream_t st);
 hipError_t launch_read(const void* src, size_t nbytes, float* sink, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t st);

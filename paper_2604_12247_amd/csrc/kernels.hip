@@ -10,6 +10,7 @@
 #include "device_utils.h"
 
 #include <math.h>
+#include <mutex>
 
 namespace sb {
 
@@ -684,6 +685,39 @@ hipError_t launch_gemv_mfma(const GemvArgs& a, hipStream_t st) {
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- head evaluation without a workspace
+// For callers that cannot allocate device memory (code under graph capture, tight serving
+// loops): the head partials and the split-bf16 operand of a single head evaluation live in a
+// file-scope device array instead of a caller's scratch buffer.  Each GPU holds its own copy
+// of the array at its own address, looked up once per device; every call on a GPU shares it,
+// so calls that overlap on one GPU race.  Nothing in it has to start at zero: every element a
+// launch reads was written by that launch sequence (partials of all blocks of rows < M, the
+// operand rows of rows < M).
+static __device__ __align__(256) unsigned char scratch[SB_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, once looked up
+std::mutex g_scratch_mu;
+}  // namespace
+
+hipError_t static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the array's address on the current device
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
 }
 
 // ---------------------------------------------------------------- RoPE + KV append + attention

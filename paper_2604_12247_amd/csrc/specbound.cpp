@@ -1236,6 +1236,36 @@ int32_t sb_op_head(const void* W, int32_t w_dtype, int32_t N, int32_t K, const f
     return SB_OK;
 }
 
+int32_t sb_op_head_static(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, int32_t M, float T,
+                          int32_t kernel, int32_t* argmax_out, float* conf_out, void* stream) {
+    int rc = op_check(W, w_dtype, N, K, x, M, kernel);
+    if (rc) return rc;
+    if (!argmax_out || !conf_out) return fail(SB_EINVAL, "op_head_static: NULL output");
+    if (!(T > 0.f)) return fail(SB_EINVAL, "op_head_static: T must be positive");
+    if (N > SB_STATIC_MAX_N || K > SB_STATIC_MAX_K)
+        return fail(SB_ECAPACITY, "op_head_static: N = %d, K = %d exceed the static scratch area (N <= %d, K <= %d)", N, K,
+                    SB_STATIC_MAX_N, SB_STATIC_MAX_K);
+    static_assert(SB_STATIC_MAX_N % 16 == 0, "partials are sized per 16 output rows");
+    void* base = nullptr;
+    hipError_t e = static_scratch(&base);   // address of the library's own device array on this GPU
+    if (e != hipSuccess) return fail(SB_EDEVICE, "op_head_static: static scratch area: %s", hipGetErrorString(e));
+    char* sc = (char*)base;
+    const int nb = head_blocks_valu(N);
+    GemvArgs g{};
+    g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.M = M; g.epi = EPI_HEAD;
+    g.head.T = T; g.head.partials = (float*)(sc + 256);
+    g.head.logits = nullptr; g.head.argmax_out = argmax_out; g.head.conf_out = conf_out; g.head.post = POST_NONE;
+    g.packed = kernel == SB_PROJ_MFMA_PACKED;
+    if (kernel != SB_PROJ_VALU) {
+        g.xs = (uint16_t*)(sc + 256 + align_up((size_t)SB_MAX_W * nb * 16, 256));
+        HIP_TRY(launch_split(x, const_cast<uint16_t*>(g.xs), M, K, (hipStream_t)stream));
+        HIP_TRY(launch_gemv_mfma(g, (hipStream_t)stream));
+    } else {
+        HIP_TRY(launch_gemv_valu(g, (hipStream_t)stream));
+    }
+    return SB_OK;
+}
+
 int32_t sb_op_copy(void* dst, const void* src, size_t nbytes, void* stream) {
     if (!dst || !src || (nbytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
         return fail(SB_EINVAL, "op_copy: NULL / misaligned operand");
