@@ -146,6 +146,15 @@ typedef struct sb_stats {
     int64_t weight_bytes; /* algorithmic bytes of weights swept (layers + heads) */
     int64_t kv_bytes;     /* algorithmic bytes of K/V read by attention */
     double prefill_ms, decode_ms; /* wall time of the last sb_generate */
+    /* Time account of the decode phase, summed over its rounds, in ms.
+     * host_*: wall time of the calling thread -- enqueueing the draft steps, enqueueing
+     * alignment + verification, and blocked until the round record has come back.  When
+     * host_wait_ms is near zero the host, not the GPU, paces the rounds.
+     * gpu_*: time on the model's stream between HIP events at the phase boundaries (first
+     * draft kernel .. last exit head joined | alignment | remaining layers + final head |
+     * copy of the round record); filled only while sb_phase_timing is on. */
+    double host_draft_ms, host_verify_ms, host_wait_ms;
+    double gpu_draft_ms, gpu_align_ms, gpu_verify_ms, gpu_readback_ms;
 } sb_stats;
 
 typedef struct sb_sizes { size_t kv_pool_bytes, workspace_bytes; } sb_sizes;
@@ -215,6 +224,11 @@ int32_t sb_decode(sb_session *s, int32_t max_new, const sb_params *p, int32_t *o
  * counter (index into forced_exit / forced_draft) and clear the statistics.
  * Lets a caller decode again from the end of a prefill. */
 int32_t sb_rewind(sb_session *s, int32_t n_keep, int32_t pending_token, int64_t draft_counter);
+
+/* on != 0: every round records five events on the model's stream (phase boundaries) and adds
+ * the times between them to the gpu_*_ms fields of the statistics.  SB_ENOMEM if the events
+ * cannot be created. */
+int32_t sb_phase_timing(sb_session *s, int32_t on);
 
 int32_t sb_get_stats(const sb_session *s, sb_stats *out);
 int32_t sb_committed_len(const sb_session *s);

@@ -66,7 +66,9 @@ class sb_stats(C.Structure):
                [("accept_hist", C.c_int64 * (SB_MAX_W + 1)),
                 ("exit_hist", C.c_int64 * (SB_MAX_EXIT_LAYERS + 1)),
                 ("weight_bytes", C.c_int64), ("kv_bytes", C.c_int64),
-                ("prefill_ms", C.c_double), ("decode_ms", C.c_double)]
+                ("prefill_ms", C.c_double), ("decode_ms", C.c_double)] + \
+               [(n, C.c_double) for n in ("host_draft_ms", "host_verify_ms", "host_wait_ms", "gpu_draft_ms",
+                                          "gpu_align_ms", "gpu_verify_ms", "gpu_readback_ms")]
 
 
 class sb_sizes(C.Structure):
@@ -80,7 +82,7 @@ SYMBOLS = ["sb_last_error", "sb_temperature_schedule", "sb_query_sizes", "sb_loa
            "sb_debug_kv", "sb_op_rmsnorm", "sb_op_gemv", "sb_op_gemv_scratch_bytes", "sb_op_head",
            "sb_op_head_scratch_bytes", "sb_rope_table_host", "sb_op_attention",
            "sb_op_attention_scratch_bytes", "sb_op_prompt_attention", "sb_decode", "sb_rewind", "sb_profile_begin", "sb_profile_end", "sb_op_copy",
-           "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes", "sb_op_head_static"]
+           "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes", "sb_op_head_static", "sb_phase_timing"]
 
 KERNEL_CLASSES = ["rmsnorm", "qkv", "attention", "wo", "gate_up", "down", "exit_head",
                   "final_head"]
@@ -117,6 +119,7 @@ def lib() -> C.CDLL:
         L.sb_profile_begin.argtypes = [vp, C.c_uint32, i32, i32]
         L.sb_profile_end.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_double)]
         L.sb_get_stats.argtypes = [vp, C.POINTER(sb_stats)]
+        L.sb_phase_timing.argtypes = [vp, i32]
         L.sb_committed_len.argtypes = [vp]
         L.sb_debug_enable.argtypes = [vp, i32]
         L.sb_debug_logits.argtypes = [vp, i32, i32, vp, i32]
@@ -342,6 +345,9 @@ class Session:
         self.empty_pair_ms = empty.value
         return {k: dict(launches=int(launches[i]), total_ms=float(ms[i]), bytes=int(nbytes[i]))
                 for i, k in enumerate(KERNEL_CLASSES) if launches[i]}
+
+    def phase_timing(self, on: bool = True):
+        check(lib().sb_phase_timing(self.h, int(on)))
 
     def stats(self) -> dict:
         st = sb_stats()

@@ -27,6 +27,9 @@ struct DevRound {
 
 struct RowToks { int32_t tok[SB_MAX_W]; };  // >= 0: host-known id; -1: read slot_tok on the device
 
+// RMSNorm outputs produced together with an embedding row (first layer's input).
+struct EmbedNorm { const float* gain; uint16_t* nx; float* ssq_out; int32_t ssq_ld; };
+
 enum Epilogue { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
 enum HeadPost { POST_NONE = 0, POST_EXIT = 1, POST_ACCEPT = 2 };
 
@@ -46,6 +49,13 @@ struct HeadArgs {
     int32_t forced_draft;  // POST_EXIT: >= 0 overrides the drafted id
     float threshold;       // POST_EXIT
     int32_t n_drafts;      // POST_ACCEPT
+    // POST_EXIT, optional (embed_E != nullptr): when the row exits, the merge also embeds the
+    // drafted token as the row after it -- embed_H: that row of the hidden cache, embed_en:
+    // what the first layer's projection reads for it (as the embedding kernel leaves it)
+    const void* embed_E;
+    int32_t embed_dtype, embed_vocab, embed_d;
+    float* embed_H;
+    EmbedNorm embed_en;
 };
 
 struct GemvArgs {
@@ -75,9 +85,6 @@ struct GemvArgs {
     const float* gainB; uint16_t* nxB;
     float* ssq_out;
 };
-
-// RMSNorm outputs produced together with an embedding row (first layer's input).
-struct EmbedNorm { const float* gain; uint16_t* nx; float* ssq_out; int32_t ssq_ld; };
 
 int head_blocks_valu(int32_t N);
 int head_blocks_mfma(int32_t N);

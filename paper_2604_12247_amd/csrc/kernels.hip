@@ -15,56 +15,71 @@
 namespace sb {
 
 // ---------------------------------------------------------------- embedding
+// Row r of the hidden cache := embedding of token `tok` (+ what the first layer's projection
+// needs: bf16 parts of gain * h and the row's sum of squares).  Executed by the first 256
+// threads of a block, which all reach the barrier inside; the same code serves the embedding
+// kernel and the head merge that embeds the token it has just drafted, so a row's values do
+// not depend on which of the two wrote it.
+template <typename WT>
+__device__ __forceinline__ void embed_row(const WT* __restrict__ E, int vocab, int d, float* __restrict__ H, int tok, int r,
+                                          EmbedNorm en, float* red /*[4] shared*/) {
+    constexpr int VMAX = 4;  // 8-element groups a thread keeps in registers (covers d <= 8192)
+    const int tid = threadIdx.x;
+    const bool act = tid < 256;
+    if (tok < 0 || tok >= vocab) tok = 0;  // never index outside the table
+    const WT* e = E + (size_t)tok * d;
+    const int ngrp = d >> 3;
+    float ss = 0.f;
+    if (act) {
+        float v[VMAX][8], gn[VMAX][8];
+#pragma unroll
+        for (int j = 0; j < VMAX; ++j) {
+            const int gi = tid + j * 256;
+            if (gi < ngrp) {
+                load8(e + gi * 8, v[j]);
+                if (en.nx) load8(en.gain + gi * 8, gn[j]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[j][k] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < VMAX; ++j) {
+            const int gi = tid + j * 256;
+            if (gi < ngrp) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    H[(size_t)r * d + gi * 8 + k] = v[j][k];
+                    ss += v[j][k] * v[j][k];
+                    if (en.nx) split_store(en.nx, d, r, gi * 8 + k, v[j][k] * gn[j][k]);
+                }
+            }
+        }
+        for (int i = VMAX * 2048 + tid; i < d; i += 256) {  // d > 8192
+            float x = ldf(e + i);
+            H[(size_t)r * d + i] = x;
+            ss += x * x;
+            if (en.nx) split_store(en.nx, d, r, i, x * en.gain[i]);
+        }
+    }
+    if (en.ssq_out) {  // the row's sum of squares, as a single partial
+        ss = wave_sum(ss);
+        if (act && (tid & 63) == 0) red[tid >> 6] = ss;
+        __syncthreads();
+        if (tid == 0) en.ssq_out[(size_t)r * en.ssq_ld] = ((red[0] + red[1]) + red[2]) + red[3];
+    }
+}
+
 template <typename WT>
 __global__ __launch_bounds__(256) void embed_kernel(const WT* __restrict__ E, int vocab, int d, float* __restrict__ H,
                                                     RowToks toks, const int32_t* __restrict__ slot_tok,
                                                     int32_t* clear_flag, EmbedNorm en) {
-    constexpr int VMAX = 4;  // 8-element groups a thread keeps in registers (covers d <= 8192)
     __shared__ float red[4];
     int r = blockIdx.x, tid = threadIdx.x;
     int tok = toks.tok[r];
     if (tok < 0) tok = slot_tok[r];
-    if (tok < 0 || tok >= vocab) tok = 0;  // never index outside the table
     if (clear_flag && r == 0 && tid == 0) *clear_flag = 0;
-    const WT* e = E + (size_t)tok * d;
-    const int ngrp = d >> 3;
-    float v[VMAX][8], gn[VMAX][8];
-#pragma unroll
-    for (int j = 0; j < VMAX; ++j) {
-        const int gi = tid + j * 256;
-        if (gi < ngrp) {
-            load8(e + gi * 8, v[j]);
-            if (en.nx) load8(en.gain + gi * 8, gn[j]);
-        } else {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[j][k] = 0.f;
-        }
-    }
-    float ss = 0.f;
-#pragma unroll
-    for (int j = 0; j < VMAX; ++j) {
-        const int gi = tid + j * 256;
-        if (gi < ngrp) {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                H[(size_t)r * d + gi * 8 + k] = v[j][k];
-                ss += v[j][k] * v[j][k];
-                if (en.nx) split_store(en.nx, d, r, gi * 8 + k, v[j][k] * gn[j][k]);
-            }
-        }
-    }
-    for (int i = VMAX * 2048 + tid; i < d; i += 256) {  // d > 8192
-        float x = ldf(e + i);
-        H[(size_t)r * d + i] = x;
-        ss += x * x;
-        if (en.nx) split_store(en.nx, d, r, i, x * en.gain[i]);
-    }
-    if (en.ssq_out) {  // the row's sum of squares, as a single partial
-        ss = wave_sum(ss);
-        if ((tid & 63) == 0) red[tid >> 6] = ss;
-        __syncthreads();
-        if (tid == 0) en.ssq_out[(size_t)r * en.ssq_ld] = ((red[0] + red[1]) + red[2]) + red[3];
-    }
+    embed_row<WT>(E, vocab, d, H, tok, r, en, red);
 }
 
 hipError_t launch_embed(const void* E, int32_t w_dtype, int32_t vocab, int32_t d, float* H, int32_t M,
@@ -192,25 +207,33 @@ hipError_t launch_read(const void* src, size_t nbytes, float* sink, hipStream_t 
 // Second stage of a head evaluation: one block merges the per-block partials
 // (max, arg max, sum of exp((z - max)/T)) of every row in a fixed order -- so the
 // result does not depend on block scheduling -- and carries out the exit test
-// (Eq. 2) or the acceptance rule.  It is a kernel of its own: publishing the
+// (Eq. 2) or the acceptance rule.  Rows are merged side by side, 128 threads each (a
+// row's order of additions does not depend on how many rows there are).  When a draft
+// exits, the block also embeds the drafted token as the next row (the next draft step
+// then starts at its first layer).  It is a kernel of its own: publishing the
 // partials inside the projection kernel would need a device-wide fence per
 // block, which on this chip writes back and invalidates a whole L2.
-__global__ __launch_bounds__(256) void head_merge_kernel(HeadArgs h, int M, int nb) {
-    __shared__ float r_max[4], r_sum[4];
-    __shared__ int r_idx[4];
-    __shared__ float s_gmax;
-    __shared__ int s_gidx;
+__global__ __launch_bounds__(1024) void head_merge_kernel(HeadArgs h, int M, int nb) {
+    __shared__ float r_max[SB_MAX_W][2], r_sum[SB_MAX_W][2];
+    __shared__ int r_idx[SB_MAX_W][2];
     __shared__ int s_am[SB_MAX_W];
     __shared__ float s_cf[SB_MAX_W];
-    int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int m = 0; m < M; ++m) {
-        const float* p = h.partials + (size_t)m * nb * 4;
-        float mx = -SB_INF;
-        int idx = 0x7fffffff;
-        for (int b = tid; b < nb; b += 256) {
-            float v = p[b * 4];
-            int i = __float_as_int(p[b * 4 + 1]);
-            if (v > mx || (v == mx && i < idx)) { mx = v; idx = i; }
+    __shared__ int s_embed_tok;
+    __shared__ float e_red[4];
+    const int tid = threadIdx.x, lane = tid & 63, m = tid >> 7, t = tid & 127, half = (tid >> 6) & 1;
+    const float4* p = reinterpret_cast<const float4*>(h.partials) + (size_t)(m < M ? m : 0) * nb;
+    float mx = -SB_INF;
+    int idx = 0x7fffffff;
+    if (m < M) {
+        for (int b0 = t; b0 < nb; b0 += 512) {  // four independent loads per round
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = (b0 + 128 * u < nb) ? p[b0 + 128 * u] : make_float4(-SB_INF, __int_as_float(0x7fffffff), 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = __float_as_int(v[u].y);
+                if (v[u].x > mx || (v[u].x == mx && i < idx)) { mx = v[u].x; idx = i; }
+            }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
@@ -218,34 +241,34 @@ __global__ __launch_bounds__(256) void head_merge_kernel(HeadArgs h, int M, int 
             int oi = __shfl_xor(idx, o, 64);
             if (ov > mx || (ov == mx && oi < idx)) { mx = ov; idx = oi; }
         }
-        if (lane == 0) { r_max[wave] = mx; r_idx[wave] = idx; }
-        __syncthreads();
-        if (tid == 0) {
-            float gm = r_max[0];
-            int gi = r_idx[0];
-            for (int w = 1; w < 4; ++w)
-                if (r_max[w] > gm || (r_max[w] == gm && r_idx[w] < gi)) { gm = r_max[w]; gi = r_idx[w]; }
-            s_gmax = gm;
-            s_gidx = gi == 0x7fffffff ? 0 : gi;
-        }
-        __syncthreads();
-        float gmax = s_gmax;
-        float s = 0.f;
-        for (int b = tid; b < nb; b += 256) s += p[b * 4 + 2] * expf((p[b * 4] - gmax) / h.T);
-        s = wave_sum(s);
-        if (lane == 0) r_sum[wave] = s;
-        __syncthreads();
-        if (tid == 0) {
-            float S = ((r_sum[0] + r_sum[1]) + r_sum[2]) + r_sum[3];
-            s_am[m] = s_gidx;
-            s_cf[m] = 1.0f / S;
-        }
-        __syncthreads();
+        if (lane == 0) { r_max[m][half] = mx; r_idx[m][half] = idx; }
     }
+    __syncthreads();
+    float gmax = 0.f;
+    if (m < M) {
+        gmax = r_max[m][0];
+        int gi = r_idx[m][0];
+        if (r_max[m][1] > gmax || (r_max[m][1] == gmax && r_idx[m][1] < gi)) { gmax = r_max[m][1]; gi = r_idx[m][1]; }
+        if (t == 0) s_am[m] = gi == 0x7fffffff ? 0 : gi;
+        float sum = 0.f;
+        for (int b0 = t; b0 < nb; b0 += 512) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = (b0 + 128 * u < nb) ? p[b0 + 128 * u] : make_float4(-SB_INF, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) sum += v[u].z * expf((v[u].x - gmax) / h.T);
+        }
+        sum = wave_sum(sum);
+        if (lane == 0) r_sum[m][half] = sum;
+    }
+    __syncthreads();
+    if (tid < M) s_cf[tid] = 1.0f / (r_sum[tid][0] + r_sum[tid][1]);
+    if (tid == 0) s_embed_tok = -1;
+    __syncthreads();
     if (tid == 0) {
-        for (int m = 0; m < M; ++m) {
-            if (h.argmax_out) h.argmax_out[m] = s_am[m];
-            if (h.conf_out) h.conf_out[m] = s_cf[m];
+        for (int r = 0; r < M; ++r) {
+            if (h.argmax_out) h.argmax_out[r] = s_am[r];
+            if (h.conf_out) h.conf_out[r] = s_cf[r];
         }
         if (h.post == POST_EXIT) {
             // Early exit at the first layer whose confidence reaches the threshold
@@ -257,28 +280,37 @@ __global__ __launch_bounds__(256) void head_merge_kernel(HeadArgs h, int M, int 
             R->conf[s] = cf;
             R->head_argmax[s] = am;
             bool ex = h.forced_exit >= 0 ? (h.layer == h.forced_exit) : (cf >= h.threshold);
+            R->exit_flag = ex ? 1 : 0;
             if (ex) {
                 int tok = h.forced_draft >= 0 ? h.forced_draft : am;
                 R->drafts[s] = tok;
                 R->slot_tok[s + 1] = tok;
                 R->exit_layer[s] = h.layer;
-                R->exit_flag = 1;
+                if (h.embed_E) s_embed_tok = tok;
             }
         } else if (h.post == POST_ACCEPT) {
             // Keep the longest prefix of drafts equal to the greedy tokens; the row
             // after it yields one more token: min(m + 1, M) >= 1 are emitted.
             DevRound* R = h.round;
             int mt = 0;
-            for (int m = 0; m < M; ++m) { R->g[m] = s_am[m]; R->gconf[m] = s_cf[m]; }
+            for (int r = 0; r < M; ++r) { R->g[r] = s_am[r]; R->gconf[r] = s_cf[r]; }
             while (mt < h.n_drafts && mt < M && R->drafts[mt] == s_am[mt]) ++mt;
             R->n_matched = mt;
             R->n_emit = mt + 1 < M ? mt + 1 : M;
         }
     }
+    if (h.post == POST_EXIT && h.embed_E) {   // (uniform for the block)
+        __syncthreads();
+        const int tok = s_embed_tok;
+        if (tok >= 0) {   // the drafted token becomes the next row of the round
+            if (h.embed_dtype == SB_BF16) embed_row<uint16_t>((const uint16_t*)h.embed_E, h.embed_vocab, h.embed_d, h.embed_H, tok, 0, h.embed_en, e_red);
+            else embed_row<float>((const float*)h.embed_E, h.embed_vocab, h.embed_d, h.embed_H, tok, 0, h.embed_en, e_red);
+        }
+    }
 }
 
 hipError_t launch_head_merge(const HeadArgs& h, int32_t M, int32_t nb, hipStream_t st) {
-    head_merge_kernel<<<1, 256, 0, st>>>(h, M, nb);
+    head_merge_kernel<<<1, 1024, 0, st>>>(h, M, nb);
     return hipGetLastError();
 }
 
@@ -1287,6 +1319,58 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     }
 }
 
+// The same merge for short contexts (at most 8 chunks), a wave per (row, query head) with
+// every load issued at once and no barrier.  The additions are carried out in exactly the
+// order of attn_merge_kernel (chunk c belongs to group c mod NG, a group adds its chunks in
+// ascending order, the groups are added in index order), so both kernels give the same bits
+// and the choice between them cannot show in any result.
+template <int HD, int CH>
+__global__ __launch_bounds__(256) void attn_merge_wave_kernel(AttnArgs a) {
+    constexpr int TPG = HD / 2, NG = 256 / TPG, MAXNC = 8;
+    const int lane = threadIdx.x & 63;
+    const int task = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int Hq = a.n_heads, stride = HD + 2;
+    if (task >= a.M * Hq) return;
+    const int r = task / Hq, hq = task - r * Hq;
+    const int nc = (a.pos0 + r) / CH + 1;   // <= MAXNC (the launcher checks the last row)
+    const int dp = lane < TPG ? lane : TPG - 1;
+    const float* p = a.partials + (size_t)(r * Hq + hq) * a.max_chunks * stride;
+    float2 av[MAXNC], ml[MAXNC];
+#pragma unroll
+    for (int c = 0; c < MAXNC; ++c) {
+        av[c] = make_float2(0.f, 0.f);
+        ml[c] = make_float2(-SB_INF, 0.f);
+        if (c < nc) {
+            av[c] = *reinterpret_cast<const float2*>(p + (size_t)c * stride + 2 + 2 * dp);
+            ml[c] = *reinterpret_cast<const float2*>(p + (size_t)c * stride);
+        }
+    }
+    float mx = -SB_INF;
+#pragma unroll
+    for (int c = 0; c < MAXNC; ++c) mx = fmaxf(mx, ml[c].x);
+    float Ls = 0.f, O0s = 0.f, O1s = 0.f;
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+        float L = 0.f, O0 = 0.f, O1 = 0.f;
+#pragma unroll
+        for (int c = gi; c < MAXNC; c += NG)
+            if (c < nc) {
+                const float w = expf(ml[c].x - mx);
+                L += ml[c].y * w; O0 += av[c].x * w; O1 += av[c].y * w;
+            }
+        Ls += L; O0s += O0; O1s += O1;
+    }
+    if (lane < TPG) {
+        const float v0 = O0s / Ls, v1 = O1s / Ls;
+        const size_t col = (size_t)hq * HD + 2 * lane;
+        if (a.out) { a.out[(size_t)r * Hq * HD + col] = v0; a.out[(size_t)r * Hq * HD + col + 1] = v1; }
+        if (a.out_split) {
+            split_store_rows(a.out_split, Hq * HD, a.split_rows, r, (int)col, v0);
+            split_store_rows(a.out_split, Hq * HD, a.split_rows, r, (int)col + 1, v1);
+        }
+    }
+}
+
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype) {
     return (head_dim * (kv_dtype == SB_BF16 ? 2 : 4) <= 256) ? 128 : 64;
 }
@@ -1311,9 +1395,18 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     dim3 grid1(a.kv.n_kv_heads, n_chunks, n_qg);
     if (!a.rope_cos || !a.rope_sin) return hipErrorInvalidValue;
     dim3 mgrid(a.n_heads, a.M);
+    const bool wave_merge = n_chunks <= 8;   // (same bits either way)
+    const unsigned wgrid = (unsigned)((a.M * a.n_heads + 3) / 4);
     if (a.kv.kv_dtype == SB_BF16) {
-        if (hd == 128) { attn_mfma_kernel<128><<<grid, 256, 0, st>>>(b); attn_merge_kernel<128, 128><<<mgrid, 256, 0, st>>>(a); }
-        else { attn_mfma_kernel<64><<<grid, 256, 0, st>>>(b); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }
+        if (hd == 128) {
+            attn_mfma_kernel<128><<<grid, 256, 0, st>>>(b);
+            if (wave_merge) attn_merge_wave_kernel<128, 128><<<wgrid, 256, 0, st>>>(a);
+            else attn_merge_kernel<128, 128><<<mgrid, 256, 0, st>>>(a);
+        } else {
+            attn_mfma_kernel<64><<<grid, 256, 0, st>>>(b);
+            if (wave_merge) attn_merge_wave_kernel<64, 128><<<wgrid, 256, 0, st>>>(a);
+            else attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a);
+        }
     } else {
         if (hd == 128) { attn_kernel<float, 128><<<grid1, 256, 0, st>>>(a); attn_merge_kernel<128, 64><<<mgrid, 256, 0, st>>>(a); }
         else { attn_kernel<float, 64><<<grid1, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }

@@ -35,6 +35,10 @@ int fail(int code, const char* fmt, ...) {
         if (e_ != hipSuccess) return fail(SB_EDEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
+double now_ms() {
+    return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 size_t esize(int dtype) { return dtype == SB_BF16 ? 2 : 4; }
 
@@ -174,6 +178,7 @@ struct sb_session {
     int reached[SB_MAX_W], exit_layer[SB_MAX_W];
     int32_t draft_host[SB_MAX_W];  // drafted id if the host knows it, else -1
     bool round_closed;
+    bool next_embedded;  // the last draft step's head merge has already embedded the next row
     int64_t draft_counter;
     bool debug;
     sb_stats st;
@@ -184,6 +189,9 @@ struct sb_session {
     unsigned ev_i;
     bool head_pending;      // ev_head[(ev_i - 1) % 4] not yet waited for by the main stream
     int head_pending_ev;
+    // phase timing: events at the boundaries of a round's phases (sb_phase_timing)
+    bool phase_timing;
+    hipEvent_t ev_ph[5];
     // per-kernel event timing
     uint32_t prof_mask;
     int prof_every;                    // time every n-th launch of a class
@@ -393,6 +401,7 @@ EmbedNorm embed_norm(sb_session* s, int slot0) {
 
 void reset_session(sb_session* s) {
     s->c = 0; s->has_pending = false; s->n_slots = 0; s->n_drafts = 0; s->round_closed = false;
+    s->next_embedded = false;
     s->draft_counter = 0;
     memset(&s->st, 0, sizeof s->st);
 }
@@ -590,8 +599,13 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
     for (int r = 0; r < SB_MAX_W; ++r) t.tok[r] = 0;
     t.tok[0] = idx == 0 ? s->pending : s->draft_host[idx - 1];  // -1: the id is on the device only
     float* Hrow = wsp<float>(s, s->L.H) + (size_t)idx * c.d_model;
-    HIP_TRY(launch_embed(m->embed, c.weight_dtype, c.vocab, c.d_model, Hrow, 1, t, s->d_round->slot_tok + idx,
-                         &s->d_round->exit_flag, embed_norm(s, idx), m->stream));
+    if (s->phase_timing && idx == 0) HIP_TRY(hipEventRecord(s->ev_ph[0], m->stream));   // the round begins
+    if (!(idx > 0 && s->next_embedded))   // (else the head merge that drafted this row's token has embedded it)
+        HIP_TRY(launch_embed(m->embed, c.weight_dtype, c.vocab, c.d_model, Hrow, 1, t, s->d_round->slot_tok + idx,
+                             &s->d_round->exit_flag, embed_norm(s, idx), m->stream));
+    s->next_embedded = false;
+    // a draft that exits is embedded as the next row by its own head merge, if a next step can follow
+    const bool embed_next = s->n_drafts + 1 < p->w_max && idx + 1 < SB_MAX_W;
     s->draft_counter++;
     s->st.draft_steps++;
     s->n_slots++;
@@ -612,7 +626,15 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
         h.T = p->T[l - 1]; h.post = POST_EXIT; h.slot = idx; h.layer = l; h.forced_exit = forced; h.forced_draft = over;
         h.threshold = p->threshold;
         h.logits = s->debug ? wsp<float>(s, s->L.logits_exit) + (size_t)(l - 1) * c.vocab : nullptr;
-        if (overlap) {
+        if (embed_next) {
+            h.embed_E = m->embed; h.embed_dtype = c.weight_dtype; h.embed_vocab = c.vocab; h.embed_d = c.d_model;
+            h.embed_H = Hrow + c.d_model;
+            h.embed_en = embed_norm(s, idx + 1);
+        }
+        // The head only reads what W_down left for it, so it can run beside the next layer on the
+        // second stream -- except the head at which the row exits: the next step starts from its
+        // result, so it stays on the main stream (no hop between streams on the critical path).
+        if (overlap && l != forced) {
             // the head only reads what W_down left for it: let it run beside the next layer
             const unsigned e = s->ev_i++ & 3;
             HIP_TRY(hipEventRecord(s->ev_main[e], m->stream));
@@ -641,6 +663,7 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
     if (have) res.confidence = s->h_round->conf[idx];
     if (exit_at) {
         s->exit_layer[idx] = exit_at;
+        s->next_embedded = embed_next;
         s->draft_host[idx] = over >= 0 ? over : (have ? s->h_round->drafts[idx] : -1);
         s->n_drafts++;
         s->st.drafts++;
@@ -663,6 +686,8 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     sb_model* m = s->m;
     const sb_config& c = m->cfg;
     if ((rc = join_head(s))) return rc;
+    const bool pt = s->phase_timing;
+    if (pt) HIP_TRY(hipEventRecord(s->ev_ph[1], m->stream));   // drafting (with its last exit head) is over
     const int M = s->n_slots, D = s->reached[0];
     for (int j = 1; j < M; ++j)
         if (s->reached[j] > s->reached[j - 1]) return fail(SB_ESTATE, "verify: reached layers not monotone");
@@ -674,6 +699,7 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
         if ((rc = run_layer(s, l - 1, j0, M - j0, nullptr))) return rc;
         for (int j = j0; j < M; ++j) s->reached[j] = l;
     }
+    if (pt) HIP_TRY(hipEventRecord(s->ev_ph[2], m->stream));   // aligned
     // one parallel pass of all rows through the remaining layers
     for (int l = D + 1; l <= c.n_layers; ++l) {
         if ((rc = run_layer(s, l - 1, 0, M, l == c.n_layers ? m->final_norm : nullptr))) return rc;
@@ -685,7 +711,19 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     if ((rc = join_head(s))) return rc;
     if ((rc = run_head(s, m->lm_head, m->final_norm, 0, M, h, m->stream))) return rc;
     s->st.final_head_sweeps++;
-    if ((rc = readback(s))) return rc;
+    if (pt) HIP_TRY(hipEventRecord(s->ev_ph[3], m->stream));   // verified
+    const double tw0 = now_ms();
+    HIP_TRY(hipMemcpyAsync(s->h_round, s->d_round, sizeof(DevRound), hipMemcpyDeviceToHost, m->stream));
+    if (pt) HIP_TRY(hipEventRecord(s->ev_ph[4], m->stream));
+    HIP_TRY(hipStreamSynchronize(m->stream));
+    s->st.host_wait_ms += now_ms() - tw0;
+    if (pt) {
+        double* acc[4] = {&s->st.gpu_draft_ms, &s->st.gpu_align_ms, &s->st.gpu_verify_ms, &s->st.gpu_readback_ms};
+        for (int i = 0; i < 4; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, s->ev_ph[i], s->ev_ph[i + 1]) == hipSuccess) *acc[i] += ms;
+        }
+    }
     const DevRound& R = *s->h_round;
     if (R.n_emit < 1 || R.n_emit > M) return fail(SB_EDEVICE, "verify: device returned n_emit = %d", R.n_emit);
     sb_verify_result res{};
@@ -695,7 +733,7 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     // beyond the committed length and overwritten by the next round
     s->c += R.n_emit;
     s->pending = R.g[R.n_emit - 1];
-    s->n_slots = 0; s->n_drafts = 0; s->round_closed = false;
+    s->n_slots = 0; s->n_drafts = 0; s->round_closed = false; s->next_embedded = false;
     s->st.rounds++; s->st.emitted += R.n_emit; s->st.accept_hist[R.n_emit]++;
     if (out) *out = res;
     return SB_OK;
@@ -710,6 +748,8 @@ hipError_t sync_all(sb_session* s) {
 
 void free_session_resources(sb_session* s) {
     if (s->h_round) (void)hipHostFree(s->h_round);
+    for (int i = 0; i < 5; ++i)
+        if (s->ev_ph[i]) { (void)hipEventDestroy(s->ev_ph[i]); s->ev_ph[i] = nullptr; }
     for (int i = 0; i < 4; ++i) {
         if (s->ev_main[i]) (void)hipEventDestroy(s->ev_main[i]);
         if (s->ev_head[i]) (void)hipEventDestroy(s->ev_head[i]);
@@ -721,10 +761,6 @@ void free_session_resources(sb_session* s) {
     s->prof_cal.clear();
 }
 
-double now_ms() {
-    return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
-}
-
 // Rounds of draft steps + verification until *cnt == max_new or eos.  While the
 // exit decisions are forced the host knows the round's shape in advance, so a
 // whole round is enqueued without waiting and read back once, after verification.
@@ -733,11 +769,15 @@ int decode_impl(sb_session* s, const sb_params* p, int32_t* out_tokens, int* cnt
     double t1 = now_ms();
     while (cnt < max_new && !(p->eos_id >= 0 && cnt > 0 && out_tokens[cnt - 1] == p->eos_id)) {
         sb_draft_result dr;
+        const double th0 = now_ms();
         do {
             if ((rc = draft_step_impl(s, p, &dr, false))) return rc;
         } while (dr.status == SB_EXITED);
+        const double th1 = now_ms(), w0 = s->st.host_wait_ms;
         sb_verify_result vr;
         if ((rc = verify_impl(s, p, &vr))) return rc;
+        s->st.host_draft_ms += th1 - th0;
+        s->st.host_verify_ms += (now_ms() - th1) - (s->st.host_wait_ms - w0);
         int take = 0;
         while (take < vr.n_emit && cnt < max_new) {
             out_tokens[cnt++] = vr.tokens[take++];
@@ -903,6 +943,8 @@ int32_t sb_new_session(sb_model* m, void* kv_pool, size_t kv_bytes, void* worksp
     s->head_pending_ev = 0;
     for (int i = 0; i < 4; ++i) { s->ev_main[i] = nullptr; s->ev_head[i] = nullptr; }
     s->h_round = nullptr;
+    s->phase_timing = false;
+    for (int i = 0; i < 5; ++i) s->ev_ph[i] = nullptr;
     reset_session(s);
     hipError_t e = hipHostMalloc((void**)&s->h_round, sizeof(DevRound), hipHostMallocDefault);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&s->head_stream, hipStreamNonBlocking);  // default priority
@@ -1060,6 +1102,19 @@ int32_t sb_profile_end(sb_session* s, int64_t* launches, double* total_ms, int64
     s->prof_ev.clear();
     s->prof_used = 0;
     if (e != hipSuccess) return fail(SB_EDEVICE, "profile_end: %s", hipGetErrorString(e));
+    return SB_OK;
+}
+
+int32_t sb_phase_timing(sb_session* s, int32_t on) {
+    if (!s) return fail(SB_EINVAL, "phase_timing: session is NULL");
+    if (on && !s->ev_ph[0])
+        for (int i = 0; i < 5; ++i)
+            if (hipEventCreate(&s->ev_ph[i]) != hipSuccess) {
+                for (int j = 0; j < i; ++j) { (void)hipEventDestroy(s->ev_ph[j]); s->ev_ph[j] = nullptr; }
+                s->ev_ph[i] = nullptr;
+                return fail(SB_ENOMEM, "phase_timing: cannot create events");
+            }
+    s->phase_timing = on != 0;
     return SB_OK;
 }
 
