@@ -1319,58 +1319,6 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     }
 }
 
-// The same merge for short contexts (at most 8 chunks), a wave per (row, query head) with
-// every load issued at once and no barrier.  The additions are carried out in exactly the
-// order of attn_merge_kernel (chunk c belongs to group c mod NG, a group adds its chunks in
-// ascending order, the groups are added in index order), so both kernels give the same bits
-// and the choice between them cannot show in any result.
-template <int HD, int CH>
-__global__ __launch_bounds__(256) void attn_merge_wave_kernel(AttnArgs a) {
-    constexpr int TPG = HD / 2, NG = 256 / TPG, MAXNC = 8;
-    const int lane = threadIdx.x & 63;
-    const int task = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int Hq = a.n_heads, stride = HD + 2;
-    if (task >= a.M * Hq) return;
-    const int r = task / Hq, hq = task - r * Hq;
-    const int nc = (a.pos0 + r) / CH + 1;   // <= MAXNC (the launcher checks the last row)
-    const int dp = lane < TPG ? lane : TPG - 1;
-    const float* p = a.partials + (size_t)(r * Hq + hq) * a.max_chunks * stride;
-    float2 av[MAXNC], ml[MAXNC];
-#pragma unroll
-    for (int c = 0; c < MAXNC; ++c) {
-        av[c] = make_float2(0.f, 0.f);
-        ml[c] = make_float2(-SB_INF, 0.f);
-        if (c < nc) {
-            av[c] = *reinterpret_cast<const float2*>(p + (size_t)c * stride + 2 + 2 * dp);
-            ml[c] = *reinterpret_cast<const float2*>(p + (size_t)c * stride);
-        }
-    }
-    float mx = -SB_INF;
-#pragma unroll
-    for (int c = 0; c < MAXNC; ++c) mx = fmaxf(mx, ml[c].x);
-    float Ls = 0.f, O0s = 0.f, O1s = 0.f;
-#pragma unroll
-    for (int gi = 0; gi < NG; ++gi) {
-        float L = 0.f, O0 = 0.f, O1 = 0.f;
-#pragma unroll
-        for (int c = gi; c < MAXNC; c += NG)
-            if (c < nc) {
-                const float w = expf(ml[c].x - mx);
-                L += ml[c].y * w; O0 += av[c].x * w; O1 += av[c].y * w;
-            }
-        Ls += L; O0s += O0; O1s += O1;
-    }
-    if (lane < TPG) {
-        const float v0 = O0s / Ls, v1 = O1s / Ls;
-        const size_t col = (size_t)hq * HD + 2 * lane;
-        if (a.out) { a.out[(size_t)r * Hq * HD + col] = v0; a.out[(size_t)r * Hq * HD + col + 1] = v1; }
-        if (a.out_split) {
-            split_store_rows(a.out_split, Hq * HD, a.split_rows, r, (int)col, v0);
-            split_store_rows(a.out_split, Hq * HD, a.split_rows, r, (int)col + 1, v1);
-        }
-    }
-}
-
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype) {
     return (head_dim * (kv_dtype == SB_BF16 ? 2 : 4) <= 256) ? 128 : 64;
 }
@@ -1395,18 +1343,9 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     dim3 grid1(a.kv.n_kv_heads, n_chunks, n_qg);
     if (!a.rope_cos || !a.rope_sin) return hipErrorInvalidValue;
     dim3 mgrid(a.n_heads, a.M);
-    const bool wave_merge = n_chunks <= 8;   // (same bits either way)
-    const unsigned wgrid = (unsigned)((a.M * a.n_heads + 3) / 4);
     if (a.kv.kv_dtype == SB_BF16) {
-        if (hd == 128) {
-            attn_mfma_kernel<128><<<grid, 256, 0, st>>>(b);
-            if (wave_merge) attn_merge_wave_kernel<128, 128><<<wgrid, 256, 0, st>>>(a);
-            else attn_merge_kernel<128, 128><<<mgrid, 256, 0, st>>>(a);
-        } else {
-            attn_mfma_kernel<64><<<grid, 256, 0, st>>>(b);
-            if (wave_merge) attn_merge_wave_kernel<64, 128><<<wgrid, 256, 0, st>>>(a);
-            else attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a);
-        }
+        if (hd == 128) { attn_mfma_kernel<128><<<grid, 256, 0, st>>>(b); attn_merge_kernel<128, 128><<<mgrid, 256, 0, st>>>(a); }
+        else { attn_mfma_kernel<64><<<grid, 256, 0, st>>>(b); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }
     } else {
         if (hd == 128) { attn_kernel<float, 128><<<grid1, 256, 0, st>>>(a); attn_merge_kernel<128, 64><<<mgrid, 256, 0, st>>>(a); }
         else { attn_kernel<float, 64><<<grid1, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }

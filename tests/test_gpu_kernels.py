@@ -359,16 +359,3 @@ def test_attention_row_result_does_not_depend_on_m(T):
         _, out1 = _attention_case(T, *args, 250 + r, 1, 1e4, True, seed=77)
         assert np.array_equal(out1[0], out6[r])
 
-
-@pytest.mark.parametrize("hd", [128, 64])
-def test_attention_merge_variants_give_the_same_bits(T, hd):
-    """Up to 8 chunks of 128 keys are merged by a wave per (row, head), longer contexts by a
-    block: a row at position 1020..1023 decoded alone takes the first, the same row in a pass
-    of 6 rows (1026 keys, 9 chunks) the second.  Same bits, and both within 2e-5 of the oracle."""
-    args = (8, 8, hd, True)
-    worst6, out6 = _attention_case(T, *args, 1020, 6, 1e4, True, seed=79)
-    assert worst6 <= 2e-5
-    for r in (0, 3):
-        worst1, out1 = _attention_case(T, *args, 1020 + r, 1, 1e4, True, seed=79)
-        assert worst1 <= 2e-5
-        assert np.array_equal(out1[0], out6[r])
