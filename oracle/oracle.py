@@ -36,7 +36,9 @@ class _Params(C.Structure):
     _fields_ = [("d_max", C.c_int32), ("w_max", C.c_int32), ("T", C.POINTER(C.c_float)),
                 ("threshold", C.c_float), ("eos_id", C.c_int32),
                 ("forced_exit", C.POINTER(C.c_int32)), ("forced_draft", C.POINTER(C.c_int32)),
-                ("n_forced", C.c_int64), ("head_mask", C.c_uint32)]
+                ("n_forced", C.c_int64), ("head_mask", C.c_uint32),
+                ("sample_temperature", C.c_float), ("top_p", C.c_float),
+                ("sample_u", C.POINTER(C.c_float)), ("n_sample_u", C.c_int64)]
 
 
 class _DraftResult(C.Structure):
@@ -132,6 +134,24 @@ def act(z: np.ndarray, T: float, bits: int = 64):
     return am.value, conf.value
 
 
+def sample_dist(z: np.ndarray, temp: float, top_p: float = 1.0, bits: int = 64) -> np.ndarray:
+    """The distribution sampling-mode decoding draws from (temperature, top-p nucleus)."""
+    lib = load_lib(bits)
+    z = np.ascontiguousarray(z, dtype=_real(bits))
+    p = np.empty_like(z)
+    tmp = np.empty_like(z)
+    R = C.c_double if bits == 64 else C.c_float
+    lib.orc_sample_dist(_ptr(z), C.c_int32(z.size), R(temp), R(top_p), _ptr(p), _ptr(tmp))
+    return p
+
+
+def sample_token(p: np.ndarray, u: float, exclude: int = -1, bits: int = 64) -> int:
+    lib = load_lib(bits)
+    p = np.ascontiguousarray(p, dtype=_real(bits))
+    R = C.c_double if bits == 64 else C.c_float
+    return lib.orc_sample_token(_ptr(p), C.c_int32(p.size), R(u), C.c_int32(exclude))
+
+
 def rope_angles(pos: int, hd: int, base: float):
     lib = load_lib(64)
     c = np.empty(hd // 2, dtype=np.float32)
@@ -187,9 +207,11 @@ class OrcParams:
 
     def __init__(self, d_max: int, w_max: int, T: Sequence[float], threshold: float,
                  forced_exit: Optional[Sequence[int]] = None,
-                 forced_draft: Optional[Sequence[int]] = None, eos_id: int = -1, head_mask: int = 0):
+                 forced_draft: Optional[Sequence[int]] = None, eos_id: int = -1, head_mask: int = 0,
+                 sample_temperature: float = 0.0, top_p: float = 1.0, sample_u=None):
         self.T = np.ascontiguousarray(T, dtype=np.float32)
         assert len(self.T) >= d_max
+        self.su = None if sample_u is None else np.ascontiguousarray(sample_u, dtype=np.float32)
         self.fe = None if forced_exit is None else np.ascontiguousarray(forced_exit, dtype=np.int32)
         self.fd = None if forced_draft is None else np.ascontiguousarray(forced_draft, dtype=np.int32)
         n_forced = 0
@@ -201,7 +223,9 @@ class OrcParams:
                          self.T.ctypes.data_as(C.POINTER(C.c_float)), threshold, eos_id,
                          None if self.fe is None else self.fe.ctypes.data_as(C.POINTER(C.c_int32)),
                          None if self.fd is None else self.fd.ctypes.data_as(C.POINTER(C.c_int32)),
-                         n_forced, head_mask)
+                         n_forced, head_mask, sample_temperature, top_p,
+                         None if self.su is None else self.su.ctypes.data_as(C.POINTER(C.c_float)),
+                         0 if self.su is None else len(self.su))
 
 
 class Oracle:
@@ -368,6 +392,16 @@ class OracleSession:
         out = np.empty(self.model.shape.vocab, dtype=np.float64)
         self.lib.orc_verify_logits(self.h, C.c_int32(row), _ptr(out))
         return out
+
+    def verify_dist(self, row: int) -> np.ndarray:
+        out = np.empty(self.model.shape.vocab, dtype=np.float64)
+        self.lib.orc_verify_dist(self.h, C.c_int32(row), _ptr(out))
+        return out
+
+    def rewind(self, n_keep: int, pending: int):
+        rc = self.lib.orc_rewind(self.h, C.c_int32(n_keep), C.c_int32(pending))
+        if rc != 0:
+            raise RuntimeError(f"orc_rewind failed: {rc}")
 
     def kv_read(self, layer: int, pos: int):
         s = self.model.shape

@@ -73,6 +73,14 @@ typedef struct {
     uint32_t head_mask;          /* 0: an exit head after every layer 1..d_max (Sec. 3.2); else bit l-1
                                     set = layer l has its head evaluated, the others are passed without a
                                     test (a variant, not the paper's rule) */
+    /* Sampling-mode verification (Sec. 4.3, "sampling strategies"; the paper gives results for
+     * temperature and top-p sampling but not the mechanism -- the rule taken here is stated at
+     * orc_verify).  sample_temperature == 0: greedy verification. */
+    float sample_temperature;    /* > 0: the output is sampled from softmax(z / sample_temperature) ... */
+    float top_p;                 /* ... restricted to its nucleus of mass top_p (1: no restriction) */
+    const float *sample_u;       /* uniforms in [0, 1): the row at position pos uses sample_u[2 pos] for its
+                                    acceptance test and sample_u[2 pos + 1] to draw a token */
+    int64_t n_sample_u;
 } orc_params;
 
 typedef struct { int32_t token, exit_layer, status; float confidence; } orc_draft_result;
@@ -119,6 +127,8 @@ typedef struct {
     int64_t trace_cap, trace_n;
     real *head_logits;         /* [vocab] last exit-head logits */
     real *verify_logits;       /* [ORC_MAX_W][vocab] logits of the last verify / prefill / step */
+    real *verify_dist;         /* [ORC_MAX_W][vocab] sampling distributions of the last sampled verify */
+    real *sort_buf;            /* [vocab] */
     int32_t last_argmax; real last_conf;
     /* scratch */
     real *xn, *qkv, *att, *o, *gu, *u, *dn, *sc;
@@ -270,6 +280,8 @@ int32_t orc_session_new(orc_model *m, orc_session **out) {
     for (int i = 0; i < ORC_MAX_W; ++i) s->slots[i].h = (real *)calloc(c->d_model, sizeof(real));
     s->head_logits = (real *)calloc(c->vocab, sizeof(real));
     s->verify_logits = (real *)calloc((size_t)ORC_MAX_W * c->vocab, sizeof(real));
+    s->verify_dist = (real *)calloc((size_t)ORC_MAX_W * c->vocab, sizeof(real));
+    s->sort_buf = (real *)calloc(c->vocab, sizeof(real));
     s->xn = (real *)calloc(c->d_model, sizeof(real));
     s->qkv = (real *)calloc(qkv_rows, sizeof(real));
     s->att = (real *)calloc((size_t)c->n_heads * c->head_dim, sizeof(real));
@@ -287,7 +299,7 @@ void orc_session_free(orc_session *s) {
     if (!s) return;
     free(s->kc); free(s->vc);
     for (int i = 0; i < ORC_MAX_W; ++i) free(s->slots[i].h);
-    free(s->head_logits); free(s->verify_logits);
+    free(s->head_logits); free(s->verify_logits); free(s->verify_dist); free(s->sort_buf);
     free(s->xn); free(s->qkv); free(s->att); free(s->o); free(s->gu); free(s->u); free(s->dn); free(s->sc);
     free(s->trace);
     free(s);
@@ -314,6 +326,13 @@ int64_t orc_trace_read(const orc_session *s, orc_trace_entry *out, int64_t cap) 
     return s->trace_n;
 }
 void orc_get_stats(const orc_session *s, orc_stats *out) { *out = s->st; }
+/* Drop every cached position >= n_keep and any open rows; `pending` is the next token to feed. */
+int32_t orc_rewind(orc_session *s, int32_t n_keep, int32_t pending) {
+    if (n_keep < 1 || n_keep > s->c || pending < 0 || pending >= s->m->cfg.vocab) return ORC_EINVAL;
+    s->c = n_keep; s->pending = pending; s->has_pending = 1;
+    s->n_slots = 0; s->n_drafts = 0; s->round_closed = 0; s->draft_counter = 0;
+    return ORC_OK;
+}
 int32_t orc_committed_len(const orc_session *s) { return s->c; }
 int32_t orc_open_slots(const orc_session *s) { return s->n_slots; }
 int32_t orc_slot_reached(const orc_session *s, int32_t i) { return s->slots[i].reached; }
@@ -322,6 +341,10 @@ void orc_slot_hidden(const orc_session *s, int32_t i, double *out) {
 }
 void orc_head_logits(const orc_session *s, double *out) {
     for (int32_t k = 0; k < s->m->cfg.vocab; ++k) out[k] = (double)s->head_logits[k];
+}
+void orc_verify_dist(const orc_session *s, int32_t row, double *out) {
+    if (row < 0 || row >= ORC_MAX_W) return;
+    for (int32_t j = 0; j < s->m->cfg.vocab; ++j) out[j] = (double)s->verify_dist[(size_t)row * s->m->cfg.vocab + j];
 }
 void orc_verify_logits(const orc_session *s, int32_t row, double *out) {
     const real *z = s->verify_logits + (size_t)row * s->m->cfg.vocab;
@@ -451,6 +474,55 @@ static int32_t final_head(orc_session *s, const real *h, real *logits) {
     return im;
 }
 
+/* Distribution a token is sampled from (Sec. 4.3, sampling strategies: temperature, top-p):
+ * p_j proportional to exp(z_j / temp); with top_p < 1 only the nucleus keeps its mass -- the
+ * tokens of the shortest prefix, in order of decreasing probability, whose mass reaches top_p,
+ * together with every token as probable as the last of them (ties are not split) -- and is
+ * renormalised.  `tmp` is scratch of V reals. */
+void orc_sample_dist(const real *z, int32_t V, real temp, real top_p, real *p, real *tmp) {
+    real zmax = z[0];
+    for (int32_t j = 1; j < V; ++j)
+        if (z[j] > zmax) zmax = z[j];
+    real sum = 0;
+    for (int32_t j = 0; j < V; ++j) { p[j] = R_EXP((z[j] - zmax) / temp); sum += p[j]; }
+    for (int32_t j = 0; j < V; ++j) p[j] /= sum;
+    if (!(top_p < (real)1)) return;
+    /* selection sort of the largest values until their mass reaches top_p: plain and quadratic
+     * in the nucleus size, which is small whenever a nucleus is worth taking */
+    memcpy(tmp, p, sizeof(real) * V);
+    real mass = 0, cut = 0;
+    for (int32_t k = 0; k < V; ++k) {
+        int32_t im = 0;
+        for (int32_t j = 1; j < V; ++j)
+            if (tmp[j] > tmp[im]) im = j;
+        cut = tmp[im];
+        mass += cut;
+        tmp[im] = -1;
+        if (mass >= top_p) break;
+    }
+    real keep = 0;
+    for (int32_t j = 0; j < V; ++j) { if (p[j] < cut) p[j] = 0; keep += p[j]; }
+    for (int32_t j = 0; j < V; ++j) p[j] /= keep;
+}
+
+/* Inverse-CDF draw with the uniform u in [0, 1) from p, tokens in index order, leaving out
+ * token `exclude` (-1: none) and renormalising the rest: the first j with
+ * sum_{k <= j, k != exclude} p_k > u * sum_{k != exclude} p_k. */
+int32_t orc_sample_token(const real *p, int32_t V, real u, int32_t exclude) {
+    real total = 0;
+    for (int32_t j = 0; j < V; ++j)
+        if (j != exclude) total += p[j];
+    real target = u * total, c = 0;
+    int32_t last = -1;
+    for (int32_t j = 0; j < V; ++j) {
+        if (j == exclude || !(p[j] > 0)) continue;
+        c += p[j];
+        last = j;
+        if (c > target) return j;
+    }
+    return last;   /* rounding at the upper end: the last token that has mass */
+}
+
 static int check_params(const orc_session *s, const orc_params *p) {
     const orc_config *c = &s->m->cfg;
     if (!p) return ORC_EINVAL;
@@ -460,6 +532,8 @@ static int check_params(const orc_session *s, const orc_params *p) {
     for (int32_t l = 0; l < p->d_max; ++l)
         if (!(p->T[l] > 0)) return ORC_EINVAL;
     if (p->head_mask && p->d_max > 32) return ORC_EINVAL;   /* the mask has 32 bits */
+    if (p->sample_temperature < 0 || (p->sample_temperature > 0 && (!p->sample_u || !(p->top_p > 0) || p->top_p > 1)))
+        return ORC_EINVAL;
     return ORC_OK;
 }
 
@@ -593,7 +667,33 @@ int32_t orc_verify(orc_session *s, const orc_params *p, orc_verify_result *res) 
     for (int32_t i = 0; i < M; ++i)
         g[i] = final_head(s, s->slots[i].h, s->verify_logits + (size_t)i * c->vocab);
     int32_t m = 0;
-    while (m < s->n_drafts && m < M && s->drafts[m] == g[m]) ++m;
+    if (p->sample_temperature > 0) {
+        /* Sampling-mode verification.  The paper reports it (Sec. 4.3, Table 3) without giving
+         * the rule; taken here: the rule of speculative sampling for a draft that was proposed
+         * deterministically (the exit head's arg max x_i, as in greedy mode).  With P_i the
+         * distribution the full model samples from after row i (temperature, top-p):
+         *   draft x_i is accepted with probability P_i(x_i)            (u_accept < P_i(x_i));
+         *   at the first rejection the token is drawn from P_i without x_i, renormalised;
+         *   if every draft is accepted and a further row exists, its token is drawn from P_i.
+         * Then Pr[token = x] = P(x) and Pr[token = y != x] = (1 - P(x)) P(y) / (1 - P(x)) = P(y):
+         * every emitted token is distributed as the full model's own sample, and a temperature
+         * towards 0 gives back the greedy rule.  min(m + 1, rows) tokens are emitted as before. */
+        if (p->n_sample_u < 2 * (int64_t)(s->slots[M - 1].pos + 1)) return ORC_EINVAL;
+        for (int32_t i = 0; i < M; ++i)
+            orc_sample_dist(s->verify_logits + (size_t)i * c->vocab, c->vocab, (real)p->sample_temperature,
+                            (real)p->top_p, s->verify_dist + (size_t)i * c->vocab, s->sort_buf);
+        while (m < s->n_drafts && m < M) {
+            const real *P = s->verify_dist + (size_t)m * c->vocab;
+            if ((real)p->sample_u[2 * (int64_t)s->slots[m].pos] < P[s->drafts[m]]) { g[m] = s->drafts[m]; ++m; }
+            else break;
+        }
+        if (m < M)
+            g[m] = orc_sample_token(s->verify_dist + (size_t)m * c->vocab, c->vocab,
+                                    (real)p->sample_u[2 * (int64_t)s->slots[m].pos + 1], m < s->n_drafts ? s->drafts[m] : -1);
+        for (int32_t i = m + 1; i < M; ++i) g[i] = -1;   /* rows past the first rejection decide nothing */
+    } else {
+        while (m < s->n_drafts && m < M && s->drafts[m] == g[m]) ++m;
+    }
     int32_t n_emit = m + 1 < M ? m + 1 : M;
     res->n_rows = M; res->n_drafts = s->n_drafts; res->n_matched = m; res->n_emit = n_emit;
     res->align_layer = D;

@@ -115,3 +115,22 @@ class NearTies:
                 self.flag(f"{where} row {i}", osn.verify_logits(i), b)
                 return
         raise AssertionError(f"{where}: emitted counts differ with equal tokens: {vo} vs {vg}")
+
+
+# ---------------------------------------------------------------- planted mistakes (CPU)
+def oracle_with_mistake(monkeypatch, tmp_path, old, new):
+    """Build the oracle from a copy of its source with `old` replaced by `new` and make the
+    oracle package load that build for the rest of the test (monkeypatch undoes it)."""
+    import subprocess
+    import oracle.oracle as orc_mod
+    import oracle.build as orc_build
+    src = open(orc_build.SRC).read()
+    assert src.count(old) == 1, "mutation site not unique in the oracle source"
+    msrc = tmp_path / "mutant.c"
+    msrc.write_text(src.replace(old, new))
+    paths = {}
+    for bits, defs in ((64, []), (32, ["-DORC_F32"])):
+        paths[bits] = str(tmp_path / f"libmut{bits}.so")
+        subprocess.check_call(["gcc", *orc_build.FLAGS, *defs, str(msrc), "-o", paths[bits], "-lm"])
+    monkeypatch.setattr(orc_build, "lib_path", lambda bits: paths[bits])
+    monkeypatch.setattr(orc_mod, "_libs", {})

@@ -8,18 +8,12 @@ restores the greedy tokens), so the step is recomputed here from the hidden stat
 oracle exposes, with numpy and with the separately pinned primitives.  The second half
 plants the corresponding mistakes into a copy of the oracle's source, one at a time, and
 requires that the pins above turn red for each of them.  CPU only."""
-import ctypes as C
-import os
-import subprocess
-
 import numpy as np
 import pytest
 
 import sb_inputs as si
 import oracle as orc
-import oracle.oracle as orc_mod
-import oracle.build as orc_build
-from helpers import tiny_model, params
+from helpers import tiny_model, params, oracle_with_mistake
 
 D_MAX = 5
 T_DISTINCT = [3.0, 0.7, 1.9, 1.3, 0.55]       # no symmetry: T[l-1] != T[d_max-l] for every l
@@ -132,17 +126,7 @@ MUTANTS = {
 
 @pytest.mark.parametrize("name", sorted(MUTANTS))
 def test_planted_mistake_turns_a_pin_red(name, tmp_path, monkeypatch):
-    old, new = MUTANTS[name]
-    src = open(orc_build.SRC).read()
-    assert src.count(old) == 1, f"mutation site of {name} not unique in the oracle source"
-    msrc = tmp_path / "mutant.c"
-    msrc.write_text(src.replace(old, new))
-    paths = {}
-    for bits, defs in ((64, []), (32, ["-DORC_F32"])):
-        paths[bits] = str(tmp_path / f"libmut{bits}.so")
-        subprocess.check_call(["gcc", *orc_build.FLAGS, *defs, str(msrc), "-o", paths[bits], "-lm"])
-    monkeypatch.setattr(orc_build, "lib_path", lambda bits: paths[bits])
-    monkeypatch.setattr(orc_mod, "_libs", {})
+    oracle_with_mistake(monkeypatch, tmp_path, *MUTANTS[name])
     red = 0
     for pin in PINS:
         try:
