@@ -11,16 +11,32 @@ resident in HBM when the timed region starts.  Prints one JSON line.
 """
 import argparse
 import json
+import os
+import re
 import sys
 import time
 
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes fetched per launch of the gate/up projection at the C2 shape, from
-# rocprofv3 --pmc FETCH_SIZE scaled by the same counter's reading on the plain copy
-# kernel (2.000 KiB per count); summary in profiles/c2_projection_hbm_traffic.txt
-MEASURED_TRAFFIC = {"C2": 88201.1 * 2.0 * 1024}
+ROOT = os.path.dirname(os.path.abspath(__file__))
+# Where the counter-measured HBM traffic of the dominant kernel is kept: a rocprofv3 --pmc
+# summary (FETCH_SIZE / WRITE_SIZE scaled by the same counters' readings on the plain copy
+# kernel).  The bench line quotes the figure from that file and names it; null without it.
+TRAFFIC_PROFILE = {"C2": "profiles/c2_projection_hbm_traffic.txt"}
+KERNEL_PROFILE = {"C2": "profiles/c2_bench_kernel_trace.txt"}
+
+
+def measured_traffic(config):
+    """(bytes per launch, file) from the line 'traffic_bytes_per_launch = <number>' of the profile summary."""
+    rel = TRAFFIC_PROFILE.get(config)
+    if not rel:
+        return None, None
+    try:
+        m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(os.path.join(ROOT, rel)).read(), re.M)
+    except OSError:
+        return None, None
+    return (float(m.group(1)), rel) if m else (None, None)
 
 
 def log(*a):
@@ -69,14 +85,16 @@ def main():
     log(f"[bench] {wl.name}: weights generated in {time.time() - t0:.1f}s")
     t0 = time.time()
     proj = {"auto": sb.PROJ_AUTO, "valu": sb.PROJ_VALU, "mfma": sb.PROJ_MFMA}[args.proj]
+    log(f"[bench] uploading the weights and packing the projections ...")
     model = sb.Model(shape, weights, max_seq, device="cuda:0", proj_kernel=proj)
     sess = model.session()
     torch.cuda.synchronize()
-    log(f"[bench] uploaded in {time.time() - t0:.1f}s")
+    log(f"[bench] uploaded and packed in {time.time() - t0:.1f}s")
     prompt = si.make_prompt(shape.vocab, P, wl.prompt_seed)
     T = wl.temperatures()
 
     # ---- prefill (reported separately, not part of a step)
+    log(f"[bench] prefill of {P} tokens ...")
     t0 = time.perf_counter()
     first = sess.prefill(prompt)
     prefill_first_ms = (time.perf_counter() - t0) * 1e3   # includes one-off kernel loading
@@ -101,6 +119,26 @@ def main():
     log(f"[bench] greedy AR: {ar_tok_s:.1f} tok/s ({ar_bytes_per_tok / 1e9:.2f} GB/token, "
         f"{ar_tok_s * ar_bytes_per_tok / 1e9:.0f} GB/s algorithmic)")
     greedy = [first] + G.tolist()
+
+    def kernel_table(allp, pair_us):
+        out = {}
+        for k, v in allp.items():
+            raw = v["total_ms"] * 1e3 / v["launches"]
+            us = max(raw - pair_us, 0.1)
+            gbs = v["bytes"] / v["launches"] / us / 1e3
+            out[k] = {"launches": v["launches"], "avg_us": round(us, 2), "avg_us_events_raw": round(raw, 2),
+                      "GB/s": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+        return out
+
+    # per-kernel table of the greedy decoder: one stream, one row, nothing runs beside a kernel
+    kernels_greedy = None
+    if not args.no_kernel_table:
+        sess.rewind(P, first)
+        sess.profile_begin(None, max_launches=1 << 18)
+        sess.decode(min(n_ar, 128), p_ar)
+        kernels_greedy = kernel_table(sess.profile_end(), sess.empty_pair_ms * 1e3)
+        for k, v in kernels_greedy.items():
+            log(f"[bench]   greedy {k:12s} {v['launches']:7d} launches  {v['avg_us']:8.2f} us  {v['GB/s']:8.1f} GB/s")
 
     # ---- forced schedule: exit layer ~ U{exit_lo..d_max}, emitted tokens per round ~ U{1..w_max},
     # realised by draft injection so that verification is real and the output stays greedy
@@ -144,31 +182,48 @@ def main():
     gu_raw_us = gu["total_ms"] * 1e3 / gu["launches"]
     gu_us = gu_raw_us - pair_us
     gu_bytes = gu["bytes"] / gu["launches"]
+    traffic, traffic_file = measured_traffic(args.config) if not (args.gen or head_mask) else (None, None)
+    # `avg_us` is what the events read minus what an empty event pair reads (the bracket's own
+    # cost): the figure that agrees with rocprofv3's kernel duration in the named profile.  The
+    # unsubtracted reading and the fraction it would give stand beside it.
     roofline = {"bound": "hbm", "kernel": "gate_up projection + SwiGLU (gemv_mfma_kernel<2,SWIGLU,4,packed>)",
                 "achieved": round(gu_bytes / gu_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gu_bytes / gu_us / 1e3 / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get(args.config) if not args.gen else None,
-                "traffic_note": "HBM read bytes per launch (FETCH_SIZE, calibrated on a copy kernel); "
-                                "the kernel writes < 0.4 MB",
+                "frac_from_raw_event_time": round(gu_bytes / gu_raw_us / 1e3 / HBM_PEAK_GBS, 4),
+                "traffic": traffic, "traffic_source": traffic_file,
+                "traffic_note": "HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by "
+                                "the same counter's reading on the plain copy kernel (file named in traffic_source); "
+                                "null when that file does not cover this workload",
+                "rocprofv3_summary": KERNEL_PROFILE.get(args.config),
                 "bytes_per_launch": int(gu_bytes), "avg_us": round(gu_us, 2), "avg_us_events_raw": round(gu_raw_us, 2),
                 "empty_event_pair_us": round(pair_us, 2), "timed_launches": gu["launches"],
-                "timing": "HIP events around every 16th launch inside the timed steps, minus the time an "
-                          "empty event pair reads"}
+                "timing": "HIP events on the library's stream around every 16th launch inside the timed steps; "
+                          "avg_us = raw reading minus the reading of an empty event pair"}
 
-    kernels = None
+    kernels = phases = None
     if not args.no_kernel_table:
         sess.profile_begin(None, max_launches=1 << 18)
         step()
-        allp = sess.profile_end()
-        pu = sess.empty_pair_ms * 1e3
-        kernels = {}
-        for k, v in allp.items():
-            us = max(v["total_ms"] * 1e3 / v["launches"] - pu, 0.1)
-            gbs = v["bytes"] / v["launches"] / us / 1e3
-            kernels[k] = {"launches": v["launches"], "avg_us": round(us, 2), "GB/s": round(gbs, 1),
-                          "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+        kernels = kernel_table(sess.profile_end(), sess.empty_pair_ms * 1e3)
         for k, v in kernels.items():
             log(f"[bench]   {k:12s} {v['launches']:7d} launches  {v['avg_us']:8.2f} us  {v['GB/s']:8.1f} GB/s")
+        # time account of one more step, phase by phase (events at the phase boundaries of every round)
+        sess.phase_timing(True)
+        _, pst = step()
+        sess.phase_timing(False)
+        phases = {}
+        for ph in ("draft", "align", "verify"):
+            ms, by = pst[f"gpu_{ph}_ms"], pst[f"{ph}_bytes"]
+            phases[ph] = {"gpu_ms": round(ms, 2), "algorithmic_GB": round(by / 1e9, 2),
+                          "GB/s": round(by / 1e6 / ms, 1) if ms > 0 else None,
+                          "frac_of_hbm_peak": round(by / 1e6 / ms / HBM_PEAK_GBS, 4) if ms > 0 else None}
+        phases["readback_gpu_ms"] = round(pst["gpu_readback_ms"], 2)
+        phases["host_enqueue_draft_ms"] = round(pst["host_draft_ms"], 2)
+        phases["host_enqueue_verify_ms"] = round(pst["host_verify_ms"], 2)
+        phases["host_wait_ms"] = round(pst["host_wait_ms"], 2)
+        phases["note"] = ("draft: layers and exit heads of all draft steps of a round, the exit heads beside the following "
+                          "layer on a second stream (bytes of both / time of the phase); verify: remaining layers + final head")
+        log("[bench]   phases: " + ", ".join(f"{k} {v['gpu_ms']} ms {v['GB/s']} GB/s" for k, v in phases.items() if isinstance(v, dict)))
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -193,7 +248,8 @@ def main():
         "tokens_per_round": round(st["emitted"] / st["rounds"], 3), "prefill_ms": round(prefill_ms, 1), "prefill_first_call_ms": round(prefill_first_ms, 1),
         "algorithmic_GB_per_step": round(spec_bytes / 1e9, 2),
         "algorithmic_GBps_whole_path": round(spec_bytes / 1e6 / ms_per_step, 1),
-        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+        "greedy_algorithmic_GBps_whole_path": round(ar_tok_s * ar_bytes_per_tok / 1e9, 1),
+        "roofline": roofline, "kernels": kernels, "kernels_greedy": kernels_greedy, "phases": phases, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
 
@@ -217,24 +273,31 @@ def copy_probe(torch, sb):
 
 
 def cpu_baseline(shape, weights, prompt, wl):
-    """The oracle's greedy decoding on the host cores, on a bounded sample."""
-    from oracle import Oracle, OrcParams, num_threads
+    """The oracle's greedy decoding on the host cores, on a bounded sample: the double build
+    (the parity reference) and the float build."""
+    from oracle import Oracle, num_threads
     n_prompt = 4
-    om = Oracle(shape, weights, 64)
-    s = om.session()
-    t0 = time.perf_counter()
-    s.prefill(prompt[:n_prompt])
-    per_tok = (time.perf_counter() - t0) / n_prompt
-    n = int(max(2, min(24, 15.0 / max(per_tok, 1e-3))))
-    t0 = time.perf_counter()
-    tok = 0
-    for _ in range(n):
-        tok, _ = s.step(tok, want_logits=False)
-    dt = time.perf_counter() - t0
-    log(f"[bench] oracle: {n / dt:.2f} tok/s on {num_threads()} threads")
-    return {"value": round(n / dt, 3), "unit": "tokens/s", "cores": num_threads(), "kind": "oracle",
-            "sample": f"greedy decoding of {n} tokens after a {n_prompt}-token prompt at the {wl.name} shape "
-                      "(double-precision oracle, teacher-forced)"}
+    res = {}
+    for bits in (64, 32):
+        om = Oracle(shape, weights, 64, bits=bits)
+        s = om.session()
+        t0 = time.perf_counter()
+        s.prefill(prompt[:n_prompt])
+        per_tok = (time.perf_counter() - t0) / n_prompt
+        n = int(max(2, min(24, 8.0 / max(per_tok, 1e-3))))
+        t0 = time.perf_counter()
+        tok = 0
+        for _ in range(n):
+            tok, _ = s.step(tok, want_logits=False)
+        dt = time.perf_counter() - t0
+        res[bits] = (n, n / dt)
+        log(f"[bench] oracle ({'double' if bits == 64 else 'float'}): {n / dt:.2f} tok/s on {num_threads()} threads")
+        del s, om
+    return {"value": round(res[64][1], 3), "unit": "tokens/s", "cores": num_threads(), "kind": "oracle",
+            "float_build_value": round(res[32][1], 3),
+            "sample": f"greedy decoding of {res[64][0]} tokens after a {n_prompt}-token prompt at the {wl.name} shape, "
+                      "teacher-forced: `value` is the double-precision build of the oracle (the parity reference), "
+                      f"`float_build_value` its float build ({res[32][0]} tokens)"}
 
 
 if __name__ == "__main__":

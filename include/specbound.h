@@ -13,15 +13,22 @@
  *
  * Conventions
  *  - Every call returns SB_OK (0) or a negative error; sb_last_error() gives the
- *    message of the calling thread's last failure.  A failing call leaves the
- *    session as it was.
+ *    message of the calling thread's last failure.  Arguments and state are
+ *    checked before anything is changed, so a call that fails with SB_EINVAL,
+ *    SB_ESTATE, SB_ECAPACITY or SB_ENOMEM leaves the session as it was.  When a
+ *    kernel launch or a copy fails inside sb_draft_step, sb_verify, sb_decode or
+ *    sb_generate (SB_EDEVICE), the open round is abandoned: its rows and drafts are
+ *    dropped, the committed tokens, their KV entries and the pending token stay as
+ *    they were, and the next draft step starts a new round.
  *  - "device" pointers are HIP device memory on the model's GPU; "host" pointers
  *    are ordinary memory.  Nothing the caller passes is freed by the library.
  *  - Weights are BORROWED: the device buffers named in sb_weights must outlive
  *    the model.  The host arrays of pointers are copied at load time.  With
- *    SB_PROJ_MFMA_PACKED sb_load_model also allocates a tile-packed copy of every
- *    projection matrix (same size) on the device; the embedding table and the norm
- *    gains are still read from the caller's buffers.
+ *    SB_PROJ_MFMA_PACKED sb_load_model makes a tile-packed copy of every projection
+ *    matrix (same size), into sb_weights.packed if the caller provides that buffer,
+ *    else into memory it allocates; the row-major projections are not read again
+ *    after the call.  The embedding table and the norm gains are always read from
+ *    the caller's buffers.
  *  - The KV pool and the workspace are caller-owned device memory, borrowed for
  *    the session's lifetime.  sb_query_sizes() says how large they must be.
  *  - All kernels are enqueued on the stream given to sb_load_model (a
@@ -66,6 +73,10 @@ typedef struct sb_config {
     int32_t n_exit_heads;
     int32_t max_seq;       /* capacity in tokens, a multiple of SB_KV_BLOCK */
     int32_t proj_kernel;   /* SB_PROJ_*; AUTO = MFMA_PACKED for bf16 weights, VALU for fp32 */
+    int32_t kv_block;      /* tokens per KV page: SB_KV_BLOCK, or 0 for that default (the page size is
+                              built into the attention kernels) */
+    int32_t max_w;         /* largest width bound the sessions of this model accept, 1..SB_MAX_W;
+                              0 = SB_MAX_W */
 } sb_config;
 
 /* Device pointers.  Matrices are row-major [out][in] in weight_dtype; norm gains
@@ -85,6 +96,15 @@ typedef struct sb_weights {
     const void *const *w_down; /* [d_model][d_ffn] */
     const float *const *exit_norm;
     const void *const *exit_head; /* [vocab][d_model] each */
+    /* SB_PROJ_MFMA_PACKED only.  Device buffer of packed_bytes >= sb_sizes.packed_weight_bytes,
+     * 256-byte aligned, that receives the tile-packed copy of every projection matrix and is
+     * borrowed for the model's lifetime (SB_ENOMEM if too small, SB_EINVAL if misaligned).
+     * NULL: the library allocates that copy itself and frees it in sb_free_model.  Either way,
+     * once sb_load_model has returned the row-major projection matrices (w_qkv, w_o, w_gate_up,
+     * w_down, exit_head, lm_head) are no longer read and may be released by the caller; embed
+     * and the norm gains stay borrowed. */
+    void *packed;
+    size_t packed_bytes;
 } sb_weights;
 
 /* Speculation parameters (Sec. 3.2-3.3; evaluation values in Sec. 4.1).  All
@@ -155,9 +175,15 @@ typedef struct sb_stats {
      * copy of the round record); filled only while sb_phase_timing is on. */
     double host_draft_ms, host_verify_ms, host_wait_ms;
     double gpu_draft_ms, gpu_align_ms, gpu_verify_ms, gpu_readback_ms;
+    /* algorithmic bytes (weights swept + K/V read) of the decode phase by phase: drafting
+     * (layers and exit heads), alignment, verification (remaining layers + final head) */
+    int64_t draft_bytes, align_bytes, verify_bytes;
 } sb_stats;
 
-typedef struct sb_sizes { size_t kv_pool_bytes, workspace_bytes; } sb_sizes;
+typedef struct sb_sizes {
+    size_t kv_pool_bytes, workspace_bytes;
+    size_t packed_weight_bytes; /* tile-packed copy of the projections (0 unless SB_PROJ_MFMA_PACKED) */
+} sb_sizes;
 
 typedef struct sb_model sb_model;
 typedef struct sb_session sb_session;
@@ -245,6 +271,13 @@ int32_t sb_debug_hidden(sb_session *s, int32_t slot, float *out, int32_t cap);
 /* K and V (as floats, n_kv_heads*head_dim each, host) cached for (layer, pos). */
 int32_t sb_debug_kv(sb_session *s, int32_t layer, int32_t pos, float *k_out, float *v_out, int32_t cap);
 
+/* Test tap: the n-th projection launch from now on (n >= 1) is not enqueued and reports a
+ * device error instead, as a failed launch would; 0 disarms.  Lets a host test walk the
+ * SB_EDEVICE path of sb_draft_step / sb_verify without a fault on the GPU. */
+int32_t sb_debug_fail_launch(sb_session *s, int32_t n);
+/* Open rows of the current round (0 between rounds). */
+int32_t sb_open_rows(const sb_session *s);
+
 /* ---- per-kernel timing with HIP events on the model's stream -------------- */
 enum { SB_K_RMSNORM = 0, SB_K_QKV, SB_K_ATTN, SB_K_WO, SB_K_GATEUP, SB_K_DOWN, SB_K_EXIT_HEAD,
        SB_K_FINAL_HEAD, SB_K_COUNT };
@@ -309,7 +342,7 @@ int32_t sb_op_copy(void *dst, const void *src, size_t nbytes, void *stream);
 /* Plain streaming read of nbytes (sum-reduced into *sink, 4 bytes, device). */
 int32_t sb_op_read(const void *src, size_t nbytes, float *sink, void *stream);
 
-/* The projection of the prompt passes (prefill is the base model's, Sec. 3.1): y [M][N] =
+/* The projection of the prompt passes (prefill is the base model's, Sec. 4.3): y [M][N] =
  * x [M][K] W^T for 1 <= M <= 128 rows against tile-packed bf16 weights (sb_op_repack),
  * N % 16 == 0, K % 128 == 0.  x is used as a bf16 high + low pair per element, products
  * accumulate in fp32 over k splits that are added in index order.  x, y, Wp, scratch:

@@ -32,7 +32,7 @@ class sb_config(C.Structure):
                                           "d_ffn", "vocab")] + \
                [("rms_eps", C.c_float), ("rope_base", C.c_float)] + \
                [(n, C.c_int32) for n in ("weight_dtype", "kv_dtype", "n_exit_heads", "max_seq",
-                                          "proj_kernel")]
+                                          "proj_kernel", "kv_block", "max_w")]
 
 
 class sb_weights(C.Structure):
@@ -40,7 +40,8 @@ class sb_weights(C.Structure):
                 ("attn_norm", C.POINTER(C.c_void_p)), ("w_qkv", C.POINTER(C.c_void_p)),
                 ("w_o", C.POINTER(C.c_void_p)), ("ffn_norm", C.POINTER(C.c_void_p)),
                 ("w_gate_up", C.POINTER(C.c_void_p)), ("w_down", C.POINTER(C.c_void_p)),
-                ("exit_norm", C.POINTER(C.c_void_p)), ("exit_head", C.POINTER(C.c_void_p))]
+                ("exit_norm", C.POINTER(C.c_void_p)), ("exit_head", C.POINTER(C.c_void_p)),
+                ("packed", C.c_void_p), ("packed_bytes", C.c_size_t)]
 
 
 class sb_params(C.Structure):
@@ -68,11 +69,13 @@ class sb_stats(C.Structure):
                 ("weight_bytes", C.c_int64), ("kv_bytes", C.c_int64),
                 ("prefill_ms", C.c_double), ("decode_ms", C.c_double)] + \
                [(n, C.c_double) for n in ("host_draft_ms", "host_verify_ms", "host_wait_ms", "gpu_draft_ms",
-                                          "gpu_align_ms", "gpu_verify_ms", "gpu_readback_ms")]
+                                          "gpu_align_ms", "gpu_verify_ms", "gpu_readback_ms")] + \
+               [(n, C.c_int64) for n in ("draft_bytes", "align_bytes", "verify_bytes")]
 
 
 class sb_sizes(C.Structure):
-    _fields_ = [("kv_pool_bytes", C.c_size_t), ("workspace_bytes", C.c_size_t)]
+    _fields_ = [("kv_pool_bytes", C.c_size_t), ("workspace_bytes", C.c_size_t),
+                ("packed_weight_bytes", C.c_size_t)]
 
 
 # every symbol include/specbound.h declares
@@ -82,7 +85,7 @@ SYMBOLS = ["sb_last_error", "sb_temperature_schedule", "sb_query_sizes", "sb_loa
            "sb_debug_kv", "sb_op_rmsnorm", "sb_op_gemv", "sb_op_gemv_scratch_bytes", "sb_op_head",
            "sb_op_head_scratch_bytes", "sb_rope_table_host", "sb_op_attention",
            "sb_op_attention_scratch_bytes", "sb_op_prompt_attention", "sb_decode", "sb_rewind", "sb_profile_begin", "sb_profile_end", "sb_op_copy",
-           "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes", "sb_op_head_static", "sb_phase_timing"]
+           "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes", "sb_op_head_static", "sb_phase_timing", "sb_debug_fail_launch", "sb_open_rows"]
 
 KERNEL_CLASSES = ["rmsnorm", "qkv", "attention", "wo", "gate_up", "down", "exit_head",
                   "final_head"]
@@ -120,6 +123,8 @@ def lib() -> C.CDLL:
         L.sb_profile_end.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_double)]
         L.sb_get_stats.argtypes = [vp, C.POINTER(sb_stats)]
         L.sb_phase_timing.argtypes = [vp, i32]
+        L.sb_debug_fail_launch.argtypes = [vp, i32]
+        L.sb_open_rows.argtypes = [vp]
         L.sb_committed_len.argtypes = [vp]
         L.sb_debug_enable.argtypes = [vp, i32]
         L.sb_debug_logits.argtypes = [vp, i32, i32, vp, i32]
@@ -153,17 +158,23 @@ def check(rc: int) -> None:
         raise SbError(rc, lib().sb_last_error().decode())
 
 
-def make_config(shape, max_seq: int, proj_kernel: int = PROJ_AUTO) -> sb_config:
+def make_config(shape, max_seq: int, proj_kernel: int = PROJ_AUTO, max_w: int = 0) -> sb_config:
     """shape: any object with the fields of sb_config (e.g. sb_inputs.ModelShape)."""
     return sb_config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                      shape.d_ffn, shape.vocab, shape.rms_eps, shape.rope_base, shape.weight_dtype,
-                     shape.kv_dtype, shape.n_exit_heads, max_seq, proj_kernel)
+                     shape.kv_dtype, shape.n_exit_heads, max_seq, proj_kernel, SB_KV_BLOCK, max_w)
 
 
 def query_sizes(cfg: sb_config):
     out = sb_sizes()
     check(lib().sb_query_sizes(C.byref(cfg), C.byref(out)))
     return out.kv_pool_bytes, out.workspace_bytes
+
+
+def packed_weight_bytes(cfg: sb_config) -> int:
+    out = sb_sizes()
+    check(lib().sb_query_sizes(C.byref(cfg), C.byref(out)))
+    return out.packed_weight_bytes
 
 
 def temperature_schedule(alpha: float, L: int, n: int) -> np.ndarray:
@@ -209,7 +220,10 @@ class Model:
     """
 
     def __init__(self, shape, weights: Dict[str, np.ndarray], max_seq: int, device: str = "cuda:0",
-                 proj_kernel: int = PROJ_AUTO, stream=None):
+                 proj_kernel: int = PROJ_AUTO, stream=None, own_packed: bool = True):
+        """own_packed: this object allocates the buffer of the tile-packed projections and hands it
+        to the library (and drops its row-major projection tensors after the load); False leaves
+        that allocation to the library."""
         import torch
         self.torch = torch
         self.device = torch.device(device)
@@ -240,12 +254,21 @@ class Model:
                             cast(self._arrs["attn_norm"]), cast(self._arrs["w_qkv"]), cast(self._arrs["w_o"]),
                             cast(self._arrs["ffn_norm"]), cast(self._arrs["w_gate_up"]),
                             cast(self._arrs["w_down"]), cast(self._arrs["exit_norm"]),
-                            cast(self._arrs["exit_head"]))
+                            cast(self._arrs["exit_head"]), None, 0)
+        self.packed = None
+        pbytes = packed_weight_bytes(self.cfg)
+        if own_packed and pbytes:
+            with torch.cuda.device(self.device):
+                self.packed = torch.empty(pbytes, dtype=torch.uint8, device=self.device)
+            self.w.packed, self.w.packed_bytes = self.packed.data_ptr(), pbytes
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         self.h = C.c_void_p()
         with torch.cuda.device(self.device):
             check(lib().sb_load_model(C.byref(self.cfg), C.byref(self.w), C.c_void_p(self.stream.cuda_stream),
                                       C.byref(self.h)))
+        if pbytes:   # the row-major projections are not read after the load
+            for k in [k for k in t if k.split(".")[0] in ("w_qkv", "w_o", "w_gate_up", "w_down", "exit_head", "lm_head")]:
+                del t[k]
 
     def session(self, page_order: Optional[Sequence[int]] = None) -> "Session":
         return Session(self, page_order)
@@ -348,6 +371,12 @@ class Session:
 
     def phase_timing(self, on: bool = True):
         check(lib().sb_phase_timing(self.h, int(on)))
+
+    def debug_fail_launch(self, n: int):
+        check(lib().sb_debug_fail_launch(self.h, n))
+
+    def open_rows(self) -> int:
+        return lib().sb_open_rows(self.h)
 
     def stats(self) -> dict:
         st = sb_stats()

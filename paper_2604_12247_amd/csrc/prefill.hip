@@ -1,6 +1,6 @@
 // gfx950 kernels of the prompt passes: the same decoder layer as a decode pass, for
 // up to SB_PREFILL_ROWS rows at once, so that the weights are streamed once per 128
-// prompt tokens instead of once per 8 (prefill is the base model's own, Sec. 3.1;
+// prompt tokens instead of once per 8 (prefill is the base model's own, Sec. 4.3;
 // only its cost matters, not its schedule).
 //
 // A projection is two kernels.  prefill_gemm_kernel streams the tile-packed bf16

@@ -58,6 +58,8 @@ int check_config(const sb_config* c) {
         return fail(SB_EINVAL, "config: d_model, d_ffn and n_heads*head_dim must be multiples of 8");
     if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return fail(SB_EINVAL, "config: rms_eps / rope_base");
     if (c->proj_kernel < SB_PROJ_AUTO || c->proj_kernel > SB_PROJ_MFMA_PACKED) return fail(SB_EINVAL, "config: proj_kernel");
+    if (c->kv_block != 0 && c->kv_block != SB_KV_BLOCK) return fail(SB_EINVAL, "config: kv_block must be %d (or 0)", SB_KV_BLOCK);
+    if (c->max_w < 0 || c->max_w > SB_MAX_W) return fail(SB_EINVAL, "config: max_w must be in 1..%d (or 0)", SB_MAX_W);
     if (c->proj_kernel == SB_PROJ_MFMA || c->proj_kernel == SB_PROJ_MFMA_PACKED) {
         if (c->weight_dtype != SB_BF16) return fail(SB_EINVAL, "config: the MFMA projection path needs bf16 weights");
         if (c->d_model % 128 || c->d_ffn % 128 || (c->n_heads * c->head_dim) % 128 || c->vocab % 16 || c->d_ffn % 16)
@@ -144,6 +146,16 @@ WsLayout ws_layout(const sb_config* c) {
     return L;
 }
 
+// Bytes of the tile-packed copy of all projection matrices, each 256-byte aligned.
+size_t packed_weight_bytes(const sb_config* c) {
+    if (resolve_proj(c) != SB_PROJ_MFMA_PACKED) return 0;
+    const size_t d = c->d_model, f = c->d_ffn, hq = (size_t)c->n_heads * c->head_dim, V = c->vocab;
+    const size_t qkv_rows = (size_t)(c->n_heads + 2 * c->n_kv_heads) * c->head_dim;
+    const size_t per_layer = align_up(qkv_rows * d * 2, 256) + align_up(d * hq * 2, 256) + align_up(2 * f * d * 2, 256) +
+                             align_up(d * f * 2, 256);
+    return per_layer * c->n_layers + align_up(V * d * 2, 256) * ((size_t)c->n_exit_heads + 1);
+}
+
 size_t kv_pool_bytes(const sb_config* c) {
     return (size_t)c->n_layers * 2 * (c->max_seq / SB_KV_BLOCK) * c->n_kv_heads * SB_KV_BLOCK * c->head_dim *
            esize(c->kv_dtype);
@@ -179,6 +191,8 @@ struct sb_session {
     int32_t draft_host[SB_MAX_W];  // drafted id if the host knows it, else -1
     bool round_closed;
     bool next_embedded;  // the last draft step's head merge has already embedded the next row
+    int fail_countdown;  // test tap: the n-th projection launch from now reports a failure
+    int64_t* phase_bytes;  // where run_layer / run_head account their bytes (a field of st), or null
     int64_t draft_counter;
     bool debug;
     sb_stats st;
@@ -211,7 +225,8 @@ T* wsp(sb_session* s, size_t off) { return reinterpret_cast<T*>(s->ws + off); }
 int check_params(const sb_session* s, const sb_params* p) {
     const sb_config& c = s->m->cfg;
     if (!p) return fail(SB_EINVAL, "params is NULL");
-    if (p->w_max < 1 || p->w_max > SB_MAX_W) return fail(SB_EINVAL, "w_max must be in 1..%d", SB_MAX_W);
+    const int wlim = c.max_w ? c.max_w : SB_MAX_W;
+    if (p->w_max < 1 || p->w_max > wlim) return fail(SB_EINVAL, "w_max must be in 1..%d", wlim);
     int dlim = c.n_exit_heads < c.n_layers - 1 ? c.n_exit_heads : c.n_layers - 1;
     if (p->d_max < 0 || p->d_max > dlim) return fail(SB_EINVAL, "d_max must be in 0..%d", dlim);
     if (p->d_max > 0 && !p->T) return fail(SB_EINVAL, "T is NULL");
@@ -266,6 +281,8 @@ int64_t gemv_bytes(const GemvArgs& a) {
 
 int gemv(sb_session* s, GemvArgs& a, int cls, hipStream_t st) {
     a.packed = s->m->packed ? 1 : 0;
+    if (s->fail_countdown > 0 && --s->fail_countdown == 0)   // test tap (sb_debug_fail_launch)
+        return fail(SB_EDEVICE, "projection launch (N=%d K=%d M=%d epi=%d): injected failure", a.N, a.K, a.M, a.epi);
     ProfScope ps(s, cls, gemv_bytes(a), st);
     hipError_t e = s->m->proj == SB_PROJ_MFMA ? launch_gemv_mfma(a, st) : launch_gemv_valu(a, st);
     if (e != hipSuccess) return fail(SB_EDEVICE, "projection launch (N=%d K=%d M=%d epi=%d): %s", a.N, a.K, a.M, a.epi,
@@ -354,6 +371,7 @@ int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
     s->st.row_layers += M;
     s->st.weight_bytes += m->layer_bytes;
     s->st.kv_bytes += kv_read;
+    if (s->phase_bytes) *s->phase_bytes += m->layer_bytes + kv_read;
     return SB_OK;
 }
 
@@ -384,6 +402,7 @@ int run_head(sb_session* s, const void* W, const float* gain, int slot0, int M, 
     int rc = gemv(s, g, h.post == POST_EXIT ? SB_K_EXIT_HEAD : SB_K_FINAL_HEAD, st);
     if (rc) return rc;
     s->st.weight_bytes += m->head_bytes;
+    if (s->phase_bytes) *s->phase_bytes += m->head_bytes;
     return SB_OK;
 }
 
@@ -402,6 +421,7 @@ EmbedNorm embed_norm(sb_session* s, int slot0) {
 void reset_session(sb_session* s) {
     s->c = 0; s->has_pending = false; s->n_slots = 0; s->n_drafts = 0; s->round_closed = false;
     s->next_embedded = false;
+    s->phase_bytes = nullptr;   // (prefill: counted in the totals only)
     s->draft_counter = 0;
     memset(&s->st, 0, sizeof s->st);
 }
@@ -604,6 +624,7 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
         HIP_TRY(launch_embed(m->embed, c.weight_dtype, c.vocab, c.d_model, Hrow, 1, t, s->d_round->slot_tok + idx,
                              &s->d_round->exit_flag, embed_norm(s, idx), m->stream));
     s->next_embedded = false;
+    s->phase_bytes = &s->st.draft_bytes;
     // a draft that exits is embedded as the next row by its own head merge, if a next step can follow
     const bool embed_next = s->n_drafts + 1 < p->w_max && idx + 1 < SB_MAX_W;
     s->draft_counter++;
@@ -692,6 +713,7 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     for (int j = 1; j < M; ++j)
         if (s->reached[j] > s->reached[j - 1]) return fail(SB_ESTATE, "verify: reached layers not monotone");
     // align: rows standing below the deepest layer reached catch up (Appendix A)
+    s->phase_bytes = &s->st.align_bytes;
     for (int l = 2; l <= D; ++l) {
         int j0 = M;
         while (j0 > 0 && s->reached[j0 - 1] == l - 1) --j0;
@@ -700,6 +722,7 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
         for (int j = j0; j < M; ++j) s->reached[j] = l;
     }
     if (pt) HIP_TRY(hipEventRecord(s->ev_ph[2], m->stream));   // aligned
+    s->phase_bytes = &s->st.verify_bytes;
     // one parallel pass of all rows through the remaining layers
     for (int l = D + 1; l <= c.n_layers; ++l) {
         if ((rc = run_layer(s, l - 1, 0, M, l == c.n_layers ? m->final_norm : nullptr))) return rc;
@@ -739,6 +762,22 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     return SB_OK;
 }
 
+hipError_t sync_all(sb_session* s);
+
+// A launch or copy failed in the middle of a round: what the rows of the round hold on the
+// device is no longer what the host's bookkeeping says, so the round is dropped as a whole.
+// Committed positions (< c) were not touched by it: rows only write positions >= c.
+int round_guard(sb_session* s, int rc) {
+    if (rc != SB_EDEVICE) return rc;
+    const std::string msg = g_err;
+    (void)sync_all(s);
+    s->draft_counter -= s->n_slots;   // the abandoned steps' entries of the forced schedule are taken again
+    if (s->draft_counter < 0) s->draft_counter = 0;
+    s->n_slots = 0; s->n_drafts = 0; s->round_closed = false; s->next_embedded = false;
+    g_err = msg + " (the open round was abandoned)";
+    return rc;
+}
+
 hipError_t sync_all(sb_session* s) {
     hipError_t e = hipStreamSynchronize(s->m->stream);
     if (e == hipSuccess && s->head_stream) e = hipStreamSynchronize(s->head_stream);
@@ -771,11 +810,11 @@ int decode_impl(sb_session* s, const sb_params* p, int32_t* out_tokens, int* cnt
         sb_draft_result dr;
         const double th0 = now_ms();
         do {
-            if ((rc = draft_step_impl(s, p, &dr, false))) return rc;
+            if ((rc = draft_step_impl(s, p, &dr, false))) return round_guard(s, rc);
         } while (dr.status == SB_EXITED);
         const double th1 = now_ms(), w0 = s->st.host_wait_ms;
         sb_verify_result vr;
-        if ((rc = verify_impl(s, p, &vr))) return rc;
+        if ((rc = verify_impl(s, p, &vr))) return round_guard(s, rc);
         s->st.host_draft_ms += th1 - th0;
         s->st.host_verify_ms += (now_ms() - th1) - (s->st.host_wait_ms - w0);
         int take = 0;
@@ -813,6 +852,7 @@ int32_t sb_query_sizes(const sb_config* cfg, sb_sizes* out) {
     if (!out) return fail(SB_EINVAL, "query_sizes: out is NULL");
     out->kv_pool_bytes = kv_pool_bytes(cfg);
     out->workspace_bytes = ws_layout(cfg).total;
+    out->packed_weight_bytes = packed_weight_bytes(cfg);
     return SB_OK;
 }
 
@@ -824,6 +864,12 @@ int32_t sb_load_model(const sb_config* cfg, const sb_weights* w, void* stream, s
         !w->w_gate_up || !w->w_down)
         return fail(SB_EINVAL, "load_model: NULL weight pointer");
     if (cfg->n_exit_heads > 0 && (!w->exit_norm || !w->exit_head)) return fail(SB_EINVAL, "load_model: NULL exit heads");
+    const size_t pack_need = packed_weight_bytes(cfg);
+    if (w->packed && pack_need) {
+        if ((uintptr_t)w->packed & 255) return fail(SB_EINVAL, "load_model: the packed-weight buffer must be 256-byte aligned");
+        if (w->packed_bytes < pack_need)
+            return fail(SB_ENOMEM, "load_model: packed-weight buffer too small (%zu < %zu)", w->packed_bytes, pack_need);
+    }
     sb_model* m = new sb_model();
     m->cfg = *cfg;
     m->embed = w->embed; m->lm_head = w->lm_head; m->final_norm = w->final_norm;
@@ -869,12 +915,17 @@ int32_t sb_load_model(const sb_config* cfg, const sb_weights* w, void* stream, s
     // tile-packed copies of the projection matrices
     if (e == hipSuccess && m->packed) {
         const int d = cfg->d_model, f = cfg->d_ffn, hq = cfg->n_heads * cfg->head_dim, V = cfg->vocab;
+        // one buffer for all packed matrices: the caller's, or one the model owns
+        char* pbase = (char*)w->packed;
+        if (!pbase) {
+            e = hipMalloc((void**)&pbase, pack_need);
+            if (e == hipSuccess) m->owned.push_back(pbase);
+        }
+        size_t poff = 0;
         auto pack = [&](const void*& W, int N, int K) {
             if (e != hipSuccess) return;
-            void* P = nullptr;
-            e = hipMalloc(&P, (size_t)N * K * 2);
-            if (e != hipSuccess) return;
-            m->owned.push_back(P);
+            void* P = pbase + poff;
+            poff += align_up((size_t)N * K * 2, 256);
             e = launch_repack(W, P, N, K, m->stream);
             W = P;
         };
@@ -944,6 +995,7 @@ int32_t sb_new_session(sb_model* m, void* kv_pool, size_t kv_bytes, void* worksp
     for (int i = 0; i < 4; ++i) { s->ev_main[i] = nullptr; s->ev_head[i] = nullptr; }
     s->h_round = nullptr;
     s->phase_timing = false;
+    s->fail_countdown = 0;
     for (int i = 0; i < 5; ++i) s->ev_ph[i] = nullptr;
     reset_session(s);
     hipError_t e = hipHostMalloc((void**)&s->h_round, sizeof(DevRound), hipHostMallocDefault);
@@ -979,12 +1031,12 @@ int32_t sb_prefill(sb_session* s, const int32_t* prompt, int32_t n, int32_t* fir
 
 int32_t sb_draft_step(sb_session* s, const sb_params* p, sb_draft_result* out) {
     if (!s || !out) return fail(SB_EINVAL, "draft_step: NULL argument");
-    return draft_step_impl(s, p, out, true);
+    return round_guard(s, draft_step_impl(s, p, out, true));
 }
 
 int32_t sb_verify(sb_session* s, const sb_params* p, sb_verify_result* out) {
     if (!s || !out) return fail(SB_EINVAL, "verify: NULL argument");
-    return verify_impl(s, p, out);
+    return round_guard(s, verify_impl(s, p, out));
 }
 
 int32_t sb_generate(sb_session* s, const int32_t* prompt, int32_t n, int32_t max_new, const sb_params* p,
@@ -1117,6 +1169,14 @@ int32_t sb_phase_timing(sb_session* s, int32_t on) {
     s->phase_timing = on != 0;
     return SB_OK;
 }
+
+int32_t sb_debug_fail_launch(sb_session* s, int32_t n) {
+    if (!s || n < 0) return fail(SB_EINVAL, "debug_fail_launch: bad argument");
+    s->fail_countdown = n;
+    return SB_OK;
+}
+
+int32_t sb_open_rows(const sb_session* s) { return s ? s->n_slots : SB_EINVAL; }
 
 int32_t sb_get_stats(const sb_session* s, sb_stats* out) {
     if (!s || !out) return fail(SB_EINVAL, "get_stats: NULL argument");

@@ -25,10 +25,10 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layouts_match_header_sizes():
-    assert C.sizeof(B.sb_config) == 14 * 4
+    assert C.sizeof(B.sb_config) == 16 * 4
     assert C.sizeof(B.sb_draft_result) == 16
     assert C.sizeof(B.sb_verify_result) == (5 + sb.SB_MAX_W) * 4
-    assert C.sizeof(B.sb_stats) == 8 * 8 + 9 * 8 + 65 * 8 + 2 * 8 + 2 * 8 + 7 * 8
+    assert C.sizeof(B.sb_stats) == 8 * 8 + 9 * 8 + 65 * 8 + 2 * 8 + 2 * 8 + 7 * 8 + 3 * 8
 
 
 def test_temperature_schedule_eq1(golden):
@@ -106,3 +106,45 @@ def test_null_and_invalid_arguments_are_rejected_on_the_host():
     assert L.sb_op_prompt_attention(p, 4, 4, 32, p, p, 2, 0, p, p, 0, 4, p, None) == sb.EINVAL       # head_dim
     assert L.sb_op_prompt_attention(p, 4, 4, 64, p, p, 2, 0, p, p, 0, 4, None, None) == sb.EINVAL
     assert L.sb_op_gemm_scratch_bytes(4096, 4096) >= 2 * 128 * 4096 * 2 + 128 * 4096 * 4
+
+
+def test_new_config_fields_and_sizes_are_validated_on_the_host():
+    L = sb.lib()
+    shape = si.CONFIGS["C2"].shape
+    cfg = sb.make_config(shape, 1040)
+    out = B.sb_sizes()
+    assert L.sb_query_sizes(C.byref(cfg), C.byref(out)) == 0
+    # every projection matrix once more, tile-packed (each a multiple of 256 bytes here)
+    es = 2
+    per_layer = es * (shape.qkv_rows * shape.d_model + shape.d_model * shape.n_heads * shape.head_dim
+                      + 3 * shape.d_ffn * shape.d_model)
+    assert out.packed_weight_bytes == shape.n_layers * per_layer + (shape.n_exit_heads + 1) * es * shape.vocab * shape.d_model
+    c1 = sb.make_config(si.CONFIGS["C1"].shape, 112)      # fp32 weights: no packed copy
+    assert sb.packed_weight_bytes(c1) == 0
+    for kw in (dict(kv_block=32), dict(max_w=9), dict(max_w=-1)):
+        cfg = sb.make_config(shape, 1040)
+        for k, v in kw.items():
+            setattr(cfg, k, v)
+        assert L.sb_query_sizes(C.byref(cfg), C.byref(out)) == sb.EINVAL, kw
+    cfg = sb.make_config(shape, 1040)
+    cfg.kv_block, cfg.max_w = 0, 0                         # defaults
+    assert L.sb_query_sizes(C.byref(cfg), C.byref(out)) == 0
+    # a packed-weight buffer that is misaligned or too small is refused before any device call
+    w = B.sb_weights()
+    dummy = np.zeros(64, np.float32)
+    ptr = dummy.ctypes.data
+    arr = (C.c_void_p * 32)(*([ptr] * 32))
+    pa = C.cast(arr, C.POINTER(C.c_void_p))
+    for name in ("embed", "final_norm", "lm_head"):
+        setattr(w, name, ptr)
+    for name in ("attn_norm", "w_qkv", "w_o", "ffn_norm", "w_gate_up", "w_down", "exit_norm", "exit_head"):
+        setattr(w, name, pa)
+    h = C.c_void_p()
+    w.packed, w.packed_bytes = 4096 + 8, 1 << 40
+    assert L.sb_load_model(C.byref(cfg), C.byref(w), None, C.byref(h)) == sb.EINVAL
+    w.packed, w.packed_bytes = 4096, 1024
+    assert L.sb_load_model(C.byref(cfg), C.byref(w), None, C.byref(h)) == sb.ENOMEM
+    assert L.sb_debug_fail_launch(None, 1) == sb.EINVAL and L.sb_open_rows(None) == sb.EINVAL
+    assert L.sb_phase_timing(None, 1) == sb.EINVAL
+    x = np.zeros(64, np.float32).ctypes.data
+    assert L.sb_op_head_static(x, 0, 131072 + 16, 64, x, 1, 1.0, sb.PROJ_VALU, x, x, None) == sb.ECAPACITY

@@ -519,3 +519,42 @@ def test_head_subset_variant_matches_the_oracle(sb, mask):
     out, st = gm2.session().generate(p2, 48, sb.Params(8, 6, T8, 0.3, head_mask=0b10101010))
     assert out.tolist() == ar.tolist()
     assert st["drafts"] > 0 and all(st["exit_hist"][l] == 0 for l in (1, 3, 5, 7))
+
+
+def test_failed_launch_abandons_the_round_and_keeps_the_committed_state(sb):
+    """A projection launch that fails in the middle of a round (forced from the host, nothing
+    faults on the GPU) makes the call return a device error and drops the open round; the
+    committed tokens, their cache entries and the pending token are as before, so decoding on
+    gives the reference output.  A library-owned packed copy of the weights behaves like the
+    caller-owned one."""
+    import paper_2604_12247_amd as sbm
+    shape, w, om, gm = _build(sb, "bf16-mfma-packed", n_layers=6, n_exit=3, seed=45)
+    gm_lib = sbm.Model(shape, w, 160, proj_kernel=sb.PROJ_MFMA_PACKED, own_packed=False)
+    prompt = si.make_prompt(shape.vocab, 18, 55)
+    fe = si.forced_exit_schedule(11, 400, 1, 3)
+    p = gpu_params(3, 4, 0.5, forced_exit=fe)
+    ref, _ = gm.session().generate(prompt, 40, p)
+    ref_lib, _ = gm_lib.session().generate(prompt, 40, p)
+    assert ref.tolist() == ref_lib.tolist()
+    s = gm.session()
+    first = s.prefill(prompt)
+    out, _ = s.decode(9, p)
+    c0, steps0 = s.committed_len(), s.stats()["draft_steps"]
+    for nth in (2, 7, 30):          # in the first draft step, in a later one, in the verification
+        s.debug_fail_launch(nth)
+        with pytest.raises(sb.SbError) as e:
+            while True:
+                r = s.draft_step(p)
+                if r["status"] != sb.EXITED:
+                    s.verify(p)
+                    raise AssertionError("the injected failure did not show")
+        assert e.value.code == sb.EDEVICE and "abandoned" in str(e.value)
+        assert s.open_rows() == 0 and s.committed_len() == c0
+    s.debug_fail_launch(0)
+    rest, _ = s.decode(30, p)
+    assert [first] + out.tolist() + rest.tolist() == ref.tolist()
+    # w_max beyond the model's max_w is refused
+    gm2 = sbm.Model(shape, w, 160, proj_kernel=sb.PROJ_AUTO)
+    assert gm2.cfg.max_w == 0
+    cfg_small = sb.make_config(shape, 160, max_w=2)
+    assert cfg_small.max_w == 2
