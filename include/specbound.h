@@ -137,6 +137,21 @@ typedef struct sb_params {
     const int32_t *forced_draft;
     int64_t n_forced;
     uint32_t head_mask;
+    /* Sampling-mode verification (Sec. 4.3, sampling strategies).  sample_temperature == 0:
+     * greedy verification (the fields below are ignored).  sample_temperature > 0: every emitted
+     * token is a sample of softmax(z / sample_temperature) of the full model, restricted to its
+     * nucleus of mass top_p in (0, 1] (1: no restriction) -- the draft x of a row (the exit
+     * head's arg max, as in greedy mode) is accepted with probability P(x), at the first
+     * rejection the token is drawn from P without x, and after the last accepted draft of a
+     * depth-bound round from P.  sample_u: host array of n_sample_u uniforms in [0, 1); the row
+     * at position pos uses sample_u[2 pos] for its acceptance test and sample_u[2 pos + 1] for
+     * its draw (SB_EINVAL if the array is too short for the rows of a round).  The first token
+     * of sb_prefill stays the greedy one; a caller who wants it sampled passes its own choice
+     * to sb_rewind. */
+    float sample_temperature;
+    float top_p;
+    const float *sample_u;
+    int64_t n_sample_u;
 } sb_params;
 
 typedef struct sb_draft_result {
@@ -152,7 +167,9 @@ typedef struct sb_verify_result {
     int32_t n_matched;   /* m: leading drafts equal to the greedy tokens */
     int32_t n_emit;      /* min(m + 1, M) tokens emitted, >= 1 */
     int32_t align_layer; /* D: deepest layer reached while drafting */
-    int32_t tokens[SB_MAX_W]; /* greedy token after each row; the first n_emit are emitted */
+    int32_t tokens[SB_MAX_W]; /* greedy token after each row; the first n_emit are emitted.  Sampling
+                                 mode: the emitted tokens, -1 for the rows after them */
+    float accept_prob[SB_MAX_W]; /* sampling mode: P(draft) of each row that was examined, else 0 */
 } sb_verify_result;
 
 typedef struct sb_stats {

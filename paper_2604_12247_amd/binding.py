@@ -48,7 +48,9 @@ class sb_params(C.Structure):
     _fields_ = [("d_max", C.c_int32), ("w_max", C.c_int32), ("T", C.POINTER(C.c_float)),
                 ("threshold", C.c_float), ("eos_id", C.c_int32),
                 ("forced_exit", C.POINTER(C.c_int32)), ("forced_draft", C.POINTER(C.c_int32)),
-                ("n_forced", C.c_int64), ("head_mask", C.c_uint32)]
+                ("n_forced", C.c_int64), ("head_mask", C.c_uint32),
+                ("sample_temperature", C.c_float), ("top_p", C.c_float),
+                ("sample_u", C.POINTER(C.c_float)), ("n_sample_u", C.c_int64)]
 
 
 class sb_draft_result(C.Structure):
@@ -58,7 +60,7 @@ class sb_draft_result(C.Structure):
 
 class sb_verify_result(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_rows", "n_drafts", "n_matched", "n_emit", "align_layer")] + \
-               [("tokens", C.c_int32 * SB_MAX_W)]
+               [("tokens", C.c_int32 * SB_MAX_W), ("accept_prob", C.c_float * SB_MAX_W)]
 
 
 class sb_stats(C.Structure):
@@ -188,8 +190,10 @@ class Params:
 
     def __init__(self, d_max: int, w_max: int, T: Sequence[float], threshold: float,
                  forced_exit: Optional[Sequence[int]] = None, forced_draft: Optional[Sequence[int]] = None,
-                 eos_id: int = -1, head_mask: int = 0):
+                 eos_id: int = -1, head_mask: int = 0, sample_temperature: float = 0.0, top_p: float = 1.0,
+                 sample_u=None):
         self.T = np.ascontiguousarray(T, dtype=np.float32)
+        self.su = None if sample_u is None else np.ascontiguousarray(sample_u, dtype=np.float32)
         self.fe = None if forced_exit is None else np.ascontiguousarray(forced_exit, dtype=np.int32)
         self.fd = None if forced_draft is None else np.ascontiguousarray(forced_draft, dtype=np.int32)
         n_forced = 0
@@ -202,7 +206,9 @@ class Params:
                            threshold, eos_id,
                            None if self.fe is None else self.fe.ctypes.data_as(C.POINTER(C.c_int32)),
                            None if self.fd is None else self.fd.ctypes.data_as(C.POINTER(C.c_int32)),
-                           n_forced, head_mask)
+                           n_forced, head_mask, sample_temperature, top_p,
+                           None if self.su is None else self.su.ctypes.data_as(C.POINTER(C.c_float)),
+                           0 if self.su is None else len(self.su))
 
 
 def _stats_dict(st: sb_stats) -> dict:
@@ -328,7 +334,8 @@ class Session:
         r = sb_verify_result()
         check(lib().sb_verify(self.h, C.byref(p.c), C.byref(r)))
         return dict(n_rows=r.n_rows, n_drafts=r.n_drafts, n_matched=r.n_matched, n_emit=r.n_emit,
-                    align_layer=r.align_layer, tokens=list(r.tokens)[:r.n_rows])
+                    align_layer=r.align_layer, tokens=list(r.tokens)[:r.n_rows],
+                    accept_prob=list(r.accept_prob)[:r.n_rows])
 
     def generate(self, prompt, max_new: int, p: Params):
         """Returns (tokens, stats dict)."""

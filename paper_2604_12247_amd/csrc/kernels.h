@@ -86,6 +86,16 @@ struct GemvArgs {
     float* ssq_out;
 };
 
+// Sampling-mode acceptance over the final-head logits of the M verified rows (device, [M][V]).
+struct SampleArgs {
+    const float* logits;
+    int32_t V, M, n_drafts;
+    float temp, top_p;
+    float ua[SB_MAX_W], ur[SB_MAX_W];  // per row: uniform of the acceptance test, uniform of the draw
+    DevRound* round;                   // reads drafts[], writes g[], gconf[] (= P(draft)), n_matched, n_emit
+};
+hipError_t launch_sample_accept(const SampleArgs& a, hipStream_t st);
+
 int head_blocks_valu(int32_t N);
 int head_blocks_mfma(int32_t N);
 

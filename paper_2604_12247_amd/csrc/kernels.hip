@@ -314,6 +314,160 @@ hipError_t launch_head_merge(const HeadArgs& h, int32_t M, int32_t nb, hipStream
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- sampling-mode acceptance
+// Verification when the output is sampled (Sec. 4.3, "sampling strategies": temperature and
+// top-p; the paper gives no rule, the one taken is that of speculative sampling for a draft
+// proposed deterministically): with P the distribution the full model samples from after a row
+// -- softmax(z / temp), cut to its nucleus of mass top_p and renormalised -- the row's draft x is
+// accepted with probability P(x); at the first rejection the token is drawn from P without x;
+// when every draft is accepted and one more row exists its token is drawn from P.  Each emitted
+// token is then distributed exactly as the full model's own sample.  One block, rows in order;
+// all sums are taken in a fixed order.  Works on unnormalised weights e_j = exp((z_j - max)/temp).
+struct BlockRed {
+    float* red;  // [16] shared
+    __device__ __forceinline__ float sum(float v) {
+        v = wave_sum(v);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+        __syncthreads();
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += red[w];
+        return t;
+    }
+    __device__ __forceinline__ float max(float v) {
+        v = wave_max(v);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+        __syncthreads();
+        float t = red[0];
+#pragma unroll
+        for (int w = 1; w < 16; ++w) t = fmaxf(t, red[w]);
+        return t;
+    }
+};
+
+__global__ __launch_bounds__(1024) void sample_accept_kernel(SampleArgs a) {
+    __shared__ float red[16];
+    __shared__ float seg[1024];
+    __shared__ float s_base;
+    __shared__ int s_seg, s_tok;
+    BlockRed br{red};
+    const int tid = threadIdx.x, V = a.V;
+    DevRound* R = a.round;
+    int m = 0;       // accepted drafts so far (uniform)
+    int drawn = -1;  // row at which a token was drawn
+    for (int row = 0; row < a.M; ++row) {
+        const float* z = a.logits + (size_t)row * V;
+        float mx = -SB_INF;
+        for (int j = tid; j < V; j += 1024) mx = fmaxf(mx, z[j]);
+        mx = br.max(mx);
+        float sm = 0.f;
+        for (int j = tid; j < V; j += 1024) sm += expf((z[j] - mx) / a.temp);
+        const float S = br.sum(sm);
+        // nucleus: the largest weight value `cut` such that the weights >= cut hold a share top_p
+        // of S (so equal weights at its edge stay together); found by bisection on the bit
+        // pattern of a positive float, which is monotone in its value
+        float cut = 0.f, keep = S;
+        if (a.top_p < 1.0f) {
+            const float need = a.top_p * S;
+            uint32_t lo = 0u, hi = __float_as_uint(1.0f) + 1u;  // the largest weight is exp(0) = 1
+            while (hi - lo > 1u) {
+                const uint32_t mid = lo + (hi - lo) / 2u;
+                const float t = __uint_as_float(mid);
+                float f = 0.f;
+                for (int j = tid; j < V; j += 1024) {
+                    const float e = expf((z[j] - mx) / a.temp);
+                    if (e >= t) f += e;
+                }
+                f = br.sum(f);
+                if (f >= need) lo = mid; else hi = mid;
+            }
+            cut = __uint_as_float(lo);
+            float f = 0.f;
+            for (int j = tid; j < V; j += 1024) {
+                const float e = expf((z[j] - mx) / a.temp);
+                if (e >= cut) f += e;
+            }
+            keep = br.sum(f);
+        }
+        const bool has_draft = row < a.n_drafts;
+        const int x = has_draft ? R->drafts[row] : -1;
+        float ex = 0.f;
+        if (x >= 0 && x < V) {
+            ex = expf((z[x] - mx) / a.temp);
+            if (ex < cut) ex = 0.f;
+        }
+        if (tid == 0) R->gconf[row] = ex / keep;   // P(x): the row's acceptance probability
+        if (has_draft && a.ua[row] * keep < ex) {  // accepted
+            if (tid == 0) R->g[row] = x;
+            ++m;
+            continue;
+        }
+        // draw from P without x: inverse CDF over the tokens in index order
+        const float total = keep - ex, target = a.ur[row] * total;
+        const int per = (V + 1023) / 1024, j0 = tid * per, j1 = (j0 + per < V) ? j0 + per : V;
+        float ssum = 0.f;
+        int last_mass = -1;
+        for (int j = j0; j < j1; ++j) {
+            const float e = expf((z[j] - mx) / a.temp);
+            if (e >= cut && j != x) { ssum += e; last_mass = j; }
+        }
+        seg[tid] = ssum;
+        __syncthreads();
+        if (tid == 0) {
+            float c = 0.f;
+            int chosen = -1;
+            for (int t = 0; t < 1024; ++t) {
+                if (c + seg[t] > target) { chosen = t; break; }
+                c += seg[t];
+            }
+            s_seg = chosen;
+            s_base = c;
+            s_tok = -1;
+        }
+        __syncthreads();
+        const int chosen = s_seg;
+        if (chosen >= 0) {
+            if (tid == chosen) {
+                float c = s_base;
+                int tok = last_mass;
+                for (int j = j0; j < j1; ++j) {
+                    const float e = expf((z[j] - mx) / a.temp);
+                    if (e >= cut && j != x) {
+                        c += e;
+                        if (c > target) { tok = j; break; }
+                    }
+                }
+                s_tok = tok;
+            }
+            __syncthreads();
+        } else {  // rounding at the upper end: the last token that has mass
+            int lm = last_mass;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) { int v = __shfl_xor(lm, o, 64); lm = v > lm ? v : lm; }
+            const float best = br.max((float)lm);   // token ids are exact in a float up to 2^24
+            if (tid == 0) s_tok = (int)best;
+            __syncthreads();
+        }
+        if (tid == 0) R->g[row] = s_tok;
+        drawn = row;
+        break;
+    }
+    if (tid == 0) {
+        for (int row = (drawn >= 0 ? drawn : a.M - 1) + 1; row < a.M; ++row) { R->g[row] = -1; R->gconf[row] = 0.f; }
+        R->n_matched = m;
+        R->n_emit = m + 1 < a.M ? m + 1 : a.M;
+    }
+}
+
+hipError_t launch_sample_accept(const SampleArgs& a, hipStream_t st) {
+    if (!a.logits || !a.round || a.V < 1 || a.V > (1 << 24) || a.M < 1 || a.M > SB_MAX_W || !(a.temp > 0.f) || !(a.top_p > 0.f))
+        return hipErrorInvalidValue;
+    sample_accept_kernel<<<1, 1024, 0, st>>>(a);
+    return hipGetLastError();
+}
+
 // Partial (max, arg max, sum exp) of the block's logits zs[i][m], i < rows.
 template <int ROWS>
 __device__ __forceinline__ void head_partial(const HeadArgs& h, float (*zs)[SB_MAX_W], int M, int n0, int N, int nb) {

@@ -234,6 +234,11 @@ int check_params(const sb_session* s, const sb_params* p) {
         if (!(p->T[l] > 0.f)) return fail(SB_EINVAL, "T[%d] must be positive", l);
     if (p->n_forced < 0) return fail(SB_EINVAL, "n_forced < 0");
     if (p->head_mask && p->d_max > 32) return fail(SB_EINVAL, "head_mask has 32 bits: d_max must be <= 32 with it");
+    if (p->sample_temperature < 0.f) return fail(SB_EINVAL, "sample_temperature < 0");
+    if (p->sample_temperature > 0.f) {
+        if (!(p->top_p > 0.f) || p->top_p > 1.f) return fail(SB_EINVAL, "top_p must be in (0, 1]");
+        if (!p->sample_u || p->n_sample_u < 0) return fail(SB_EINVAL, "sample_u is NULL");
+    }
     return SB_OK;
 }
 
@@ -728,11 +733,26 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
         if ((rc = run_layer(s, l - 1, 0, M, l == c.n_layers ? m->final_norm : nullptr))) return rc;
         for (int j = 0; j < M; ++j) s->reached[j] = l;
     }
+    const bool sampling = p->sample_temperature > 0.f;
+    if (sampling && p->n_sample_u < 2 * (int64_t)(s->c + M))
+        return fail(SB_EINVAL, "verify: sample_u has %lld entries, the rows of this round need %lld", (long long)p->n_sample_u,
+                    2 * (long long)(s->c + M));
     HeadArgs h{};
-    h.T = 1.0f; h.post = POST_ACCEPT; h.n_drafts = s->n_drafts;
-    h.logits = s->debug ? wsp<float>(s, s->L.logits_final) : nullptr;
+    h.T = 1.0f; h.post = sampling ? POST_NONE : POST_ACCEPT; h.n_drafts = s->n_drafts;
+    h.logits = (s->debug || sampling) ? wsp<float>(s, s->L.logits_final) : nullptr;
+    if (sampling) { h.argmax_out = s->d_round->g; h.conf_out = s->d_round->gconf; }   // (overwritten by the acceptance kernel)
     if ((rc = join_head(s))) return rc;
     if ((rc = run_head(s, m->lm_head, m->final_norm, 0, M, h, m->stream))) return rc;
+    if (sampling) {
+        SampleArgs sa{};
+        sa.logits = wsp<float>(s, s->L.logits_final); sa.V = c.vocab; sa.M = M; sa.n_drafts = s->n_drafts;
+        sa.temp = p->sample_temperature; sa.top_p = p->top_p; sa.round = s->d_round;
+        for (int i = 0; i < M; ++i) {
+            sa.ua[i] = p->sample_u[2 * (int64_t)(s->c + i)];
+            sa.ur[i] = p->sample_u[2 * (int64_t)(s->c + i) + 1];
+        }
+        HIP_TRY(launch_sample_accept(sa, m->stream));
+    }
     s->st.final_head_sweeps++;
     if (pt) HIP_TRY(hipEventRecord(s->ev_ph[3], m->stream));   // verified
     const double tw0 = now_ms();
@@ -752,6 +772,7 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     sb_verify_result res{};
     res.n_rows = M; res.n_drafts = s->n_drafts; res.n_matched = R.n_matched; res.n_emit = R.n_emit; res.align_layer = D;
     for (int i = 0; i < SB_MAX_W; ++i) res.tokens[i] = i < M ? R.g[i] : -1;
+    for (int i = 0; i < SB_MAX_W; ++i) res.accept_prob[i] = (sampling && i < M) ? R.gconf[i] : 0.f;
     // commit the emitted rows; KV entries of the other rows are simply left
     // beyond the committed length and overwritten by the next round
     s->c += R.n_emit;

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_header_sizes():
     assert C.sizeof(B.sb_config) == 16 * 4
     assert C.sizeof(B.sb_draft_result) == 16
-    assert C.sizeof(B.sb_verify_result) == (5 + sb.SB_MAX_W) * 4
+    assert C.sizeof(B.sb_verify_result) == (5 + 2 * sb.SB_MAX_W) * 4
     assert C.sizeof(B.sb_stats) == 8 * 8 + 9 * 8 + 65 * 8 + 2 * 8 + 2 * 8 + 7 * 8 + 3 * 8
 
 
