@@ -273,6 +273,29 @@ int32_t sb_rewind(sb_session *s, int32_t n_keep, int32_t pending_token, int64_t 
  * cannot be created. */
 int32_t sb_phase_timing(sb_session *s, int32_t on);
 
+/* ---- batch > 1: several sequences decoded together ------------------------ */
+/* The rounds of B sequences run side by side (the paper evaluates batch 1, Sec. 4.3; this is
+ * the same method with the rows of several sequences in every pass): each draft super-step
+ * adds a row to every sequence that is still drafting, a layer pass takes the rows of all
+ * sequences that need that layer in ONE sweep over its weights, each sequence attends to its
+ * own KV cache, exits, bounds and acceptance are decided per sequence.  Every sequence's
+ * output is bit-identical to what sb_decode gives for it alone.
+ * sessions: B in 2..SB_MAX_W sessions of one model (MFMA projection path), each with its own
+ * KV pool and workspace, each after sb_prefill / sb_rewind.  The sessions stay usable on their
+ * own between calls; the batch borrows them.  A sequence has SB_MAX_W / B rows per round, so
+ * params[b]->w_max must not exceed that (SB_EINVAL).  The shared layer sweeps are counted in
+ * the statistics of sessions[0]; per-sequence counters (rounds, drafts, emitted, histograms)
+ * in each session's own. */
+typedef struct sb_batch sb_batch;
+int32_t sb_new_batch(sb_session *const *sessions, int32_t B, sb_batch **out);
+void sb_free_batch(sb_batch *b);
+/* Rounds until every sequence has max_new further tokens (or emitted its eos_id).
+ * params: B pointers (a sequence's forced arrays are indexed by its own draft-step counter);
+ * out_tokens: B host arrays of max_new ids; n_out: B counts.  Errors as sb_decode; on
+ * SB_EDEVICE the open rounds of all sequences are abandoned. */
+int32_t sb_batch_decode(sb_batch *b, int32_t max_new, const sb_params *const *params, int32_t *const *out_tokens,
+                        int32_t *n_out);
+
 int32_t sb_get_stats(const sb_session *s, sb_stats *out);
 int32_t sb_committed_len(const sb_session *s);
 

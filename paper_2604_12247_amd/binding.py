@@ -87,7 +87,8 @@ SYMBOLS = ["sb_last_error", "sb_temperature_schedule", "sb_query_sizes", "sb_loa
            "sb_debug_kv", "sb_op_rmsnorm", "sb_op_gemv", "sb_op_gemv_scratch_bytes", "sb_op_head",
            "sb_op_head_scratch_bytes", "sb_rope_table_host", "sb_op_attention",
            "sb_op_attention_scratch_bytes", "sb_op_prompt_attention", "sb_decode", "sb_rewind", "sb_profile_begin", "sb_profile_end", "sb_op_copy",
-           "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes", "sb_op_head_static", "sb_phase_timing", "sb_debug_fail_launch", "sb_open_rows"]
+           "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes", "sb_op_head_static", "sb_phase_timing", "sb_debug_fail_launch", "sb_open_rows", "sb_new_batch", "sb_free_batch",
+           "sb_batch_decode"]
 
 KERNEL_CLASSES = ["rmsnorm", "qkv", "attention", "wo", "gate_up", "down", "exit_head",
                   "final_head"]
@@ -127,6 +128,10 @@ def lib() -> C.CDLL:
         L.sb_phase_timing.argtypes = [vp, i32]
         L.sb_debug_fail_launch.argtypes = [vp, i32]
         L.sb_open_rows.argtypes = [vp]
+        L.sb_new_batch.argtypes = [C.POINTER(vp), i32, C.POINTER(vp)]
+        L.sb_free_batch.argtypes = [vp]
+        L.sb_free_batch.restype = None
+        L.sb_batch_decode.argtypes = [vp, i32, C.POINTER(C.POINTER(sb_params)), C.POINTER(vp), C.POINTER(i32)]
         L.sb_committed_len.argtypes = [vp]
         L.sb_debug_enable.argtypes = [vp, i32]
         L.sb_debug_logits.argtypes = [vp, i32, i32, vp, i32]
@@ -415,6 +420,38 @@ class Session:
 
 
 # ---------------------------------------------------------------- single kernels
+class Batch:
+    """Several sessions of one model decoded together (sb_new_batch / sb_batch_decode)."""
+
+    def __init__(self, sessions: Sequence[Session]):
+        self.sessions = list(sessions)
+        arr = (C.c_void_p * len(self.sessions))(*[s.h for s in self.sessions])
+        self.h = C.c_void_p()
+        check(lib().sb_new_batch(arr, len(self.sessions), C.byref(self.h)))
+
+    def decode(self, max_new: int, params: Sequence[Params]):
+        """Returns a list of token arrays, one per sequence."""
+        B = len(self.sessions)
+        assert len(params) == B
+        outs = [np.empty(max_new, dtype=np.int32) for _ in range(B)]
+        pp = (C.POINTER(sb_params) * B)(*[C.pointer(p.c) for p in params])
+        op = (C.c_void_p * B)(*[o.ctypes.data for o in outs])
+        n = (C.c_int32 * B)()
+        check(lib().sb_batch_decode(self.h, max_new, pp, op, n))
+        return [outs[b][: n[b]].copy() for b in range(B)]
+
+    def close(self):
+        if self.h:
+            lib().sb_free_batch(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 def _stream_ptr(torch, device):
     return C.c_void_p(torch.cuda.current_stream(device).cuda_stream)
 

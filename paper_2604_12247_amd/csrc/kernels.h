@@ -49,6 +49,8 @@ struct HeadArgs {
     int32_t forced_draft;  // POST_EXIT: >= 0 overrides the drafted id
     float threshold;       // POST_EXIT
     int32_t n_drafts;      // POST_ACCEPT
+    int32_t row0;          // merge: the M rows merged are rows row0 .. row0 + M - 1 of the partials
+    int32_t skip_merge;    // projection launch: leave the partials, the caller launches the merges itself
     // POST_EXIT, optional (embed_E != nullptr): when the row exits, the merge also embeds the
     // drafted token as the row after it -- embed_H: that row of the hidden cache, embed_en:
     // what the first layer's projection reads for it (as the embedding kernel leaves it)
@@ -70,6 +72,7 @@ struct GemvArgs {
     uint16_t* ys;      // MFMA pipeline: optional split-bf16 copy of the output [16][ldy]
     int32_t ldy;
     int32_t M;
+    uint32_t row_mask; // 0: rows 0..M-1 of x / y; else bit m set = row (slot) m takes part (MFMA path, M ignored)
     int32_t epi;       // Epilogue
     HeadArgs head;     // EPI_HEAD
     // RMSNorm folded into the MFMA projections.  Input side: xs holds the two bf16
@@ -96,6 +99,8 @@ struct SampleArgs {
 };
 hipError_t launch_sample_accept(const SampleArgs& a, hipStream_t st);
 
+// Second stage of a head evaluation (launched by launch_gemv_* unless head.skip_merge is set).
+hipError_t launch_head_merge(const HeadArgs& h, int32_t M, int32_t nb, hipStream_t st);
 int head_blocks_valu(int32_t N);
 int head_blocks_mfma(int32_t N);
 

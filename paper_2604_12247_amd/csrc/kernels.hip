@@ -221,7 +221,7 @@ __global__ __launch_bounds__(1024) void head_merge_kernel(HeadArgs h, int M, int
     __shared__ int s_embed_tok;
     __shared__ float e_red[4];
     const int tid = threadIdx.x, lane = tid & 63, m = tid >> 7, t = tid & 127, half = (tid >> 6) & 1;
-    const float4* p = reinterpret_cast<const float4*>(h.partials) + (size_t)(m < M ? m : 0) * nb;
+    const float4* p = reinterpret_cast<const float4*>(h.partials) + (size_t)(h.row0 + (m < M ? m : 0)) * nb;
     float mx = -SB_INF;
     int idx = 0x7fffffff;
     if (m < M) {
@@ -470,9 +470,9 @@ hipError_t launch_sample_accept(const SampleArgs& a, hipStream_t st) {
 
 // Partial (max, arg max, sum exp) of the block's logits zs[i][m], i < rows.
 template <int ROWS>
-__device__ __forceinline__ void head_partial(const HeadArgs& h, float (*zs)[SB_MAX_W], int M, int n0, int N, int nb) {
+__device__ __forceinline__ void head_partial(const HeadArgs& h, float (*zs)[SB_MAX_W], uint32_t rows, int n0, int N, int nb) {
     int tid = threadIdx.x;
-    if (tid < M) {
+    if (tid < SB_MAX_W && ((rows >> tid) & 1u)) {
         int m = tid;
         float mx = -SB_INF;
         int idx = 0x7fffffff;
@@ -596,7 +596,7 @@ __global__ __launch_bounds__(256) void gemv_valu_kernel(GemvArgs a) {
             for (int m = 0; m < M; ++m)
                 if (lane == r * M + m) zs[wave * 4 + r][m] = acc[r][m];
         __syncthreads();
-        head_partial<16>(a.head, zs, M, n0, N, gridDim.x);
+        head_partial<16>(a.head, zs, (1u << M) - 1u, n0, N, gridDim.x);
     }
 }
 
@@ -707,8 +707,10 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
             wp[t] = W + (size_t)row * K;
         }
     }
-    // lanes whose column is a row that is not there (m >= M) load nothing
-    const bool bact = (li & 7) < M;
+    // Rows of this launch: the first M slots, or (passes that gather the rows of several
+    // sequences) the slots of a bit mask.  Lanes whose column is a row that is not there load nothing.
+    const uint32_t rows = a.row_mask ? a.row_mask : ((1u << M) - 1u);
+    const bool bact = (rows >> (li & 7)) & 1u;
     const uint16_t* bp = a.xs + (size_t)li * K;
 
     f32x4 acc[RT];
@@ -753,7 +755,8 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     // RMSNorm scale of each row from the partial sums of squares its producer left
     // (added in index order; the first weight loads are already in flight)
     if (a.ssq_in) {
-        for (int m = wave; m < M; m += WPB) {
+        for (int m = wave; m < SB_MAX_W; m += WPB) {
+            if (!((rows >> m) & 1u)) continue;   // (wave-uniform)
             float t = 0.f;
             for (int b = lane; b < a.ssq_nb; b += 64) t += a.ssq_in[(size_t)m * a.ssq_ld + b];
             t = wave_sum(t);
@@ -791,7 +794,7 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
             int t = e >> 7, m = (e >> 4) & 7, i = e & 15;
             int n = n0 + t * 16 + i;
             float sq = 0.f;
-            if (m < M && n < N) {
+            if (((rows >> m) & 1u) && n < N) {
                 float v = (cs[t][i][m] + cs[t][i][m + 8]) * s_inv[m];
                 float* yp = a.y + (size_t)m * a.ldy + n;
                 if (EPI == EPI_RESID) v += *yp;
@@ -808,7 +811,7 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
             __syncthreads();
             if (tid < RT * 8) {
                 int t = tid >> 3, m = tid & 7;
-                if (m < M && n0 + t * 16 < N) {
+                if (((rows >> m) & 1u) && n0 + t * 16 < N) {
                     float sum = 0.f;
                     for (int i = 0; i < 16; ++i) sum += zs[t * 16 + i][m];
                     a.ssq_out[(size_t)m * a.ssq_ld + blockIdx.x * RT + t] = sum;
@@ -819,7 +822,7 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
         if (tid < 128) {
             int m = tid >> 4, i = tid & 15;
             int n = n0 + i;
-            if (m < M && n < N) {
+            if (((rows >> m) & 1u) && n < N) {
                 float g = (cs[0][i][m] + cs[0][i][m + 8]) * s_inv[m];
                 float u = (cs[1][i][m] + cs[1][i][m + 8]) * s_inv[m];
                 float v = silu_mul(g, u);
@@ -830,10 +833,10 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     } else {  // EPI_HEAD
         for (int e = tid; e < RT * 16 * 8; e += NT) {
             int t = e >> 7, m = (e >> 4) & 7, i = e & 15;
-            zs[t * 16 + i][m] = (cs[t][i][m] + cs[t][i][m + 8]) * (m < M ? s_inv[m] : 0.f);
+            zs[t * 16 + i][m] = (cs[t][i][m] + cs[t][i][m + 8]) * (((rows >> m) & 1u) ? s_inv[m] : 0.f);
         }
         __syncthreads();
-        head_partial<16 * RT>(a.head, zs, M, n0, N, gridDim.x);
+        head_partial<16 * RT>(a.head, zs, rows, n0, N, gridDim.x);
     }
 }
 
@@ -866,7 +869,8 @@ hipError_t launch_gemv_mfma(const GemvArgs& a, hipStream_t st) {
         case EPI_HEAD: {
             a.packed ? launch_gemv_mfma_e<EPI_HEAD, true>(a, st) : launch_gemv_mfma_e<EPI_HEAD, false>(a, st);
             hipError_t e = hipGetLastError();
-            return e != hipSuccess ? e : launch_head_merge(a.head, a.M, head_blocks_mfma(a.N), st);
+            if (e != hipSuccess || a.head.skip_merge) return e;
+            return launch_head_merge(a.head, a.M, head_blocks_mfma(a.N), st);
         }
         default: return hipErrorInvalidValue;
     }
