@@ -57,6 +57,8 @@ def main():
                     help="variant: evaluate exit heads only at the layers of this bit mask (bit l-1 = layer l, e.g. "
                          "0xAA = even layers); forced exit layers move up to the next layer of the mask.  0 = the "
                          "paper's rule, a head after every layer (the workload the headline number is quoted on)")
+    ap.add_argument("--batch", default="", help="also measure batches of these sizes (e.g. 2,4): aggregate tokens/s of B "
+                    "sequences decoded together, greedy and speculative (w_max = 8 / B); reported under 'batch', not the headline")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run the plain copy kernel on 1 GiB (a yardstick of known traffic for "
                          "calibrating profiler counters) and exit")
@@ -225,6 +227,10 @@ def main():
                           "layer on a second stream (bytes of both / time of the phase); verify: remaining layers + final head")
         log("[bench]   phases: " + ", ".join(f"{k} {v['gpu_ms']} ms {v['GB/s']} GB/s" for k, v in phases.items() if isinstance(v, dict)))
 
+    batch = None
+    if args.batch:
+        batch = batch_runs(sb, si, model, wl, [int(x) for x in args.batch.split(",")], min(gen_len, 256), ar_tok_s, tok_s)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(shape, weights, prompt, wl)
@@ -249,9 +255,57 @@ def main():
         "algorithmic_GB_per_step": round(spec_bytes / 1e9, 2),
         "algorithmic_GBps_whole_path": round(spec_bytes / 1e6 / ms_per_step, 1),
         "greedy_algorithmic_GBps_whole_path": round(ar_tok_s * ar_bytes_per_tok / 1e9, 1),
-        "roofline": roofline, "kernels": kernels, "kernels_greedy": kernels_greedy, "phases": phases, "cpu_baseline": cpu,
+        "batch": batch, "roofline": roofline, "kernels": kernels, "kernels_greedy": kernels_greedy, "phases": phases, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
+
+
+def batch_runs(sb, si, model, wl, sizes, gen, ar1, spec1):
+    """B sequences (different prompts) decoded together: aggregate generated tokens/s."""
+    import torch
+    shape, P = wl.shape, wl.prompt_len
+    out = {}
+    for B in sizes:
+        w_max = max(1, min(wl.w_max, sb.SB_MAX_W // B))
+        sess = [model.session() for _ in range(B)]
+        prompts = [si.make_prompt(shape.vocab, P, wl.prompt_seed + 17 * (b + 1)) for b in range(B)]
+        firsts = [s.prefill(p) for s, p in zip(sess, prompts)]
+        bt = sb.Batch(sess)
+        p_ar = sb.Params(0, 1, [], wl.threshold)
+        n_ar = gen + 2 * w_max
+        best = None
+        for _ in range(2):
+            for s, f in zip(sess, firsts):
+                s.rewind(P, f)
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            G = bt.decode(n_ar, [p_ar] * B)
+            torch.cuda.synchronize(); dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        ar = B * n_ar / best
+        params = []
+        for b in range(B):
+            greedy = [firsts[b]] + G[b].tolist()
+            acc = si.accept_schedule(wl.sched_seed + b, 2 * gen, w_max)
+            fd, _ = si.injection_schedule(greedy, acc, w_max, shape.vocab)
+            fe = si.forced_exit_schedule(wl.sched_seed + b, len(fd), wl.exit_lo, wl.d_max)
+            params.append(sb.Params(wl.d_max, w_max, wl.temperatures(), wl.threshold, forced_exit=fe, forced_draft=fd))
+        best = None
+        for _ in range(2):
+            for s, f in zip(sess, firsts):
+                s.rewind(P, f)
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            O = bt.decode(gen, params)
+            torch.cuda.synchronize(); dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        for b in range(B):
+            assert O[b].tolist() == G[b].tolist()[:gen], "batched speculative output differs from greedy decoding"
+        spec = B * gen / best
+        out[str(B)] = {"w_max": w_max, "greedy_tokens_per_s": round(ar, 1), "speculative_tokens_per_s": round(spec, 1),
+                       "greedy_vs_batch1": round(ar / ar1, 3), "speculative_vs_batch1": round(spec / spec1, 3)}
+        log(f"[bench] batch {B} (w_max {w_max}): greedy {ar:.1f} tok/s ({ar / ar1:.2f}x batch 1), speculative {spec:.1f} tok/s "
+            f"({spec / spec1:.2f}x batch 1's {spec1:.1f})")
+        del bt, sess
+    return out
 
 
 def copy_probe(torch, sb):
