@@ -222,6 +222,11 @@ ATT_CASES = [  # Hq, Hkv, hd, kv_bf16, n_ctx, M, rope base, shuffled pages
     (8, 8, 128, True, 300, 6, 1e4, True),
     (8, 2, 128, True, 257, 6, 5e5, True),      # GQA, two query groups
     (2, 2, 128, False, 70, 3, 1e4, False),     # fp32 cache with 64-key chunks
+    (8, 8, 128, True, 1018, 6, 1e4, True),     # eight whole 128-key chunks at the last row
+    (8, 8, 128, True, 1020, 6, 1e4, True),     # the pass's rows straddle a chunk boundary
+    (4, 2, 64, True, 1000, 8, 5e5, True),      # two query heads per kv head, sixteen query columns, head_dim 64, long context
+    (8, 8, 128, True, 63, 3, 1e4, False),      # shorter than one chunk
+    (8, 8, 128, True, 1030, 5, 1e4, True),     # nine chunks, the last one nearly empty
 ]
 
 
@@ -358,4 +363,10 @@ def test_attention_row_result_does_not_depend_on_m(T):
     for r in (0, 3, 5):
         _, out1 = _attention_case(T, *args, 250 + r, 1, 1e4, True, seed=77)
         assert np.array_equal(out1[0], out6[r])
+    # a pass whose rows straddle a chunk boundary (1024): the number of chunks a row sees is a
+    # function of its own position, alone or beside rows that see one chunk less
+    _, out6 = _attention_case(T, *args, 1021, 6, 1e4, True, seed=78)
+    for r in (0, 2, 3, 5):
+        _, out1 = _attention_case(T, *args, 1021 + r, 1, 1e4, True, seed=78)
+        assert np.array_equal(out1[0], out6[r]), r
 
