@@ -62,6 +62,10 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run the plain copy kernel on 1 GiB (a yardstick of known traffic for "
                          "calibrating profiler counters) and exit")
+    ap.add_argument("--head-probe", action="store_true",
+                    help="only run the head projection alone (sb_op_head: RMSNorm-folded [V x d] sweep with the Eq. 2 "
+                         "epilogue, then the merge) at the 7B / 32000 and the 8B / 128256 shapes, rotating over several "
+                         "matrices so that no sweep finds its weights in a cache, and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (the decode path is one sequence at batch 1); "
@@ -75,6 +79,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.copy_probe:
         copy_probe(torch, sb)
+        return
+    if args.head_probe:
+        head_probe(torch, sb)
         return
     wl = si.CONFIGS[args.config]
     shape = wl.shape
@@ -306,6 +313,41 @@ def batch_runs(sb, si, model, wl, sizes, gen, ar1, spec1):
             f"({spec / spec1:.2f}x batch 1's {spec1:.1f})")
         del bt, sess
     return out
+
+
+def head_probe(torch, sb):
+    """The exit / final head by itself (Sec. 3.2, Eq. 2): activation split + [V x d] projection + merge per call."""
+    import ctypes as C
+    from paper_2604_12247_amd import binding as B
+    L = sb.lib()
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    for V, d in ((32000, 4096), (128256, 4096)):
+        n_mat = max(2, min(6, (3 << 30) // (V * d * 2)))
+        Ws = [sb.op_repack(torch.randint(-2000, 2000, (V, d), dtype=torch.int16, device="cuda")) for _ in range(n_mat)]
+        for M in (1, 6):
+            x = torch.randn(M, d, device="cuda")
+            am = torch.empty(8, dtype=torch.int32, device="cuda")
+            cf = torch.empty(8, dtype=torch.float32, device="cuda")
+            scratch = torch.zeros(L.sb_op_head_scratch_bytes(M, V, d), dtype=torch.uint8, device="cuda")
+
+            def run(W):
+                B.check(L.sb_op_head(W.data_ptr(), 1, V, d, x.data_ptr(), M, 1.5, 3, am.data_ptr(), cf.data_ptr(), None,
+                                     scratch.data_ptr(), st))
+            for i in range(3):
+                run(Ws[i % n_mat])
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(20):
+                run(Ws[i % n_mat])
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 20
+            print(json.dumps({"op": "sb_op_head", "V": V, "d": d, "rows": M, "weight_bytes": V * d * 2,
+                              "avg_us_three_kernels": round(us, 1),
+                              "GB/s_three_kernels": round(V * d * 2 / us / 1e3, 1),
+                              "frac_of_hbm_peak_three_kernels": round(V * d * 2 / us / 1e3 / HBM_PEAK_GBS, 4)}), flush=True)
+        del Ws
 
 
 def copy_probe(torch, sb):

@@ -101,6 +101,12 @@ hipError_t launch_sample_accept(const SampleArgs& a, hipStream_t st);
 
 // Second stage of a head evaluation (launched by launch_gemv_* unless head.skip_merge is set).
 hipError_t launch_head_merge(const HeadArgs& h, int32_t M, int32_t nb, hipStream_t st);
+// The same for the first n entries (n <= SB_MAX_W sequences, M[i] rows each) in one launch.
+struct HeadMergeBatch {
+    HeadArgs h[SB_MAX_W];
+    int32_t M[SB_MAX_W];
+};
+hipError_t launch_head_merge_batch(const HeadMergeBatch& hb, int32_t n, int32_t nb, hipStream_t st);
 int head_blocks_valu(int32_t N);
 int head_blocks_mfma(int32_t N);
 
@@ -138,6 +144,13 @@ struct AttnArgs {
 };
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
+// The passes of up to SB_MAX_W sequences (each on its own cache, at most SB_MAX_W rows) in one
+// pair of launches; every value equals the one launch_attention computes for that sequence.
+struct AttnBatchArgs {
+    AttnArgs seq[SB_MAX_W];
+    int32_t zdim;  // query-group slices per sequence in grid.z
+};
+hipError_t launch_attention_batch(const AttnArgs* seqs, int n, hipStream_t st);
 // The prompt's attention for a bf16 cache: K/V append for all M rows, then every row's attention
 // with a running softmax per query (no partials; `partials` is not used); M is not limited.
 hipError_t launch_prefill_attention(const AttnArgs& a, hipStream_t st);

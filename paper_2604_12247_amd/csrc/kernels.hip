@@ -213,7 +213,7 @@ hipError_t launch_read(const void* src, size_t nbytes, float* sink, hipStream_t 
 // then starts at its first layer).  It is a kernel of its own: publishing the
 // partials inside the projection kernel would need a device-wide fence per
 // block, which on this chip writes back and invalidates a whole L2.
-__global__ __launch_bounds__(1024) void head_merge_kernel(HeadArgs h, int M, int nb) {
+__device__ __forceinline__ void head_merge_body(const HeadArgs& h, const int M, const int nb) {
     __shared__ float r_max[SB_MAX_W][2], r_sum[SB_MAX_W][2];
     __shared__ int r_idx[SB_MAX_W][2];
     __shared__ int s_am[SB_MAX_W];
@@ -309,8 +309,24 @@ __global__ __launch_bounds__(1024) void head_merge_kernel(HeadArgs h, int M, int
     }
 }
 
+__global__ __launch_bounds__(1024) void head_merge_kernel(HeadArgs h, int M, int nb) { head_merge_body(h, M, nb); }
+
+// The merges of several sequences after one shared head sweep (batch > 1): block b is the
+// single-sequence merge on sequence b's arguments.
+__global__ __launch_bounds__(1024) void head_merge_batch_kernel(HeadMergeBatch hb, int nb) {
+    const HeadArgs h = hb.h[blockIdx.x];
+    head_merge_body(h, hb.M[blockIdx.x], nb);
+}
+
 hipError_t launch_head_merge(const HeadArgs& h, int32_t M, int32_t nb, hipStream_t st) {
     head_merge_kernel<<<1, 1024, 0, st>>>(h, M, nb);
+    return hipGetLastError();
+}
+
+hipError_t launch_head_merge_batch(const HeadMergeBatch& hb, int32_t n, int32_t nb, hipStream_t st) {
+    if (n < 1 || n > SB_MAX_W) return hipErrorInvalidValue;
+    if (n == 1) return launch_head_merge(hb.h[0], hb.M[0], nb, st);
+    head_merge_batch_kernel<<<n, 1024, 0, st>>>(hb, nb);
     return hipGetLastError();
 }
 
@@ -1159,7 +1175,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
 // Every output row of an MFMA depends on its own operand row only, so a query's
 // partial does not depend on which other queries share the block.
 template <int HD>
-__global__ __launch_bounds__(256, 3) void attn_mfma_kernel(AttnArgs a) {
+__device__ __forceinline__ void attn_mfma_body(const AttnArgs& a, const int g, const int chunk, const int zb) {
     constexpr int CH = 128, QG = 16, HALF = HD / 2;
     constexpr int KSQ = HD / 32;      // k steps (of 32 dims) of the score product
     constexpr int KSV = CH / 32;      // k steps (of 32 keys) of the value product
@@ -1174,13 +1190,12 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(AttnArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lq = lane >> 4;
-    const int g = blockIdx.x, chunk = blockIdx.y;
     const int Hq = a.n_heads, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
     const int nq_total = a.M * G;
     // this block's query groups (16 queries each), handled one after the other with the
     // chunk's K and V held in registers
     const int n_qg = (nq_total + QG - 1) / QG;
-    const int qg_first = blockIdx.z * a.qg_per_block;
+    const int qg_first = zb * a.qg_per_block;
     const int qg_last = (qg_first + a.qg_per_block < n_qg) ? qg_first + a.qg_per_block : n_qg;
     const int key0 = chunk * CH, n_total = a.pos0 + a.M;
     const float scale = 1.0f / sqrtf((float)HD);
@@ -1269,7 +1284,7 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(AttnArgs a) {
                         f[e] = lo ? (x * c - y * sn) : (y * c + x * sn);
                     }
                     kreg[t][ks] = KvVec<uint16_t>::pack(f);
-                    if (blockIdx.z == 0) *reinterpret_cast<uint4*>(kbase + kaddr[t] + ks * 32) = kreg[t][ks];
+                    if (zb == 0) *reinterpret_cast<uint4*>(kbase + kaddr[t] + ks * 32) = kreg[t][ks];
                 }
             }
         }
@@ -1291,7 +1306,7 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(AttnArgs a) {
                         }
                     }
                     vreg[dt][ks] = make_uint4(w[0], w[1], w[2], w[3]);
-                    if (blockIdx.z == 0) *reinterpret_cast<uint4*>(vbase + vaddr[ks] + dt * 16 * SB_KV_BLOCK) = vreg[dt][ks];
+                    if (zb == 0) *reinterpret_cast<uint4*>(vbase + vaddr[ks] + dt * 16 * SB_KV_BLOCK) = vreg[dt][ks];
                 }
             }
         }
@@ -1397,6 +1412,25 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(AttnArgs a) {
     }
 }
 
+template <int HD>
+__global__ __launch_bounds__(256, 3) void attn_mfma_kernel(AttnArgs a) {
+    attn_mfma_body<HD>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// Several sequences' passes in one launch (batch > 1): grid.z = sequence x query-group slice, grid.y
+// = the longest sequence's chunks; a block outside its sequence's range leaves at once.  A block
+// inside runs the code above on its sequence's arguments, so every value is the one the
+// sequence's own launch computes.
+template <int HD>
+__global__ __launch_bounds__(256, 3) void attn_mfma_batch_kernel(AttnBatchArgs ab) {
+    const int sq = blockIdx.z / ab.zdim, zb = blockIdx.z - sq * ab.zdim;
+    const AttnArgs a = ab.seq[sq];
+    const int n_chunks = (a.pos0 + a.M + 127) / 128;
+    const int n_qg = (a.M * (a.n_heads / a.kv.n_kv_heads) + 15) / 16;
+    if ((int)blockIdx.y >= n_chunks || zb * a.qg_per_block >= n_qg) return;
+    attn_mfma_body<HD>(a, blockIdx.x, blockIdx.y, zb);
+}
+
 // Second stage: one block per (row, query head) merges that row's chunk partials
 // (online-softmax rule against the row's overall maximum).  A thread owns two dims;
 // the chunks are dealt round-robin to the block's thread groups so that all loads
@@ -1404,7 +1438,7 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(AttnArgs a) {
 // order and the groups are added in index order.  The order depends on the row's
 // position only.
 template <int HD, int CH>
-__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
+__device__ __forceinline__ void attn_merge_body(const AttnArgs& a, const int hq, const int r) {
     constexpr int MAXC = 512;
     constexpr int TPG = HD / 2;       // threads per group
     constexpr int NG = 256 / TPG;     // chunk groups
@@ -1413,7 +1447,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     __shared__ float red[4];
     __shared__ __attribute__((aligned(8))) float go[NG][HD];
     __shared__ float gl[NG];
-    const int r = blockIdx.y, hq = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const int grp = tid / TPG, dp = tid % TPG;
     const int Hq = a.n_heads, stride = HD + 2;
     const int nc = (a.pos0 + r) / CH + 1;
@@ -1477,29 +1511,49 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     }
 }
 
+template <int HD, int CH>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
+    attn_merge_body<HD, CH>(a, blockIdx.x, blockIdx.y);
+}
+
+template <int HD, int CH>
+__global__ __launch_bounds__(256) void attn_merge_batch_kernel(AttnBatchArgs ab) {
+    const AttnArgs a = ab.seq[blockIdx.z];
+    if ((int)blockIdx.y >= a.M) return;
+    attn_merge_body<HD, CH>(a, blockIdx.x, blockIdx.y);
+}
+
 int attn_chunk_keys(int32_t head_dim, int32_t kv_dtype) {
     return (head_dim * (kv_dtype == SB_BF16 ? 2 : 4) <= 256) ? 128 : 64;
 }
 
-hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
+// Checks one pass's arguments and gives its launch shape: chunks, query groups, groups per block.
+static bool attn_shape(const AttnArgs& a, int* n_chunks, int* n_qg, int* qpb) {
     const int hd = a.kv.head_dim;
-    if ((hd != 64 && hd != 128) || a.M < 1 || a.M > SB_PREFILL_ROWS || a.n_heads % a.kv.n_kv_heads) return hipErrorInvalidValue;
-    if (a.out_split && a.split_rows < a.M) return hipErrorInvalidValue;
+    if ((hd != 64 && hd != 128) || a.M < 1 || a.M > SB_PREFILL_ROWS || a.n_heads % a.kv.n_kv_heads) return false;
+    if (a.out_split && a.split_rows < a.M) return false;
+    if (!a.rope_cos || !a.rope_sin) return false;
     const int ch = attn_chunk_keys(hd, a.kv.kv_dtype);
-    const int n_chunks = (a.pos0 + a.M + ch - 1) / ch;
-    if (n_chunks > a.max_chunks || n_chunks > 512) return hipErrorInvalidValue;
+    *n_chunks = (a.pos0 + a.M + ch - 1) / ch;
+    if (*n_chunks > a.max_chunks || *n_chunks > 512) return false;
     const int G = a.n_heads / a.kv.n_kv_heads;
     // Query groups of 16: one block each while the launch is small; in a large launch (a prompt
     // pass over a long context) a block takes several groups in turn on one load of its K/V
     // chunk.  A query's result does not depend on the grouping.
-    const int n_qg = (a.M * G + 15) / 16;
-    int qpb = (int)(((long)a.kv.n_kv_heads * n_chunks * n_qg + 1023) / 1024);
-    if (qpb > n_qg) qpb = n_qg;
+    *n_qg = (a.M * G + 15) / 16;
+    *qpb = (int)(((long)a.kv.n_kv_heads * *n_chunks * *n_qg + 1023) / 1024);
+    if (*qpb > *n_qg) *qpb = *n_qg;
+    return true;
+}
+
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
+    const int hd = a.kv.head_dim;
+    int n_chunks, n_qg, qpb;
+    if (!attn_shape(a, &n_chunks, &n_qg, &qpb)) return hipErrorInvalidValue;
     AttnArgs b = a;
     b.qg_per_block = qpb;
     dim3 grid(a.kv.n_kv_heads, n_chunks, (n_qg + qpb - 1) / qpb);
     dim3 grid1(a.kv.n_kv_heads, n_chunks, n_qg);
-    if (!a.rope_cos || !a.rope_sin) return hipErrorInvalidValue;
     dim3 mgrid(a.n_heads, a.M);
     if (a.kv.kv_dtype == SB_BF16) {
         if (hd == 128) { attn_mfma_kernel<128><<<grid, 256, 0, st>>>(b); attn_merge_kernel<128, 128><<<mgrid, 256, 0, st>>>(a); }
@@ -1507,6 +1561,44 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     } else {
         if (hd == 128) { attn_kernel<float, 128><<<grid1, 256, 0, st>>>(a); attn_merge_kernel<128, 64><<<mgrid, 256, 0, st>>>(a); }
         else { attn_kernel<float, 64><<<grid1, 256, 0, st>>>(a); attn_merge_kernel<64, 128><<<mgrid, 256, 0, st>>>(a); }
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attention_batch(const AttnArgs* seqs, int n, hipStream_t st) {
+    if (n < 1 || n > SB_MAX_W) return hipErrorInvalidValue;
+    bool one_shape = seqs[0].kv.kv_dtype == SB_BF16;
+    for (int i = 1; i < n; ++i)
+        one_shape = one_shape && seqs[i].kv.kv_dtype == SB_BF16 && seqs[i].kv.head_dim == seqs[0].kv.head_dim &&
+                    seqs[i].kv.n_kv_heads == seqs[0].kv.n_kv_heads && seqs[i].n_heads == seqs[0].n_heads;
+    if (n == 1 || !one_shape) {  // (an fp32 cache takes the vector-ALU kernel, a launch per sequence)
+        for (int i = 0; i < n; ++i) {
+            hipError_t e = launch_attention(seqs[i], st);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    AttnBatchArgs ab{};
+    int max_chunks = 0, max_m = 0;
+    ab.zdim = 1;
+    for (int i = 0; i < n; ++i) {
+        int n_chunks, n_qg, qpb;
+        if (!attn_shape(seqs[i], &n_chunks, &n_qg, &qpb) || seqs[i].M > SB_MAX_W) return hipErrorInvalidValue;
+        ab.seq[i] = seqs[i];
+        ab.seq[i].qg_per_block = qpb;
+        const int z = (n_qg + qpb - 1) / qpb;
+        if (z > ab.zdim) ab.zdim = z;
+        if (n_chunks > max_chunks) max_chunks = n_chunks;
+        if (seqs[i].M > max_m) max_m = seqs[i].M;
+    }
+    dim3 grid(seqs[0].kv.n_kv_heads, max_chunks, n * ab.zdim);
+    dim3 mgrid(seqs[0].n_heads, max_m, n);
+    if (seqs[0].kv.head_dim == 128) {
+        attn_mfma_batch_kernel<128><<<grid, 256, 0, st>>>(ab);
+        attn_merge_batch_kernel<128, 128><<<mgrid, 256, 0, st>>>(ab);
+    } else {
+        attn_mfma_batch_kernel<64><<<grid, 256, 0, st>>>(ab);
+        attn_merge_batch_kernel<64, 128><<<mgrid, 256, 0, st>>>(ab);
     }
     return hipGetLastError();
 }

@@ -892,7 +892,8 @@ int batch_layer(sb_batch* bt, int l, uint32_t mask, const int* j0, const int* cn
     g.ssq_in = ssq_attn; g.ssq_nb = l == 0 ? 1 : d / 16;
     if ((rc = gemv(hs, g, SB_K_QKV, st))) return rc;
     int64_t kv_total = 0;
-    int rows = 0;
+    AttnArgs passes[SB_MAX_W];
+    int n_pass = 0;
     for (int b = 0; b < bt->B; ++b) {
         if (!cnt[b]) continue;
         sb_session* s = bt->seq[b];
@@ -903,14 +904,14 @@ int batch_layer(sb_batch* bt, int l, uint32_t mask, const int* j0, const int* cn
         a.partials = wsp<float>(s, s->L.attn_part); a.max_chunks = s->L.max_chunks;
         a.out = nullptr; a.out_split = atts + (size_t)slot * hq; a.split_rows = 8;
         const int64_t kv_read = (int64_t)(a.pos0 + a.M) * 2 * c.n_kv_heads * c.head_dim * (int64_t)esize(c.kv_dtype);
-        {
-            ProfScope ps(hs, SB_K_ATTN, kv_read, st);
-            HIP_TRY(launch_attention(a, st));
-        }
+        passes[n_pass++] = a;
         s->st.kv_bytes += kv_read;
         s->st.row_layers += cnt[b];
         kv_total += kv_read;
-        rows += cnt[b];
+    }
+    if (n_pass) {  // all sequences' passes in one pair of launches
+        ProfScope ps(hs, SB_K_ATTN, kv_total, st);
+        HIP_TRY(launch_attention_batch(passes, n_pass, st));
     }
     g.ssq_in = nullptr;
     g.W = m->w_o[l]; g.N = d; g.K = hq; g.xs = atts; g.y = H; g.ldy = d; g.epi = EPI_RESID;
@@ -929,7 +930,6 @@ int batch_layer(sb_batch* bt, int l, uint32_t mask, const int* j0, const int* cn
     hs->st.layer_sweeps += 1;      // the shared sweep is counted once, on the first sequence
     hs->st.weight_bytes += m->layer_bytes;
     if (hs->phase_bytes) *hs->phase_bytes += m->layer_bytes + kv_total;
-    (void)rows;
     return SB_OK;
 }
 
@@ -1045,10 +1045,12 @@ int batch_round(sb_batch* bt, const std::vector<int>& act, const sb_params* cons
                 float* logits = hs->debug ? wsp<float>(hs, hs->L.logits_exit) + (size_t)(l - 1) * c.vocab : nullptr;
                 (void)logits;
                 if ((rc = batch_head(bt, m->exit_head[l - 1], hm, T, nullptr, SB_K_EXIT_HEAD))) return rc;
+                HeadMergeBatch hb{};
+                int n_merge = 0;
                 for (int b : now) {
                     sb_session* s = bt->seq[b];
                     const int idx = s->n_slots - 1, slot = b * wc + idx;
-                    HeadArgs h{};
+                    HeadArgs& h = hb.h[n_merge];
                     h.T = T; h.partials = wsp<float>(hs, hs->L.head_part); h.post = POST_EXIT; h.round = s->d_round;
                     h.slot = idx; h.layer = l; h.forced_exit = forced[b]; h.forced_draft = over[b]; h.threshold = P[b]->threshold;
                     h.row0 = slot;
@@ -1058,10 +1060,11 @@ int batch_round(sb_batch* bt, const std::vector<int>& act, const sb_params* cons
                         h.embed_en = EmbedNorm{m->attn_norm[0], wsp<uint16_t>(hs, hs->L.xs_attn) + (size_t)(slot + 1) * d,
                                                wsp<float>(hs, hs->L.ssq_attn) + (size_t)(slot + 1) * hs->L.ssq_ld, hs->L.ssq_ld};
                     }
-                    HIP_TRY(launch_head_merge(h, 1, nb_head, st));
+                    hb.M[n_merge++] = 1;
                     s->st.head_evals++;
                     heads_run[b]++;
                 }
+                HIP_TRY(launch_head_merge_batch(hb, n_merge, nb_head, st));
                 todo.swap(later);
             }
             // exits: known to the host under a forced schedule, else read back
@@ -1121,6 +1124,8 @@ int batch_round(sb_batch* bt, const std::vector<int>& act, const sb_params* cons
     float* logits = (sampling || hs->debug) ? wsp<float>(hs, hs->L.logits_final) : nullptr;
     if ((rc = batch_head(bt, m->lm_head, all, 1.0f, logits, SB_K_FINAL_HEAD))) return rc;
     hs->st.final_head_sweeps++;
+    HeadMergeBatch hb{};
+    int n_merge = 0;
     for (int b : act) {
         sb_session* s = bt->seq[b];
         const sb_params* p = P[b];
@@ -1138,12 +1143,13 @@ int batch_round(sb_batch* bt, const std::vector<int>& act, const sb_params* cons
             }
             HIP_TRY(launch_sample_accept(sa, st));
         } else {
-            HeadArgs h{};
+            HeadArgs& h = hb.h[n_merge];
             h.T = 1.0f; h.partials = wsp<float>(hs, hs->L.head_part); h.post = POST_ACCEPT; h.round = s->d_round;
             h.n_drafts = s->n_drafts; h.row0 = b * wc;
-            HIP_TRY(launch_head_merge(h, M, nb_head, st));
+            hb.M[n_merge++] = M;
         }
     }
+    if (n_merge) HIP_TRY(launch_head_merge_batch(hb, n_merge, nb_head, st));
     if ((rc = batch_readback(bt, act))) return rc;
     for (int b : act) {
         sb_session* s = bt->seq[b];
