@@ -51,11 +51,13 @@ def gpu_params(d_max, w_max, threshold=0.5, forced_exit=None, forced_draft=None,
 
 
 def progress(msg):
-    """A progress line on stdout and, when the run has a gpurun_out/ folder to write to, in
-    gpurun_out/test_progress.log: long full-size tests are then not mistaken for hung ones."""
+    """A progress line on stdout and in test_progress.log under the folder SB_PROGRESS_DIR names
+    (default: the run-output folder at the repository root), so that a long full-size test
+    that prints nothing for minutes is not mistaken for a hung one."""
     import os, time
     print(msg, flush=True)
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    d = os.environ.get("SB_PROGRESS_DIR") or os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                                                          "gpurun_out")
     try:
         os.makedirs(d, exist_ok=True)
         with open(os.path.join(d, "test_progress.log"), "a") as f:
