@@ -128,7 +128,46 @@ def _run_config(sb, name, prompt_len, gen_len):
     if ro["token"] != rg["token"]:
         NearTies(GAP_RULE).flag("exit head of a draft step", zo, rg["token"])
     del osn, om
+    if name in BATCH_CHECK:
+        _batch_check(sb, gm, wl, prompt)
     return st_ar, st
+
+
+# workloads whose model also decodes a batch (MHA at 7B, GQA with the 128256-row heads at 8B)
+BATCH_CHECK = ("C2", "C5")
+
+
+def _batch_check(sb, gm, wl, prompt):
+    """Four sequences with contexts of 1 to 5 attention chunks decoded together, speculative with
+    forced schedules and greedy: each must be bit-identical to its own single-sequence run."""
+    B, w_max, n_new = 4, 2, 24
+    lens = [40, 300, min(len(prompt), 512), 130]
+    prompts = [prompt[:n] for n in lens]
+    P = []
+    for b in range(B):
+        fe = si.forced_exit_schedule(wl.sched_seed + 7 * b, 4 * n_new, wl.exit_lo, wl.d_max)
+        fd = np.where(np.random.default_rng(b).random(4 * n_new) < 0.4, 11 + b, -1).astype(np.int32)
+        P.append(sb.Params(wl.d_max, w_max, wl.temperatures(), wl.threshold, forced_exit=fe, forced_draft=fd))
+    alone = []
+    for b in range(B):
+        s = gm.session()
+        f = s.prefill(prompts[b])
+        o, st = s.decode(n_new, P[b])
+        alone.append(([f] + o.tolist(), st))
+        del s
+    sess = [gm.session() for _ in range(B)]
+    firsts = [s.prefill(p) for s, p in zip(sess, prompts)]
+    outs = sb.Batch(sess).decode(n_new, P)
+    for b in range(B):
+        assert [firsts[b]] + outs[b].tolist() == alone[b][0], b
+        st = sess[b].stats()
+        assert st["accept_hist"] == alone[b][1]["accept_hist"] and st["exit_hist"] == alone[b][1]["exit_hist"], b
+    for s, f, n in zip(sess, firsts, lens):
+        s.rewind(n, f)
+    g_batch = sb.Batch(sess).decode(n_new, [sb.Params(0, 1, [], wl.threshold)] * B)
+    for b in range(B):   # speculative == greedy for every sequence, and the batch's greedy == the spec run alone
+        assert g_batch[b].tolist() == alone[b][0][1:], b
+    progress(f"[fullsize] {wl.name}: batch of {B} (contexts {lens}) equals the single-sequence runs")
 
 
 def test_c2_7b_full_shape(sb):
