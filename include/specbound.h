@@ -349,6 +349,13 @@ int32_t sb_op_rmsnorm(const float *x, const float *gain, float *out, int32_t M, 
 int32_t sb_op_gemv(const void *W, int32_t w_dtype, int32_t N, int32_t K, const float *x, float *y,
                    int32_t M, int32_t kernel, void *scratch, void *stream);
 size_t sb_op_gemv_scratch_bytes(int32_t M, int32_t K);
+/* The FFN's first half as the decode path runs it (step S7: one sweep over the gate and up
+ * matrices with the SwiGLU in the epilogue; the decoder's definition, Sec. 4.1 model families):
+ * u[m][n] = silu(W[n] . x[m]) * (W[N + n] . x[m]), W [2N][K] = gate rows, then up rows (for
+ * SB_PROJ_MFMA_PACKED: sb_op_repack of that matrix, N % 16 == 0).  x [M][K], u [M][N] float,
+ * device; scratch as for sb_op_gemv.  Errors as sb_op_gemv. */
+int32_t sb_op_gate_up(const void *W, int32_t w_dtype, int32_t N, int32_t K, const float *x, float *u,
+                      int32_t M, int32_t kernel, void *scratch, void *stream);
 /* Tile-packed copy of a bf16 matrix W [N][K] (N % 16 == 0, K % 128 == 0) for
  * kernel = SB_PROJ_MFMA_PACKED of sb_op_gemv / sb_op_head: packed, N*K*2 bytes. */
 int32_t sb_op_repack(const void *W, int32_t N, int32_t K, void *packed, void *stream);

@@ -123,6 +123,16 @@ def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float, bits: int = 64) -> np.ndar
     return out
 
 
+def swiglu(gu: np.ndarray, bits: int = 64) -> np.ndarray:
+    """gu = f gate values, then f up values -> silu(gate) * up."""
+    lib = load_lib(bits)
+    gu = np.ascontiguousarray(gu, dtype=_real(bits))
+    f = gu.size // 2
+    out = np.empty(f, dtype=_real(bits))
+    lib.orc_swiglu(_ptr(gu), C.c_int32(f), _ptr(out))
+    return out
+
+
 def act(z: np.ndarray, T: float, bits: int = 64):
     """(argmax, confidence) of Eq. 2."""
     lib = load_lib(bits)

@@ -180,6 +180,16 @@ void orc_rmsnorm(const real *x, const float *g, int32_t d, float eps, real *out)
 
 /* Rotary embedding, half-split pairing (i, i + hd/2), theta_i = base^(-2i/hd),
  * angle = pos * theta_i evaluated in double and rounded to float. */
+/* Gated FFN activation of the LLaMA-family decoders the paper evaluates (Sec. 4.1):
+ * u_i = silu(g_i) * v_i with silu(g) = g / (1 + exp(-g)); gu holds the f gate values, then
+ * the f up values. */
+void orc_swiglu(const real *gu, int32_t f, real *u) {
+    for (int32_t i = 0; i < f; ++i) {
+        real g = gu[i];
+        u[i] = g / ((real)1 + R_EXP(-g)) * gu[f + i];
+    }
+}
+
 void orc_rope_angles(int32_t pos, int32_t hd, float base, float *cos_out, float *sin_out) {
     for (int32_t i = 0; i < hd / 2; ++i) {
         double theta = pow((double)base, -2.0 * (double)i / (double)hd);
@@ -437,10 +447,7 @@ static void layer_row(orc_session *s, int32_t l, int32_t pos, real *h) {
 
     orc_rmsnorm(h, m->w.ffn_norm[l], d, c->rms_eps, s->xn);
     orc_matvec(m->w.w_gate_up[l], c->weight_dtype, 2 * f, d, s->xn, s->gu);
-    for (int32_t i = 0; i < f; ++i) {
-        real g = s->gu[i];
-        s->u[i] = g / ((real)1 + R_EXP(-g)) * s->gu[f + i];
-    }
+    orc_swiglu(s->gu, f, s->u);
     orc_matvec(m->w.w_down[l], c->weight_dtype, d, f, s->u, s->dn);
     for (int32_t i = 0; i < d; ++i) h[i] += s->dn[i];
 }

@@ -84,7 +84,7 @@ class sb_sizes(C.Structure):
 SYMBOLS = ["sb_last_error", "sb_temperature_schedule", "sb_query_sizes", "sb_load_model", "sb_free_model",
            "sb_new_session", "sb_free_session", "sb_prefill", "sb_draft_step", "sb_verify", "sb_generate",
            "sb_get_stats", "sb_committed_len", "sb_debug_enable", "sb_debug_logits", "sb_debug_hidden",
-           "sb_debug_kv", "sb_op_rmsnorm", "sb_op_gemv", "sb_op_gemv_scratch_bytes", "sb_op_head",
+           "sb_debug_kv", "sb_op_rmsnorm", "sb_op_gemv", "sb_op_gemv_scratch_bytes", "sb_op_gate_up", "sb_op_head",
            "sb_op_head_scratch_bytes", "sb_rope_table_host", "sb_op_attention",
            "sb_op_attention_scratch_bytes", "sb_op_prompt_attention", "sb_decode", "sb_rewind", "sb_profile_begin", "sb_profile_end", "sb_op_copy",
            "sb_op_read", "sb_op_repack", "sb_op_gemm", "sb_op_gemm_scratch_bytes", "sb_op_head_static", "sb_phase_timing", "sb_debug_fail_launch", "sb_open_rows", "sb_new_batch", "sb_free_batch",
@@ -140,6 +140,7 @@ def lib() -> C.CDLL:
         L.sb_op_rmsnorm.argtypes = [vp, vp, vp, i32, i32, f32, vp]
         L.sb_op_gemv.argtypes = [vp, i32, i32, i32, vp, vp, i32, i32, vp, vp]
         L.sb_op_gemv_scratch_bytes.argtypes = [i32, i32]
+        L.sb_op_gate_up.argtypes = [vp, i32, i32, i32, vp, vp, i32, i32, vp, vp]
         L.sb_op_gemv_scratch_bytes.restype = sz
         L.sb_op_head.argtypes = [vp, i32, i32, i32, vp, i32, f32, i32, vp, vp, vp, vp, vp]
         L.sb_op_head_static.argtypes = [vp, i32, i32, i32, vp, i32, f32, i32, vp, vp, vp]
@@ -508,6 +509,19 @@ def op_gemv(W, x, kernel: int = PROJ_VALU):
     check(lib().sb_op_gemv(W.data_ptr(), _wdtype(W), N, K, x.data_ptr(), y.data_ptr(), M, kernel,
                            scratch.data_ptr(), _stream_ptr(torch, x.device)))
     return y
+
+
+def op_gate_up(W, x, kernel: int = PROJ_VALU):
+    """W [2N, K] (gate rows, then up rows; op_repack of it for PROJ_MFMA_PACKED), x [M, K] float32 ->
+    u [M, N] float32 = silu(gate) * up."""
+    import torch
+    N, K = W.shape[0] // 2, W.shape[1]
+    M = x.shape[0]
+    u = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    scratch = torch.empty(max(lib().sb_op_gemv_scratch_bytes(M, K), 256), dtype=torch.uint8, device=x.device)
+    check(lib().sb_op_gate_up(W.data_ptr(), _wdtype(W), N, K, x.data_ptr(), u.data_ptr(), M, kernel,
+                              scratch.data_ptr(), _stream_ptr(torch, x.device)))
+    return u
 
 
 def op_head(W, x, T: float, kernel: int = PROJ_VALU, want_logits: bool = False):

@@ -1705,6 +1705,26 @@ int32_t sb_op_gemv(const void* W, int32_t w_dtype, int32_t N, int32_t K, const f
     return SB_OK;
 }
 
+int32_t sb_op_gate_up(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, float* u, int32_t M,
+                      int32_t kernel, void* scratch, void* stream) {
+    int rc = op_check(W, w_dtype, N, K, x, M, kernel);
+    if (rc) return rc;
+    if (N > 0x3fffffff) return fail(SB_EINVAL, "op_gate_up: N too large");
+    if (!u) return fail(SB_EINVAL, "op_gate_up: u is NULL");
+    GemvArgs g{};
+    g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.y = u; g.ldy = N; g.M = M; g.epi = EPI_SWIGLU;
+    g.packed = kernel == SB_PROJ_MFMA_PACKED;
+    if (kernel != SB_PROJ_VALU) {
+        if (!scratch || ((uintptr_t)scratch & 15)) return fail(SB_EINVAL, "op_gate_up: MFMA path needs aligned scratch");
+        g.xs = (uint16_t*)scratch;
+        HIP_TRY(launch_split(x, (uint16_t*)scratch, M, K, (hipStream_t)stream));
+        HIP_TRY(launch_gemv_mfma(g, (hipStream_t)stream));
+    } else {
+        HIP_TRY(launch_gemv_valu(g, (hipStream_t)stream));
+    }
+    return SB_OK;
+}
+
 int32_t sb_op_repack(const void* W, int32_t N, int32_t K, void* packed, void* stream) {
     if (!W || !packed || ((uintptr_t)W & 15) || ((uintptr_t)packed & 15)) return fail(SB_EINVAL, "op_repack: NULL / misaligned operand");
     if (N < 16 || N % 16 || K < 128 || K % 128) return fail(SB_EINVAL, "op_repack: need N %% 16 == 0 and K %% 128 == 0");

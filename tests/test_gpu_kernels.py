@@ -106,6 +106,29 @@ def test_prompt_pass_gemm(T, N, K, M):
         assert np.array_equal(y3, y[:3])
 
 
+GATE_UP_SHAPES = [(64, 256, 3), (11008, 4096, 1), (11008, 4096, 6), (14336, 4096, 8)]
+GATE_UP_CASES = [(k, *c) for k in ("valu", "mfma", "mfma_packed") for c in GATE_UP_SHAPES] + [("valu", 1000, 512, 5)]
+
+
+@pytest.mark.parametrize("kernel,N,K,M", GATE_UP_CASES)   # (the MFMA kernels take whole 16-row tiles: no ragged N there)
+def test_gate_up_swiglu(T, kernel, N, K, M):
+    """The gate/up sweep with its SwiGLU epilogue as the decode path runs it, against the oracle's
+    mat-vec and SwiGLU, at the 7B and 8B FFN shapes and a ragged one."""
+    import paper_2604_12247_amd as sb
+    g = np.random.default_rng(N + K + M)
+    W = _rand_w(g, 2 * N, K, True, std=0.03)
+    x = g.standard_normal((M, K)).astype(np.float32)
+    kid = {"valu": sb.PROJ_VALU, "mfma": sb.PROJ_MFMA, "mfma_packed": sb.PROJ_MFMA_PACKED}[kernel]
+    Wd = _dev(T, W)
+    if kernel == "mfma_packed":
+        Wd = sb.op_repack(Wd)
+    u = sb.op_gate_up(Wd, _dev(T, x), kid).cpu().numpy()
+    for m in range(M):
+        ref = orc.swiglu(orc.matvec(W, x[m].astype(np.float64)))
+        scale = np.max(np.abs(ref))
+        assert np.max(np.abs(u[m] - ref)) <= 1e-4 * scale, (m, np.max(np.abs(u[m] - ref)), scale)
+
+
 @pytest.mark.parametrize("kernel", ["valu", "mfma", "mfma_packed"])
 def test_gemv_row_result_does_not_depend_on_m(T, kernel):
     """A row's output is bit-identical whether it is computed alone or with others."""
@@ -127,7 +150,7 @@ def test_gemv_row_result_does_not_depend_on_m(T, kernel):
 
 
 @pytest.mark.parametrize("kernel", ["valu", "mfma", "mfma_packed"])
-@pytest.mark.parametrize("N,K,M", [(1024, 256, 1), (32000, 4096, 1), (32000, 4096, 6), (128256, 512, 2)])
+@pytest.mark.parametrize("N,K,M", [(1024, 256, 1), (32000, 4096, 1), (32000, 4096, 6), (128256, 512, 2), (128256, 4096, 3)])
 def test_head_argmax_and_confidence(T, kernel, N, K, M):
     import paper_2604_12247_amd as sb
     k = {"valu": sb.PROJ_VALU, "mfma": sb.PROJ_MFMA, "mfma_packed": sb.PROJ_MFMA_PACKED}[kernel]

@@ -60,6 +60,30 @@ def test_rmsnorm_hand_values(bits):
 
 
 @pytest.mark.parametrize("bits", BITS)
+def test_swiglu_closed_forms_and_library_routine(bits):
+    """silu(g) * v: hand values, the identities silu(g) - silu(-g) = g and silu(g) + silu(-g) =
+    g tanh(g / 2), the limits, operand order (gate first, up second), and torch's own silu."""
+    import torch
+    t = tol(bits)
+    # silu(0) = 0; silu(ln 3) = ln 3 * 3/4; the up value multiplies
+    out = orc.swiglu(np.array([0.0, math.log(3.0), 5.0, 2.0]), bits)       # gates 0, ln 3; ups 5, 2
+    assert np.allclose(out, [0.0, math.log(3.0) * 0.75 * 2.0], atol=t)
+    g = np.linspace(-9.0, 9.0, 37)
+    one = np.ones_like(g)
+    sp, sm = orc.swiglu(np.concatenate([g, one]), bits), orc.swiglu(np.concatenate([-g, one]), bits)
+    assert np.allclose(sp - sm, g, atol=t * 10)
+    assert np.allclose(sp + sm, g * np.tanh(g / 2), atol=t * 10)
+    # large gates pass through, very negative ones close
+    assert np.allclose(orc.swiglu(np.array([40.0, -40.0, 1.5, 1.5]), bits), [60.0, 0.0], atol=1e-12 if bits == 64 else 1e-5)
+    # gate and up are not interchangeable
+    assert not np.allclose(orc.swiglu(np.array([1.0, 3.0]), bits), orc.swiglu(np.array([3.0, 1.0]), bits))
+    r = np.random.default_rng(5)
+    gu = r.standard_normal(2 * 300) * 3
+    ref = (torch.nn.functional.silu(torch.from_numpy(gu[:300])) * torch.from_numpy(gu[300:])).numpy()
+    assert np.allclose(orc.swiglu(gu, bits), ref, atol=t * 30, rtol=t * 10)
+
+
+@pytest.mark.parametrize("bits", BITS)
 def test_rope_rotation_hand_values(bits):
     # hd = 2: one pair, theta_0 = 1, so position p rotates (1,0) by p radians
     v = orc.rope_apply(np.array([1.0, 0.0]), 1, 10000.0, bits)
