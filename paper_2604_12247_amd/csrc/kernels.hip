@@ -484,29 +484,35 @@ hipError_t launch_sample_accept(const SampleArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-// Partial (max, arg max, sum exp) of the block's logits zs[i][m], i < rows.
+// Partial (max, arg max, sum exp) of the block's logits zs[i][m], i < ROWS: thread (m, i) holds one
+// logit, the ROWS lanes of a row are reduced with a fixed shuffle tree (ties: the lower index).
+// Every thread of the block calls it (blocks have at least 8 * ROWS threads).
 template <int ROWS>
 __device__ __forceinline__ void head_partial(const HeadArgs& h, float (*zs)[SB_MAX_W], uint32_t rows, int n0, int N, int nb) {
-    int tid = threadIdx.x;
-    if (tid < SB_MAX_W && ((rows >> tid) & 1u)) {
-        int m = tid;
-        float mx = -SB_INF;
-        int idx = 0x7fffffff;
-        for (int i = 0; i < ROWS; ++i) {
-            int n = n0 + i;
-            if (n < N) {
-                float z = zs[i][m];
-                if (z > mx) { mx = z; idx = n; }
-                if (h.logits) h.logits[(size_t)m * N + n] = z;
-            }
-        }
-        float s = 0.f;
-        for (int i = 0; i < ROWS; ++i)
-            if (n0 + i < N) s += expf((zs[i][m] - mx) / h.T);
+    static_assert(ROWS == 16 || ROWS == 32, "a row's lanes lie in one wave");
+    const int tid = threadIdx.x;
+    if (tid >= SB_MAX_W * ROWS) return;   // (whole waves: 8 * ROWS is a multiple of 64)
+    const int m = tid / ROWS, i = tid % ROWS, n = n0 + i;
+    const bool live = n < N;
+    const float z = live ? zs[i][m] : -SB_INF;
+    const bool row_on = (rows >> m) & 1u;
+    if (h.logits && live && row_on) h.logits[(size_t)m * N + n] = z;
+    float mx = z;
+    int idx = live ? n : 0x7fffffff;
+#pragma unroll
+    for (int o = ROWS / 2; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(mx, o, 64);
+        const int oi = __shfl_xor(idx, o, 64);
+        if (ov > mx || (ov == mx && oi < idx)) { mx = ov; idx = oi; }
+    }
+    float sum = live ? expf((z - mx) / h.T) : 0.f;
+#pragma unroll
+    for (int o = ROWS / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (i == 0 && row_on) {
         float* p = h.partials + ((size_t)m * nb + blockIdx.x) * 4;
         p[0] = mx;
         p[1] = __int_as_float(idx);
-        p[2] = s;
+        p[2] = sum;
     }
 }
 
