@@ -704,6 +704,7 @@ hipError_t launch_repack(const void* W, void* P, int32_t N, int32_t K, hipStream
 template <int RT, int EPI, int WPB, bool PACKED>
 __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     constexpr int NT = 64 * WPB;
+    static_assert(NT >= RT * 128, "the tails take one element per thread");
     __shared__ __attribute__((aligned(16))) float red[WPB][RT][64][4];
     __shared__ float cs[RT][16][17];
     __shared__ float zs[16 * RT][SB_MAX_W];
@@ -774,6 +775,17 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
     const int nkb = KB > wave ? (KB - wave + WPB - 1) / WPB : 0;  // k blocks of this wave
 #pragma unroll
     for (int s = 0; s < DEPTH - 1; ++s) load_block(wbuf[s], bbuf[s], kb0 + s * WPB);
+    // What the residual tail needs from memory (the element this thread finishes, its norm gains)
+    // is requested now, behind the first weight loads, instead of at the end of the k loop.
+    float pre_y = 0.f, pre_gA = 0.f, pre_gB = 0.f;
+    if (EPI == EPI_RESID && tid < RT * 16 * 8) {
+        const int t = tid >> 7, m = (tid >> 4) & 7, i = tid & 15, n = n0 + t * 16 + i;
+        if (((rows >> m) & 1u) && n < N) {
+            pre_y = a.y[(size_t)m * a.ldy + n];
+            if (a.nxA) pre_gA = a.gainA[n];
+            if (a.nxB) pre_gB = a.gainB[n];
+        }
+    }
     // RMSNorm scale of each row from the partial sums of squares its producer left
     // (added in index order; the first weight loads are already in flight)
     if (a.ssq_in) {
@@ -819,11 +831,11 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
             if (((rows >> m) & 1u) && n < N) {
                 float v = (cs[t][i][m] + cs[t][i][m + 8]) * s_inv[m];
                 float* yp = a.y + (size_t)m * a.ldy + n;
-                if (EPI == EPI_RESID) v += *yp;
+                if (EPI == EPI_RESID) v += pre_y;   // (e == tid: a block has at least RT * 128 threads)
                 *yp = v;
                 if (EPI == EPI_RESID) {
-                    if (a.nxA) split_store(a.nxA, a.ldy, m, n, v * a.gainA[n]);
-                    if (a.nxB) split_store(a.nxB, a.ldy, m, n, v * a.gainB[n]);
+                    if (a.nxA) split_store(a.nxA, a.ldy, m, n, v * pre_gA);
+                    if (a.nxB) split_store(a.nxB, a.ldy, m, n, v * pre_gB);
                     sq = v * v;
                 }
             }
