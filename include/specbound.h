@@ -1,6 +1,7 @@
 /*
- * specbound.h -- C ABI of libspecbound: the batch-1 bounded self-speculative
- * decode step (SpecBound) as hand-written gfx950 kernels.
+ * specbound.h -- C ABI of libspecbound: the bounded self-speculative decode step
+ * (SpecBound; batch 1 as in the paper, and batches of sessions) as hand-written
+ * gfx950 kernels.
  *
  * The calls follow the paper's statement of the method: a draft phase that runs
  * each new token through the shallow layers and tests an early-exit head after
@@ -35,7 +36,17 @@
  *    hipStream_t cast to void*; NULL = the default stream).  Calls that return
  *    results to the host synchronise that stream before returning.
  *  - One session = one sequence (batch 1).  Calls on one session must not
- *    overlap; sessions of one model share its stream.
+ *    overlap; sessions of one model share its stream.  sb_new_batch groups
+ *    prefilled sessions so that sb_batch_decode runs their rounds side by side.
+ *
+ * Typical sequence
+ *    sb_query_sizes(&cfg, &sizes);                    sizes of the caller's buffers
+ *    sb_load_model(&cfg, &weights, stream, &model);   once per model
+ *    sb_new_session(model, kv_pool, .., workspace, .., &session);
+ *    sb_prefill(session, prompt, n, &first_token);
+ *    loop { loop { sb_draft_step(session, &params, &d); } while (d.status == SB_EXITED);
+ *           sb_verify(session, &params, &v);  emit v.tokens[0 .. v.n_emit) }
+ *    -- or sb_decode / sb_generate, which run that loop inside the library.
  */
 #ifndef SPECBOUND_H
 #define SPECBOUND_H
