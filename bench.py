@@ -234,6 +234,21 @@ def main():
                           "layer on a second stream (bytes of both / time of the phase); verify: remaining layers + final head")
         log("[bench]   phases: " + ", ".join(f"{k} {v['gpu_ms']} ms {v['GB/s']} GB/s" for k, v in phases.items() if isinstance(v, dict)))
 
+    # the same schedule with every exit decision read back from the device after each head, as the host
+    # has to do when exits are computed rather than forced (no head beside the next layer, one wait per layer)
+    readback_tok_s = None
+    if not args.no_kernel_table:
+        p_rb = sb.Params(wl.d_max, wl.w_max, T, wl.threshold, forced_exit=fe, forced_draft=fd, head_mask=head_mask,
+                         exit_readback=True)
+        best = None
+        for _ in range(2):
+            sess.rewind(P, first)
+            out_rb, st_rb = sess.decode(gen_len, p_rb)
+            best = st_rb["decode_ms"] if best is None else min(best, st_rb["decode_ms"])
+        assert out_rb.tolist() == greedy[1:gen_len + 1]
+        readback_tok_s = gen_len / best * 1e3
+        log(f"[bench] exit decisions read back per layer: {readback_tok_s:.1f} tok/s ({readback_tok_s / tok_s:.3f} of the headline)")
+
     batch = None
     if args.batch:
         batch = batch_runs(sb, si, model, wl, [int(x) for x in args.batch.split(",")], min(gen_len, 256), ar_tok_s, tok_s)
@@ -258,6 +273,7 @@ def main():
                    "batch": 1, **({"variant": f"exit heads only at the layers of mask {head_mask:#x}; forced exit layers "
                                               "moved up to the next such layer"} if head_mask else {})},
         "greedy_ar_tokens_per_s": round(ar_tok_s, 2), "speedup_vs_greedy_ar": round(tok_s / ar_tok_s, 4),
+        "tokens_per_s_with_exit_decisions_read_back_per_layer": None if readback_tok_s is None else round(readback_tok_s, 2),
         "tokens_per_round": round(st["emitted"] / st["rounds"], 3), "prefill_ms": round(prefill_ms, 1), "prefill_first_call_ms": round(prefill_first_ms, 1),
         "algorithmic_GB_per_step": round(spec_bytes / 1e9, 2),
         "algorithmic_GBps_whole_path": round(spec_bytes / 1e6 / ms_per_step, 1),

@@ -163,6 +163,12 @@ typedef struct sb_params {
     float top_p;
     const float *sample_u;
     int64_t n_sample_u;
+    /* 0: under a forced schedule the host knows every exit in advance, enqueues a round without
+     * waiting and lets the exit heads run beside the following layers.  1: the host takes every exit
+     * decision from the device's flag after each head, as it has to when exits are computed -- the
+     * same decisions, tokens and counters, with the control flow (and cost) of computed exits.  Steps
+     * without a forced entry always work this way.  sb_batch_decode ignores the field. */
+    int32_t exit_readback;
 } sb_params;
 
 typedef struct sb_draft_result {

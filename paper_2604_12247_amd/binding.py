@@ -50,7 +50,7 @@ class sb_params(C.Structure):
                 ("forced_exit", C.POINTER(C.c_int32)), ("forced_draft", C.POINTER(C.c_int32)),
                 ("n_forced", C.c_int64), ("head_mask", C.c_uint32),
                 ("sample_temperature", C.c_float), ("top_p", C.c_float),
-                ("sample_u", C.POINTER(C.c_float)), ("n_sample_u", C.c_int64)]
+                ("sample_u", C.POINTER(C.c_float)), ("n_sample_u", C.c_int64), ("exit_readback", C.c_int32)]
 
 
 class sb_draft_result(C.Structure):
@@ -197,7 +197,7 @@ class Params:
     def __init__(self, d_max: int, w_max: int, T: Sequence[float], threshold: float,
                  forced_exit: Optional[Sequence[int]] = None, forced_draft: Optional[Sequence[int]] = None,
                  eos_id: int = -1, head_mask: int = 0, sample_temperature: float = 0.0, top_p: float = 1.0,
-                 sample_u=None):
+                 sample_u=None, exit_readback: bool = False):
         self.T = np.ascontiguousarray(T, dtype=np.float32)
         self.su = None if sample_u is None else np.ascontiguousarray(sample_u, dtype=np.float32)
         self.fe = None if forced_exit is None else np.ascontiguousarray(forced_exit, dtype=np.int32)
@@ -214,7 +214,7 @@ class Params:
                            None if self.fd is None else self.fd.ctypes.data_as(C.POINTER(C.c_int32)),
                            n_forced, head_mask, sample_temperature, top_p,
                            None if self.su is None else self.su.ctypes.data_as(C.POINTER(C.c_float)),
-                           0 if self.su is None else len(self.su))
+                           0 if self.su is None else len(self.su), 1 if exit_readback else 0)
 
 
 def _stats_dict(st: sb_stats) -> dict:

@@ -624,7 +624,7 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
     if (over >= c.vocab) return fail(SB_EINVAL, "forced_draft[%lld] = %d out of range", (long long)k, over);
     if (forced < -1) forced = -1;
     if (over < -1) over = -1;
-    const bool computed = forced < 0;
+    const bool computed = forced < 0 || p->exit_readback != 0;   // the exit decision is read from the device after each head
 
     // the previous step's last exit head wrote the token this step embeds
     if ((rc = join_head(s))) return rc;

@@ -217,6 +217,28 @@ def test_draft_injection_realises_accept_schedule_on_gpu(sb):
     assert st2["accept_hist"][4] >= st2["rounds"] - 1 and st2["rounds"] == 6
 
 
+def test_exit_decisions_read_back_per_layer_give_the_same_rounds(sb):
+    """sb_params.exit_readback: under a forced schedule the host may take every exit decision from
+    the device's flag after each head (the control flow of computed exits) instead of knowing it in
+    advance -- tokens, counters and histograms must not change."""
+    shape, w, om, gm = _build(sb, "bf16-mfma", n_layers=6, n_exit=3, seed=36)
+    prompt = si.make_prompt(shape.vocab, 23, 46)
+    n_new = 48
+    ar, _ = gm.session().generate(prompt, n_new + 8, gpu_params(0, 1))
+    acc = si.accept_schedule(11, 64, 4)
+    fd, _ = si.injection_schedule(ar.tolist(), acc, 4, shape.vocab)
+    fe = si.forced_exit_schedule(12, len(fd), 0, 3)          # includes steps that never exit (depth bound)
+    T = linear_T(3)
+    runs = []
+    for rb in (False, True):
+        p = sb.Params(3, 4, T, 0.5, forced_exit=fe, forced_draft=fd, exit_readback=rb)
+        runs.append(gm.session().generate(prompt, n_new, p))
+    (o0, s0), (o1, s1) = runs
+    assert o0.tolist() == o1.tolist() == ar[:n_new].tolist()
+    for k in ("rounds", "drafts", "emitted", "draft_steps", "head_evals", "layer_sweeps", "row_layers", "accept_hist", "exit_hist"):
+        assert s0[k] == s1[k], k
+
+
 def test_paged_kv_order_determinism_and_reuse_of_session(sb):
     shape, w, om, gm = _build(sb, "bf16-mfma-gqa", n_layers=4, n_exit=2, seed=37)
     prompt = si.make_prompt(shape.vocab, 33, 47)
