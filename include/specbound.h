@@ -82,7 +82,8 @@ typedef struct sb_config {
     int32_t weight_dtype;  /* SB_FP32 or SB_BF16: element type of every matrix */
     int32_t kv_dtype;      /* SB_FP32 or SB_BF16: K and V are rounded to this on cache store */
     int32_t n_exit_heads;
-    int32_t max_seq;       /* capacity in tokens, a multiple of SB_KV_BLOCK */
+    int32_t max_seq;       /* capacity in tokens, a multiple of SB_KV_BLOCK, at most 65536 (32768 with an
+                              fp32 cache and head_dim 128) */
     int32_t proj_kernel;   /* SB_PROJ_*; AUTO = MFMA_PACKED for bf16 weights, VALU for fp32 */
     int32_t kv_block;      /* tokens per KV page: SB_KV_BLOCK, or 0 for that default (the page size is
                               built into the attention kernels) */

@@ -54,6 +54,10 @@ int check_config(const sb_config* c) {
         return fail(SB_EINVAL, "config: n_exit_heads out of range");
     if (c->max_seq < SB_KV_BLOCK || c->max_seq % SB_KV_BLOCK)
         return fail(SB_EINVAL, "config: max_seq must be a positive multiple of %d", SB_KV_BLOCK);
+    // the attention kernels merge at most 512 key chunks (of 128 keys, 64 where a key's row exceeds 256 bytes)
+    if ((c->max_seq + attn_chunk_keys(c->head_dim, c->kv_dtype) - 1) / attn_chunk_keys(c->head_dim, c->kv_dtype) > 512)
+        return fail(SB_EINVAL, "config: max_seq = %d exceeds the longest context the attention kernels take (%d tokens)", c->max_seq,
+                    512 * attn_chunk_keys(c->head_dim, c->kv_dtype));
     if (c->d_model % 8 || c->d_ffn % 8 || (c->n_heads * c->head_dim) % 8)
         return fail(SB_EINVAL, "config: d_model, d_ffn and n_heads*head_dim must be multiples of 8");
     if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return fail(SB_EINVAL, "config: rms_eps / rope_base");

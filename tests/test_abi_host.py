@@ -54,7 +54,9 @@ def test_query_sizes_and_config_validation():
     assert kv == 32 * 2 * 1040 * 32 * 128 * 2
     assert ws > 8 * 4096 * 4
     bad = [dict(max_seq=1000), dict(head_dim=96), dict(n_kv_heads=5), dict(weight_dtype=7),
-           dict(n_exit_heads=99), dict(d_model=4100), dict(vocab=0), dict(proj_kernel=9)]
+           dict(n_exit_heads=99), dict(d_model=4100), dict(vocab=0), dict(proj_kernel=9),
+           dict(max_seq=65536 + 16),                       # more than 512 chunks of 128 keys
+           dict(max_seq=32768 + 16, kv_dtype=sb.FP32)]     # an fp32 cache at head_dim 128 has 64-key chunks
     for kw in bad:
         cfg = sb.make_config(shape, 1040)
         for k, v in kw.items():
@@ -62,6 +64,8 @@ def test_query_sizes_and_config_validation():
         with pytest.raises(sb.SbError) as e:
             sb.query_sizes(cfg)
         assert e.value.code == sb.EINVAL, kw
+    cfg = sb.make_config(shape, 65536)                     # the longest context is accepted
+    assert sb.query_sizes(cfg)[0] == 32 * 2 * 65536 * 32 * 128 * 2
     # the MFMA path is refused for fp32 weights
     cfg = sb.make_config(si.CONFIGS["C1"].shape, 112, sb.PROJ_MFMA)
     with pytest.raises(sb.SbError):

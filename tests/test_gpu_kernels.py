@@ -250,6 +250,7 @@ ATT_CASES = [  # Hq, Hkv, hd, kv_bf16, n_ctx, M, rope base, shuffled pages
     (4, 2, 64, True, 1000, 8, 5e5, True),      # two query heads per kv head, sixteen query columns, head_dim 64, long context
     (8, 8, 128, True, 63, 3, 1e4, False),      # shorter than one chunk
     (8, 8, 128, True, 1030, 5, 1e4, True),     # nine chunks, the last one nearly empty
+    (2, 1, 128, True, 65532, 4, 1e4, True),    # the longest context the kernels take: 512 chunks, 4096 shuffled pages
 ]
 
 
