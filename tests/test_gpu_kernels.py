@@ -251,6 +251,8 @@ ATT_CASES = [  # Hq, Hkv, hd, kv_bf16, n_ctx, M, rope base, shuffled pages
     (8, 8, 128, True, 63, 3, 1e4, False),      # shorter than one chunk
     (8, 8, 128, True, 1030, 5, 1e4, True),     # nine chunks, the last one nearly empty
     (2, 1, 128, True, 65532, 4, 1e4, True),    # the longest context the kernels take: 512 chunks, 4096 shuffled pages
+    (32, 1, 64, True, 200, 3, 1e4, True),      # one kv head for 32 query heads: six 16-query groups per block
+    (16, 1, 128, False, 90, 5, 1e4, False),    # the same on the fp32-cache kernel
 ]
 
 
@@ -279,6 +281,7 @@ PROMPT_ATT_CASES = [  # Hq, Hkv, hd, rows already cached, rows of this call, rop
     (4, 2, 64, 37, 200, 1e4),       # GQA, a cached prefix, chunk boundary inside a query block
     (6, 2, 128, 0, 150, 5e5),       # group of 3: query blocks straddle rows
     (8, 8, 128, 130, 333, 1e4),     # several chunks, ragged last block and last page
+    (16, 1, 128, 40, 100, 1e4),     # one kv head for 16 query heads: a row fills a wave's 16 queries
 ]
 
 
