@@ -61,7 +61,9 @@ def test_gemv_valu(T, N, K, bf16, M):
     assert np.max(np.abs(y - ref)) <= 1e-5 * np.max(np.abs(ref)) + 1e-7
 
 
-MFMA_CASES = [(16, 128), (64, 256), (4096, 4096), (12288, 4096), (4096, 11008), (32000, 4096), (48, 384)]
+MFMA_CASES = [(16, 128), (64, 256), (4096, 4096), (12288, 4096), (4096, 11008), (32000, 4096), (48, 384),
+              (15024, 256),      # two row tiles per block, an odd number of tiles: the last block owns one
+              (4096, 14336)]
 
 
 @pytest.mark.parametrize("N,K", MFMA_CASES)
@@ -150,7 +152,8 @@ def test_gemv_row_result_does_not_depend_on_m(T, kernel):
 
 
 @pytest.mark.parametrize("kernel", ["valu", "mfma", "mfma_packed"])
-@pytest.mark.parametrize("N,K,M", [(1024, 256, 1), (32000, 4096, 1), (32000, 4096, 6), (128256, 512, 2), (128256, 4096, 3)])
+@pytest.mark.parametrize("N,K,M", [(1024, 256, 1), (32000, 4096, 1), (32000, 4096, 6), (128256, 512, 2), (128256, 4096, 3),
+                                   (15024, 256, 3)])   # an odd number of 16-row tiles, two per block
 def test_head_argmax_and_confidence(T, kernel, N, K, M):
     import paper_2604_12247_amd as sb
     k = {"valu": sb.PROJ_VALU, "mfma": sb.PROJ_MFMA, "mfma_packed": sb.PROJ_MFMA_PACKED}[kernel]
