@@ -49,6 +49,10 @@ struct HeadArgs {
     int32_t forced_draft;  // POST_EXIT: >= 0 overrides the drafted id
     float threshold;       // POST_EXIT
     int32_t n_drafts;      // POST_ACCEPT
+    int32_t* note;         // POST_EXIT, optional: five ints in host memory the device can write (mapped, coherent) --
+                           // the merge leaves {note_seq, exit?, drafted id or -1, confidence bits, arg max} there,
+                           // the sequence number last, so that the host can read the decision without a copy
+    int32_t note_seq;
     int32_t row0;          // merge: the M rows merged are rows row0 .. row0 + M - 1 of the partials
     int32_t skip_merge;    // projection launch: leave the partials, the caller launches the merges itself
     // POST_EXIT, optional (embed_E != nullptr): when the row exits, the merge also embeds the

@@ -281,12 +281,20 @@ __device__ __forceinline__ void head_merge_body(const HeadArgs& h, const int M, 
             R->head_argmax[s] = am;
             bool ex = h.forced_exit >= 0 ? (h.layer == h.forced_exit) : (cf >= h.threshold);
             R->exit_flag = ex ? 1 : 0;
+            int tok = -1;
             if (ex) {
-                int tok = h.forced_draft >= 0 ? h.forced_draft : am;
+                tok = h.forced_draft >= 0 ? h.forced_draft : am;
                 R->drafts[s] = tok;
                 R->slot_tok[s + 1] = tok;
                 R->exit_layer[s] = h.layer;
                 if (h.embed_E) s_embed_tok = tok;
+            }
+            if (h.note) {   // the decision for the host, the sequence number last (system-scope release)
+                h.note[1] = ex ? 1 : 0;
+                h.note[2] = tok;
+                h.note[3] = __float_as_int(cf);
+                h.note[4] = am;
+                __hip_atomic_store(&h.note[0], h.note_seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
             }
         } else if (h.post == POST_ACCEPT) {
             // Keep the longest prefix of drafts equal to the greedy tokens; the row

@@ -188,6 +188,11 @@ struct sb_session {
     KvLayout kv;
     DevRound* d_round;
     DevRound* h_round;  // pinned host copy
+    // Exit decisions that gate the host's next launch (computed exits) arrive without a copy: the
+    // head merge writes them into this mapped host memory, the host polls the sequence number.
+    int32_t* note_h;
+    int32_t* note_d;    // the same memory as the device addresses it
+    int32_t note_seq;
     int32_t c, pending;
     bool has_pending;
     int n_slots, n_drafts;
@@ -263,6 +268,35 @@ int readback(sb_session* s) {
     if (jrc) return jrc;
     HIP_TRY(hipMemcpyAsync(s->h_round, s->d_round, sizeof(DevRound), hipMemcpyDeviceToHost, s->m->stream));
     HIP_TRY(hipStreamSynchronize(s->m->stream));
+    return SB_OK;
+}
+
+// Waits until the head merge that carries sequence number `seq` has left its note, then takes the
+// exit decision and what belongs to it into the host's copy of the round record.  The wait is a
+// poll of host memory; if the note does not come (a failed launch), the stream's own error decides.
+int wait_note(sb_session* s, int32_t seq, int idx) {
+    volatile int32_t* n = s->note_h;
+    const double t0 = now_ms();
+    bool seen = false;
+    for (int64_t spin = 0;; ++spin) {
+        if (__atomic_load_n(&s->note_h[0], __ATOMIC_ACQUIRE) == seq) { seen = true; break; }
+        if ((spin & 0x3ff) == 0x3ff) {
+            const hipError_t q = hipStreamQuery(s->m->stream);
+            if (q != hipErrorNotReady) {   // the stream is idle (or failed): the note is there now, or never comes
+                HIP_TRY(q);
+                seen = __atomic_load_n(&s->note_h[0], __ATOMIC_ACQUIRE) == seq;
+                break;
+            }
+            if (now_ms() - t0 > 10000.0) break;
+        }
+    }
+    s->st.host_wait_ms += now_ms() - t0;
+    if (!seen) return fail(SB_EDEVICE, "draft_step: the exit decision did not arrive from the device");
+    s->h_round->exit_flag = n[1];
+    s->h_round->drafts[idx] = n[2];
+    int32_t cb = n[3];
+    memcpy(&s->h_round->conf[idx], &cb, 4);
+    s->h_round->head_argmax[idx] = n[4];
     return SB_OK;
 }
 
@@ -671,6 +705,7 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
             h.embed_H = Hrow + c.d_model;
             h.embed_en = embed_norm(s, idx + 1);
         }
+        if (computed) { h.note = s->note_d; h.note_seq = ++s->note_seq; }   // the host's next launch waits for this decision
         // The head only reads what W_down left for it, so it can run beside the next layer on the
         // second stream -- except the head at which the row exits: the next step starts from its
         // result, so it stays on the main stream (no hop between streams on the critical path).
@@ -688,7 +723,7 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
         }
         s->st.head_evals++;
         if (computed) {
-            if ((rc = readback(s))) return rc;
+            if ((rc = wait_note(s, h.note_seq, idx))) return rc;
             if (s->h_round->exit_flag) { exit_at = l; break; }
         } else if (l == forced) {
             exit_at = l;
@@ -822,6 +857,7 @@ hipError_t sync_all(sb_session* s) {
 
 void free_session_resources(sb_session* s) {
     if (s->h_round) (void)hipHostFree(s->h_round);
+    if (s->note_h) (void)hipHostFree(s->note_h);
     for (int i = 0; i < 5; ++i)
         if (s->ev_ph[i]) { (void)hipEventDestroy(s->ev_ph[i]); s->ev_ph[i] = nullptr; }
     for (int i = 0; i < 4; ++i) {
@@ -1333,11 +1369,14 @@ int32_t sb_new_session(sb_model* m, void* kv_pool, size_t kv_bytes, void* worksp
     s->head_pending_ev = 0;
     for (int i = 0; i < 4; ++i) { s->ev_main[i] = nullptr; s->ev_head[i] = nullptr; }
     s->h_round = nullptr;
+    s->note_h = nullptr; s->note_d = nullptr; s->note_seq = 0;
     s->phase_timing = false;
     s->fail_countdown = 0;
     for (int i = 0; i < 5; ++i) s->ev_ph[i] = nullptr;
     reset_session(s);
     hipError_t e = hipHostMalloc((void**)&s->h_round, sizeof(DevRound), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&s->note_h, 64, hipHostMallocMapped | hipHostMallocCoherent);
+    if (e == hipSuccess) { memset(s->note_h, 0, 64); e = hipHostGetDevicePointer((void**)&s->note_d, s->note_h, 0); }
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&s->head_stream, hipStreamNonBlocking);  // default priority
     for (int i = 0; i < 4 && e == hipSuccess; ++i) {
         e = hipEventCreateWithFlags(&s->ev_main[i], hipEventDisableTiming);
