@@ -2,20 +2,19 @@
 // machine of Bounded Speculation with Cached States (Sec. 3.3, Appendix A) that
 // decides which rows go through which layer and enqueues the kernels.  All
 // arithmetic of the method runs in the kernels; the host only keeps integers
-// (positions, reached layers, counters).
+// (positions, reached layers, counters).  This file: configuration, model and session
+// life cycle, the rounds of one sequence.  batch.cpp: several sequences side by side;
+// ops.cpp: the single-kernel entry points; host.h: what the three share.
 #include <chrono>
 #include <cmath>
-#include <cstdarg>
 #include <cstdio>
-#include <cstring>
-#include <string>
-#include <vector>
 
-#include "kernels.h"
+#include "host.h"
 
 using namespace sb;
+using namespace sbhost;
 
-namespace {
+namespace sbhost {
 
 thread_local std::string g_err;
 
@@ -29,18 +28,13 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 
-#define HIP_TRY(expr)                                                                         \
-    do {                                                                                      \
-        hipError_t e_ = (expr);                                                               \
-        if (e_ != hipSuccess) return fail(SB_EDEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
-    } while (0)
-
 double now_ms() {
     return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
 
-size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-size_t esize(int dtype) { return dtype == SB_BF16 ? 2 : 4; }
+}  // namespace sbhost
+
+namespace {
 
 int check_config(const sb_config* c) {
     if (!c) return fail(SB_EINVAL, "config is NULL");
@@ -79,15 +73,6 @@ int resolve_proj(const sb_config* c) {
     return ok ? SB_PROJ_MFMA_PACKED : SB_PROJ_VALU;
 }
 
-struct WsLayout {
-    size_t H, xn, xs_attn, xs_ffn, xs_exit, ssq_attn, ssq_ffn, qkv, att, atts, u, us, attn_part, head_part,
-        logits_exit, logits_final, round, table, total;
-    int max_chunks, head_blocks, n_pages, ssq_ld;
-    // prompt passes of SB_PREFILL_ROWS rows (packed bf16 weights only)
-    bool prefill_gemm;
-    size_t p_tok, p_H, p_xs, p_ssq, p_qkv, p_atts, p_us, p_part, p_attn_part;
-    int p_ssq_ld, p_rows;
-};
 
 WsLayout ws_layout(const sb_config* c) {
     WsLayout L{};
@@ -167,79 +152,8 @@ size_t kv_pool_bytes(const sb_config* c) {
 
 }  // namespace
 
-struct sb_model {
-    sb_config cfg;
-    const void *embed, *lm_head;
-    const float* final_norm;
-    std::vector<const float*> attn_norm, ffn_norm, exit_norm;
-    std::vector<const void*> w_qkv, w_o, w_gate_up, w_down, exit_head;
-    hipStream_t stream;
-    float *rope_cos, *rope_sin;
-    int proj;      // SB_PROJ_VALU or SB_PROJ_MFMA (row-major or packed, see `packed`)
-    bool packed;   // the projection pointers below name tile-packed copies owned by the model
-    std::vector<void*> owned;  // device allocations to free
-    int64_t layer_bytes, head_bytes;
-};
 
-struct sb_session {
-    sb_model* m;
-    char* ws;
-    WsLayout L;
-    KvLayout kv;
-    DevRound* d_round;
-    DevRound* h_round;  // pinned host copy
-    // Exit decisions that gate the host's next launch (computed exits) arrive without a copy: the
-    // head merge writes them into this mapped host memory, the host polls the sequence number.
-    int32_t* note_h;
-    int32_t* note_d;    // the same memory as the device addresses it
-    int32_t note_seq;
-    int32_t c, pending;
-    bool has_pending;
-    int n_slots, n_drafts;
-    int reached[SB_MAX_W], exit_layer[SB_MAX_W];
-    int32_t draft_host[SB_MAX_W];  // drafted id if the host knows it, else -1
-    bool round_closed;
-    bool next_embedded;  // the last draft step's head merge has already embedded the next row
-    int fail_countdown;  // test tap: the n-th projection launch from now reports a failure
-    int64_t* phase_bytes;  // where run_layer / run_head account their bytes (a field of st), or null
-    int64_t draft_counter;
-    bool debug;
-    sb_stats st;
-    // Exit heads run on a second stream next to the following layer when the exit
-    // layer is known in advance (forced schedules): events order the two streams.
-    hipStream_t head_stream;
-    hipEvent_t ev_main[4], ev_head[4];
-    unsigned ev_i;
-    bool head_pending;      // ev_head[(ev_i - 1) % 4] not yet waited for by the main stream
-    int head_pending_ev;
-    // phase timing: events at the boundaries of a round's phases (sb_phase_timing)
-    bool phase_timing;
-    hipEvent_t ev_ph[5];
-    // per-kernel event timing
-    uint32_t prof_mask;
-    int prof_every;                    // time every n-th launch of a class
-    int64_t prof_seen[SB_K_COUNT];
-    std::vector<hipEvent_t> prof_ev;   // pairs
-    std::vector<hipEvent_t> prof_cal;  // empty pairs (calibration)
-    std::vector<int> prof_cls;
-    std::vector<int64_t> prof_bytes;
-    size_t prof_used;                  // pairs used
-};
-
-// Several sequences decoded together (Sec. 4.3 evaluates batch 1; this is the batch > 1 form of
-// the same rounds): the rows of all sequences share every sweep over a layer's or a head's
-// weights, each sequence keeps its own KV cache and its own round.  Sequence b owns the rows
-// (slots) b * w_cap .. b * w_cap + w_cap - 1 of the first session's hidden cache.
-struct sb_batch {
-    sb_model* m;
-    int B, w_cap;
-    std::vector<sb_session*> seq;
-};
-
-namespace {
-
-template <typename T>
-T* wsp(sb_session* s, size_t off) { return reinterpret_cast<T*>(s->ws + off); }
+namespace sbhost {
 
 int check_params(const sb_session* s, const sb_params* p) {
     const sb_config& c = s->m->cfg;
@@ -300,23 +214,6 @@ int wait_note(sb_session* s, int32_t seq, int idx) {
     return SB_OK;
 }
 
-// Event pair around the launches of one kernel class, when that class is timed.
-struct ProfScope {
-    sb_session* s;
-    hipStream_t st;
-    long idx;
-    ProfScope(sb_session* s_, int cls, int64_t bytes, hipStream_t st_) : s(s_), st(st_), idx(-1) {
-        if (!(s->prof_mask & (1u << cls)) || s->prof_used * 2 + 2 > s->prof_ev.size()) return;
-        if (s->prof_seen[cls]++ % s->prof_every) return;
-        idx = (long)s->prof_used++;
-        s->prof_cls[idx] = cls;
-        s->prof_bytes[idx] = bytes;
-        (void)hipEventRecord(s->prof_ev[2 * idx], st);
-    }
-    ~ProfScope() {
-        if (idx >= 0) (void)hipEventRecord(s->prof_ev[2 * idx + 1], st);
-    }
-};
 
 // Main stream waits for the exit head that is still running on the head stream.
 int join_head(sb_session* s) {
@@ -904,311 +801,7 @@ int decode_impl(sb_session* s, const sb_params* p, int32_t* out_tokens, int* cnt
     return SB_OK;
 }
 
-// ---------------------------------------------------------------- batch > 1
-// One decoder layer (0-based l) on the rows of `mask`: sequence b contributes its local rows
-// j0[b] .. j0[b] + cnt[b] - 1 (cnt 0: none).  Projections: one launch each for all rows (the rows
-// are gathered by slot).  Attention: per sequence, on its own cache.  Values of a row are what the
-// single-sequence pass computes for it (a row's result never depends on the rows beside it).
-int batch_layer(sb_batch* bt, int l, uint32_t mask, const int* j0, const int* cnt, const float* head_gain) {
-    sb_session* hs = bt->seq[0];
-    sb_model* m = bt->m;
-    const sb_config& c = m->cfg;
-    hipStream_t st = m->stream;
-    const int d = c.d_model, f = c.d_ffn, hq = c.n_heads * c.head_dim;
-    const int qkv_rows = (c.n_heads + 2 * c.n_kv_heads) * c.head_dim;
-    float* H = wsp<float>(hs, hs->L.H);
-    uint16_t* xs_attn = wsp<uint16_t>(hs, hs->L.xs_attn);
-    uint16_t* xs_ffn = wsp<uint16_t>(hs, hs->L.xs_ffn);
-    uint16_t* xs_exit = wsp<uint16_t>(hs, hs->L.xs_exit);
-    float* ssq_attn = wsp<float>(hs, hs->L.ssq_attn);
-    float* ssq_ffn = wsp<float>(hs, hs->L.ssq_ffn);
-    float* qkv = wsp<float>(hs, hs->L.qkv);
-    uint16_t* atts = wsp<uint16_t>(hs, hs->L.atts);
-    uint16_t* us = wsp<uint16_t>(hs, hs->L.us);
-    int rc;
-    GemvArgs g{};
-    g.w_dtype = c.weight_dtype; g.M = SB_MAX_W; g.row_mask = mask; g.eps = c.rms_eps; g.ssq_ld = hs->L.ssq_ld;
-    g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = d; g.xs = xs_attn; g.y = qkv; g.ldy = qkv_rows; g.epi = EPI_STORE;
-    g.ssq_in = ssq_attn; g.ssq_nb = l == 0 ? 1 : d / 16;
-    if ((rc = gemv(hs, g, SB_K_QKV, st))) return rc;
-    int64_t kv_total = 0;
-    AttnArgs passes[SB_MAX_W];
-    int n_pass = 0;
-    for (int b = 0; b < bt->B; ++b) {
-        if (!cnt[b]) continue;
-        sb_session* s = bt->seq[b];
-        const int slot = b * bt->w_cap + j0[b];
-        AttnArgs a{};
-        a.q = qkv + (size_t)slot * qkv_rows; a.rope_cos = m->rope_cos; a.rope_sin = m->rope_sin; a.qkv_rows = qkv_rows;
-        a.n_heads = c.n_heads; a.kv = s->kv; a.layer = l; a.pos0 = s->c + j0[b]; a.M = cnt[b];
-        a.partials = wsp<float>(s, s->L.attn_part); a.max_chunks = s->L.max_chunks;
-        a.out = nullptr; a.out_split = atts + (size_t)slot * hq; a.split_rows = 8;
-        const int64_t kv_read = (int64_t)(a.pos0 + a.M) * 2 * c.n_kv_heads * c.head_dim * (int64_t)esize(c.kv_dtype);
-        passes[n_pass++] = a;
-        s->st.kv_bytes += kv_read;
-        s->st.row_layers += cnt[b];
-        kv_total += kv_read;
-    }
-    if (n_pass) {  // all sequences' passes in one pair of launches
-        ProfScope ps(hs, SB_K_ATTN, kv_total, st);
-        HIP_TRY(launch_attention_batch(passes, n_pass, st));
-    }
-    g.ssq_in = nullptr;
-    g.W = m->w_o[l]; g.N = d; g.K = hq; g.xs = atts; g.y = H; g.ldy = d; g.epi = EPI_RESID;
-    g.gainA = m->ffn_norm[l]; g.nxA = xs_ffn; g.ssq_out = ssq_ffn;
-    if ((rc = gemv(hs, g, SB_K_WO, st))) return rc;
-    g.gainA = nullptr; g.nxA = nullptr; g.ssq_out = nullptr;
-    g.W = m->w_gate_up[l]; g.N = f; g.K = d; g.xs = xs_ffn; g.y = nullptr; g.ys = us; g.ldy = f; g.epi = EPI_SWIGLU;
-    g.ssq_in = ssq_ffn; g.ssq_nb = d / 16;
-    if ((rc = gemv(hs, g, SB_K_GATEUP, st))) return rc;
-    g.ssq_in = nullptr;
-    g.W = m->w_down[l]; g.N = d; g.K = f; g.xs = us; g.y = H; g.ys = nullptr; g.ldy = d; g.epi = EPI_RESID;
-    if (l + 1 < c.n_layers) { g.gainA = m->attn_norm[l + 1]; g.nxA = xs_attn; }
-    if (head_gain) { g.gainB = head_gain; g.nxB = xs_exit; }
-    g.ssq_out = ssq_attn;
-    if ((rc = gemv(hs, g, SB_K_DOWN, st))) return rc;
-    hs->st.layer_sweeps += 1;      // the shared sweep is counted once, on the first sequence
-    hs->st.weight_bytes += m->layer_bytes;
-    if (hs->phase_bytes) *hs->phase_bytes += m->layer_bytes + kv_total;
-    return SB_OK;
-}
-
-// Head projection of the rows of `mask` (partials only; the caller merges per sequence).
-int batch_head(sb_batch* bt, const void* W, uint32_t mask, float T, float* logits, int cls) {
-    sb_session* hs = bt->seq[0];
-    const sb_config& c = bt->m->cfg;
-    GemvArgs g{};
-    g.W = W; g.w_dtype = c.weight_dtype; g.N = c.vocab; g.K = c.d_model; g.M = SB_MAX_W; g.row_mask = mask;
-    g.xs = wsp<uint16_t>(hs, hs->L.xs_exit);
-    g.ssq_in = wsp<float>(hs, hs->L.ssq_attn); g.ssq_nb = c.d_model / 16; g.ssq_ld = hs->L.ssq_ld; g.eps = c.rms_eps;
-    g.epi = EPI_HEAD;
-    g.head.T = T; g.head.partials = wsp<float>(hs, hs->L.head_part); g.head.logits = logits; g.head.skip_merge = 1;
-    int rc = gemv(hs, g, cls, bt->m->stream);
-    if (rc) return rc;
-    hs->st.weight_bytes += bt->m->head_bytes;
-    if (hs->phase_bytes) *hs->phase_bytes += bt->m->head_bytes;
-    return SB_OK;
-}
-
-int batch_readback(sb_batch* bt, const std::vector<int>& who) {
-    for (int b : who) {
-        sb_session* s = bt->seq[b];
-        HIP_TRY(hipMemcpyAsync(s->h_round, s->d_round, sizeof(DevRound), hipMemcpyDeviceToHost, bt->m->stream));
-    }
-    HIP_TRY(hipStreamSynchronize(bt->m->stream));
-    return SB_OK;
-}
-
-// One round of every sequence of `act`: draft super-steps (each adds a row to every sequence that
-// is still drafting; layer passes gather the rows of all of them), then alignment and
-// verification of all open rows layer by layer, one head sweep, and per sequence the accept rule.
-int batch_round(sb_batch* bt, const std::vector<int>& act, const sb_params* const* P, sb_verify_result* vres) {
-    sb_model* m = bt->m;
-    const sb_config& c = m->cfg;
-    sb_session* hs = bt->seq[0];
-    hipStream_t st = m->stream;
-    const int B = bt->B, wc = bt->w_cap, d = c.d_model;
-    const int nb_head = head_blocks_mfma(c.vocab);
-    int rc;
-    std::vector<char> drafting(B, 0), inflight(B, 0);
-    for (int b : act) { drafting[b] = 1; bt->seq[b]->n_slots = 0; bt->seq[b]->n_drafts = 0; bt->seq[b]->round_closed = false; }
-    int d_max_all = 0;
-    for (int b : act) d_max_all = P[b]->d_max > d_max_all ? P[b]->d_max : d_max_all;
-    hs->phase_bytes = &hs->st.draft_bytes;
-    // ---- draft super-steps
-    for (;;) {
-        std::vector<int> step;  // sequences that add a row in this super-step
-        for (int b : act)
-            if (drafting[b]) step.push_back(b);
-        if (step.empty()) break;
-        std::vector<int> forced(B, -1), over(B, -1);
-        for (int b : step) {
-            sb_session* s = bt->seq[b];
-            const sb_params* p = P[b];
-            if (s->c + s->n_slots >= c.max_seq) return fail(SB_ECAPACITY, "batch_decode: KV capacity of sequence %d exceeded", b);
-            const int64_t k = s->draft_counter;
-            forced[b] = (p->forced_exit && k < p->n_forced) ? p->forced_exit[k] : -1;
-            over[b] = (p->forced_draft && k < p->n_forced) ? p->forced_draft[k] : -1;
-            if (forced[b] > p->d_max) return fail(SB_EINVAL, "forced_exit[%lld] = %d exceeds d_max", (long long)k, forced[b]);
-            if (forced[b] >= 1 && p->head_mask && !((p->head_mask >> (forced[b] - 1)) & 1u))
-                return fail(SB_EINVAL, "forced_exit[%lld] = %d names a layer outside head_mask", (long long)k, forced[b]);
-            if (over[b] >= c.vocab) return fail(SB_EINVAL, "forced_draft[%lld] = %d out of range", (long long)k, over[b]);
-            if (forced[b] < -1) forced[b] = -1;
-            if (over[b] < -1) over[b] = -1;
-            const int idx = s->n_slots, slot = b * wc + idx;
-            if (!(idx > 0 && s->next_embedded)) {
-                RowToks t;
-                for (int r = 0; r < SB_MAX_W; ++r) t.tok[r] = 0;
-                t.tok[0] = idx == 0 ? s->pending : s->draft_host[idx - 1];
-                EmbedNorm en{m->attn_norm[0], wsp<uint16_t>(hs, hs->L.xs_attn) + (size_t)slot * d,
-                             wsp<float>(hs, hs->L.ssq_attn) + (size_t)slot * hs->L.ssq_ld, hs->L.ssq_ld};
-                HIP_TRY(launch_embed(m->embed, c.weight_dtype, c.vocab, d, wsp<float>(hs, hs->L.H) + (size_t)slot * d, 1, t,
-                                     s->d_round->slot_tok + idx, &s->d_round->exit_flag, en, st));
-            }
-            s->next_embedded = false;
-            s->draft_counter++; s->st.draft_steps++; s->n_slots++;
-            s->reached[idx] = 0; s->exit_layer[idx] = 0; s->draft_host[idx] = -1;
-            inflight[b] = 1;
-        }
-        std::vector<int> exit_at(B, 0), heads_run(B, 0);
-        for (int l = 1; l <= d_max_all; ++l) {
-            uint32_t mask = 0, newest = 0;
-            int j0[SB_MAX_W] = {0}, cnt[SB_MAX_W] = {0};
-            bool any_head = false;
-            for (int b : step) {
-                if (!inflight[b] || l > P[b]->d_max) { inflight[b] = 0; continue; }
-                sb_session* s = bt->seq[b];
-                const int idx = s->n_slots - 1;
-                int j = idx;
-                while (j > 0 && s->reached[j - 1] == l - 1) --j;
-                j0[b] = j; cnt[b] = idx - j + 1;
-                for (int r = j; r <= idx; ++r) mask |= 1u << (b * wc + r);
-                if (!P[b]->head_mask || ((P[b]->head_mask >> (l - 1)) & 1u)) { newest |= 1u << (b * wc + idx); any_head = true; }
-            }
-            if (!mask) break;
-            if ((rc = batch_layer(bt, l - 1, mask, j0, cnt, any_head ? m->exit_norm[l - 1] : nullptr))) return rc;
-            for (int b : step)
-                for (int r = j0[b]; r < j0[b] + cnt[b]; ++r) bt->seq[b]->reached[r] = l;
-            if (!newest) continue;
-            // the exit head of layer l for the newest row of every sequence that tests here: one sweep.
-            // (Each row's logits are scaled by its own temperature in the merge: T enters the partial
-            // sums, so the sweep is taken per distinct temperature; the usual case is one.)
-            std::vector<int> todo;
-            for (int b : step)
-                if (cnt[b] && ((newest >> (b * wc + bt->seq[b]->n_slots - 1)) & 1u)) todo.push_back(b);
-            while (!todo.empty()) {
-                const float T = P[todo[0]]->T[l - 1];
-                uint32_t hm = 0;
-                std::vector<int> now, later;
-                for (int b : todo) (P[b]->T[l - 1] == T ? now : later).push_back(b);
-                for (int b : now) hm |= 1u << (b * wc + bt->seq[b]->n_slots - 1);
-                float* logits = hs->debug ? wsp<float>(hs, hs->L.logits_exit) + (size_t)(l - 1) * c.vocab : nullptr;
-                (void)logits;
-                if ((rc = batch_head(bt, m->exit_head[l - 1], hm, T, nullptr, SB_K_EXIT_HEAD))) return rc;
-                HeadMergeBatch hb{};
-                int n_merge = 0;
-                for (int b : now) {
-                    sb_session* s = bt->seq[b];
-                    const int idx = s->n_slots - 1, slot = b * wc + idx;
-                    HeadArgs& h = hb.h[n_merge];
-                    h.T = T; h.partials = wsp<float>(hs, hs->L.head_part); h.post = POST_EXIT; h.round = s->d_round;
-                    h.slot = idx; h.layer = l; h.forced_exit = forced[b]; h.forced_draft = over[b]; h.threshold = P[b]->threshold;
-                    h.row0 = slot;
-                    if (s->n_drafts + 1 < P[b]->w_max && idx + 1 < wc) {
-                        h.embed_E = m->embed; h.embed_dtype = c.weight_dtype; h.embed_vocab = c.vocab; h.embed_d = d;
-                        h.embed_H = wsp<float>(hs, hs->L.H) + (size_t)(slot + 1) * d;
-                        h.embed_en = EmbedNorm{m->attn_norm[0], wsp<uint16_t>(hs, hs->L.xs_attn) + (size_t)(slot + 1) * d,
-                                               wsp<float>(hs, hs->L.ssq_attn) + (size_t)(slot + 1) * hs->L.ssq_ld, hs->L.ssq_ld};
-                    }
-                    hb.M[n_merge++] = 1;
-                    s->st.head_evals++;
-                    heads_run[b]++;
-                }
-                HIP_TRY(launch_head_merge_batch(hb, n_merge, nb_head, st));
-                todo.swap(later);
-            }
-            // exits: known to the host under a forced schedule, else read back
-            std::vector<int> ask;
-            for (int b : step)
-                if (cnt[b] && ((newest >> (b * wc + bt->seq[b]->n_slots - 1)) & 1u)) {
-                    if (forced[b] >= 0) { if (l == forced[b]) { exit_at[b] = l; inflight[b] = 0; } }
-                    else ask.push_back(b);
-                }
-            if (!ask.empty()) {
-                if ((rc = batch_readback(bt, ask))) return rc;
-                for (int b : ask)
-                    if (bt->seq[b]->h_round->exit_flag) { exit_at[b] = l; inflight[b] = 0; }
-            }
-        }
-        for (int b : step) {
-            sb_session* s = bt->seq[b];
-            const int idx = s->n_slots - 1;
-            inflight[b] = 0;
-            if (exit_at[b]) {
-                s->exit_layer[idx] = exit_at[b];
-                s->next_embedded = s->n_drafts + 1 < P[b]->w_max && idx + 1 < wc;
-                s->draft_host[idx] = over[b] >= 0 ? over[b] : (forced[b] < 0 ? s->h_round->drafts[idx] : -1);
-                s->n_drafts++; s->st.drafts++; s->st.exit_hist[exit_at[b]]++;
-                if (s->n_drafts == P[b]->w_max) { s->round_closed = true; drafting[b] = 0; }
-            } else {
-                s->st.exit_hist[0]++;
-                s->round_closed = true; drafting[b] = 0;
-            }
-        }
-    }
-    // ---- alignment and verification: every open row of every sequence through the layers it has not seen
-    hs->phase_bytes = &hs->st.verify_bytes;
-    std::vector<int> D(B, 0);
-    for (int b : act) D[b] = bt->seq[b]->reached[0];
-    for (int l = 1; l <= c.n_layers; ++l) {
-        uint32_t mask = 0;
-        int j0[SB_MAX_W] = {0}, cnt[SB_MAX_W] = {0};
-        for (int b : act) {
-            sb_session* s = bt->seq[b];
-            int j = s->n_slots;
-            while (j > 0 && s->reached[j - 1] == l - 1) --j;
-            j0[b] = j; cnt[b] = s->n_slots - j;
-            for (int r = j; r < s->n_slots; ++r) mask |= 1u << (b * wc + r);
-        }
-        if (!mask) continue;
-        if ((rc = batch_layer(bt, l - 1, mask, j0, cnt, l == c.n_layers ? m->final_norm : nullptr))) return rc;
-        for (int b : act)
-            for (int r = j0[b]; r < j0[b] + cnt[b]; ++r) bt->seq[b]->reached[r] = l;
-    }
-    uint32_t all = 0;
-    bool sampling = false;
-    for (int b : act) {
-        for (int r = 0; r < bt->seq[b]->n_slots; ++r) all |= 1u << (b * wc + r);
-        sampling = sampling || P[b]->sample_temperature > 0.f;
-    }
-    float* logits = (sampling || hs->debug) ? wsp<float>(hs, hs->L.logits_final) : nullptr;
-    if ((rc = batch_head(bt, m->lm_head, all, 1.0f, logits, SB_K_FINAL_HEAD))) return rc;
-    hs->st.final_head_sweeps++;
-    HeadMergeBatch hb{};
-    int n_merge = 0;
-    for (int b : act) {
-        sb_session* s = bt->seq[b];
-        const sb_params* p = P[b];
-        const int M = s->n_slots;
-        if (p->sample_temperature > 0.f) {
-            if (p->n_sample_u < 2 * (int64_t)(s->c + M))
-                return fail(SB_EINVAL, "batch_decode: sample_u of sequence %d has %lld entries, this round needs %lld", b,
-                            (long long)p->n_sample_u, 2 * (long long)(s->c + M));
-            SampleArgs sa{};
-            sa.logits = logits + (size_t)(b * wc) * c.vocab; sa.V = c.vocab; sa.M = M; sa.n_drafts = s->n_drafts;
-            sa.temp = p->sample_temperature; sa.top_p = p->top_p; sa.round = s->d_round;
-            for (int i = 0; i < M; ++i) {
-                sa.ua[i] = p->sample_u[2 * (int64_t)(s->c + i)];
-                sa.ur[i] = p->sample_u[2 * (int64_t)(s->c + i) + 1];
-            }
-            HIP_TRY(launch_sample_accept(sa, st));
-        } else {
-            HeadArgs& h = hb.h[n_merge];
-            h.T = 1.0f; h.partials = wsp<float>(hs, hs->L.head_part); h.post = POST_ACCEPT; h.round = s->d_round;
-            h.n_drafts = s->n_drafts; h.row0 = b * wc;
-            hb.M[n_merge++] = M;
-        }
-    }
-    if (n_merge) HIP_TRY(launch_head_merge_batch(hb, n_merge, nb_head, st));
-    if ((rc = batch_readback(bt, act))) return rc;
-    for (int b : act) {
-        sb_session* s = bt->seq[b];
-        const DevRound& R = *s->h_round;
-        const int M = s->n_slots;
-        if (R.n_emit < 1 || R.n_emit > M) return fail(SB_EDEVICE, "batch_decode: device returned n_emit = %d for sequence %d", R.n_emit, b);
-        sb_verify_result& res = vres[b];
-        res = sb_verify_result{};
-        res.n_rows = M; res.n_drafts = s->n_drafts; res.n_matched = R.n_matched; res.n_emit = R.n_emit; res.align_layer = D[b];
-        for (int i = 0; i < SB_MAX_W; ++i) res.tokens[i] = i < M ? R.g[i] : -1;
-        s->c += R.n_emit;
-        s->pending = R.g[R.n_emit - 1];
-        s->n_slots = 0; s->n_drafts = 0; s->round_closed = false; s->next_embedded = false;
-        s->st.rounds++; s->st.emitted += R.n_emit; s->st.accept_hist[R.n_emit]++;
-    }
-    return SB_OK;
-}
-
-}  // namespace
+}  // namespace sbhost
 
 // ============================================================================ C ABI
 extern "C" {
@@ -1556,86 +1149,6 @@ int32_t sb_debug_fail_launch(sb_session* s, int32_t n) {
 
 int32_t sb_open_rows(const sb_session* s) { return s ? s->n_slots : SB_EINVAL; }
 
-int32_t sb_new_batch(sb_session* const* sessions, int32_t B, sb_batch** out) {
-    if (!sessions || !out) return fail(SB_EINVAL, "new_batch: NULL argument");
-    if (B < 2 || B > SB_MAX_W) return fail(SB_EINVAL, "new_batch: B must be in 2..%d", SB_MAX_W);
-    for (int b = 0; b < B; ++b) {
-        if (!sessions[b]) return fail(SB_EINVAL, "new_batch: session %d is NULL", b);
-        if (sessions[b]->m != sessions[0]->m) return fail(SB_EINVAL, "new_batch: the sessions must share one model");
-        for (int a = 0; a < b; ++a)
-            if (sessions[a] == sessions[b]) return fail(SB_EINVAL, "new_batch: session %d is listed twice", b);
-    }
-    if (sessions[0]->m->proj != SB_PROJ_MFMA) return fail(SB_EINVAL, "new_batch: needs the MFMA projection path (bf16 weights)");
-    sb_batch* bt = new sb_batch();
-    bt->m = sessions[0]->m; bt->B = B; bt->w_cap = SB_MAX_W / B;
-    bt->seq.assign(sessions, sessions + B);
-    *out = bt;
-    return SB_OK;
-}
-
-void sb_free_batch(sb_batch* bt) { delete bt; }
-
-int32_t sb_batch_decode(sb_batch* bt, int32_t max_new, const sb_params* const* params, int32_t* const* out_tokens,
-                        int32_t* n_out) {
-    if (!bt || !params || !out_tokens || !n_out || max_new < 1) return fail(SB_EINVAL, "batch_decode: bad argument");
-    const int B = bt->B;
-    int rc;
-    for (int b = 0; b < B; ++b) {
-        sb_session* s = bt->seq[b];
-        if (!params[b] || !out_tokens[b]) return fail(SB_EINVAL, "batch_decode: NULL params / output of sequence %d", b);
-        if ((rc = check_params(s, params[b]))) return rc;
-        if (params[b]->w_max > bt->w_cap)
-            return fail(SB_EINVAL, "batch_decode: w_max = %d exceeds the %d rows a sequence has in a batch of %d", params[b]->w_max,
-                        bt->w_cap, B);
-        if (!s->has_pending) return fail(SB_ESTATE, "batch_decode: sequence %d has no pending token (prefill first)", b);
-        if (s->n_slots) return fail(SB_ESTATE, "batch_decode: sequence %d has an open round", b);
-        if ((int64_t)s->c + max_new + params[b]->w_max > bt->m->cfg.max_seq)
-            return fail(SB_ECAPACITY, "batch_decode: committed + max_new + w_max exceeds max_seq for sequence %d", b);
-        if ((rc = join_head(s))) return rc;
-    }
-    std::vector<int> cnt(B, 0);
-    std::vector<sb_verify_result> vres(B);
-    const double t0 = now_ms();
-    for (;;) {
-        std::vector<int> act;
-        for (int b = 0; b < B; ++b) {
-            const sb_params* p = params[b];
-            const bool eos = p->eos_id >= 0 && cnt[b] > 0 && out_tokens[b][cnt[b] - 1] == p->eos_id;
-            if (cnt[b] < max_new && !eos) act.push_back(b);
-        }
-        if (act.empty()) break;
-        if ((rc = batch_round(bt, act, params, vres.data()))) {
-            if (rc == SB_EDEVICE)
-                for (int b : act) (void)round_guard(bt->seq[b], rc);
-            else
-                for (int b : act) {   // refused before the device was touched for this sequence: drop the rows that were opened
-                    sb_session* s = bt->seq[b];
-                    s->draft_counter -= s->n_slots;
-                    s->n_slots = 0; s->n_drafts = 0; s->round_closed = false; s->next_embedded = false;
-                }
-            return rc;
-        }
-        for (int b : act) {
-            sb_session* s = bt->seq[b];
-            const sb_params* p = params[b];
-            const sb_verify_result& vr = vres[b];
-            int take = 0;
-            while (take < vr.n_emit && cnt[b] < max_new) {
-                out_tokens[b][cnt[b]++] = vr.tokens[take++];
-                if (p->eos_id >= 0 && out_tokens[b][cnt[b] - 1] == p->eos_id) break;
-            }
-            if (take < vr.n_emit) {
-                s->c -= vr.n_emit - take;
-                s->st.emitted -= vr.n_emit - take;
-                s->pending = out_tokens[b][cnt[b] - 1];
-            }
-        }
-    }
-    const double ms = now_ms() - t0;
-    for (int b = 0; b < B; ++b) { n_out[b] = cnt[b]; bt->seq[b]->st.decode_ms = ms; }
-    return SB_OK;
-}
-
 int32_t sb_get_stats(const sb_session* s, sb_stats* out) {
     if (!s || !out) return fail(SB_EINVAL, "get_stats: NULL argument");
     *out = s->st;
@@ -1705,243 +1218,6 @@ int32_t sb_debug_kv(sb_session* s, int32_t layer, int32_t pos, float* k_out, flo
                 }
             }
         }
-    return SB_OK;
-}
-
-// ---- single kernels -------------------------------------------------------
-int32_t sb_op_rmsnorm(const float* x, const float* gain, float* out, int32_t M, int32_t d, float eps, void* stream) {
-    if (!x || !gain || !out || M < 1 || M > SB_MAX_W || d < 1) return fail(SB_EINVAL, "op_rmsnorm: bad argument");
-    HIP_TRY(launch_rmsnorm(x, gain, out, nullptr, 0, M, d, eps, (hipStream_t)stream));
-    return SB_OK;
-}
-
-size_t sb_op_gemv_scratch_bytes(int32_t M, int32_t K) { return K > 0 ? align_up((size_t)16 * K * 2, 256) : 0; }
-
-static int op_check(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, int32_t M, int32_t kernel) {
-    if (!W || !x) return fail(SB_EINVAL, "op: NULL operand");
-    if (w_dtype != SB_FP32 && w_dtype != SB_BF16) return fail(SB_EINVAL, "op: w_dtype");
-    if (N < 1 || K < 8 || K % 8 || M < 1 || M > SB_MAX_W) return fail(SB_EINVAL, "op: need N >= 1, K %% 8 == 0, 1 <= M <= %d", SB_MAX_W);
-    if (kernel != SB_PROJ_VALU && kernel != SB_PROJ_MFMA && kernel != SB_PROJ_MFMA_PACKED)
-        return fail(SB_EINVAL, "op: kernel must be VALU, MFMA or MFMA_PACKED");
-    if (kernel != SB_PROJ_VALU && (w_dtype != SB_BF16 || K % 128 || N % 16))
-        return fail(SB_EINVAL, "op: MFMA path needs bf16 weights, K %% 128 == 0, N %% 16 == 0");
-    if (((uintptr_t)W & 15) || ((uintptr_t)x & 15)) return fail(SB_EINVAL, "op: operands must be 16-byte aligned");
-    return SB_OK;
-}
-
-int32_t sb_op_gemv(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, float* y, int32_t M,
-                   int32_t kernel, void* scratch, void* stream) {
-    int rc = op_check(W, w_dtype, N, K, x, M, kernel);
-    if (rc) return rc;
-    if (!y) return fail(SB_EINVAL, "op_gemv: y is NULL");
-    GemvArgs g{};
-    g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.y = y; g.ldy = N; g.M = M; g.epi = EPI_STORE;
-    g.packed = kernel == SB_PROJ_MFMA_PACKED;
-    if (kernel != SB_PROJ_VALU) {
-        if (!scratch || ((uintptr_t)scratch & 15)) return fail(SB_EINVAL, "op_gemv: MFMA path needs aligned scratch");
-        g.xs = (uint16_t*)scratch;
-        HIP_TRY(launch_split(x, (uint16_t*)scratch, M, K, (hipStream_t)stream));
-        HIP_TRY(launch_gemv_mfma(g, (hipStream_t)stream));
-    } else {
-        HIP_TRY(launch_gemv_valu(g, (hipStream_t)stream));
-    }
-    return SB_OK;
-}
-
-int32_t sb_op_gate_up(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, float* u, int32_t M,
-                      int32_t kernel, void* scratch, void* stream) {
-    int rc = op_check(W, w_dtype, N, K, x, M, kernel);
-    if (rc) return rc;
-    if (N > 0x3fffffff) return fail(SB_EINVAL, "op_gate_up: N too large");
-    if (!u) return fail(SB_EINVAL, "op_gate_up: u is NULL");
-    GemvArgs g{};
-    g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.y = u; g.ldy = N; g.M = M; g.epi = EPI_SWIGLU;
-    g.packed = kernel == SB_PROJ_MFMA_PACKED;
-    if (kernel != SB_PROJ_VALU) {
-        if (!scratch || ((uintptr_t)scratch & 15)) return fail(SB_EINVAL, "op_gate_up: MFMA path needs aligned scratch");
-        g.xs = (uint16_t*)scratch;
-        HIP_TRY(launch_split(x, (uint16_t*)scratch, M, K, (hipStream_t)stream));
-        HIP_TRY(launch_gemv_mfma(g, (hipStream_t)stream));
-    } else {
-        HIP_TRY(launch_gemv_valu(g, (hipStream_t)stream));
-    }
-    return SB_OK;
-}
-
-int32_t sb_op_repack(const void* W, int32_t N, int32_t K, void* packed, void* stream) {
-    if (!W || !packed || ((uintptr_t)W & 15) || ((uintptr_t)packed & 15)) return fail(SB_EINVAL, "op_repack: NULL / misaligned operand");
-    if (N < 16 || N % 16 || K < 128 || K % 128) return fail(SB_EINVAL, "op_repack: need N %% 16 == 0 and K %% 128 == 0");
-    HIP_TRY(launch_repack(W, packed, N, K, (hipStream_t)stream));
-    return SB_OK;
-}
-
-size_t sb_op_gemm_scratch_bytes(int32_t N, int32_t K) {
-    if (N < 16 || K < 128 || N % 16 || K % 128) return 0;
-    return align_up((size_t)2 * SB_PREFILL_ROWS * K * 2, 256) + (size_t)gemm_splits(N, K, 1) * SB_PREFILL_ROWS * N * 4;
-}
-
-int32_t sb_op_gemm(const void* Wp, int32_t N, int32_t K, const float* x, float* y, int32_t M, void* scratch,
-                   void* stream) {
-    if (!Wp || !x || !y || !scratch) return fail(SB_EINVAL, "op_gemm: NULL argument");
-    if (N < 16 || K < 128 || N % 16 || K % 128 || M < 1 || M > SB_PREFILL_ROWS)
-        return fail(SB_EINVAL, "op_gemm: need N %% 16 == 0, K %% 128 == 0, 1 <= M <= %d", SB_PREFILL_ROWS);
-    hipStream_t st = (hipStream_t)stream;
-    uint16_t* xs = (uint16_t*)scratch;
-    float* part = (float*)((char*)scratch + align_up((size_t)2 * SB_PREFILL_ROWS * K * 2, 256));
-    HIP_TRY(launch_prefill_split(x, xs, SB_PREFILL_ROWS, M, K, st));
-    GemmArgs g{};
-    g.Wp = Wp; g.rows = N; g.K = K; g.xs = xs; g.plane_rows = SB_PREFILL_ROWS; g.M = M; g.n_pass = 1;
-    g.part = part; g.S = gemm_splits(N, K, 1);
-    HIP_TRY(launch_prefill_gemm(g, st));
-    GemmEpiArgs e{};
-    e.part = part; e.S = g.S; e.rows = N; e.N = N; e.M = M; e.n_pass = 1; e.plane_rows = SB_PREFILL_ROWS;
-    e.epi = EPI_STORE; e.K = K; e.y = y; e.ldy = N;
-    HIP_TRY(launch_prefill_epilogue(e, st));
-    return SB_OK;
-}
-
-size_t sb_op_head_scratch_bytes(int32_t M, int32_t N, int32_t K) {
-    if (N < 1 || K < 1) return 0;
-    int nb = head_blocks_valu(N);
-    return 256 + align_up((size_t)SB_MAX_W * nb * 16, 256) + align_up((size_t)16 * K * 2, 256);
-}
-
-int32_t sb_op_head(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, int32_t M, float T,
-                   int32_t kernel, int32_t* argmax_out, float* conf_out, float* logits, void* scratch, void* stream) {
-    int rc = op_check(W, w_dtype, N, K, x, M, kernel);
-    if (rc) return rc;
-    if (!argmax_out || !conf_out || !scratch || ((uintptr_t)scratch & 255)) return fail(SB_EINVAL, "op_head: bad output / scratch");
-    if (!(T > 0.f)) return fail(SB_EINVAL, "op_head: T must be positive");
-    int nb = head_blocks_valu(N);
-    char* sc = (char*)scratch;
-    GemvArgs g{};
-    g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.M = M; g.epi = EPI_HEAD;
-    g.head.T = T; g.head.partials = (float*)(sc + 256);
-    g.head.logits = logits; g.head.argmax_out = argmax_out; g.head.conf_out = conf_out; g.head.post = POST_NONE;
-    g.packed = kernel == SB_PROJ_MFMA_PACKED;
-    if (kernel != SB_PROJ_VALU) {
-        g.xs = (uint16_t*)(sc + 256 + align_up((size_t)SB_MAX_W * nb * 16, 256));
-        HIP_TRY(launch_split(x, const_cast<uint16_t*>(g.xs), M, K, (hipStream_t)stream));
-        HIP_TRY(launch_gemv_mfma(g, (hipStream_t)stream));
-    } else {
-        HIP_TRY(launch_gemv_valu(g, (hipStream_t)stream));
-    }
-    return SB_OK;
-}
-
-int32_t sb_op_head_static(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, int32_t M, float T,
-                          int32_t kernel, int32_t* argmax_out, float* conf_out, void* stream) {
-    int rc = op_check(W, w_dtype, N, K, x, M, kernel);
-    if (rc) return rc;
-    if (!argmax_out || !conf_out) return fail(SB_EINVAL, "op_head_static: NULL output");
-    if (!(T > 0.f)) return fail(SB_EINVAL, "op_head_static: T must be positive");
-    if (N > SB_STATIC_MAX_N || K > SB_STATIC_MAX_K)
-        return fail(SB_ECAPACITY, "op_head_static: N = %d, K = %d exceed the static scratch area (N <= %d, K <= %d)", N, K,
-                    SB_STATIC_MAX_N, SB_STATIC_MAX_K);
-    static_assert(SB_STATIC_MAX_N % 16 == 0, "partials are sized per 16 output rows");
-    void* base = nullptr;
-    hipError_t e = static_scratch(&base);   // address of the library's own device array on this GPU
-    if (e != hipSuccess) return fail(SB_EDEVICE, "op_head_static: static scratch area: %s", hipGetErrorString(e));
-    char* sc = (char*)base;
-    const int nb = head_blocks_valu(N);
-    GemvArgs g{};
-    g.W = W; g.w_dtype = w_dtype; g.N = N; g.K = K; g.x = x; g.M = M; g.epi = EPI_HEAD;
-    g.head.T = T; g.head.partials = (float*)(sc + 256);
-    g.head.logits = nullptr; g.head.argmax_out = argmax_out; g.head.conf_out = conf_out; g.head.post = POST_NONE;
-    g.packed = kernel == SB_PROJ_MFMA_PACKED;
-    if (kernel != SB_PROJ_VALU) {
-        g.xs = (uint16_t*)(sc + 256 + align_up((size_t)SB_MAX_W * nb * 16, 256));
-        HIP_TRY(launch_split(x, const_cast<uint16_t*>(g.xs), M, K, (hipStream_t)stream));
-        HIP_TRY(launch_gemv_mfma(g, (hipStream_t)stream));
-    } else {
-        HIP_TRY(launch_gemv_valu(g, (hipStream_t)stream));
-    }
-    return SB_OK;
-}
-
-int32_t sb_op_copy(void* dst, const void* src, size_t nbytes, void* stream) {
-    if (!dst || !src || (nbytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
-        return fail(SB_EINVAL, "op_copy: NULL / misaligned operand");
-    HIP_TRY(launch_copy(dst, src, nbytes, (hipStream_t)stream));
-    return SB_OK;
-}
-
-int32_t sb_op_read(const void* src, size_t nbytes, float* sink, void* stream) {
-    if (!src || !sink || (nbytes & 15) || ((uintptr_t)src & 15)) return fail(SB_EINVAL, "op_read: NULL / misaligned operand");
-    HIP_TRY(launch_read(src, nbytes, sink, (hipStream_t)stream));
-    return SB_OK;
-}
-
-int32_t sb_rope_table_host(int32_t head_dim, float base, int32_t n_pos, float* cos_out, float* sin_out) {
-    if (head_dim < 2 || (head_dim & 1) || !(base > 0.f) || n_pos < 0 || !cos_out || !sin_out)
-        return fail(SB_EINVAL, "rope_table_host: bad argument");
-    const int half = head_dim / 2;
-    for (int p = 0; p < n_pos; ++p)
-        for (int i = 0; i < half; ++i) {
-            double theta = std::pow((double)base, -2.0 * (double)i / (double)head_dim);
-            double a = (double)p * theta;
-            cos_out[(size_t)p * half + i] = (float)std::cos(a);
-            sin_out[(size_t)p * half + i] = (float)std::sin(a);
-        }
-    return SB_OK;
-}
-
-static int attn_op_check(int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype, const void* pool,
-                         const int32_t* table, int32_t n_pages, int32_t layer, int32_t pos0, int32_t M) {
-    if (n_heads < 1 || n_kv_heads < 1 || n_heads % n_kv_heads) return fail(SB_EINVAL, "op: head counts");
-    if (head_dim != 64 && head_dim != 128) return fail(SB_EINVAL, "op: head_dim must be 64 or 128");
-    if (kv_dtype != SB_FP32 && kv_dtype != SB_BF16) return fail(SB_EINVAL, "op: kv_dtype");
-    if (!pool || !table || n_pages < 1 || layer < 0) return fail(SB_EINVAL, "op: pool / table");
-    if (M < 1 || M > SB_MAX_W || pos0 < 0 || pos0 + M > n_pages * SB_KV_BLOCK)
-        return fail(SB_ECAPACITY, "op: rows %d..%d outside the %d-page pool", pos0, pos0 + M - 1, n_pages);
-    if ((uintptr_t)pool & 15) return fail(SB_EINVAL, "op: pool must be 16-byte aligned");
-    return SB_OK;
-}
-
-size_t sb_op_attention_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t kv_dtype, int32_t n_pages) {
-    if (n_heads < 1 || n_pages < 1 || (head_dim != 64 && head_dim != 128)) return 0;
-    const int ch = attn_chunk_keys(head_dim, kv_dtype);
-    const int max_chunks = (n_pages * SB_KV_BLOCK + ch - 1) / ch;
-    return align_up((size_t)SB_MAX_W * n_heads * max_chunks * (head_dim + 2) * 4, 256);
-}
-
-int32_t sb_op_attention(const float* qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t kv_dtype,
-                        void* pool, const int32_t* table, int32_t n_pages, int32_t layer, const float* rope_cos,
-                        const float* rope_sin, int32_t pos0, int32_t M, float* out, void* scratch, void* stream) {
-    int rc = attn_op_check(n_heads, n_kv_heads, head_dim, kv_dtype, pool, table, n_pages, layer, pos0, M);
-    if (rc) return rc;
-    if (!qkv || !out || !rope_cos || !rope_sin || !scratch || ((uintptr_t)scratch & 255))
-        return fail(SB_EINVAL, "op_attention: NULL / misaligned operand");
-    const int ch = attn_chunk_keys(head_dim, kv_dtype);
-    AttnArgs a{};
-    a.q = qkv; a.rope_cos = rope_cos; a.rope_sin = rope_sin;
-    a.qkv_rows = (n_heads + 2 * n_kv_heads) * head_dim; a.n_heads = n_heads;
-    a.kv = KvLayout{pool, table, n_pages, n_kv_heads, head_dim, kv_dtype};
-    a.layer = layer; a.pos0 = pos0; a.M = M;
-    a.partials = (float*)scratch;
-    a.max_chunks = (n_pages * SB_KV_BLOCK + ch - 1) / ch;
-    a.out = out; a.out_split = nullptr; a.split_rows = 8;
-    HIP_TRY(launch_attention(a, (hipStream_t)stream));
-    return SB_OK;
-}
-
-int32_t sb_op_prompt_attention(const float* qkv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, void* pool,
-                               const int32_t* table, int32_t n_pages, int32_t layer, const float* rope_cos,
-                               const float* rope_sin, int32_t pos0, int32_t M, float* out, void* stream) {
-    int rc = attn_op_check(n_heads, n_kv_heads, head_dim, SB_BF16, pool, table, n_pages, layer, pos0, 1);
-    if (rc) return rc;
-    if (M < 1 || pos0 + (int64_t)M > (int64_t)n_pages * SB_KV_BLOCK)
-        return fail(SB_ECAPACITY, "op: rows %d..%lld outside the %d-page pool", pos0, (long long)pos0 + M - 1, n_pages);
-    if (!qkv || !out || !rope_cos || !rope_sin) return fail(SB_EINVAL, "op_prompt_attention: NULL operand");
-    if (((uintptr_t)qkv | (uintptr_t)out | (uintptr_t)rope_cos | (uintptr_t)rope_sin) & 15)
-        return fail(SB_EINVAL, "op_prompt_attention: operands must be 16-byte aligned");
-    AttnArgs a{};
-    a.q = qkv; a.rope_cos = rope_cos; a.rope_sin = rope_sin;
-    a.qkv_rows = (n_heads + 2 * n_kv_heads) * head_dim; a.n_heads = n_heads;
-    a.kv = KvLayout{pool, table, n_pages, n_kv_heads, head_dim, SB_BF16};
-    a.layer = layer; a.pos0 = pos0; a.M = M;
-    a.out = out; a.out_split = nullptr; a.split_rows = M;
-    HIP_TRY(launch_prefill_attention(a, (hipStream_t)stream));
     return SB_OK;
 }
 
