@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecbound.so")
-SOURCES = ["kernels.hip", "prefill.hip", "specbound.cpp", "batch.cpp", "ops.cpp"]
+SOURCES = ["kernels.hip", "gemv.hip", "attention.hip", "prefill.hip", "specbound.cpp", "batch.cpp", "ops.cpp"]
 HEADERS = ["kernels.h", "device_utils.h", "host.h", os.path.join("..", "..", "include", "specbound.h")]
 # packed fp32 instructions are switched off for all device code
 HIPFLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
