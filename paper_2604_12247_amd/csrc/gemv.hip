@@ -376,6 +376,7 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
                     float sum = 0.f;
                     for (int i = 0; i < 16; ++i) sum += zs[t * 16 + i][m];
                     a.ssq_out[(size_t)m * a.ssq_ld + blockIdx.x * RT + t] = sum;
+                    if (a.ssq_out2) a.ssq_out2[(size_t)m * a.ssq_ld + blockIdx.x * RT + t] = sum;
                 }
             }
         }

@@ -27,7 +27,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t esize(int dtype) { return dtype == SB_BF16 ? 2 : 4; }
 
 struct WsLayout {
-    size_t H, xn, xs_attn, xs_ffn, xs_exit, ssq_attn, ssq_ffn, qkv, att, atts, u, us, attn_part, head_part,
+    size_t H, xn, xs_attn, xs_ffn, xs_exit, xs_exit2, ssq_exit, ssq_attn, ssq_ffn, qkv, att, atts, u, us, attn_part, head_part,
         logits_exit, logits_final, round, table, total;
     int max_chunks, head_blocks, n_pages, ssq_ld;
     // prompt passes of SB_PREFILL_ROWS rows (packed bf16 weights only)
@@ -81,8 +81,11 @@ struct sb_session {
     hipStream_t head_stream;
     hipEvent_t ev_main[4], ev_head[4];
     unsigned ev_i;
-    bool head_pending;      // ev_head[(ev_i - 1) % 4] not yet waited for by the main stream
-    int head_pending_ev;
+    // What W_down leaves for an exit head (the row's bf16 parts with the exit norm's gains, its sums
+    // of squares) goes to one of two buffers, by layer parity: the head of layer l on the head stream
+    // may still be reading its buffer while W_down of layer l + 1 writes the other one.
+    bool head_pending[2];   // a head on the head stream reads buffer b; ev_head[head_pending_ev[b]] marks its end
+    int head_pending_ev[2];
     // phase timing: events at the boundaries of a round's phases (sb_phase_timing)
     bool phase_timing;
     hipEvent_t ev_ph[5];
@@ -113,7 +116,7 @@ template <typename T>
 T* wsp(sb_session* s, size_t off) { return reinterpret_cast<T*>(s->ws + off); }
 
 int check_params(const sb_session* s, const sb_params* p);
-int join_head(sb_session* s);
+int join_head(sb_session* s);              // the main stream waits for every head still running on the head stream
 int round_guard(sb_session* s, int rc);
 int gemv(sb_session* s, sb::GemvArgs& a, int cls, hipStream_t st);
 

@@ -91,6 +91,7 @@ struct GemvArgs {
     const float* gainA; uint16_t* nxA;
     const float* gainB; uint16_t* nxB;
     float* ssq_out;
+    float* ssq_out2;   // optional second copy of the same sums (for a reader on another stream)
 };
 
 // Sampling-mode acceptance over the final-head logits of the M verified rows (device, [M][V]).

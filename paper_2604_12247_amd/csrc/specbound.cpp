@@ -93,6 +93,8 @@ WsLayout ws_layout(const sb_config* c) {
     L.xs_attn = take(16 * d * 2);
     L.xs_ffn = take(16 * d * 2);
     L.xs_exit = take(16 * d * 2);
+    L.xs_exit2 = take(16 * d * 2);
+    L.ssq_exit = take((size_t)2 * SB_MAX_W * L.ssq_ld * 4);
     L.ssq_attn = take((size_t)SB_MAX_W * L.ssq_ld * 4);
     L.ssq_ffn = take((size_t)SB_MAX_W * L.ssq_ld * 4);
     L.qkv = take(SB_MAX_W * qkv_rows * 4);
@@ -215,12 +217,17 @@ int wait_note(sb_session* s, int32_t seq, int idx) {
 }
 
 
-// Main stream waits for the exit head that is still running on the head stream.
-int join_head(sb_session* s) {
-    if (!s->head_pending) return SB_OK;
-    HIP_TRY(hipStreamWaitEvent(s->m->stream, s->ev_head[s->head_pending_ev], 0));
-    s->head_pending = false;
+// Main stream waits for the exit head on the head stream that reads exit-operand buffer b.
+int join_head_buf(sb_session* s, int b) {
+    if (!s->head_pending[b]) return SB_OK;
+    HIP_TRY(hipStreamWaitEvent(s->m->stream, s->ev_head[s->head_pending_ev[b]], 0));
+    s->head_pending[b] = false;
     return SB_OK;
+}
+// Main stream waits for every exit head that is still running on the head stream.
+int join_head(sb_session* s) {
+    int rc = join_head_buf(s, 0);
+    return rc ? rc : join_head_buf(s, 1);
 }
 
 int64_t gemv_bytes(const GemvArgs& a) {
@@ -247,7 +254,10 @@ int gemv(sb_session* s, GemvArgs& a, int cls, hipStream_t st) {
 // writes a hidden row (embedding, W_o, W_down) also leaves gain * h in bf16 parts
 // and the partial sums of squares, per slot, for the projection that reads it
 // next.  head_gain (nullable) asks W_down to do the same for the head that follows.
-int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
+// exit_buf: which of the two exit-operand buffers W_down fills for the head (draft steps alternate
+// them by layer, so that only the head of two layers ago has to be over); -1 = the first one, after
+// every head still running has finished (alignment, verification).
+int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain, int exit_buf = -1) {
     sb_model* m = s->m;
     const sb_config& c = m->cfg;
     const bool mf = m->proj == SB_PROJ_MFMA;
@@ -260,7 +270,7 @@ int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
     float* xn = wsp<float>(s, s->L.xn);
     uint16_t* xs_attn = wsp<uint16_t>(s, s->L.xs_attn) + (size_t)slot0 * d;
     uint16_t* xs_ffn = wsp<uint16_t>(s, s->L.xs_ffn) + (size_t)slot0 * d;
-    uint16_t* xs_exit = wsp<uint16_t>(s, s->L.xs_exit) + (size_t)slot0 * d;
+    uint16_t* xs_exit = wsp<uint16_t>(s, exit_buf == 1 ? s->L.xs_exit2 : s->L.xs_exit) + (size_t)slot0 * d;
     float* ssq_attn = wsp<float>(s, s->L.ssq_attn) + (size_t)slot0 * s->L.ssq_ld;
     float* ssq_ffn = wsp<float>(s, s->L.ssq_ffn) + (size_t)slot0 * s->L.ssq_ld;
     float* qkv = wsp<float>(s, s->L.qkv);
@@ -312,9 +322,11 @@ int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
         if (l + 1 < c.n_layers) { g.gainA = m->attn_norm[l + 1]; g.nxA = xs_attn; }
         if (head_gain) { g.gainB = head_gain; g.nxB = xs_exit; }
         g.ssq_out = ssq_attn;
+        if (head_gain && exit_buf >= 0)
+            g.ssq_out2 = wsp<float>(s, s->L.ssq_exit) + ((size_t)exit_buf * SB_MAX_W + slot0) * s->L.ssq_ld;
     }
     // W_down overwrites what a still-running exit head reads (its slot's parts and sums of squares)
-    if ((rc = join_head(s))) return rc;
+    if ((rc = exit_buf >= 0 ? join_head_buf(s, exit_buf) : join_head(s))) return rc;
     if ((rc = gemv(s, g, SB_K_DOWN, st))) return rc;
 
     s->st.layer_sweeps += 1;
@@ -329,7 +341,7 @@ int run_layer(sb_session* s, int l, int slot0, int M, const float* head_gain) {
 // VALU path: RMSNorm kernel first.  MFMA path: the last W_down already left
 // gain * h and the sums of squares for these slots (run_layer's head_gain).
 int run_head(sb_session* s, const void* W, const float* gain, int slot0, int M, HeadArgs h, hipStream_t st,
-             bool prenormed = false) {
+             bool prenormed = false, int exit_buf = -1) {
     sb_model* m = s->m;
     const sb_config& c = m->cfg;
     const bool mf = m->proj == SB_PROJ_MFMA;
@@ -343,9 +355,10 @@ int run_head(sb_session* s, const void* W, const float* gain, int slot0, int M, 
     h.round = s->d_round;
     GemvArgs g{};
     g.W = W; g.w_dtype = c.weight_dtype; g.N = c.vocab; g.K = c.d_model; g.x = xn; g.M = M;
-    g.xs = wsp<uint16_t>(s, s->L.xs_exit) + (size_t)slot0 * c.d_model;
+    g.xs = wsp<uint16_t>(s, exit_buf == 1 ? s->L.xs_exit2 : s->L.xs_exit) + (size_t)slot0 * c.d_model;
     if (mf && !prenormed) {  // (prenormed: xs already holds the normalised rows)
-        g.ssq_in = wsp<float>(s, s->L.ssq_attn) + (size_t)slot0 * s->L.ssq_ld;
+        g.ssq_in = exit_buf >= 0 ? wsp<float>(s, s->L.ssq_exit) + ((size_t)exit_buf * SB_MAX_W + slot0) * s->L.ssq_ld
+                                 : wsp<float>(s, s->L.ssq_attn) + (size_t)slot0 * s->L.ssq_ld;
         g.ssq_nb = c.d_model / 16; g.ssq_ld = s->L.ssq_ld; g.eps = c.rms_eps;
     }
     g.epi = EPI_HEAD; g.head = h;
@@ -589,7 +602,8 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
         int j0 = idx;
         while (j0 > 0 && s->reached[j0 - 1] == l - 1) --j0;
         const bool has_head = !p->head_mask || ((p->head_mask >> (l - 1)) & 1u);
-        if ((rc = run_layer(s, l - 1, j0, idx - j0 + 1, has_head ? m->exit_norm[l - 1] : nullptr))) return rc;
+        const int xb = overlap ? (l & 1) : -1;   // exit-operand buffer of this layer's head
+        if ((rc = run_layer(s, l - 1, j0, idx - j0 + 1, has_head ? m->exit_norm[l - 1] : nullptr, xb))) return rc;
         for (int j = j0; j <= idx; ++j) s->reached[j] = l;
         if (!has_head) continue;  // (variant: no exit test at this layer)
         ++n_heads_run;
@@ -611,12 +625,14 @@ int draft_step_impl(sb_session* s, const sb_params* p, sb_draft_result* out, boo
             const unsigned e = s->ev_i++ & 3;
             HIP_TRY(hipEventRecord(s->ev_main[e], m->stream));
             HIP_TRY(hipStreamWaitEvent(s->head_stream, s->ev_main[e], 0));
-            if ((rc = run_head(s, m->exit_head[l - 1], m->exit_norm[l - 1], idx, 1, h, s->head_stream))) return rc;
+            if ((rc = run_head(s, m->exit_head[l - 1], m->exit_norm[l - 1], idx, 1, h, s->head_stream, false, xb))) return rc;
             HIP_TRY(hipEventRecord(s->ev_head[e], s->head_stream));
-            s->head_pending = true;
-            s->head_pending_ev = (int)e;
+            s->head_pending[xb] = true;
+            s->head_pending_ev[xb] = (int)e;
         } else {
-            if ((rc = run_head(s, m->exit_head[l - 1], m->exit_norm[l - 1], idx, 1, h, m->stream))) return rc;
+            // (the merges write one round record: this head's comes after those of the heads still running)
+            if ((rc = join_head(s))) return rc;
+            if ((rc = run_head(s, m->exit_head[l - 1], m->exit_norm[l - 1], idx, 1, h, m->stream, false, xb))) return rc;
         }
         s->st.head_evals++;
         if (computed) {
@@ -748,7 +764,7 @@ int round_guard(sb_session* s, int rc) {
 hipError_t sync_all(sb_session* s) {
     hipError_t e = hipStreamSynchronize(s->m->stream);
     if (e == hipSuccess && s->head_stream) e = hipStreamSynchronize(s->head_stream);
-    s->head_pending = false;
+    s->head_pending[0] = s->head_pending[1] = false;
     return e;
 }
 
@@ -958,8 +974,8 @@ int32_t sb_new_session(sb_model* m, void* kv_pool, size_t kv_bytes, void* worksp
     s->prof_every = 1;
     s->head_stream = nullptr;
     s->ev_i = 0;
-    s->head_pending = false;
-    s->head_pending_ev = 0;
+    s->head_pending[0] = s->head_pending[1] = false;
+    s->head_pending_ev[0] = s->head_pending_ev[1] = 0;
     for (int i = 0; i < 4; ++i) { s->ev_main[i] = nullptr; s->ev_head[i] = nullptr; }
     s->h_round = nullptr;
     s->note_h = nullptr; s->note_d = nullptr; s->note_seq = 0;
