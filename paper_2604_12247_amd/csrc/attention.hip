@@ -256,242 +256,289 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
 //            and a wave's loads cover whole pages.  A wave owns HD/4 output dims.
 // Every output row of an MFMA depends on its own operand row only, so a query's
 // partial does not depend on which other queries share the block.
+// LDS of one block of the matrix-core attention kernels (one work item is computed at a time).
 template <int HD>
-__device__ __forceinline__ void attn_mfma_body(const AttnArgs& a, const int g, const int chunk, const int zb) {
-    constexpr int CH = 128, QG = 16, HALF = HD / 2;
-    constexpr int KSQ = HD / 32;      // k steps (of 32 dims) of the score product
-    constexpr int KSV = CH / 32;      // k steps (of 32 keys) of the value product
-    constexpr int DT = HD / 64;       // 16-dim output tiles per wave
-    constexpr int QS = HD + 8;        // padded LDS row strides (bf16 elements / floats)
-    constexpr int PS = CH + 8;
-    constexpr int SS = CH + 4;
-    __shared__ __attribute__((aligned(16))) uint16_t q_hi[QG * QS], q_lo[QG * QS];
-    __shared__ __attribute__((aligned(16))) uint16_t p_hi[QG * PS], p_lo[QG * PS];
-    __shared__ __attribute__((aligned(16))) float s_s[QG * SS];
-    __shared__ float s_m[QG], s_l[QG];
+struct AttnLds {
+    static constexpr int CH = 128, QG = 16, QS = HD + 8, PS = CH + 8, SS = CH + 4;   // padded row strides
+    __attribute__((aligned(16))) uint16_t q_hi[QG * QS], q_lo[QG * QS];
+    __attribute__((aligned(16))) uint16_t p_hi[QG * PS], p_lo[QG * PS];
+    __attribute__((aligned(16))) float s_s[QG * SS];
+    float s_m[QG], s_l[QG];
+};
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int li = lane & 15, lq = lane >> 4;
-    const int Hq = a.n_heads, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
-    const int nq_total = a.M * G;
-    // this block's query groups (16 queries each), handled one after the other with the
-    // chunk's K and V held in registers
-    const int n_qg = (nq_total + QG - 1) / QG;
-    const int qg_first = zb * a.qg_per_block;
-    const int qg_last = (qg_first + a.qg_per_block < n_qg) ? qg_first + a.qg_per_block : n_qg;
-    const int key0 = chunk * CH, n_total = a.pos0 + a.M;
-    const float scale = 1.0f / sqrtf((float)HD);
-    const size_t page_elems = (size_t)Hkv * SB_KV_BLOCK * HD;
-    uint16_t* const kbase = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 0) * a.kv.n_pages * page_elems;
-    uint16_t* const vbase = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 1) * a.kv.n_pages * page_elems;
-    const bool has_new = key0 + CH > a.pos0;  // the chunk holds keys of the new rows
-
-    // ---- issue every global load first: q (+ its rotary factors) of the first group, K, V
-    constexpr int QIT = QG * HALF / 256;
+// One work item of the kernel -- (kv head g, key chunk, slice zb of the query groups) -- in two
+// steps: load() requests everything the item reads from memory (the first query group with its
+// rotary factors, the chunk's K and V operands) into registers, compute() does the rest.  A block
+// that owns several items requests the next item's operands before it computes the current one.
+template <int HD>
+struct AttnItem {
+    static constexpr int CH = 128, QG = 16, HALF = HD / 2;
+    static constexpr int KSQ = HD / 32;      // k steps (of 32 dims) of the score product
+    static constexpr int KSV = CH / 32;      // k steps (of 32 keys) of the value product
+    static constexpr int DT = HD / 64;       // 16-dim output tiles per wave
+    static constexpr int QS = HD + 8, PS = CH + 8, SS = CH + 4;
+    static constexpr int QIT = QG * HALF / 256;
+    int g, chunk, zb;
     float qx[QIT], qy[QIT], qc[QIT], qsn[QIT];
-    auto load_q = [&](int qg) {
+    uint4 kreg[2][KSQ];
+    size_t kaddr[2];
+    uint4 vreg[DT][KSV];
+    size_t vaddr[KSV];
+
+    __device__ __forceinline__ void load_q(const AttnArgs& a, int qg) {
+        const int tid = threadIdx.x;
+        const int G = a.n_heads / a.kv.n_kv_heads, nq_total = a.M * G;
+            const int q0 = qg * QG;
+            const int nq = (nq_total - q0 < QG) ? (nq_total - q0) : QG;
+    #pragma unroll
+            for (int it = 0; it < QIT; ++it) {
+                const int i = tid + it * 256;
+                const int qi = i / HALF, j = i - qi * HALF;
+                qx[it] = qy[it] = qsn[it] = 0.f;
+                qc[it] = 1.f;
+                if (qi < nq) {
+                    int qq = q0 + qi, r = qq / G, gi = qq - r * G;
+                    const float* qp = a.q + (size_t)r * a.qkv_rows + (size_t)(g * G + gi) * HD;
+                    qx[it] = qp[j];
+                    qy[it] = qp[j + HALF];
+                    qc[it] = a.rope_cos[(size_t)(a.pos0 + r) * HALF + j];
+                    qsn[it] = a.rope_sin[(size_t)(a.pos0 + r) * HALF + j];
+                }
+            }
+    }
+
+    __device__ __forceinline__ void load(const AttnArgs& a, int g_, int chunk_, int zb_) {
+        g = g_; chunk = chunk_; zb = zb_;
+        const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+        const int li = lane & 15, lq = lane >> 4;
+        const int Hq = a.n_heads, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
+        const int nq_total = a.M * G;
+        // this block's query groups (16 queries each), handled one after the other with the
+        // chunk's K and V held in registers
+        const int n_qg = (nq_total + QG - 1) / QG;
+        const int qg_first = zb * a.qg_per_block;
+        const int qg_last = (qg_first + a.qg_per_block < n_qg) ? qg_first + a.qg_per_block : n_qg;
+        const int key0 = chunk * CH, n_total = a.pos0 + a.M;
+        const float scale = 1.0f / sqrtf((float)HD);
+        const size_t page_elems = (size_t)Hkv * SB_KV_BLOCK * HD;
+        uint16_t* const kbase = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 0) * a.kv.n_pages * page_elems;
+        uint16_t* const vbase = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 1) * a.kv.n_pages * page_elems;
+        const bool has_new = key0 + CH > a.pos0;  // the chunk holds keys of the new rows
+        (void)lane; (void)wave; (void)li; (void)lq; (void)n_qg; (void)qg_first; (void)qg_last; (void)n_total; (void)scale;
+        (void)kbase; (void)vbase; (void)has_new; (void)page_elems; (void)nq_total;
+        // ---- every global load of the item: q (+ its rotary factors) of the first group, K, V
+        load_q(a, qg_first);
+        // K operands: tile t of this wave = keys key0 + wave*32 + t*16 + li (one page), dims ks*32 + lq*8 ..
+    #pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int key = key0 + wave * 32 + t * 16 + li;
+            // a tile is one page: its table entry is wave-uniform, read through the scalar cache
+            const int kpage = __builtin_amdgcn_readfirstlane((key0 + wave * 32 + t * 16) / SB_KV_BLOCK);
+            kaddr[t] = 0;
+            if (kpage * SB_KV_BLOCK < n_total)
+                kaddr[t] = (size_t)a.kv.table[kpage] * page_elems + ((size_t)g * SB_KV_BLOCK + li) * HD + lq * 8;
+    #pragma unroll
+            for (int ks = 0; ks < KSQ; ++ks) {
+                kreg[t][ks] = make_uint4(0, 0, 0, 0);
+                if (key < a.pos0) kreg[t][ks] = *reinterpret_cast<const uint4*>(kbase + kaddr[t] + ks * 32);
+            }
+        }
+        // V operands: dim (wave*DT + dt)*16 + li, keys key0 + ks*32 + lq*8 .. +8 (half a page row)
+    #pragma unroll
+        for (int ks = 0; ks < KSV; ++ks) {
+            const int kf = key0 + ks * 32 + lq * 8;  // first key of this lane's 8
+            // the 32 keys of a step lie in two pages (lq 0-1, lq 2-3): two wave-uniform table entries
+            const int vpage = (key0 + ks * 32) / SB_KV_BLOCK;
+            const int pg0 = vpage * SB_KV_BLOCK < n_total ? a.kv.table[vpage] : 0;
+            const int pg1 = (vpage + 1) * SB_KV_BLOCK < n_total ? a.kv.table[vpage + 1] : 0;
+            vaddr[ks] = 0;
+            if (kf < n_total) vaddr[ks] = (size_t)(lq < 2 ? pg0 : pg1) * page_elems + ((size_t)g * HD + wave * DT * 16 + li) * SB_KV_BLOCK + (lq & 1) * 8;
+    #pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                vreg[dt][ks] = make_uint4(0, 0, 0, 0);
+                if (kf < a.pos0) vreg[dt][ks] = *reinterpret_cast<const uint4*>(vbase + vaddr[ks] + dt * 16 * SB_KV_BLOCK);
+            }
+        }
+
+    }
+
+    __device__ __forceinline__ void compute(const AttnArgs& a, AttnLds<HD>& lds) {
+        const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+        const int li = lane & 15, lq = lane >> 4;
+        const int Hq = a.n_heads, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
+        const int nq_total = a.M * G;
+        // this block's query groups (16 queries each), handled one after the other with the
+        // chunk's K and V held in registers
+        const int n_qg = (nq_total + QG - 1) / QG;
+        const int qg_first = zb * a.qg_per_block;
+        const int qg_last = (qg_first + a.qg_per_block < n_qg) ? qg_first + a.qg_per_block : n_qg;
+        const int key0 = chunk * CH, n_total = a.pos0 + a.M;
+        const float scale = 1.0f / sqrtf((float)HD);
+        const size_t page_elems = (size_t)Hkv * SB_KV_BLOCK * HD;
+        uint16_t* const kbase = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 0) * a.kv.n_pages * page_elems;
+        uint16_t* const vbase = reinterpret_cast<uint16_t*>(a.kv.pool) + (size_t)(a.layer * 2 + 1) * a.kv.n_pages * page_elems;
+        const bool has_new = key0 + CH > a.pos0;  // the chunk holds keys of the new rows
+        (void)lane; (void)wave; (void)li; (void)lq; (void)n_qg; (void)qg_first; (void)qg_last; (void)n_total; (void)scale;
+        (void)kbase; (void)vbase; (void)has_new; (void)page_elems; (void)nq_total;
+        uint16_t* const q_hi = lds.q_hi; uint16_t* const q_lo = lds.q_lo;
+        uint16_t* const p_hi = lds.p_hi; uint16_t* const p_lo = lds.p_lo;
+        float* const s_s = lds.s_s; float* const s_m = lds.s_m; float* const s_l = lds.s_l;
+        // ---- keys and values of the new rows: built from qkv, appended by query group 0
+        if (has_new) {
+    #pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int key = key0 + wave * 32 + t * 16 + li;
+                if (key >= a.pos0 && key < n_total) {
+                    const float* kp = a.q + (size_t)(key - a.pos0) * a.qkv_rows + (size_t)(Hq + g) * HD;
+    #pragma unroll
+                    for (int ks = 0; ks < KSQ; ++ks) {
+                        const int d0 = ks * 32 + lq * 8;
+                        const bool lo = d0 < HALF;
+                        const int dj = lo ? d0 : d0 - HALF;
+                        float f[8];
+    #pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const int j = dj + e;
+                            float c = a.rope_cos[(size_t)key * HALF + j], sn = a.rope_sin[(size_t)key * HALF + j];
+                            float x = kp[j], y = kp[j + HALF];
+                            f[e] = lo ? (x * c - y * sn) : (y * c + x * sn);
+                        }
+                        kreg[t][ks] = KvVec<uint16_t>::pack(f);
+                        if (zb == 0) *reinterpret_cast<uint4*>(kbase + kaddr[t] + ks * 32) = kreg[t][ks];
+                    }
+                }
+            }
+    #pragma unroll
+            for (int ks = 0; ks < KSV; ++ks) {
+                const int kf = key0 + ks * 32 + lq * 8;
+                if (kf + 8 > a.pos0 && kf < n_total) {  // some of the 8 keys are new
+    #pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) {
+                        const int d = (wave * DT + dt) * 16 + li;
+                        uint32_t w[4] = {vreg[dt][ks].x, vreg[dt][ks].y, vreg[dt][ks].z, vreg[dt][ks].w};
+    #pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const int key = kf + e;
+                            if (key >= a.pos0) {  // new row, or past the end: zero
+                                uint32_t h = 0;
+                                if (key < n_total) h = f2bf(a.q[(size_t)(key - a.pos0) * a.qkv_rows + (size_t)(Hq + Hkv + g) * HD + d]);
+                                w[e >> 1] = (e & 1) ? ((w[e >> 1] & 0x0000ffffu) | (h << 16)) : ((w[e >> 1] & 0xffff0000u) | h);
+                            }
+                        }
+                        vreg[dt][ks] = make_uint4(w[0], w[1], w[2], w[3]);
+                        if (zb == 0) *reinterpret_cast<uint4*>(vbase + vaddr[ks] + dt * 16 * SB_KV_BLOCK) = vreg[dt][ks];
+                    }
+                }
+            }
+        }
+        for (int qg = qg_first; qg < qg_last; ++qg) {
         const int q0 = qg * QG;
         const int nq = (nq_total - q0 < QG) ? (nq_total - q0) : QG;
-#pragma unroll
+        // ---- rotated queries -> LDS as hi + lo
+    #pragma unroll
         for (int it = 0; it < QIT; ++it) {
             const int i = tid + it * 256;
             const int qi = i / HALF, j = i - qi * HALF;
-            qx[it] = qy[it] = qsn[it] = 0.f;
-            qc[it] = 1.f;
-            if (qi < nq) {
-                int qq = q0 + qi, r = qq / G, gi = qq - r * G;
-                const float* qp = a.q + (size_t)r * a.qkv_rows + (size_t)(g * G + gi) * HD;
-                qx[it] = qp[j];
-                qy[it] = qp[j + HALF];
-                qc[it] = a.rope_cos[(size_t)(a.pos0 + r) * HALF + j];
-                qsn[it] = a.rope_sin[(size_t)(a.pos0 + r) * HALF + j];
-            }
+            const float u = qx[it] * qc[it] - qy[it] * qsn[it], v = qy[it] * qc[it] + qx[it] * qsn[it];
+            const uint16_t uh = f2bf(u), vh = f2bf(v);
+            q_hi[qi * QS + j] = uh;
+            q_lo[qi * QS + j] = f2bf(u - bf2f(uh));
+            q_hi[qi * QS + j + HALF] = vh;
+            q_lo[qi * QS + j + HALF] = f2bf(v - bf2f(vh));
         }
-    };
-    load_q(qg_first);
-    // K operands: tile t of this wave = keys key0 + wave*32 + t*16 + li (one page), dims ks*32 + lq*8 ..
-    uint4 kreg[2][KSQ];
-    size_t kaddr[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const int key = key0 + wave * 32 + t * 16 + li;
-        // a tile is one page: its table entry is wave-uniform, read through the scalar cache
-        const int kpage = __builtin_amdgcn_readfirstlane((key0 + wave * 32 + t * 16) / SB_KV_BLOCK);
-        kaddr[t] = 0;
-        if (kpage * SB_KV_BLOCK < n_total)
-            kaddr[t] = (size_t)a.kv.table[kpage] * page_elems + ((size_t)g * SB_KV_BLOCK + li) * HD + lq * 8;
-#pragma unroll
-        for (int ks = 0; ks < KSQ; ++ks) {
-            kreg[t][ks] = make_uint4(0, 0, 0, 0);
-            if (key < a.pos0) kreg[t][ks] = *reinterpret_cast<const uint4*>(kbase + kaddr[t] + ks * 32);
-        }
-    }
-    // V operands: dim (wave*DT + dt)*16 + li, keys key0 + ks*32 + lq*8 .. +8 (half a page row)
-    uint4 vreg[DT][KSV];
-    size_t vaddr[KSV];
-#pragma unroll
-    for (int ks = 0; ks < KSV; ++ks) {
-        const int kf = key0 + ks * 32 + lq * 8;  // first key of this lane's 8
-        // the 32 keys of a step lie in two pages (lq 0-1, lq 2-3): two wave-uniform table entries
-        const int vpage = (key0 + ks * 32) / SB_KV_BLOCK;
-        const int pg0 = vpage * SB_KV_BLOCK < n_total ? a.kv.table[vpage] : 0;
-        const int pg1 = (vpage + 1) * SB_KV_BLOCK < n_total ? a.kv.table[vpage + 1] : 0;
-        vaddr[ks] = 0;
-        if (kf < n_total) vaddr[ks] = (size_t)(lq < 2 ? pg0 : pg1) * page_elems + ((size_t)g * HD + wave * DT * 16 + li) * SB_KV_BLOCK + (lq & 1) * 8;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            vreg[dt][ks] = make_uint4(0, 0, 0, 0);
-            if (kf < a.pos0) vreg[dt][ks] = *reinterpret_cast<const uint4*>(vbase + vaddr[ks] + dt * 16 * SB_KV_BLOCK);
-        }
-    }
+        if (qg + 1 < qg_last) load_q(a, qg + 1);  // (in flight during this group's products)
+        __syncthreads();
 
-    // ---- keys and values of the new rows: built from qkv, appended by query group 0
-    if (has_new) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int key = key0 + wave * 32 + t * 16 + li;
-            if (key >= a.pos0 && key < n_total) {
-                const float* kp = a.q + (size_t)(key - a.pos0) * a.qkv_rows + (size_t)(Hq + g) * HD;
-#pragma unroll
-                for (int ks = 0; ks < KSQ; ++ks) {
-                    const int d0 = ks * 32 + lq * 8;
-                    const bool lo = d0 < HALF;
-                    const int dj = lo ? d0 : d0 - HALF;
-                    float f[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int j = dj + e;
-                        float c = a.rope_cos[(size_t)key * HALF + j], sn = a.rope_sin[(size_t)key * HALF + j];
-                        float x = kp[j], y = kp[j + HALF];
-                        f[e] = lo ? (x * c - y * sn) : (y * c + x * sn);
-                    }
-                    kreg[t][ks] = KvVec<uint16_t>::pack(f);
-                    if (zb == 0) *reinterpret_cast<uint4*>(kbase + kaddr[t] + ks * 32) = kreg[t][ks];
+        // ---- scores of this wave's 32 keys against the 16 query rows
+        {
+            f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    #pragma unroll
+            for (int ks = 0; ks < KSQ; ++ks) {
+                const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&q_hi[li * QS + ks * 32 + lq * 8]));
+                const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&q_lo[li * QS + ks * 32 + lq * 8]));
+    #pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const bf16x8 kb = __builtin_bit_cast(bf16x8, kreg[t][ks]);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, kb, acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, kb, acc[t], 0, 0, 0);
                 }
             }
+            // result register r of lane (li, lq): query 4*lq + r, key li of the tile
+    #pragma unroll
+            for (int t = 0; t < 2; ++t)
+    #pragma unroll
+                for (int r = 0; r < 4; ++r) s_s[(4 * lq + r) * SS + wave * 32 + t * 16 + li] = acc[t][r];
         }
-#pragma unroll
-        for (int ks = 0; ks < KSV; ++ks) {
-            const int kf = key0 + ks * 32 + lq * 8;
-            if (kf + 8 > a.pos0 && kf < n_total) {  // some of the 8 keys are new
-#pragma unroll
+        __syncthreads();
+        // ---- softmax partial of each query over the chunk (one wave per query)
+        for (int qi = wave; qi < QG; qi += 4) {
+            if (qi >= nq) {  // unused operand rows: defined values
+                p_hi[qi * PS + lane] = p_hi[qi * PS + lane + 64] = 0;
+                p_lo[qi * PS + lane] = p_lo[qi * PS + lane + 64] = 0;
+                continue;
+            }
+            const int r = (q0 + qi) / G;
+            float sc[2];
+            float mx = -SB_INF;
+    #pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int t = lane + 64 * h;
+                sc[h] = (key0 + t <= a.pos0 + r) ? s_s[qi * SS + t] * scale : -SB_INF;
+                mx = fmaxf(mx, sc[h]);
+            }
+            mx = wave_max(mx);
+            float l = 0.f;
+    #pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float p = (mx == -SB_INF) ? 0.f : expf(sc[h] - mx);
+                const uint16_t ph = f2bf(p);
+                p_hi[qi * PS + lane + 64 * h] = ph;
+                p_lo[qi * PS + lane + 64 * h] = f2bf(p - bf2f(ph));
+                l += p;
+            }
+            l = wave_sum(l);
+            if (lane == 0) { s_m[qi] = mx; s_l[qi] = l; }
+        }
+        __syncthreads();
+        // ---- weighted values: this wave's DT tiles of 16 dims, all keys of the chunk
+        {
+            f32x4 o[DT];
+    #pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    #pragma unroll
+            for (int ks = 0; ks < KSV; ++ks) {
+                const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&p_hi[li * PS + ks * 32 + lq * 8]));
+                const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&p_lo[li * PS + ks * 32 + lq * 8]));
+    #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
-                    const int d = (wave * DT + dt) * 16 + li;
-                    uint32_t w[4] = {vreg[dt][ks].x, vreg[dt][ks].y, vreg[dt][ks].z, vreg[dt][ks].w};
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int key = kf + e;
-                        if (key >= a.pos0) {  // new row, or past the end: zero
-                            uint32_t h = 0;
-                            if (key < n_total) h = f2bf(a.q[(size_t)(key - a.pos0) * a.qkv_rows + (size_t)(Hq + Hkv + g) * HD + d]);
-                            w[e >> 1] = (e & 1) ? ((w[e >> 1] & 0x0000ffffu) | (h << 16)) : ((w[e >> 1] & 0xffff0000u) | h);
-                        }
-                    }
-                    vreg[dt][ks] = make_uint4(w[0], w[1], w[2], w[3]);
-                    if (zb == 0) *reinterpret_cast<uint4*>(vbase + vaddr[ks] + dt * 16 * SB_KV_BLOCK) = vreg[dt][ks];
+                    const bf16x8 vb = __builtin_bit_cast(bf16x8, vreg[dt][ks]);
+                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, vb, o[dt], 0, 0, 0);
+                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, vb, o[dt], 0, 0, 0);
                 }
             }
+    #pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int qi = 4 * lq + r;
+                if (qi >= nq) continue;
+                const int qq = q0 + qi, rr = qq / G, gi = qq - rr * G;
+                if (key0 > a.pos0 + rr) continue;  // (a chunk with no visible key leaves no partial)
+                float* p = a.partials + ((size_t)(rr * Hq + g * G + gi) * a.max_chunks + chunk) * (HD + 2);
+    #pragma unroll
+                for (int dt = 0; dt < DT; ++dt) p[2 + (wave * DT + dt) * 16 + li] = o[dt][r];
+                if (wave == 0 && li == 0) { p[0] = s_m[qi]; p[1] = s_l[qi]; }
+            }
+        }
+        __syncthreads();  // the next group overwrites the LDS arrays
         }
     }
-    for (int qg = qg_first; qg < qg_last; ++qg) {
-    const int q0 = qg * QG;
-    const int nq = (nq_total - q0 < QG) ? (nq_total - q0) : QG;
-    // ---- rotated queries -> LDS as hi + lo
-#pragma unroll
-    for (int it = 0; it < QIT; ++it) {
-        const int i = tid + it * 256;
-        const int qi = i / HALF, j = i - qi * HALF;
-        const float u = qx[it] * qc[it] - qy[it] * qsn[it], v = qy[it] * qc[it] + qx[it] * qsn[it];
-        const uint16_t uh = f2bf(u), vh = f2bf(v);
-        q_hi[qi * QS + j] = uh;
-        q_lo[qi * QS + j] = f2bf(u - bf2f(uh));
-        q_hi[qi * QS + j + HALF] = vh;
-        q_lo[qi * QS + j + HALF] = f2bf(v - bf2f(vh));
-    }
-    if (qg + 1 < qg_last) load_q(qg + 1);  // (in flight during this group's products)
-    __syncthreads();
+};
 
-    // ---- scores of this wave's 32 keys against the 16 query rows
-    {
-        f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-        for (int ks = 0; ks < KSQ; ++ks) {
-            const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&q_hi[li * QS + ks * 32 + lq * 8]));
-            const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&q_lo[li * QS + ks * 32 + lq * 8]));
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const bf16x8 kb = __builtin_bit_cast(bf16x8, kreg[t][ks]);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, kb, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, kb, acc[t], 0, 0, 0);
-            }
-        }
-        // result register r of lane (li, lq): query 4*lq + r, key li of the tile
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) s_s[(4 * lq + r) * SS + wave * 32 + t * 16 + li] = acc[t][r];
-    }
-    __syncthreads();
-    // ---- softmax partial of each query over the chunk (one wave per query)
-    for (int qi = wave; qi < QG; qi += 4) {
-        if (qi >= nq) {  // unused operand rows: defined values
-            p_hi[qi * PS + lane] = p_hi[qi * PS + lane + 64] = 0;
-            p_lo[qi * PS + lane] = p_lo[qi * PS + lane + 64] = 0;
-            continue;
-        }
-        const int r = (q0 + qi) / G;
-        float sc[2];
-        float mx = -SB_INF;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int t = lane + 64 * h;
-            sc[h] = (key0 + t <= a.pos0 + r) ? s_s[qi * SS + t] * scale : -SB_INF;
-            mx = fmaxf(mx, sc[h]);
-        }
-        mx = wave_max(mx);
-        float l = 0.f;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const float p = (mx == -SB_INF) ? 0.f : expf(sc[h] - mx);
-            const uint16_t ph = f2bf(p);
-            p_hi[qi * PS + lane + 64 * h] = ph;
-            p_lo[qi * PS + lane + 64 * h] = f2bf(p - bf2f(ph));
-            l += p;
-        }
-        l = wave_sum(l);
-        if (lane == 0) { s_m[qi] = mx; s_l[qi] = l; }
-    }
-    __syncthreads();
-    // ---- weighted values: this wave's DT tiles of 16 dims, all keys of the chunk
-    {
-        f32x4 o[DT];
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KSV; ++ks) {
-            const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&p_hi[li * PS + ks * 32 + lq * 8]));
-            const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&p_lo[li * PS + ks * 32 + lq * 8]));
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                const bf16x8 vb = __builtin_bit_cast(bf16x8, vreg[dt][ks]);
-                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, vb, o[dt], 0, 0, 0);
-                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, vb, o[dt], 0, 0, 0);
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int qi = 4 * lq + r;
-            if (qi >= nq) continue;
-            const int qq = q0 + qi, rr = qq / G, gi = qq - rr * G;
-            if (key0 > a.pos0 + rr) continue;  // (a chunk with no visible key leaves no partial)
-            float* p = a.partials + ((size_t)(rr * Hq + g * G + gi) * a.max_chunks + chunk) * (HD + 2);
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) p[2 + (wave * DT + dt) * 16 + li] = o[dt][r];
-            if (wave == 0 && li == 0) { p[0] = s_m[qi]; p[1] = s_l[qi]; }
-        }
-    }
-    __syncthreads();  // the next group overwrites the LDS arrays
-    }
+template <int HD>
+__device__ __forceinline__ void attn_mfma_body(const AttnArgs& a, const int g, const int chunk, const int zb) {
+    __shared__ AttnLds<HD> lds;
+    AttnItem<HD> it;
+    it.load(a, g, chunk, zb);
+    it.compute(a, lds);
 }
 
 template <int HD>
