@@ -194,7 +194,7 @@ def test_head_ties_take_lowest_index(T):
             assert int(am.cpu()[0]) == min(rows)
 
 
-def _attention_case(T, Hq, Hkv, hd, kv_bf16, n_ctx, M, base, shuffle, seed):
+def _attention_case(T, Hq, Hkv, hd, kv_bf16, n_ctx, M, base, shuffle, seed, oracle=True):
     """Append n_ctx + M rows in passes, then compare the last pass's output rows."""
     import paper_2604_12247_amd as sb
     g = np.random.default_rng(seed)
@@ -221,6 +221,8 @@ def _attention_case(T, Hq, Hkv, hd, kv_bf16, n_ctx, M, base, shuffle, seed):
         if pos + m == n_tot:
             out = o.cpu().numpy()
         pos += m
+    if not oracle:
+        return None, out
     # oracle: rotate, round K/V as the cache does, attend
     def rnd(a):
         return si.bf16_to_f32(si.round_to_bf16(a.astype(np.float32))) if kv_bf16 else a.astype(np.float32)
@@ -254,6 +256,8 @@ ATT_CASES = [  # Hq, Hkv, hd, kv_bf16, n_ctx, M, rope base, shuffled pages
     (8, 8, 128, True, 63, 3, 1e4, False),      # shorter than one chunk
     (8, 8, 128, True, 1030, 5, 1e4, True),     # nine chunks, the last one nearly empty
     (2, 1, 128, True, 65532, 4, 1e4, True),    # the longest context the kernels take: 512 chunks, 4096 shuffled pages
+    (32, 32, 128, True, 3300, 6, 1e4, True),   # 32 x 26 blocks: more than the chip holds at once
+    (16, 16, 64, True, 8300, 3, 1e4, True),    # 16 x 65 blocks, head_dim 64
     (32, 1, 64, True, 200, 3, 1e4, True),      # one kv head for 32 query heads: six 16-query groups per block
     (16, 1, 128, False, 90, 5, 1e4, False),    # the same on the fp32-cache kernel
 ]
@@ -398,5 +402,12 @@ def test_attention_row_result_does_not_depend_on_m(T):
     _, out6 = _attention_case(T, *args, 1021, 6, 1e4, True, seed=78)
     for r in (0, 2, 3, 5):
         _, out1 = _attention_case(T, *args, 1021 + r, 1, 1e4, True, seed=78)
+        assert np.array_equal(out1[0], out6[r]), r
+    # a pass of six rows with 32 kv heads x 25 chunks (more blocks than the chip holds at once) against
+    # single rows with 24 and with 25 chunks
+    args = (32, 32, 128, True)
+    _, out6 = _attention_case(T, *args, 3070, 6, 1e4, True, seed=79, oracle=False)
+    for r in (0, 1, 2, 5):
+        _, out1 = _attention_case(T, *args, 3070 + r, 1, 1e4, True, seed=79, oracle=False)
         assert np.array_equal(out1[0], out6[r]), r
 
