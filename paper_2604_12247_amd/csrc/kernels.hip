@@ -373,6 +373,10 @@ struct BlockRed {
     }
 };
 
+// CACHED: the vocabulary fits 32 weights per thread, which then stay in registers through the passes
+// of the nucleus search instead of being recomputed from the logits (same values, same order of
+// additions either way).
+template <bool CACHED>
 __global__ __launch_bounds__(1024) void sample_accept_kernel(SampleArgs a) {
     __shared__ float red[16];
     __shared__ float seg[1024];
@@ -389,7 +393,17 @@ __global__ __launch_bounds__(1024) void sample_accept_kernel(SampleArgs a) {
         for (int j = tid; j < V; j += 1024) mx = fmaxf(mx, z[j]);
         mx = br.max(mx);
         float sm = 0.f;
-        for (int j = tid; j < V; j += 1024) sm += expf((z[j] - mx) / a.temp);
+        float ev[32];   // (CACHED) weight of token tid + 1024 i
+        if (CACHED) {
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                const int j = tid + 1024 * i;
+                ev[i] = j < V ? expf((z[j] - mx) / a.temp) : 0.f;
+                if (j < V) sm += ev[i];
+            }
+        } else {
+            for (int j = tid; j < V; j += 1024) sm += expf((z[j] - mx) / a.temp);
+        }
         const float S = br.sum(sm);
         // nucleus: the largest weight value `cut` such that the weights >= cut hold a share top_p
         // of S (so equal weights at its edge stay together); found by bisection on the bit
@@ -402,18 +416,30 @@ __global__ __launch_bounds__(1024) void sample_accept_kernel(SampleArgs a) {
                 const uint32_t mid = lo + (hi - lo) / 2u;
                 const float t = __uint_as_float(mid);
                 float f = 0.f;
-                for (int j = tid; j < V; j += 1024) {
-                    const float e = expf((z[j] - mx) / a.temp);
-                    if (e >= t) f += e;
+                if (CACHED) {
+#pragma unroll
+                    for (int i = 0; i < 32; ++i)
+                        if (tid + 1024 * i < V && ev[i] >= t) f += ev[i];
+                } else {
+                    for (int j = tid; j < V; j += 1024) {
+                        const float e = expf((z[j] - mx) / a.temp);
+                        if (e >= t) f += e;
+                    }
                 }
                 f = br.sum(f);
                 if (f >= need) lo = mid; else hi = mid;
             }
             cut = __uint_as_float(lo);
             float f = 0.f;
-            for (int j = tid; j < V; j += 1024) {
-                const float e = expf((z[j] - mx) / a.temp);
-                if (e >= cut) f += e;
+            if (CACHED) {
+#pragma unroll
+                for (int i = 0; i < 32; ++i)
+                    if (tid + 1024 * i < V && ev[i] >= cut) f += ev[i];
+            } else {
+                for (int j = tid; j < V; j += 1024) {
+                    const float e = expf((z[j] - mx) / a.temp);
+                    if (e >= cut) f += e;
+                }
             }
             keep = br.sum(f);
         }
@@ -490,7 +516,8 @@ __global__ __launch_bounds__(1024) void sample_accept_kernel(SampleArgs a) {
 hipError_t launch_sample_accept(const SampleArgs& a, hipStream_t st) {
     if (!a.logits || !a.round || a.V < 1 || a.V > (1 << 24) || a.M < 1 || a.M > SB_MAX_W || !(a.temp > 0.f) || !(a.top_p > 0.f))
         return hipErrorInvalidValue;
-    sample_accept_kernel<<<1, 1024, 0, st>>>(a);
+    if (a.V <= 32 * 1024) sample_accept_kernel<true><<<1, 1024, 0, st>>>(a);
+    else sample_accept_kernel<false><<<1, 1024, 0, st>>>(a);
     return hipGetLastError();
 }
 
