@@ -100,6 +100,34 @@ def test_batch_with_computed_exits_and_sampling(sb):
     assert [firsts[1]] + outs[1].tolist() == alone[1][0].tolist()
 
 
+def test_failed_launch_in_a_batch_abandons_the_open_rounds_of_all_sequences(sb):
+    """A projection launch that fails inside a batched round (forced from the host, nothing faults on
+    the GPU): sb_batch_decode returns a device error, every sequence keeps its committed tokens and
+    cache, and decoding on -- together or alone -- gives what an undisturbed run gives."""
+    shape, w, om = tiny_model(n_layers=6, n_exit_heads=3, seed=33, max_seq=160, **KW)
+    gm = gpu_model(shape, w, 160)
+    prompts = _prompts(shape.vocab, 2, 970)
+    P = [gpu_params(3, 4, 0.5, forced_exit=si.forced_exit_schedule(50 + b, 300, 0, 3)) for b in range(2)]
+    ref = [gm.session().generate(prompts[b], 31, P[b])[0].tolist() for b in range(2)]
+    sess = [gm.session() for _ in range(2)]
+    firsts = [s.prefill(p) for s, p in zip(sess, prompts)]
+    bt = sb.Batch(sess)
+    got = [o.tolist() for o in bt.decode(8, P)]
+    c0 = [s.committed_len() for s in sess]
+    for nth in (3, 40):                       # in a draft super-step, in the verification
+        sess[0].debug_fail_launch(nth)        # (the shared sweeps are launched through the first session)
+        with pytest.raises(sb.SbError) as e:
+            bt.decode(20, P)
+        assert e.value.code == sb.EDEVICE
+        assert [s.committed_len() for s in sess] == c0 and all(s.open_rows() == 0 for s in sess)
+    sess[0].debug_fail_launch(0)
+    more = [o.tolist() for o in bt.decode(12, P)]
+    rest1, _ = sess[1].decode(10, P[1])
+    for b in range(2):
+        assert [firsts[b]] + got[b] + more[b] == ref[b][:21], b
+    assert ref[1][21:31] == rest1.tolist()
+
+
 def test_batch_argument_errors(sb):
     shape, w, om = tiny_model(n_layers=4, n_exit_heads=2, seed=3, max_seq=96, **KW)
     gm = gpu_model(shape, w, 96)
