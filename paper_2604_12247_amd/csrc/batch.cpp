@@ -278,7 +278,8 @@ int batch_round(sb_batch* bt, const std::vector<int>& act, const sb_params* cons
                 return fail(SB_EINVAL, "batch_decode: sample_u of sequence %d has %lld entries, this round needs %lld", b,
                             (long long)p->n_sample_u, 2 * (long long)(s->c + M));
             SampleArgs sa{};
-            sa.logits = logits + (size_t)(b * wc) * c.vocab; sa.V = c.vocab; sa.M = M; sa.n_drafts = s->n_drafts;
+            sa.logits = logits + (size_t)(b * wc) * c.vocab; sa.wts = wsp<float>(hs, hs->L.sample_w) + (size_t)(b * wc) * (c.vocab > 32 * 1024 ? c.vocab - 32 * 1024 : 0);
+            sa.V = c.vocab; sa.M = M; sa.n_drafts = s->n_drafts;
             sa.temp = p->sample_temperature; sa.top_p = p->top_p; sa.round = s->d_round;
             for (int i = 0; i < M; ++i) {
                 sa.ua[i] = p->sample_u[2 * (int64_t)(s->c + i)];

@@ -28,7 +28,7 @@ inline size_t esize(int dtype) { return dtype == SB_BF16 ? 2 : 4; }
 
 struct WsLayout {
     size_t H, xn, xs_attn, xs_ffn, xs_exit, xs_exit2, ssq_exit, ssq_attn, ssq_ffn, qkv, att, atts, u, us, attn_part, head_part,
-        logits_exit, logits_final, round, table, total;
+        logits_exit, logits_final, sample_w, round, table, total;
     int max_chunks, head_blocks, n_pages, ssq_ld;
     // prompt passes of SB_PREFILL_ROWS rows (packed bf16 weights only)
     bool prefill_gemm;

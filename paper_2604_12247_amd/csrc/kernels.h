@@ -97,6 +97,7 @@ struct GemvArgs {
 // Sampling-mode acceptance over the final-head logits of the M verified rows (device, [M][V]).
 struct SampleArgs {
     const float* logits;
+    float* wts;   // scratch [M][V - 32768] for the soft-max weights of a vocabulary's tokens from 32768 on (unused below that)
     int32_t V, M, n_drafts;
     float temp, top_p;
     float ua[SB_MAX_W], ur[SB_MAX_W];  // per row: uniform of the acceptance test, uniform of the draw

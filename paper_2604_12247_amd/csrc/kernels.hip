@@ -373,38 +373,61 @@ struct BlockRed {
     }
 };
 
-// CACHED: the vocabulary fits 32 weights per thread, which then stay in registers through the passes
-// of the nucleus search instead of being recomputed from the logits (same values, same order of
-// additions either way).
-template <bool CACHED>
+// A thread's share (tokens tid, tid + 1024, ... of the V in w) of the sum of the weights >= t, added to f
+// in index order; sixteen loads are in flight at a time.
+__device__ __forceinline__ float add_at_least(const float* w, int V, float t, float f) {
+    int j = threadIdx.x;
+    for (; j + 15 * 1024 < V; j += 16 * 1024) {
+        float e[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) e[i] = w[j + 1024 * i];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (e[i] >= t) f += e[i];
+    }
+    for (; j < V; j += 1024) { const float e = w[j]; if (e >= t) f += e; }
+    return f;
+}
+
+// Thread tid owns the weights of tokens tid, tid + 1024, ...: the first 32 of them stay in registers
+// through the passes of the nucleus search, the rest (vocabularies above 32768) in a.wts, where a
+// thread re-reads only what it wrote itself.
 __global__ __launch_bounds__(1024) void sample_accept_kernel(SampleArgs a) {
+    constexpr int NR = 32, VR = NR * 1024;
     __shared__ float red[16];
     __shared__ float seg[1024];
     __shared__ float s_base;
     __shared__ int s_seg, s_tok;
     BlockRed br{red};
     const int tid = threadIdx.x, V = a.V;
+    const int Vw = V > VR ? V - VR : 0;   // weights kept in a.wts
     DevRound* R = a.round;
     int m = 0;       // accepted drafts so far (uniform)
     int drawn = -1;  // row at which a token was drawn
     for (int row = 0; row < a.M; ++row) {
         const float* z = a.logits + (size_t)row * V;
+        float* w = a.wts + (size_t)row * Vw;
         float mx = -SB_INF;
         for (int j = tid; j < V; j += 1024) mx = fmaxf(mx, z[j]);
         mx = br.max(mx);
         float sm = 0.f;
-        float ev[32];   // (CACHED) weight of token tid + 1024 i
-        if (CACHED) {
+        float ev[NR];   // weight of token tid + 1024 i
 #pragma unroll
-            for (int i = 0; i < 32; ++i) {
-                const int j = tid + 1024 * i;
-                ev[i] = j < V ? expf((z[j] - mx) / a.temp) : 0.f;
-                if (j < V) sm += ev[i];
-            }
-        } else {
-            for (int j = tid; j < V; j += 1024) sm += expf((z[j] - mx) / a.temp);
+        for (int i = 0; i < NR; ++i) {
+            const int j = tid + 1024 * i;
+            ev[i] = j < V ? expf((z[j] - mx) / a.temp) : 0.f;
+            if (j < V) sm += ev[i];
         }
+        for (int j = tid; j < Vw; j += 1024) { const float e = expf((z[VR + j] - mx) / a.temp); w[j] = e; sm += e; }
         const float S = br.sum(sm);
+        auto mass_at_least = [&](float t) {   // sum of the weights >= t, in a fixed order
+            float f = 0.f;
+#pragma unroll
+            for (int i = 0; i < NR; ++i)
+                if (tid + 1024 * i < V && ev[i] >= t) f += ev[i];
+            if (Vw > 0) f = add_at_least(w, Vw, t, f);
+            return br.sum(f);
+        };
         // nucleus: the largest weight value `cut` such that the weights >= cut hold a share top_p
         // of S (so equal weights at its edge stay together); found by bisection on the bit
         // pattern of a positive float, which is monotone in its value
@@ -414,34 +437,10 @@ __global__ __launch_bounds__(1024) void sample_accept_kernel(SampleArgs a) {
             uint32_t lo = 0u, hi = __float_as_uint(1.0f) + 1u;  // the largest weight is exp(0) = 1
             while (hi - lo > 1u) {
                 const uint32_t mid = lo + (hi - lo) / 2u;
-                const float t = __uint_as_float(mid);
-                float f = 0.f;
-                if (CACHED) {
-#pragma unroll
-                    for (int i = 0; i < 32; ++i)
-                        if (tid + 1024 * i < V && ev[i] >= t) f += ev[i];
-                } else {
-                    for (int j = tid; j < V; j += 1024) {
-                        const float e = expf((z[j] - mx) / a.temp);
-                        if (e >= t) f += e;
-                    }
-                }
-                f = br.sum(f);
-                if (f >= need) lo = mid; else hi = mid;
+                if (mass_at_least(__uint_as_float(mid)) >= need) lo = mid; else hi = mid;
             }
             cut = __uint_as_float(lo);
-            float f = 0.f;
-            if (CACHED) {
-#pragma unroll
-                for (int i = 0; i < 32; ++i)
-                    if (tid + 1024 * i < V && ev[i] >= cut) f += ev[i];
-            } else {
-                for (int j = tid; j < V; j += 1024) {
-                    const float e = expf((z[j] - mx) / a.temp);
-                    if (e >= cut) f += e;
-                }
-            }
-            keep = br.sum(f);
+            keep = mass_at_least(cut);
         }
         const bool has_draft = row < a.n_drafts;
         const int x = has_draft ? R->drafts[row] : -1;
@@ -516,8 +515,8 @@ __global__ __launch_bounds__(1024) void sample_accept_kernel(SampleArgs a) {
 hipError_t launch_sample_accept(const SampleArgs& a, hipStream_t st) {
     if (!a.logits || !a.round || a.V < 1 || a.V > (1 << 24) || a.M < 1 || a.M > SB_MAX_W || !(a.temp > 0.f) || !(a.top_p > 0.f))
         return hipErrorInvalidValue;
-    if (a.V <= 32 * 1024) sample_accept_kernel<true><<<1, 1024, 0, st>>>(a);
-    else sample_accept_kernel<false><<<1, 1024, 0, st>>>(a);
+    if (a.V > 32 * 1024 && !a.wts) return hipErrorInvalidValue;
+    sample_accept_kernel<<<1, 1024, 0, st>>>(a);
     return hipGetLastError();
 }
 

@@ -106,6 +106,8 @@ WsLayout ws_layout(const sb_config* c) {
     L.head_part = take((size_t)SB_MAX_W * L.head_blocks * 16);
     L.logits_exit = take((size_t)(c->n_exit_heads > 0 ? c->n_exit_heads : 1) * V * 4);
     L.logits_final = take((size_t)SB_MAX_W * V * 4);
+    // the sampling-mode acceptance kernel keeps the soft-max weights of a large vocabulary here
+    L.sample_w = take(V > 32 * 1024 ? (size_t)SB_MAX_W * (V - 32 * 1024) * 4 : 0);
     L.round = take(sizeof(DevRound));
     L.table = take((size_t)L.n_pages * 4);
     L.prefill_gemm = resolve_proj(c) == SB_PROJ_MFMA_PACKED;
@@ -707,7 +709,7 @@ int verify_impl(sb_session* s, const sb_params* p, sb_verify_result* out) {
     if ((rc = run_head(s, m->lm_head, m->final_norm, 0, M, h, m->stream))) return rc;
     if (sampling) {
         SampleArgs sa{};
-        sa.logits = wsp<float>(s, s->L.logits_final); sa.V = c.vocab; sa.M = M; sa.n_drafts = s->n_drafts;
+        sa.logits = wsp<float>(s, s->L.logits_final); sa.wts = wsp<float>(s, s->L.sample_w); sa.V = c.vocab; sa.M = M; sa.n_drafts = s->n_drafts;
         sa.temp = p->sample_temperature; sa.top_p = p->top_p; sa.round = s->d_round;
         for (int i = 0; i < M; ++i) {
             sa.ua[i] = p->sample_u[2 * (int64_t)(s->c + i)];
