@@ -16,7 +16,7 @@ int32_t sb_op_rmsnorm(const float* x, const float* gain, float* out, int32_t M, 
     return SB_OK;
 }
 
-size_t sb_op_gemv_scratch_bytes(int32_t M, int32_t K) { return K > 0 ? align_up((size_t)16 * K * 2, 256) : 0; }
+size_t sb_op_gemv_scratch_bytes(int32_t /*M: sized for the maximum*/, int32_t K) { return K > 0 ? align_up((size_t)16 * K * 2, 256) : 0; }
 
 static int op_check(const void* W, int32_t w_dtype, int32_t N, int32_t K, const float* x, int32_t M, int32_t kernel) {
     if (!W || !x) return fail(SB_EINVAL, "op: NULL operand");
@@ -101,7 +101,7 @@ int32_t sb_op_gemm(const void* Wp, int32_t N, int32_t K, const float* x, float* 
     return SB_OK;
 }
 
-size_t sb_op_head_scratch_bytes(int32_t M, int32_t N, int32_t K) {
+size_t sb_op_head_scratch_bytes(int32_t /*M: sized for the maximum*/, int32_t N, int32_t K) {
     if (N < 1 || K < 1) return 0;
     int nb = head_blocks_valu(N);
     return 256 + align_up((size_t)SB_MAX_W * nb * 16, 256) + align_up((size_t)16 * K * 2, 256);

@@ -900,7 +900,7 @@ int32_t sb_load_model(const sb_config* cfg, const sb_weights* w, void* stream, s
     if (e == hipSuccess) e = hipMemcpy(m->rope_sin, hs.data(), hs.size() * 4, hipMemcpyHostToDevice);
     // tile-packed copies of the projection matrices
     if (e == hipSuccess && m->packed) {
-        const int d = cfg->d_model, f = cfg->d_ffn, hq = cfg->n_heads * cfg->head_dim, V = cfg->vocab;
+        const int dm = cfg->d_model, ff = cfg->d_ffn, hq = cfg->n_heads * cfg->head_dim, V = cfg->vocab;
         // one buffer for all packed matrices: the caller's, or one the model owns
         char* pbase = (char*)w->packed;
         if (!pbase) {
@@ -916,13 +916,13 @@ int32_t sb_load_model(const sb_config* cfg, const sb_weights* w, void* stream, s
             W = P;
         };
         for (int l = 0; l < cfg->n_layers; ++l) {
-            pack(m->w_qkv[l], (int)qkv_rows, d);
-            pack(m->w_o[l], d, hq);
-            pack(m->w_gate_up[l], 2 * f, d);
-            pack(m->w_down[l], d, f);
+            pack(m->w_qkv[l], (int)qkv_rows, dm);
+            pack(m->w_o[l], dm, hq);
+            pack(m->w_gate_up[l], 2 * ff, dm);
+            pack(m->w_down[l], dm, ff);
         }
-        for (int l = 0; l < cfg->n_exit_heads; ++l) pack(m->exit_head[l], V, d);
-        pack(m->lm_head, V, d);
+        for (int l = 0; l < cfg->n_exit_heads; ++l) pack(m->exit_head[l], V, dm);
+        pack(m->lm_head, V, dm);
         if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
     }
     if (e != hipSuccess) {
