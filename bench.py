@@ -66,6 +66,9 @@ def main():
                     help="only run the head projection alone (sb_op_head: RMSNorm-folded [V x d] sweep with the Eq. 2 "
                          "epilogue, then the merge) at the 7B / 32000 and the 8B / 128256 shapes, rotating over several "
                          "matrices so that no sweep finds its weights in a cache, and exit")
+    ap.add_argument("--sampling-probe", action="store_true",
+                    help="only time a round with greedy verification against a round with sampling-mode verification "
+                         "(temperature 1.0, top-p 0.9; Sec. 4.3) on --config's shape and forced exit schedule, and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (the decode path is one sequence at batch 1); "
@@ -82,6 +85,9 @@ def main():
         return
     if args.head_probe:
         head_probe(torch, sb)
+        return
+    if args.sampling_probe:
+        sampling_probe(torch, sb, si, args.config)
         return
     wl = si.CONFIGS[args.config]
     shape = wl.shape
@@ -364,6 +370,39 @@ def head_probe(torch, sb):
                               "GB/s_three_kernels": round(V * d * 2 / us / 1e3, 1),
                               "frac_of_hbm_peak_three_kernels": round(V * d * 2 / us / 1e3 / HBM_PEAK_GBS, 4)}), flush=True)
         del Ws
+
+
+def sampling_probe(torch, sb, si, config):
+    """Cost of the sampling-mode acceptance kernel per round (Sec. 4.3): the same forced exit schedule decoded with
+    greedy and with sampled verification.  Random-init exit heads propose tokens the full model gives almost no
+    mass, so every round rejects its first draft and emits one drawn token: rounds of equal shape in both modes,
+    whose difference is the acceptance kernel (nucleus search + draw over one row) and the logits it reads."""
+    import numpy as np
+    wl = si.CONFIGS[config]
+    shape, P, gen = wl.shape, min(wl.prompt_len, 512), 128
+    model = sb.Model(shape, si.make_weights(shape, wl.weight_seed), (P + 4 * gen + 64) // 16 * 16)
+    sess = model.session()
+    first = sess.prefill(si.make_prompt(shape.vocab, P, wl.prompt_seed))
+    T = wl.temperatures()
+    fe = si.forced_exit_schedule(wl.sched_seed, 8 * gen, wl.exit_lo, wl.d_max)
+    U = np.random.default_rng(1).random(2 * (P + 4 * gen + 64)).astype(np.float32)
+    res = {}
+    for name, kw in (("greedy", {}), ("sampled", dict(sample_temperature=1.0, top_p=0.9, sample_u=U))):
+        p = sb.Params(wl.d_max, wl.w_max, T, wl.threshold, forced_exit=fe, **kw)
+        for _ in range(2):
+            sess.rewind(P, first)
+            _, st = sess.decode(gen, p)
+        res[name] = st["decode_ms"] * 1e3 / st["rounds"]
+        res[name + "_rounds"] = st["rounds"]
+        res[name + "_drafts_per_round"] = st["drafts"] / st["rounds"]
+    print(json.dumps({"probe": "sampling-mode verification", "workload": wl.name, "vocab": shape.vocab, "prompt": P,
+                      "generated": gen, "temperature": 1.0, "top_p": 0.9,
+                      "us_per_round_greedy_verification": round(res["greedy"], 1),
+                      "us_per_round_sampled_verification": round(res["sampled"], 1),
+                      "added_us_per_round": round(res["sampled"] - res["greedy"], 1),
+                      "rounds": [res["greedy_rounds"], res["sampled_rounds"]],
+                      "drafts_per_round": [round(res["greedy_drafts_per_round"], 2), round(res["sampled_drafts_per_round"], 2)]}),
+          flush=True)
 
 
 def copy_probe(torch, sb):
