@@ -406,7 +406,7 @@ __global__ __launch_bounds__(64 * WPB) void gemv_mfma_kernel(GemvArgs a) {
 // Few output rows -> one tile per block and eight waves splitting K, so that
 // enough loads are in flight; many rows -> two tiles sharing one B operand.
 static int mfma_row_tiles(int32_t N) { return N >= 15000 ? 2 : 1; }  // (measured: [15360 x 5120] gains 13 % at six rows with two, [12288 x 4096] loses 5 %)
-static int mfma_waves(int32_t N) { return N <= 8192 ? 8 : 4; }
+static int mfma_waves(int32_t N) { return N <= 4096 ? 8 : 4; }  // (measured: [6144 x 4096] is 9-12 % faster with four waves and the deeper ring, [5120 x K] the same with either)
 int head_blocks_mfma(int32_t N) { return (N + 16 * mfma_row_tiles(N) - 1) / (16 * mfma_row_tiles(N)); }
 
 template <int EPI, bool PACKED>
