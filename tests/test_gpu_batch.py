@@ -100,6 +100,28 @@ def test_batch_with_computed_exits_and_sampling(sb):
     assert [firsts[1]] + outs[1].tolist() == alone[1][0].tolist()
 
 
+def test_batch_of_sampled_sequences_at_a_large_vocabulary(sb):
+    """Two sampled sequences (different temperatures and uniforms) over a vocabulary above 32768, where the
+    acceptance kernel keeps part of each row's soft-max weights in the workspace: every sequence has a region of
+    its own there, so each output equals the sequence's single run, token for token."""
+    shape = si.tiny_shape(n_layers=5, n_exit_heads=3, vocab=32768 + 1040, **KW)
+    w = si.make_weights(shape, 93)
+    gm = gpu_model(shape, w, 128)
+    prompts = _prompts(shape.vocab, 2, 990)
+    T = linear_T(3)
+    g = np.random.default_rng(17)
+    P = [sb.Params(3, 4, T, 0.0, sample_temperature=t, top_p=tp, sample_u=g.random(2 * 128).astype(np.float32))
+         for t, tp in ((1.0, 0.9), (0.6, 0.7))]
+    alone = [gm.session().generate(prompts[b], 24, P[b]) for b in range(2)]
+    sess = [gm.session() for _ in range(2)]
+    firsts = [s.prefill(p) for s, p in zip(sess, prompts)]
+    outs = sb.Batch(sess).decode(23, P)
+    for b in range(2):
+        assert [firsts[b]] + outs[b].tolist() == alone[b][0].tolist()
+        assert sess[b].stats()["rounds"] == alone[b][1]["rounds"]
+    assert alone[0][0].tolist() != alone[1][0].tolist()
+
+
 def test_failed_launch_in_a_batch_abandons_the_open_rounds_of_all_sequences(sb):
     """A projection launch that fails inside a batched round (forced from the host, nothing faults on
     the GPU): sb_batch_decode returns a device error, every sequence keeps its committed tokens and
