@@ -63,7 +63,8 @@ def test_gemv_valu(T, N, K, bf16, M):
 
 MFMA_CASES = [(16, 128), (64, 256), (4096, 4096), (12288, 4096), (4096, 11008), (32000, 4096), (48, 384),
               (15024, 256),      # two row tiles per block, an odd number of tiles: the last block owns one
-              (4096, 14336)]
+              (4096, 14336),
+              (6144, 4096), (5120, 5120), (5120, 13824)]   # between 4096 and 8192 output rows: one tile per block, four waves
 
 
 @pytest.mark.parametrize("N,K", MFMA_CASES)
@@ -137,7 +138,7 @@ def test_gemv_row_result_does_not_depend_on_m(T, kernel):
     import paper_2604_12247_amd as sb
     k = {"valu": sb.PROJ_VALU, "mfma": sb.PROJ_MFMA, "mfma_packed": sb.PROJ_MFMA_PACKED}[kernel]
     g = np.random.default_rng(5)
-    for N, K in ((4096, 4096), (1024, 11008), (32000, 256)):
+    for N, K in ((4096, 4096), (1024, 11008), (32000, 256), (6144, 512), (15360, 256)):
         W = _dev(T, _rand_w(g, N, K, True))
         if kernel == "mfma_packed":
             W = sb.op_repack(W)
